@@ -1,0 +1,251 @@
+"""CPU oracle (fp64, NumPy) for the CCA / CCGQA prefill block.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP
+path is checked against.  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import it; the product path never
+does.  It shares no code with the HIP path and imports nothing from it.
+
+CCA is its own function (not an approximation of MHA), so the oracle takes the
+method's steps in the paper's order, each by its plain definition:
+
+  1. down-projection of x to latent q, k and the two value streams
+     (Sec. 2.2, first CCA equation and the value-shift equation);
+  2. depth-wise causal sequence convolution on q and k (conv1_seq);
+  3. head-wise grouped causal convolution mixing the channels of one head
+     across k_ch time steps (conv2_seq+ch);
+  4. qk-mean: add the mean of the *pre-convolution* q and (group-broadcast) k;
+  5. value-shift: half of the value channels come from the previous token;
+  6. L2 normalisation of q, k over the head width, scaled by sqrt(d_h); the
+     key additionally by beta = exp(temp) per KV head;
+  7. RoPE on q and k in the latent space;
+  8. causal softmax attention per latent head, KV heads shared by groups of
+     consecutive query heads (CCGQA);
+  9. up-projection to d_model.
+
+All arithmetic is fp64.  Inputs are whatever the caller hands over (already
+rounded to the storage type), upcast to fp64; nothing is rounded in between.
+
+Pins (tests/test_oracle_pins.py): reduction to textbook MHA / GQA; identity
+convolutions; causality; brute-force softmax on tiny inputs; norm / RoPE
+closed forms; the first-token closed form; a cross-check of steps 1-6 against
+library convolution / normalisation routines; RoPE as complex multiplication.
+Readings that no printed value can pin (k_ch = 2, softmax scale 1/sqrt(d_h)
+when d_h != E/16, rotate-half RoPE pairing with base 10000) are "parity
+unpinned": the HIP path is checked against this oracle's reading of them.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "down_project", "conv_seq", "conv_ch", "qk_mean", "value_shift",
+    "qk_norm_temp", "rope", "attention", "up_project", "cca_forward",
+]
+
+
+def _f64(a):
+    return np.asarray(a, dtype=np.float64)
+
+
+def _shift_time(a, s):
+    """a[:, t] -> a[:, t - s] along axis 1 with zeros entering at the start of
+    every sequence (axis 0 is the batch, so sequences never leak into each
+    other)."""
+    if s == 0:
+        return a
+    out = np.zeros_like(a)
+    if s < a.shape[1]:
+        out[:, s:] = a[:, : a.shape[1] - s]
+    return out
+
+
+# -- step 1 -----------------------------------------------------------------
+def down_project(x, w_down, n_q_heads, n_kv_heads, head_dim):
+    """q0 = x W_Q, k0 = x W_K, vc = x W_V, vp = x W_Vbar (Sec. 2.2: the
+    down-projection equation and the value-shift equation).  ``w_down`` packs
+    the four matrices column-wise as [W_Q | W_K | W_V | W_Vbar]."""
+    x, w_down = _f64(x), _f64(w_down)
+    B, T, E = x.shape
+    e_q, e_kv = n_q_heads * head_dim, n_kv_heads * head_dim
+    half = e_kv // 2
+    assert w_down.shape == (E, e_q + 2 * e_kv)
+    lat = x @ w_down
+    q0 = lat[..., :e_q].reshape(B, T, n_q_heads, head_dim)
+    k0 = lat[..., e_q:e_q + e_kv].reshape(B, T, n_kv_heads, head_dim)
+    vc = lat[..., e_q + e_kv:e_q + e_kv + half]
+    vp = lat[..., e_q + e_kv + half:]
+    return q0, k0, vc, vp
+
+
+# -- step 2 -----------------------------------------------------------------
+def conv_seq(u, w0):
+    """Depth-wise causal convolution along time (conv1_seq in the conv
+    equation of Sec. 2.2).  u: (B,T,C), w0: (C,k_seq).  Tap k_seq-1 multiplies
+    the current token, tap j the token k_seq-1-j steps back."""
+    u, w0 = _f64(u), _f64(w0)
+    k = w0.shape[1]
+    y = np.zeros_like(u)
+    for j in range(k):
+        y += w0[:, j] * _shift_time(u, k - 1 - j)
+    return y
+
+
+# -- step 3 -----------------------------------------------------------------
+def conv_ch(u, w1):
+    """Grouped causal convolution, one group per head (conv2_seq+ch).
+    u: (B,T,H,d), w1: (H, d_out, d_in, k_ch).  Each head has a dense d x d
+    filter per tap; tap k_ch-1 multiplies the current token."""
+    u, w1 = _f64(u), _f64(w1)
+    H, d_out, d_in, k = w1.shape
+    y = np.zeros(u.shape[:3] + (d_out,))
+    for j in range(k):
+        us = _shift_time(u, k - 1 - j)
+        for h in range(H):
+            # y[b,t,h,o] += sum_i w1[h,o,i,j] * us[b,t,h,i]
+            y[:, :, h, :] += us[:, :, h, :] @ w1[h, :, :, j].T
+    return y
+
+
+# -- step 4 -----------------------------------------------------------------
+def qk_mean(q2, k2, q0, k0):
+    """qk-mean equation of Sec. 2.2.  m_q = (q_pre + B_group(k_pre)) / 2 per
+    query head; m_k = E_group(m_q) = mean of m_q over the query heads that
+    share a KV head.  q_pre, k_pre are the step-1 latents."""
+    Hq, Hk = q0.shape[2], k0.shape[2]
+    R = Hq // Hk
+    k_b = np.repeat(k0, R, axis=2)                     # q head h <- kv head h // R
+    m_q = 0.5 * (q0 + k_b)
+    m_k = m_q.reshape(m_q.shape[0], m_q.shape[1], Hk, R, -1).mean(axis=3)
+    return q2 + m_q, k2 + m_k
+
+
+# -- step 5 -----------------------------------------------------------------
+def value_shift(vc, vp, n_kv_heads, head_dim, shift=True):
+    """Value-shift equation: v_t = [W_V x_t , W_Vbar x_{t-1}], zero for the
+    first token of each sequence.  First half of the value channels is the
+    current-token stream, second half the previous-token stream."""
+    vc, vp = _f64(vc), _f64(vp)
+    if shift:
+        vp = _shift_time(vp, 1)
+    v = np.concatenate([vc, vp], axis=-1)
+    return v.reshape(v.shape[0], v.shape[1], n_kv_heads, head_dim)
+
+
+# -- step 6 -----------------------------------------------------------------
+def qk_norm_temp(q3, k3, temp=None):
+    """q <- q sqrt(d_h) / ||q||_2, k <- k sqrt(d_h) / ||k||_2 * exp(temp_g)
+    (first two lines of the final equation block of Sec. 2.2)."""
+    d = q3.shape[-1]
+    q4 = q3 * np.sqrt(d) / np.sqrt((q3 * q3).sum(-1, keepdims=True))
+    k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True))
+    if temp is not None:
+        k4 = k4 * np.exp(_f64(temp))[None, None, :, None]
+    return q4, k4
+
+
+# -- step 7 -----------------------------------------------------------------
+def rope(u, base=10000.0, interleaved=False, positions=None):
+    """Rotary position embedding on the full head width.  u: (B,T,H,d).
+    Pair i rotates by angle t * base^(-2i/d); pairs are (i, i + d/2)
+    (rotate-half) or (2i, 2i+1) when ``interleaved``."""
+    u = _f64(u)
+    B, T, H, d = u.shape
+    half = d // 2
+    t = np.arange(T, dtype=np.float64) if positions is None else _f64(positions)
+    theta = base ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    ang = t[:, None] * theta[None, :]                   # (T, d/2)
+    c, s = np.cos(ang)[None, :, None, :], np.sin(ang)[None, :, None, :]
+    out = np.empty_like(u)
+    if interleaved:
+        a, b = u[..., 0::2], u[..., 1::2]
+        out[..., 0::2] = a * c - b * s
+        out[..., 1::2] = b * c + a * s
+    else:
+        a, b = u[..., :half], u[..., half:]
+        out[..., :half] = a * c - b * s
+        out[..., half:] = b * c + a * s
+    return out
+
+
+# -- step 8 -----------------------------------------------------------------
+def attention(q, k, v, scale, causal=True, rows=None):
+    """o[t,h] = sum_s softmax_s(scale <q[t,h], k[s,h//R]>) v[s,h//R]; with
+    ``causal`` only s <= t (attention line of the final equation block;
+    KV-head sharing as in the CCGQA paragraph).
+
+    q: (B,T,Hq,d); k, v: (B,T,Hk,d).  Each query row is handled on its own by
+    the two-pass definition (max, exp, normalise); the T x T matrix is never
+    held for more than a chunk of rows.  ``rows`` (1-D int array) restricts
+    the computation to those query positions.  Returns o (B,n_rows,Hq,d) and
+    the natural-log sum-exp of the scaled logits, lse (B,Hq,n_rows).
+    """
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, T, Hq, d = q.shape
+    Hk = k.shape[2]
+    R = Hq // Hk
+    rows = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
+    n = len(rows)
+    o = np.zeros((B, n, Hq, v.shape[-1]))
+    lse = np.zeros((B, Hq, n))
+    chunk = 256
+    for b in range(B):
+        for h in range(Hq):
+            g = h // R
+            kh, vh = k[b, :, g, :], v[b, :, g, :]
+            for c0 in range(0, n, chunk):
+                r = rows[c0:c0 + chunk]
+                s_max = int(r.max()) + 1 if causal else T
+                s = scale * (q[b, r, h, :] @ kh[:s_max].T)          # (len(r), s_max)
+                if causal:
+                    s = np.where(np.arange(s_max)[None, :] <= r[:, None], s, -np.inf)
+                m = s.max(axis=1, keepdims=True)
+                p = np.exp(s - m)
+                z = p.sum(axis=1, keepdims=True)
+                o[b, c0:c0 + len(r), h, :] = (p / z) @ vh[:s_max]
+                lse[b, h, c0:c0 + len(r)] = (m + np.log(z))[:, 0]
+    return o, lse
+
+
+# -- step 9 -----------------------------------------------------------------
+def up_project(o, w_out):
+    """out = [o_1 .. o_{n_h}] W_O (last line of the final equation block)."""
+    o, w_out = _f64(o), _f64(w_out)
+    B, n = o.shape[:2]
+    return o.reshape(B, n, -1) @ w_out
+
+
+def cca_forward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, *,
+                n_q_heads, n_kv_heads, head_dim,
+                causal=True, use_conv_seq=True, use_conv_ch=True,
+                use_qk_mean=True, use_v_shift=True, use_qk_norm=True,
+                use_key_temp=True, use_rope=True, rope_interleaved=False,
+                rope_base=10000.0, softmax_scale=None, rows=None):
+    """Whole block, steps 1-9.  Returns a dict with ``out`` (B,n_rows,E) and
+    every intermediate (q0, k0 pre-conv latents; q, k, v as they enter
+    attention; o; lse)."""
+    Hq, Hk, dh = n_q_heads, n_kv_heads, head_dim
+    e_q = Hq * dh
+    x = _f64(x)
+    B, T, _ = x.shape
+    q0, k0, vc, vp = down_project(x, w_down, Hq, Hk, dh)
+    q, k = q0, k0
+    if use_conv_seq:
+        w0 = _f64(w_conv_seq)
+        q = conv_seq(q.reshape(B, T, -1), w0[:e_q]).reshape(q0.shape)
+        k = conv_seq(k.reshape(B, T, -1), w0[e_q:]).reshape(k0.shape)
+    if use_conv_ch:
+        w1 = _f64(w_conv_ch)
+        q = conv_ch(q, w1[:Hq])
+        k = conv_ch(k, w1[Hq:])
+    if use_qk_mean:
+        q, k = qk_mean(q, k, q0, k0)
+    v = value_shift(vc, vp, Hk, dh, shift=use_v_shift)
+    if use_qk_norm:
+        q, k = qk_norm_temp(q, k, temp if use_key_temp else None)
+    if use_rope:
+        q = rope(q, rope_base, rope_interleaved)
+        k = rope(k, rope_base, rope_interleaved)
+    scale = 1.0 / np.sqrt(dh) if not softmax_scale else float(softmax_scale)
+    o, lse = attention(q, k, v, scale, causal=causal, rows=rows)
+    out = up_project(o, w_out)
+    return dict(out=out, q0=q0, k0=k0, vc=vc, vp=vp, q=q, k=k, v=v, o=o, lse=lse)
