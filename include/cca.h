@@ -1,0 +1,149 @@
+/*
+ * cca.h — C ABI of the MI355X (gfx950) implementation of the prefill hot path
+ * of Compressed Convolutional Attention (CCA) and its grouped-query variant
+ * CCGQA (arXiv 2510.04476, Sec. 2.2 and App. A).
+ *
+ * The block maps hidden states x (B,T,E) to out (B,T,E):
+ *   down-projection to latent q, k and two value streams  (Sec. 2.2, down-projection eq.; value-shift eq.)
+ *   conv1_seq, conv2_seq+ch on q and k                     (Sec. 2.2, convolution eq.)
+ *   qk-mean                                                (Sec. 2.2, qk-mean eq.)
+ *   value-shift                                            (Sec. 2.2, value-shift eq.)
+ *   L2 norm * sqrt(d_h), key temperature, RoPE             (Sec. 2.2, final eq. block, lines 1-2)
+ *   causal softmax attention in the latent space, KV heads
+ *   shared by groups of query heads (CCGQA)                (final eq. block, line 3; CCGQA paragraph)
+ *   up-projection                                          (final eq. block, line 4)
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer (HIP), row-major, contiguous,
+ *     16-byte aligned, owned by the caller.  The config / weight / saved
+ *     structs themselves live in HOST memory.
+ *   - The library never allocates, frees or synchronises.  All work is
+ *     enqueued on the caller's stream (`hip_stream` is a hipStream_t, NULL =
+ *     the default stream) and the call returns at once.
+ *   - Arguments are validated on the host before the first HIP call; a failed
+ *     validation enqueues nothing.  Errors are negative cca_status values.
+ *   - Storage type (`dtype`) applies to x, weights (except temp), latents and
+ *     out.  Accumulation is always fp32.  bf16 tensors are rounded to nearest
+ *     even once per stored tensor.
+ *   - No global mutable state: calls on different streams may run
+ *     concurrently as long as their buffers (workspace included) are disjoint.
+ *
+ * Symbols: B batch, T sequence length, E = d_model, H_q / H_k latent query /
+ * KV heads, d_h latent head width, e_q = H_q*d_h (= E/C1), e_kv = H_k*d_h
+ * (= E/C2), R = H_q/H_k query heads per KV head, N_lat = e_q + 2*e_kv.
+ */
+#ifndef CCA_H_
+#define CCA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CCA_OK = 0,
+  CCA_ERR_NULL = -1,        /* a required pointer is NULL */
+  CCA_ERR_SHAPE = -2,       /* a size is non-positive or the sizes are inconsistent */
+  CCA_ERR_LAYOUT = -3,      /* head/group layout invalid (H_q % H_k, odd e_kv with value-shift, odd d_h with RoPE) */
+  CCA_ERR_UNSUPPORTED = -4, /* valid request this build has no kernel for */
+  CCA_ERR_WORKSPACE = -5,   /* workspace NULL or smaller than cca_workspace_size says */
+  CCA_ERR_ALIGN = -6,       /* a pointer is not 16-byte aligned */
+  CCA_ERR_DTYPE = -7,       /* dtype is neither CCA_BF16 nor CCA_F32 */
+  CCA_ERR_LAUNCH = -8       /* HIP reported an error while enqueuing */
+} cca_status;
+
+typedef enum { CCA_BF16 = 0, CCA_F32 = 1 } cca_dtype;
+
+/* Feature flags: each optional transform of Sec. 2.2 can be switched on its
+ * own (the paper's ablation tables switch the same ones). */
+enum {
+  CCA_CAUSAL = 1u << 0,           /* attend to s <= t only */
+  CCA_CONV_SEQ = 1u << 1,         /* conv1_seq: depth-wise causal conv, width k_seq */
+  CCA_CONV_CH = 1u << 2,          /* conv2_seq+ch: per-head dense d_h x d_h causal conv, width k_ch */
+  CCA_QK_MEAN = 1u << 3,          /* qk-mean skip branch from the pre-conv latents */
+  CCA_V_SHIFT = 1u << 4,          /* second half of the value channels comes from token t-1 */
+  CCA_QK_NORM = 1u << 5,          /* L2 norm over d_h, times sqrt(d_h) */
+  CCA_KEY_TEMP = 1u << 6,         /* key times exp(temp[g]); requires CCA_QK_NORM */
+  CCA_ROPE = 1u << 7,             /* rotary embedding on q and k, full head width, positions 0..T-1 */
+  CCA_ROPE_INTERLEAVED = 1u << 8  /* pairs (2i,2i+1) instead of (i, i+d_h/2) */
+};
+#define CCA_FLAGS_PAPER                                                                         \
+  (CCA_CAUSAL | CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_V_SHIFT | CCA_QK_NORM | CCA_KEY_TEMP | \
+   CCA_ROPE)
+/* Plain MHA / GQA (Sec. 2.1) through the same kernels: e_q = E, no transforms. */
+#define CCA_FLAGS_MHA (CCA_CAUSAL)
+
+typedef struct {
+  int32_t B, T, d_model;
+  int32_t n_q_heads, n_kv_heads, head_dim; /* H_q, H_k, d_h; H_q % H_k == 0.  C1 = E/(H_q d_h), C2 = E/(H_k d_h) */
+  int32_t k_seq, k_ch;                     /* conv widths, 1..4; ignored when the conv's flag is off */
+  int32_t dtype;                           /* cca_dtype */
+  uint32_t flags;
+  float rope_base;                         /* e.g. 10000; must be > 0 when CCA_ROPE */
+  float softmax_scale;                     /* 0 => 1/sqrt(d_h) */
+} cca_config;
+
+/* Weights (device pointers, read-only).  Pointers whose flag is off may be NULL. */
+typedef struct {
+  const void *w_down;     /* (E, N_lat): columns [W_Q (e_q) | W_K (e_kv) | W_V (e_kv/2) | W_Vbar (e_kv - e_kv/2)] */
+  const void *w_conv_seq; /* (e_q + e_kv, k_seq): depth-wise filter per packed q|k channel; tap k_seq-1 multiplies token t */
+  const void *w_conv_ch;  /* (H_q + H_k, d_h_out, d_h_in, k_ch): q heads first, then KV heads; tap k_ch-1 multiplies token t */
+  const float *temp;      /* (H_k) fp32 log-temperature, beta_g = exp(temp[g]) */
+  const void *w_out;      /* (e_q, E) */
+} cca_weights;
+
+/* Intermediates (device pointers, caller-owned).  Any member may be NULL; a
+ * non-NULL member is written by cca_forward in place of workspace storage. */
+typedef struct {
+  void *lat;  /* (B,T,N_lat) down-projection output, columns as in w_down */
+  void *q;    /* (B,T,H_q,d_h) query as it enters attention */
+  void *k;    /* (B,T,H_k,d_h) key   as it enters attention */
+  void *v;    /* (B,T,H_k,d_h) value as it enters attention */
+  void *o;    /* (B,T,H_q*d_h) attention output */
+  float *lse; /* (B,H_q,T) natural-log sum-exp of the scaled logits */
+} cca_saved;
+
+/* Bytes of device workspace cca_forward needs for `cfg` (independent of which
+ * cca_saved members are given).  Returns CCA_OK or a validation error. */
+cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes);
+
+/* Whole block.  x: (B,T,E) in, out: (B,T,E) overwritten.  `saved` may be NULL.
+ * `workspace` is scratch of at least cca_workspace_size() bytes whose
+ * contents are undefined afterwards. */
+cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *x, void *out,
+                       const cca_saved *saved, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- the four stages of cca_forward, callable on their own ---------------
+ * Same validation and conventions.  They exist so that each stage can be
+ * checked against the oracle and timed separately. */
+
+/* lat (B*T, N_lat) = x (B*T, E) * w_down (E, N_lat).  Down-projection eq. of Sec. 2.2. */
+cca_status cca_down_project(const cca_config *cfg, const void *x, const void *w_down, void *lat,
+                            void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* lat -> q, k, v: convolutions, qk-mean, value-shift, norm, temperature, RoPE
+ * as selected by cfg->flags.  w->w_down / w->w_out are not read. */
+cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void *lat, void *q, void *k,
+                        void *v, void *hip_stream);
+
+/* o (B,T,H_q*d_h) = softmax(scale * q k^T [causal]) v per latent head, query
+ * head h reading KV head h / R.  lse may be NULL. */
+cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o,
+                         float *lse, void *hip_stream);
+
+/* out (B*T, E) = o (B*T, e_q) * w_out (e_q, E).  Last line of the final eq. block. */
+cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_out, void *out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Human-readable text for a status; never NULL; static storage. */
+const char *cca_strerror(cca_status s);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int cca_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CCA_H_ */

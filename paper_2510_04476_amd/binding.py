@@ -1,0 +1,256 @@
+"""ctypes binding of libcca (include/cca.h).
+
+Argument marshalling only: every step of the block runs in the HIP kernels of
+the shared library.  PyTorch supplies device memory and the current stream.
+There is no fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcca.so")
+
+# status codes / enums of include/cca.h
+CCA_OK = 0
+CCA_ERR_NULL, CCA_ERR_SHAPE, CCA_ERR_LAYOUT, CCA_ERR_UNSUPPORTED = -1, -2, -3, -4
+CCA_ERR_WORKSPACE, CCA_ERR_ALIGN, CCA_ERR_DTYPE, CCA_ERR_LAUNCH = -5, -6, -7, -8
+CCA_BF16, CCA_F32 = 0, 1
+CCA_CAUSAL, CCA_CONV_SEQ, CCA_CONV_CH, CCA_QK_MEAN = 1 << 0, 1 << 1, 1 << 2, 1 << 3
+CCA_V_SHIFT, CCA_QK_NORM, CCA_KEY_TEMP, CCA_ROPE = 1 << 4, 1 << 5, 1 << 6, 1 << 7
+CCA_ROPE_INTERLEAVED = 1 << 8
+CCA_FLAGS_PAPER = (CCA_CAUSAL | CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_V_SHIFT | CCA_QK_NORM
+                   | CCA_KEY_TEMP | CCA_ROPE)
+CCA_FLAGS_MHA = CCA_CAUSAL
+
+EXPORTS = ("cca_workspace_size", "cca_forward", "cca_down_project", "cca_prologue", "cca_attention",
+           "cca_up_project", "cca_strerror", "cca_version")
+
+
+class cca_config(C.Structure):
+    _fields_ = [("B", C.c_int32), ("T", C.c_int32), ("d_model", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("k_seq", C.c_int32), ("k_ch", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_uint32),
+                ("rope_base", C.c_float), ("softmax_scale", C.c_float)]
+
+
+class cca_weights(C.Structure):
+    _fields_ = [("w_down", C.c_void_p), ("w_conv_seq", C.c_void_p), ("w_conv_ch", C.c_void_p),
+                ("temp", C.c_void_p), ("w_out", C.c_void_p)]
+
+
+class cca_saved(C.Structure):
+    _fields_ = [("lat", C.c_void_p), ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p),
+                ("o", C.c_void_p), ("lse", C.c_void_p)]
+
+
+class CCAError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {cca_strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Loads libcca.so; raises if it has not been built (no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    vp, sz = C.c_void_p, C.c_size_t
+    cfgp = C.POINTER(cca_config)
+    lib.cca_workspace_size.argtypes = [cfgp, C.POINTER(sz)]
+    lib.cca_forward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, C.POINTER(cca_saved), vp, sz, vp]
+    lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
+    lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
+    lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp]
+    lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp]
+    for name in EXPORTS:
+        getattr(lib, name).restype = C.c_int
+    lib.cca_strerror.argtypes = [C.c_int]
+    lib.cca_strerror.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+@dataclass
+class CCAConfig:
+    B: int
+    T: int
+    d_model: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    k_seq: int = 2
+    k_ch: int = 2
+    dtype: int = CCA_BF16
+    flags: int = CCA_FLAGS_PAPER
+    rope_base: float = 10000.0
+    softmax_scale: float = 0.0
+
+    def c(self) -> cca_config:
+        return cca_config(self.B, self.T, self.d_model, self.n_q_heads, self.n_kv_heads, self.head_dim,
+                          self.k_seq, self.k_ch, self.dtype, self.flags, self.rope_base, self.softmax_scale)
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == CCA_BF16 else torch.float32
+
+    @property
+    def e_q(self):
+        return self.n_q_heads * self.head_dim
+
+    @property
+    def e_kv(self):
+        return self.n_kv_heads * self.head_dim
+
+    @property
+    def n_lat(self):
+        return self.e_q + 2 * self.e_kv
+
+
+@dataclass
+class CCAWeights:
+    w_down: torch.Tensor
+    w_out: torch.Tensor
+    w_conv_seq: torch.Tensor | None = None
+    w_conv_ch: torch.Tensor | None = None
+    temp: torch.Tensor | None = None
+
+    def c(self) -> cca_weights:
+        return cca_weights(_ptr(self.w_down), _ptr(self.w_conv_seq), _ptr(self.w_conv_ch), _ptr(self.temp),
+                           _ptr(self.w_out))
+
+
+@dataclass
+class CCASaved:
+    lat: torch.Tensor | None = None
+    q: torch.Tensor | None = None
+    k: torch.Tensor | None = None
+    v: torch.Tensor | None = None
+    o: torch.Tensor | None = None
+    lse: torch.Tensor | None = None
+
+    @staticmethod
+    def allocate(cfg: CCAConfig, device) -> "CCASaved":
+        dt = cfg.torch_dtype
+        B, T = cfg.B, cfg.T
+        return CCASaved(
+            lat=torch.empty(B, T, cfg.n_lat, dtype=dt, device=device),
+            q=torch.empty(B, T, cfg.n_q_heads, cfg.head_dim, dtype=dt, device=device),
+            k=torch.empty(B, T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=device),
+            v=torch.empty(B, T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=device),
+            o=torch.empty(B, T, cfg.e_q, dtype=dt, device=device),
+            lse=torch.empty(B, cfg.n_q_heads, T, dtype=torch.float32, device=device))
+
+    def c(self) -> cca_saved:
+        return cca_saved(_ptr(self.lat), _ptr(self.q), _ptr(self.k), _ptr(self.v), _ptr(self.o), _ptr(self.lse))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("libcca takes contiguous tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != CCA_OK:
+        raise CCAError(status, where)
+
+
+def cca_strerror(status: int) -> str:
+    return load_library().cca_strerror(int(status)).decode()
+
+
+def cca_version() -> int:
+    return load_library().cca_version()
+
+
+def cca_workspace_size(cfg: CCAConfig) -> int:
+    n = C.c_size_t(0)
+    cc = cfg.c()
+    _check(load_library().cca_workspace_size(C.byref(cc), C.byref(n)), "cca_workspace_size")
+    return n.value
+
+
+def new_workspace(cfg: CCAConfig, device) -> torch.Tensor:
+    return torch.empty(max(cca_workspace_size(cfg), 256), dtype=torch.uint8, device=device)
+
+
+def cca_forward(cfg: CCAConfig, w: CCAWeights, x: torch.Tensor, out: torch.Tensor | None = None,
+                saved: CCASaved | None = None, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    lib = load_library()
+    if out is None:
+        out = torch.empty(cfg.B, cfg.T, cfg.d_model, dtype=cfg.torch_dtype, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(cfg, x.device)
+    cc, cw = cfg.c(), w.c()
+    cs = saved.c() if saved is not None else None
+    _check(lib.cca_forward(C.byref(cc), C.byref(cw), _ptr(x), _ptr(out), C.byref(cs) if cs is not None else None,
+                           _ptr(workspace), workspace.numel(), _stream()), "cca_forward")
+    return out
+
+
+def cca_down_project(cfg: CCAConfig, x, w_down, lat=None, workspace=None):
+    lib = load_library()
+    if lat is None:
+        lat = torch.empty(cfg.B, cfg.T, cfg.n_lat, dtype=cfg.torch_dtype, device=x.device)
+    if workspace is None:
+        workspace = new_workspace(cfg, x.device)
+    cc = cfg.c()
+    _check(lib.cca_down_project(C.byref(cc), _ptr(x), _ptr(w_down), _ptr(lat), _ptr(workspace), workspace.numel(),
+                                _stream()), "cca_down_project")
+    return lat
+
+
+def cca_up_project(cfg: CCAConfig, o, w_out, out=None, workspace=None):
+    lib = load_library()
+    if out is None:
+        out = torch.empty(cfg.B, cfg.T, cfg.d_model, dtype=cfg.torch_dtype, device=o.device)
+    if workspace is None:
+        workspace = new_workspace(cfg, o.device)
+    cc = cfg.c()
+    _check(lib.cca_up_project(C.byref(cc), _ptr(o), _ptr(w_out), _ptr(out), _ptr(workspace), workspace.numel(),
+                              _stream()), "cca_up_project")
+    return out
+
+
+def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None):
+    lib = load_library()
+    dt, dev = cfg.torch_dtype, lat.device
+    if q is None:
+        q = torch.empty(cfg.B, cfg.T, cfg.n_q_heads, cfg.head_dim, dtype=dt, device=dev)
+    if k is None:
+        k = torch.empty(cfg.B, cfg.T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=dev)
+    if v is None:
+        v = torch.empty(cfg.B, cfg.T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=dev)
+    cc, cw = cfg.c(), w.c()
+    _check(lib.cca_prologue(C.byref(cc), C.byref(cw), _ptr(lat), _ptr(q), _ptr(k), _ptr(v), _stream()),
+           "cca_prologue")
+    return q, k, v
+
+
+def cca_attention(cfg: CCAConfig, q, k, v, o=None, lse=None, want_lse=False):
+    lib = load_library()
+    if o is None:
+        o = torch.empty(cfg.B, cfg.T, cfg.e_q, dtype=cfg.torch_dtype, device=q.device)
+    if lse is None and want_lse:
+        lse = torch.empty(cfg.B, cfg.n_q_heads, cfg.T, dtype=torch.float32, device=q.device)
+    cc = cfg.c()
+    _check(lib.cca_attention(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _stream()),
+           "cca_attention")
+    return (o, lse) if want_lse else o

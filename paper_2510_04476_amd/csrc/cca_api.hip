@@ -1,0 +1,226 @@
+// C ABI of libcca (declared in include/cca.h): host-side validation, workspace
+// carving and the chaining of the four stages on the caller's stream.
+#include <math.h>
+
+#include "cca_internal.h"
+
+namespace cca {
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Validates cfg and fills Dims.  Touches no HIP API.
+static cca_status make_dims(const cca_config *cfg, Dims *d) {
+  if (!cfg || !d) return CCA_ERR_NULL;
+  if (cfg->dtype != CCA_BF16 && cfg->dtype != CCA_F32) return CCA_ERR_DTYPE;
+  if (cfg->B <= 0 || cfg->T <= 0 || cfg->d_model <= 0 || cfg->n_q_heads <= 0 || cfg->n_kv_heads <= 0 ||
+      cfg->head_dim <= 0)
+    return CCA_ERR_SHAPE;
+  if ((long long)cfg->B * cfg->T > (1ll << 30)) return CCA_ERR_SHAPE;
+  if (cfg->n_q_heads % cfg->n_kv_heads != 0) return CCA_ERR_LAYOUT;
+  const uint32_t known = CCA_CAUSAL | CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_V_SHIFT | CCA_QK_NORM |
+                         CCA_KEY_TEMP | CCA_ROPE | CCA_ROPE_INTERLEAVED;
+  if (cfg->flags & ~known) return CCA_ERR_UNSUPPORTED;
+  if ((cfg->flags & CCA_KEY_TEMP) && !(cfg->flags & CCA_QK_NORM)) return CCA_ERR_UNSUPPORTED;
+  if ((cfg->flags & CCA_ROPE_INTERLEAVED) && !(cfg->flags & CCA_ROPE)) return CCA_ERR_UNSUPPORTED;
+  if ((cfg->flags & CCA_CONV_SEQ) && (cfg->k_seq < 1 || cfg->k_seq > 4)) return CCA_ERR_UNSUPPORTED;
+  if ((cfg->flags & CCA_CONV_CH) && (cfg->k_ch < 1 || cfg->k_ch > 4)) return CCA_ERR_UNSUPPORTED;
+  if (cfg->head_dim > 256) return CCA_ERR_UNSUPPORTED;
+  // rows of every tensor must keep 16-byte alignment
+  const int per16 = cfg->dtype == CCA_BF16 ? 8 : 4;
+  if (cfg->head_dim % per16 != 0 || cfg->d_model % per16 != 0) return CCA_ERR_UNSUPPORTED;
+  if ((cfg->flags & CCA_ROPE) && (cfg->head_dim % 2 != 0)) return CCA_ERR_LAYOUT;
+  if ((cfg->flags & CCA_ROPE) && !(cfg->rope_base > 0.f)) return CCA_ERR_SHAPE;
+  if (cfg->softmax_scale < 0.f || isnan(cfg->softmax_scale)) return CCA_ERR_SHAPE;
+  const long long e_kv = (long long)cfg->n_kv_heads * cfg->head_dim;
+  const long long e_q = (long long)cfg->n_q_heads * cfg->head_dim;
+  if (e_q > 65536 || e_kv > 65536 || cfg->d_model > 65536) return CCA_ERR_SHAPE;
+  if ((cfg->flags & CCA_V_SHIFT) && (e_kv % 2 != 0)) return CCA_ERR_LAYOUT;
+  // the latent must not be wider than the residual stream (compression factors >= 1)
+  if (e_q > cfg->d_model || e_kv > e_q) return CCA_ERR_SHAPE;
+  d->B = cfg->B; d->T = cfg->T; d->E = cfg->d_model;
+  d->Hq = cfg->n_q_heads; d->Hk = cfg->n_kv_heads; d->dh = cfg->head_dim;
+  d->R = d->Hq / d->Hk;
+  d->e_q = (int)e_q; d->e_kv = (int)e_kv; d->n_lat = d->e_q + 2 * d->e_kv;
+  d->v_half = d->e_kv / 2;
+  d->k_seq = (cfg->flags & CCA_CONV_SEQ) ? cfg->k_seq : 1;
+  d->k_ch = (cfg->flags & CCA_CONV_CH) ? cfg->k_ch : 1;
+  d->bf16 = cfg->dtype == CCA_BF16;
+  d->flags = cfg->flags;
+  d->rope_base = cfg->rope_base;
+  d->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+  return CCA_OK;
+}
+
+struct FwdLayout {
+  size_t wt_down, wt_out, lat, q, k, v, o, total;  // byte offsets
+};
+
+static FwdLayout fwd_layout(const Dims &d) {
+  FwdLayout L;
+  const size_t es = d.esize();
+  const size_t rows = (size_t)d.rows();
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  L.wt_down = take(d.bf16 ? (size_t)d.E * d.n_lat * 2 : 0);
+  L.wt_out = take(d.bf16 ? (size_t)d.E * d.e_q * 2 : 0);
+  L.lat = take(rows * d.n_lat * es);
+  L.q = take(rows * d.e_q * es);
+  L.k = take(rows * d.e_kv * es);
+  L.v = take(rows * d.e_kv * es);
+  L.o = take(rows * d.e_q * es);
+  L.total = off;
+  return L;
+}
+
+// C (M,N) = A (M,K) * W (K,N); the MFMA path first writes W^T into `wt`.
+static cca_status project(const Dims &d, const void *A, const void *W, void *C, long long M, int N, int K, void *wt,
+                          size_t wt_bytes, hipStream_t s) {
+  hipError_t e;
+  if (d.bf16 && gemm_mfma_supported(M, N, K)) {
+    if (!wt || wt_bytes < (size_t)N * K * 2) return CCA_ERR_WORKSPACE;
+    e = transpose_bf16(W, wt, K, N, s);
+    if (e != hipSuccess) return CCA_ERR_LAUNCH;
+    e = gemm_mfma_bf16(A, wt, C, M, N, K, s);
+  } else {
+    e = gemm_generic(d.bf16, A, W, C, M, N, K, s);
+  }
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *lat, void *q, void *k, void *v,
+                               hipStream_t s) {
+  hipError_t e = prologue_fused_supported(d) ? prologue_fused_bf16(d, *w, lat, q, k, v, s)
+                                             : prologue_generic(d, *w, lat, q, k, v, s);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+static cca_status run_attention(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
+                                hipStream_t s) {
+  hipError_t e = attention_mfma_supported(d) ? attention_mfma_bf16(d, q, k, v, o, lse, s)
+                                             : attention_generic(d, q, k, v, o, lse, s);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+static cca_status check_prologue_weights(const Dims &d, const cca_weights *w) {
+  if (!w) return CCA_ERR_NULL;
+  if ((d.flags & CCA_CONV_SEQ) && !w->w_conv_seq) return CCA_ERR_NULL;
+  if ((d.flags & CCA_CONV_CH) && !w->w_conv_ch) return CCA_ERR_NULL;
+  if ((d.flags & CCA_KEY_TEMP) && !w->temp) return CCA_ERR_NULL;
+  if (!aligned16(w->w_conv_seq) || !aligned16(w->w_conv_ch) || (reinterpret_cast<uintptr_t>(w->temp) & 3u))
+    return CCA_ERR_ALIGN;
+  return CCA_OK;
+}
+
+}  // namespace cca
+
+using namespace cca;
+
+extern "C" {
+
+cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes) {
+  if (!fwd_bytes) return CCA_ERR_NULL;
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  *fwd_bytes = fwd_layout(d).total;
+  return CCA_OK;
+}
+
+cca_status cca_down_project(const cca_config *cfg, const void *x, const void *w_down, void *lat, void *workspace,
+                            size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!x || !w_down || !lat) return CCA_ERR_NULL;
+  if (!aligned16(x) || !aligned16(w_down) || !aligned16(lat) || !aligned16(workspace)) return CCA_ERR_ALIGN;
+  return project(d, x, w_down, lat, d.rows(), d.n_lat, d.E, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_out, void *out, void *workspace,
+                          size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!o || !w_out || !out) return CCA_ERR_NULL;
+  if (!aligned16(o) || !aligned16(w_out) || !aligned16(out) || !aligned16(workspace)) return CCA_ERR_ALIGN;
+  return project(d, o, w_out, out, d.rows(), d.E, d.e_q, workspace, workspace_bytes, (hipStream_t)hip_stream);
+}
+
+cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void *lat, void *q, void *k, void *v,
+                        void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!lat || !q || !k || !v) return CCA_ERR_NULL;
+  st = check_prologue_weights(d, w);
+  if (st != CCA_OK) return st;
+  if (!aligned16(lat) || !aligned16(q) || !aligned16(k) || !aligned16(v)) return CCA_ERR_ALIGN;
+  return run_prologue(d, w, lat, q, k, v, (hipStream_t)hip_stream);
+}
+
+cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o, float *lse,
+                         void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!q || !k || !v || !o) return CCA_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return CCA_ERR_ALIGN;
+  return run_attention(d, q, k, v, o, lse, (hipStream_t)hip_stream);
+}
+
+cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *x, void *out, const cca_saved *saved,
+                       void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!w || !x || !out || !w->w_down || !w->w_out) return CCA_ERR_NULL;
+  st = check_prologue_weights(d, w);
+  if (st != CCA_OK) return st;
+  if (!aligned16(x) || !aligned16(out) || !aligned16(w->w_down) || !aligned16(w->w_out)) return CCA_ERR_ALIGN;
+  const FwdLayout L = fwd_layout(d);
+  if (!workspace || workspace_bytes < L.total) return CCA_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return CCA_ERR_ALIGN;
+  char *ws = static_cast<char *>(workspace);
+  void *lat = ws + L.lat, *q = ws + L.q, *k = ws + L.k, *v = ws + L.v, *o = ws + L.o;
+  float *lse = nullptr;
+  if (saved) {
+    if (!aligned16(saved->lat) || !aligned16(saved->q) || !aligned16(saved->k) || !aligned16(saved->v) ||
+        !aligned16(saved->o) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u))
+      return CCA_ERR_ALIGN;
+    if (saved->lat) lat = saved->lat;
+    if (saved->q) q = saved->q;
+    if (saved->k) k = saved->k;
+    if (saved->v) v = saved->v;
+    if (saved->o) o = saved->o;
+    lse = saved->lse;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, ws + L.wt_down, (size_t)d.E * d.n_lat * 2, s);
+  if (st != CCA_OK) return st;
+  st = run_prologue(d, w, lat, q, k, v, s);
+  if (st != CCA_OK) return st;
+  st = run_attention(d, q, k, v, o, lse, s);
+  if (st != CCA_OK) return st;
+  return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s);
+}
+
+const char *cca_strerror(cca_status s) {
+  switch (s) {
+    case CCA_OK: return "ok";
+    case CCA_ERR_NULL: return "a required pointer is NULL";
+    case CCA_ERR_SHAPE: return "a size is non-positive or the sizes are inconsistent";
+    case CCA_ERR_LAYOUT: return "invalid head / group layout";
+    case CCA_ERR_UNSUPPORTED: return "request not supported by this build";
+    case CCA_ERR_WORKSPACE: return "workspace missing or too small";
+    case CCA_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case CCA_ERR_DTYPE: return "dtype must be CCA_BF16 or CCA_F32";
+    case CCA_ERR_LAUNCH: return "HIP reported an error while enqueuing";
+  }
+  return "unknown status";
+}
+
+int cca_version(void) { return 100; }
+
+}  // extern "C"

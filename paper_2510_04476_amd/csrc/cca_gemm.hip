@@ -1,0 +1,225 @@
+// bf16 GEMM on the gfx950 matrix cores for the down- and up-projection
+// (Sec. 2.2: down-projection equation and last line of the final equation
+// block):  C (M,N) = A (M,K) * Bt (N,K)^T, fp32 accumulation, bf16 output.
+//
+// Both operands are K-contiguous, so a lane's 8-element MFMA fragment is one
+// 16-byte LDS read.  Workgroup tile 256 x BN x 64 with 8 wavefronts (2 along
+// M, 4 along N); LDS is double-buffered and XOR-swizzled per 16-byte chunk;
+// the next K-slab travels HBM -> registers while the current one is
+// multiplied.  The MFMA is issued with the weight rows as its first operand,
+// which leaves every lane with 4 consecutive output columns of one row, so
+// the epilogue packs them to bf16, stages the tile in LDS and writes whole
+// rows with 16-byte stores.
+#include "cca_internal.h"
+
+namespace cca {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr int BM = 256, BK = 64;
+constexpr int NTHREADS = 512;
+
+// LDS position of the 16-byte chunk c (0..7) of row r in a [rows][64] bf16 tile
+__device__ __forceinline__ int swz(int r, int c) { return r * 8 + (c ^ ((r & 7) ^ ((r >> 3) & 1))); }
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+template <int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(NTHREADS) void gemm_bf16_nt_kernel(const bf16_t *__restrict__ A,
+                                                               const bf16_t *__restrict__ Bt,
+                                                               bf16_t *__restrict__ C, long long M, int N, int K,
+                                                               int tiles_n, int tiles_total) {
+  static_assert(WAVES_M * WAVES_N * 64 == NTHREADS, "8 wavefronts");
+  constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
+  constexpr int MI = WM / 32, NI = WN / 32;            // 32x32 MFMA tiles per wave
+  static_assert(MI * 32 == WM && NI * 32 == WN, "wave tile must be a multiple of 32");
+  constexpr int A_CHUNKS = BM * 8 / NTHREADS;  // 16-byte chunks per thread per slab
+  constexpr int B_CHUNKS = BN * 8 / NTHREADS;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int STAGE = (BM + BN) * 8;  // 16-byte chunks per pipeline stage
+  u32x4 *const sbase = reinterpret_cast<u32x4 *>(smem);
+
+  // XCD-aware tile order: workgroup ids are dealt round-robin over the 8 XCDs,
+  // so give each XCD a contiguous range of tiles; within it the N tiles of one
+  // M block are adjacent and share the A panel in that XCD's L2.
+  const int wg = blockIdx.x;
+  const int per_xcd = (tiles_total + 7) / 8;
+  const int tile = (wg % 8) * per_xcd + wg / 8;
+  if (tile >= tiles_total) return;
+  const long long m0 = (long long)(tile / tiles_n) * BM;
+  const int n0 = (tile % tiles_n) * BN;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  // global source rows of this thread's chunks (clamped: rows past the edge are loaded but never stored)
+  const bf16_t *a_src[A_CHUNKS];
+  const bf16_t *b_src[B_CHUNKS];
+  int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
+#pragma unroll
+  for (int i = 0; i < A_CHUNKS; ++i) {
+    const int id = tid + i * NTHREADS, r = id >> 3, c = id & 7;
+    long long gr = m0 + r;
+    gr = gr < M ? gr : M - 1;
+    a_src[i] = A + gr * K + c * 8;
+    a_dst[i] = swz(r, c);
+  }
+#pragma unroll
+  for (int i = 0; i < B_CHUNKS; ++i) {
+    const int id = tid + i * NTHREADS, r = id >> 3, c = id & 7;
+    int gr = n0 + r;
+    gr = gr < N ? gr : N - 1;
+    b_src[i] = Bt + (long long)gr * K + c * 8;
+    b_dst[i] = swz(r, c);
+  }
+
+  f32x16 acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
+
+  u32x4 ra[A_CHUNKS], rb[B_CHUNKS];
+  auto load_slab = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + k0);
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(b_src[i] + k0);
+  };
+  auto store_slab = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) sbase[buf * STAGE + a_dst[i]] = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) sbase[buf * STAGE + BM * 8 + b_dst[i]] = rb[i];
+  };
+
+  const int nk = K / BK;
+  load_slab(0);
+  store_slab(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) load_slab((kt + 1) * BK);
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[MI], fb[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int r = wm * WM + mi * 32 + l32;
+        u32x4 t = sbase[buf * STAGE + swz(r, kk * 2 + half)];
+        fa[mi] = __builtin_bit_cast(bf16x8, t);
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        const int r = wn * WN + ni * 32 + l32;
+        u32x4 t = sbase[buf * STAGE + BM * 8 + swz(r, kk * 2 + half)];
+        fb[ni] = __builtin_bit_cast(bf16x8, t);
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[ni][mi], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_slab(buf ^ 1);
+    __syncthreads();
+  }
+
+  // Epilogue.  acc[ni][mi][r] = C[m][n] with m = wm*WM + mi*32 + l32 and
+  // n = wn*WN + ni*32 + 8*(r/4) + 4*half + r%4.
+  constexpr int ROW_BYTES = BN * 2 + 16;  // padded row: 8-byte column writes of 32 rows hit distinct banks
+  unsigned char *sC = smem;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = wm * WM + mi * 32 + l32;
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int n = wn * WN + ni * 32 + rg * 8 + half * 4;
+        u32x2 p;
+        p.x = pack_bf16x2(acc[ni][mi][rg * 4 + 0], acc[ni][mi][rg * 4 + 1]);
+        p.y = pack_bf16x2(acc[ni][mi][rg * 4 + 2], acc[ni][mi][rg * 4 + 3]);
+        *reinterpret_cast<u32x2 *>(sC + m * ROW_BYTES + n * 2) = p;
+      }
+    }
+  __syncthreads();
+  constexpr int CH_ROW = BN / 8;  // 16-byte chunks per tile row
+  for (int id = tid; id < BM * CH_ROW; id += NTHREADS) {
+    const int r = id / CH_ROW, c = id % CH_ROW;
+    const long long gm = m0 + r;
+    const int gn = n0 + c * 8;
+    if (gm < M && gn < N)
+      *reinterpret_cast<u32x4 *>(C + gm * N + gn) = *reinterpret_cast<const u32x4 *>(sC + r * ROW_BYTES + c * 16);
+  }
+}
+
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst,
+                                                            int rows, int cols) {
+  __shared__ bf16_t tile[64][66];
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int i = ty; i < 64; i += 4) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < rows && c < cols) ? src[(long long)r * cols + c] : (bf16_t)0;
+  }
+  __syncthreads();
+  for (int i = ty; i < 64; i += 4) {
+    const int c = c0 + i, r = r0 + tx;
+    if (c < cols && r < rows) dst[(long long)c * rows + r] = tile[tx][i];
+  }
+}
+
+template <int BN, int WAVES_M, int WAVES_N>
+hipError_t launch_gemm(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s) {
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  constexpr size_t main_bytes = 2ull * (BM + BN) * BK * 2;
+  constexpr size_t epi_bytes = (size_t)BM * (BN * 2 + 16);
+  constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
+  static bool attr_set = false;  // idempotent; a race only repeats the call
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N><<<per_xcd * 8, NTHREADS, smem, s>>>((const bf16_t *)A, (const bf16_t *)Bt, (bf16_t *)C, M, N,
+                                                             K, tiles_n, total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(long long M, int N, int K) { return M >= 1 && K % BK == 0 && K >= BK && N % 8 == 0 && N >= 8; }
+
+hipError_t gemm_mfma_bf16(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s) {
+  // Tile width by the number of rounds the grid needs on 256 CUs:
+  // N = 1536, M = 16384 gives 384 tiles of 256 (2 rounds, half empty) or 512 tiles of 192 (2 full rounds).
+  auto cost = [&](int bn) {
+    const long long tiles = ((M + BM - 1) / BM) * ((N + bn - 1) / bn);
+    return ((tiles + 255) / 256) * bn;
+  };
+  if (cost(192) < cost(256)) return launch_gemm<192, 4, 2>(A, Bt, C, M, N, K, s);
+  return launch_gemm<256, 2, 4>(A, Bt, C, M, N, K, s);
+}
+
+hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStream_t s) {
+  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
+  transpose_bf16_kernel<<<grid, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, rows, cols);
+  return hipGetLastError();
+}
+
+}  // namespace cca

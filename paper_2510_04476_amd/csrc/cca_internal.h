@@ -1,0 +1,63 @@
+// Internal declarations shared by the HIP translation units of libcca.
+// Not part of the C ABI (that is include/cca.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cca.h"
+
+namespace cca {
+
+// Derived sizes of a validated config.
+struct Dims {
+  int B, T, E, Hq, Hk, dh, R;
+  int e_q, e_kv, n_lat, v_half;  // v_half = channels of the current-token value stream
+  int k_seq, k_ch;
+  bool bf16;
+  uint32_t flags;
+  float rope_base, scale;
+  long long rows() const { return (long long)B * T; }
+  size_t esize() const { return bf16 ? 2 : 4; }
+};
+
+typedef uint16_t bf16_t;  // raw bf16 bits in memory
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float load_f(const float *p) { return *p; }
+__device__ __forceinline__ float load_f(const bf16_t *p) { return bf16_to_f32(*p); }
+__device__ __forceinline__ void store_f(float *p, float v) { *p = v; }
+__device__ __forceinline__ void store_f(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// ---- generic kernels (any supported shape, fp32 or bf16 storage) ----------
+// C (M,N) = A (M,K) * Bm (K,N), all row-major.
+hipError_t gemm_generic(bool bf16, const void *A, const void *Bm, void *C, long long M, int N, int K,
+                        hipStream_t s);
+hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
+                            hipStream_t s);
+hipError_t attention_generic(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
+                             hipStream_t s);
+
+// ---- gfx950 MFMA kernels (bf16 storage) -----------------------------------
+// C (M,N) = A (M,K) * Bt (N,K)^T; Bt is the K-contiguous ("transposed") weight.
+bool gemm_mfma_supported(long long M, int N, int K);
+hipError_t gemm_mfma_bf16(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s);
+// dst (cols, rows) = src (rows, cols)^T, bf16.
+hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStream_t s);
+
+bool attention_mfma_supported(const Dims &d);
+hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
+                               hipStream_t s);
+
+bool prologue_fused_supported(const Dims &d);
+hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
+                               hipStream_t s);
+
+}  // namespace cca

@@ -1,0 +1,99 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2510_04476_amd as P
+from paper_2510_04476_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    hdr = open(os.path.join(ROOT, "include", "cca.h")).read()
+    declared = set(re.findall(r"\b(cca_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = P.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert P.cca_version() >= 100
+    for s in range(-8, 1):
+        assert P.cca_strerror(s) and "unknown" not in P.cca_strerror(s)
+    assert "unknown" in P.cca_strerror(-99)
+
+
+def good():
+    return P.CCAConfig(B=1, T=64, d_model=256, n_q_heads=2, n_kv_heads=2, head_dim=32, dtype=B.CCA_F32)
+
+
+def ws(cfg):
+    n = C.c_size_t(0)
+    cc = cfg.c()
+    return P.load_library().cca_workspace_size(C.byref(cc), C.byref(n)), n.value
+
+
+def test_workspace_size_ok_and_null():
+    st, n = ws(good())
+    assert st == B.CCA_OK and n > 0
+    cc = good().c()
+    assert P.load_library().cca_workspace_size(C.byref(cc), None) == B.CCA_ERR_NULL
+    assert P.load_library().cca_workspace_size(None, C.byref(C.c_size_t())) == B.CCA_ERR_NULL
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("dtype", 7, B.CCA_ERR_DTYPE),
+    ("T", 0, B.CCA_ERR_SHAPE),
+    ("B", -1, B.CCA_ERR_SHAPE),
+    ("n_kv_heads", 3, B.CCA_ERR_LAYOUT),          # H_q % H_k != 0
+    ("n_q_heads", 16, B.CCA_ERR_SHAPE),           # latent wider than d_model
+    ("k_seq", 9, B.CCA_ERR_UNSUPPORTED),
+    ("k_ch", 0, B.CCA_ERR_UNSUPPORTED),
+    ("head_dim", 30, B.CCA_ERR_UNSUPPORTED),      # rows would lose 16-byte alignment
+    ("flags", 1 << 20, B.CCA_ERR_UNSUPPORTED),
+    ("flags", B.CCA_CAUSAL | B.CCA_KEY_TEMP, B.CCA_ERR_UNSUPPORTED),
+    ("rope_base", 0.0, B.CCA_ERR_SHAPE),
+    ("softmax_scale", -1.0, B.CCA_ERR_SHAPE),
+])
+def test_config_validation(field, value, status):
+    cfg = good()
+    setattr(cfg, field, value)
+    assert ws(cfg)[0] == status
+
+
+def test_forward_rejects_null_misaligned_and_small_workspace():
+    lib = P.load_library()
+    cfg = good()
+    cc = cfg.c()
+    # fake but never dereferenced device addresses: validation fails first
+    p = C.c_void_p(0x10000)
+    w = B.cca_weights(p, p, p, p, p)
+    need = ws(cfg)[1]
+    call = lambda w_, x, out, wsp, n: lib.cca_forward(C.byref(cc), C.byref(w_), x, out, None, wsp, n, None)
+    assert call(w, None, p, p, need) == B.CCA_ERR_NULL
+    assert call(B.cca_weights(None, p, p, p, p), p, p, p, need) == B.CCA_ERR_NULL
+    assert call(B.cca_weights(p, None, p, p, p), p, p, p, need) == B.CCA_ERR_NULL   # conv flag on, weight missing
+    assert call(w, C.c_void_p(0x10008), p, p, need) == B.CCA_ERR_ALIGN
+    assert call(w, p, p, p, need - 1) == B.CCA_ERR_WORKSPACE
+    assert call(w, p, p, None, need) == B.CCA_ERR_WORKSPACE
+    assert lib.cca_attention(C.byref(cc), p, p, None, p, None, None) == B.CCA_ERR_NULL
+    assert lib.cca_prologue(C.byref(cc), None, p, p, p, p, None) == B.CCA_ERR_NULL
+    assert lib.cca_down_project(C.byref(cc), p, None, p, p, 0, None) == B.CCA_ERR_NULL
+    assert lib.cca_up_project(C.byref(cc), p, p, None, p, 0, None) == B.CCA_ERR_NULL
+
+
+def test_flop_counter_matches_cost_table():
+    """Forward FLOPs of the cost table: (1/C1 + 1/C2) 4BSE^2 + 4BES^2/C1 + Conv
+    (dense attention term; the grouped-conv term counted per actual MAC)."""
+    cfg = P.CCAConfig(B=1, T=16384, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128,
+                      flags=B.CCA_FLAGS_PAPER & ~B.CCA_CAUSAL)
+    Bn, S, E, C1, C2 = 1, 16384, 2048, 2, 8
+    f = P.forward_flops(cfg)
+    assert f["proj"] == (1 / C1 + 1 / C2) * 4 * Bn * S * E * E
+    assert f["attn"] == 4 * Bn * E * S * S / C1
+    assert f["conv"] == 2 * Bn * S * ((E / C1 + E / C2) * 2 + (8 + 2) * 128 * 128 * 2)
+    mha = P.CCAConfig(B=1, T=16384, d_model=2048, n_q_heads=16, n_kv_heads=16, head_dim=128, flags=0)
+    fm = P.forward_flops(mha)
+    assert fm["total"] == 8 * Bn * S * E * E + 4 * Bn * E * S * S
