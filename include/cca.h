@@ -117,16 +117,19 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
 
 /* ---- the four stages of cca_forward, callable on their own ---------------
  * Same validation and conventions.  They exist so that each stage can be
- * checked against the oracle and timed separately. */
+ * checked against the oracle and timed separately.  Where a stage takes a
+ * workspace, cca_workspace_size() bytes always suffice (a stage may need
+ * none; then NULL / 0 is accepted). */
 
 /* lat (B*T, N_lat) = x (B*T, E) * w_down (E, N_lat).  Down-projection eq. of Sec. 2.2. */
 cca_status cca_down_project(const cca_config *cfg, const void *x, const void *w_down, void *lat,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* lat -> q, k, v: convolutions, qk-mean, value-shift, norm, temperature, RoPE
- * as selected by cfg->flags.  w->w_down / w->w_out are not read. */
+ * as selected by cfg->flags.  w->w_down / w->w_out are not read.  The
+ * workspace holds the folded convolution filters and the RoPE tables. */
 cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void *lat, void *q, void *k,
-                        void *v, void *hip_stream);
+                        void *v, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* o (B,T,H_q*d_h) = softmax(scale * q k^T [causal]) v per latent head, query
  * head h reading KV head h / R.  lse may be NULL. */

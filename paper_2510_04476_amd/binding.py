@@ -71,7 +71,7 @@ def load_library() -> C.CDLL:
     lib.cca_forward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, C.POINTER(cca_saved), vp, sz, vp]
     lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
-    lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp]
+    lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, sz, vp]
     lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
@@ -229,7 +229,7 @@ def cca_up_project(cfg: CCAConfig, o, w_out, out=None, workspace=None):
     return out
 
 
-def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None):
+def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None, workspace=None):
     lib = load_library()
     dt, dev = cfg.torch_dtype, lat.device
     if q is None:
@@ -238,9 +238,11 @@ def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None):
         k = torch.empty(cfg.B, cfg.T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=dev)
     if v is None:
         v = torch.empty(cfg.B, cfg.T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=dev)
+    if workspace is None:
+        workspace = new_workspace(cfg, dev)
     cc, cw = cfg.c(), w.c()
-    _check(lib.cca_prologue(C.byref(cc), C.byref(cw), _ptr(lat), _ptr(q), _ptr(k), _ptr(v), _stream()),
-           "cca_prologue")
+    _check(lib.cca_prologue(C.byref(cc), C.byref(cw), _ptr(lat), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
+                            workspace.numel(), _stream()), "cca_prologue")
     return q, k, v
 
 

@@ -53,7 +53,7 @@ static cca_status make_dims(const cca_config *cfg, Dims *d) {
 }
 
 struct FwdLayout {
-  size_t wt_down, wt_out, lat, q, k, v, o, total;  // byte offsets
+  size_t wt_down, wt_out, pro, lat, q, k, v, o, total;  // byte offsets
 };
 
 static FwdLayout fwd_layout(const Dims &d) {
@@ -64,6 +64,7 @@ static FwdLayout fwd_layout(const Dims &d) {
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
   L.wt_down = take(d.bf16 ? (size_t)d.E * d.n_lat * 2 : 0);
   L.wt_out = take(d.bf16 ? (size_t)d.E * d.e_q * 2 : 0);
+  L.pro = take(prologue_fused_scratch_bytes(d));
   L.lat = take(rows * d.n_lat * es);
   L.q = take(rows * d.e_q * es);
   L.k = take(rows * d.e_kv * es);
@@ -89,9 +90,14 @@ static cca_status project(const Dims &d, const void *A, const void *W, void *C, 
 }
 
 static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *lat, void *q, void *k, void *v,
-                               hipStream_t s) {
-  hipError_t e = prologue_fused_supported(d) ? prologue_fused_bf16(d, *w, lat, q, k, v, s)
-                                             : prologue_generic(d, *w, lat, q, k, v, s);
+                               void *scratch, size_t scratch_bytes, hipStream_t s) {
+  hipError_t e;
+  if (prologue_fused_supported(d)) {
+    if (!scratch || scratch_bytes < prologue_fused_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
+    e = prologue_fused_bf16(d, *w, lat, q, k, v, scratch, s);
+  } else {
+    e = prologue_generic(d, *w, lat, q, k, v, s);
+  }
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
@@ -148,15 +154,16 @@ cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_ou
 }
 
 cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void *lat, void *q, void *k, void *v,
-                        void *hip_stream) {
+                        void *workspace, size_t workspace_bytes, void *hip_stream) {
   Dims d;
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
   if (!lat || !q || !k || !v) return CCA_ERR_NULL;
   st = check_prologue_weights(d, w);
   if (st != CCA_OK) return st;
-  if (!aligned16(lat) || !aligned16(q) || !aligned16(k) || !aligned16(v)) return CCA_ERR_ALIGN;
-  return run_prologue(d, w, lat, q, k, v, (hipStream_t)hip_stream);
+  if (!aligned16(lat) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(workspace))
+    return CCA_ERR_ALIGN;
+  return run_prologue(d, w, lat, q, k, v, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
 cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o, float *lse,
@@ -199,7 +206,7 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   hipStream_t s = (hipStream_t)hip_stream;
   st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, ws + L.wt_down, (size_t)d.E * d.n_lat * 2, s);
   if (st != CCA_OK) return st;
-  st = run_prologue(d, w, lat, q, k, v, s);
+  st = run_prologue(d, w, lat, q, k, v, ws + L.pro, L.lat - L.pro, s);
   if (st != CCA_OK) return st;
   st = run_attention(d, q, k, v, o, lse, s);
   if (st != CCA_OK) return st;

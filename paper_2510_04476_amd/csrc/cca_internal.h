@@ -57,7 +57,8 @@ hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, cons
                                hipStream_t s);
 
 bool prologue_fused_supported(const Dims &d);
+size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE tables; 0 if unsupported
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
-                               hipStream_t s);
+                               void *scratch, hipStream_t s);
 
 }  // namespace cca

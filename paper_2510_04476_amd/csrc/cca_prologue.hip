@@ -1,0 +1,366 @@
+// Fused latent-space prologue for gfx950, bf16 storage (Sec. 2.2: convolution
+// equation, qk-mean equation, value-shift equation and the first two lines of
+// the final equation block).  One pass over the down-projected latents yields
+// the q, k, v that enter attention.
+//
+// The two causal convolutions have no bias and no nonlinearity between them,
+// so conv2_seq+ch(conv1_seq(u)) is one causal convolution of width
+// D = k_seq + k_ch - 1 with per-head filters
+//     Wc[h,o,i,d] = sum_{j + jj = d} w1[h,o,i,j] * w0[c(h,i),jj].
+// A small set-up kernel forms Wc (fp32, rounded once to bf16) and the RoPE
+// tables; the main kernel then runs the convolution as a bf16 MFMA
+// contraction per head (M = d_h outputs, N = tokens, K = D*d_h), straight on
+// the latent rows: the filter of one head lives in LDS for the lifetime of a
+// workgroup, the token operands are the latent rows of tokens t-D+1..t.
+//
+// The MFMA is issued with the filter as its first operand, so each lane ends
+// up with 64 of the 128 output channels of ONE token (the other half-wave has
+// the rest): the L2 norm is an in-lane sum plus one half-wave exchange, and
+// the rotate-half RoPE partner (o, o + d_h/2) sits in the same lane.  Results
+// are staged per wavefront in LDS and leave as whole 256-byte rows.
+//
+// RoPE angles: t * theta_i is split as (t >> 7) * 128 * theta_i + (t & 127) *
+// theta_i; both parts come from tables made in fp64, combined by the angle
+// addition formulas in fp32 (an fp32 product t * theta_i alone is off by up to
+// 1e-3 rad at t ~ 16k).
+#include "cca_internal.h"
+
+namespace cca {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+namespace {
+
+constexpr int DH = 128;
+constexpr int NT = 256;
+constexpr int TOK_PER_WG = 512;
+constexpr int OUT_ROW = 272;  // bytes per staged output row (256 + pad: 8-byte column writes stay conflict-free)
+
+struct FusedArgs {
+  int T, Hq, Hk, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch;
+  long long rows;
+  uint32_t flags;
+  int n_conv_blocks;
+  float rope_base;
+};
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float lo_f(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_f(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// ---------------------------------------------------------------------------
+// set-up: folded filters Wc [h][o][d][i] (bf16) and the two RoPE tables
+//   ropeA [t_hi][i]            float2 (cos, sin) of t_hi * 128 * theta_i
+//   ropeB [i / 4][t_lo][i % 4] float2 (cos, sin) of t_lo * theta_i
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D, const bf16_t *__restrict__ w0,
+                                                            const bf16_t *__restrict__ w1, bf16_t *__restrict__ wc,
+                                                            float2 *__restrict__ ropeA, float2 *__restrict__ ropeB,
+                                                            int n_fold_blocks, int n_thi) {
+  const int NH = a.Hq + a.Hk;
+  if ((int)blockIdx.x < n_fold_blocks) {
+    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (h, o, i)
+    if (id >= (long long)NH * DH * DH) return;
+    const int i = (int)(id % DH), o = (int)((id / DH) % DH), h = (int)(id / (DH * DH));
+    const int ch = h * DH + i;  // packed q|k channel: q heads first, then k heads
+    const int ks = (a.flags & CCA_CONV_SEQ) ? a.k_seq : 1, kc = a.k_ch;
+    for (int d = 0; d < D; ++d) {
+      float acc = 0.f;
+      for (int j = 0; j < kc; ++j) {
+        const int jj = d - j;
+        if (jj < 0 || jj >= ks) continue;
+        const float f0 = (a.flags & CCA_CONV_SEQ) ? bf16_to_f32(w0[(long long)ch * ks + jj]) : 1.f;
+        acc = fmaf(bf16_to_f32(w1[(((long long)h * DH + o) * DH + i) * kc + j]), f0, acc);
+      }
+      wc[(((long long)h * DH + o) * D + d) * DH + i] = f32_to_bf16(acc);
+    }
+    return;
+  }
+  const int id = ((int)blockIdx.x - n_fold_blocks) * 256 + threadIdx.x;
+  const int nA = n_thi * (DH / 2), nB = (DH / 2) * 128;
+  if (id < nA) {
+    const int i = id % (DH / 2), thi = id / (DH / 2);
+    const double theta = pow((double)a.rope_base, -2.0 * (double)i / (double)DH);
+    double sn, cs;
+    sincos((double)thi * 128.0 * theta, &sn, &cs);
+    ropeA[id] = make_float2((float)cs, (float)sn);
+  } else if (id < nA + nB) {
+    const int k = id - nA;
+    const int i = k / 128, tlo = k % 128;
+    const double theta = pow((double)a.rope_base, -2.0 * (double)i / (double)DH);
+    double sn, cs;
+    sincos((double)tlo * theta, &sn, &cs);
+    ropeB[((i >> 2) * 128 + tlo) * 4 + (i & 3)] = make_float2((float)cs, (float)sn);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// main kernel
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(NT) void prologue_fused_kernel(FusedArgs a, const bf16_t *__restrict__ lat,
+                                                           const u32x4 *__restrict__ wc,
+                                                           const float2 *__restrict__ ropeA,
+                                                           const float2 *__restrict__ ropeB,
+                                                           const float *__restrict__ temp, bf16_t *__restrict__ q,
+                                                           bf16_t *__restrict__ k, bf16_t *__restrict__ v) {
+  constexpr int WROW = D * 16;  // 16-byte chunks per filter row (one output channel)
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  u32x4 *sW = reinterpret_cast<u32x4 *>(smem);
+  unsigned char *sOutAll = smem + (size_t)DH * WROW * 16;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  if ((int)blockIdx.x >= a.n_conv_blocks) {
+    // ---- value-shift role: v[t] = [vc[t] | vp[t-1]], 16 bytes per thread, whole rows per wavefront
+    const int cpr = a.e_kv / 8;  // chunks per row
+    const long long total = a.rows * cpr;
+    const long long first = ((long long)blockIdx.x - a.n_conv_blocks) * (NT * 8);
+    for (int it = 0; it < 8; ++it) {
+      const long long id = first + it * NT + tid;
+      if (id >= total) break;
+      const long long row = id / cpr;
+      const int ch = (int)(id % cpr) * 8;
+      const int t = (int)(row % a.T);
+      u32x4 val = {0, 0, 0, 0};
+      const bool shifted = (a.flags & CCA_V_SHIFT) && ch >= a.v_half;
+      if (!shifted || t > 0)
+        val = *reinterpret_cast<const u32x4 *>(lat + (row - (shifted ? 1 : 0)) * a.n_lat + a.e_q + a.e_kv + ch);
+      *reinterpret_cast<u32x4 *>(v + row * a.e_kv + ch) = val;
+    }
+    return;
+  }
+
+  const int NH = a.Hq + a.Hk;
+  const int head = blockIdx.x % NH;
+  const long long row_begin = (long long)(blockIdx.x / NH) * TOK_PER_WG;
+  const bool is_q = head < a.Hq;
+  const int g = is_q ? head / a.R : head - a.Hq;
+  const int ch0 = is_q ? head * DH : a.e_q + g * DH;
+
+  // ---- filter of this head -> LDS, chunk-swizzled by output channel
+  {
+    const u32x4 *src = wc + (long long)head * DH * WROW;
+    for (int id = tid; id < DH * WROW; id += NT) {
+      const int o = id / WROW, c = id % WROW;
+      sW[o * WROW + ((c & ~15) | ((c ^ o) & 15))] = src[id];
+    }
+  }
+  __syncthreads();
+  const float beta = (!is_q && (a.flags & CCA_KEY_TEMP)) ? expf(temp[g]) : 1.f;
+  unsigned char *sOut = sOutAll + wave * (32 * OUT_ROW);
+  bf16_t *dst = is_q ? q + head * DH : k + g * DH;
+  const int dst_stride = is_q ? a.e_q : a.e_kv;
+
+  for (int it = 0; it < TOK_PER_WG / 256; ++it) {
+    const long long wrow0 = row_begin + it * 256 + wave * 64;
+    if (wrow0 >= a.rows) break;  // wave-uniform; nothing below synchronises across wavefronts
+
+    long long rowc[2];
+    int tpos[2];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const long long row = wrow0 + tt * 32 + l32;
+      rowc[tt] = row < a.rows ? row : a.rows - 1;
+      tpos[tt] = (int)(rowc[tt] % a.T);
+    }
+
+    // ---- y1^T = Wc * [u(t-D+1) .. u(t)]^T
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[tt][nt][r] = 0.f;
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+      const int back = D - 1 - d;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        bf16x8 uf[2];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
+          u32x4 raw = {0, 0, 0, 0};
+          if (tpos[tt] >= back)  // tokens before the start of the sequence are zero
+            raw = *reinterpret_cast<const u32x4 *>(lat + (rowc[tt] - back) * a.n_lat + ch0 + kk * 16 + half * 8);
+          uf[tt] = __builtin_bit_cast(bf16x8, raw);
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+          const int o = nt * 32 + l32;
+          const int c = d * 16 + kk * 2 + half;
+          const bf16x8 wf = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~15) | ((c ^ o) & 15))]);
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt)
+            acc[tt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[tt], acc[tt][nt], 0, 0, 0);
+        }
+      }
+    }
+
+    // ---- per token: qk-mean, norm, temperature, RoPE.  Lane (l32, half) holds
+    //      channels o = 32*nt + 8*rg + 4*half + e of token l32 in acc[tt][nt][4*rg + e].
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const bf16_t *lrow = lat + rowc[tt] * a.n_lat;
+      if (a.flags & CCA_QK_MEAN) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            const int o0 = nt * 32 + rg * 8 + half * 4;
+            const u32x2 kk0 = *reinterpret_cast<const u32x2 *>(lrow + a.e_q + g * DH + o0);
+            float m[4] = {lo_f(kk0.x), hi_f(kk0.x), lo_f(kk0.y), hi_f(kk0.y)};
+            if (is_q) {
+              const u32x2 q0 = *reinterpret_cast<const u32x2 *>(lrow + head * DH + o0);
+              m[0] += lo_f(q0.x); m[1] += hi_f(q0.x); m[2] += lo_f(q0.y); m[3] += hi_f(q0.y);
+            } else {
+              float s[4] = {0.f, 0.f, 0.f, 0.f};
+              for (int r = 0; r < a.R; ++r) {
+                const u32x2 q0 = *reinterpret_cast<const u32x2 *>(lrow + (g * a.R + r) * DH + o0);
+                s[0] += lo_f(q0.x); s[1] += hi_f(q0.x); s[2] += lo_f(q0.y); s[3] += hi_f(q0.y);
+              }
+              const float invR = 1.f / (float)a.R;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) m[e] = fmaf(s[e], invR, m[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[tt][nt][rg * 4 + e] = fmaf(0.5f, m[e], acc[tt][nt][rg * 4 + e]);
+          }
+      }
+      if (a.flags & CCA_QK_NORM) {
+        float ssq = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) ssq = fmaf(acc[tt][nt][r], acc[tt][nt][r], ssq);
+        ssq += __shfl_xor(ssq, 32);
+        const float mul = sqrtf((float)DH) / sqrtf(ssq) * beta;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[tt][nt][r] *= mul;
+      }
+      if (a.flags & CCA_ROPE) {
+        const int thi = tpos[tt] >> 7, tlo = tpos[tt] & 127;
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            const int i0 = nt * 32 + rg * 8 + half * 4;  // 4 consecutive pair indices
+            const f32x4 *pa = reinterpret_cast<const f32x4 *>(ropeA + thi * (DH / 2) + i0);
+            const f32x4 *pb = reinterpret_cast<const f32x4 *>(ropeB + ((i0 >> 2) * 128 + tlo) * 4);
+            const f32x4 a01 = pa[0], a23 = pa[1], b01 = pb[0], b23 = pb[1];
+            const float ca[4] = {a01.x, a01.z, a23.x, a23.z}, sa[4] = {a01.y, a01.w, a23.y, a23.w};
+            const float cb[4] = {b01.x, b01.z, b23.x, b23.z}, sb[4] = {b01.y, b01.w, b23.y, b23.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float cs = ca[e] * cb[e] - sa[e] * sb[e];
+              const float sn = sa[e] * cb[e] + ca[e] * sb[e];
+              const float x1 = acc[tt][nt][rg * 4 + e], x2 = acc[tt][nt + 2][rg * 4 + e];
+              acc[tt][nt][rg * 4 + e] = x1 * cs - x2 * sn;
+              acc[tt][nt + 2][rg * 4 + e] = x2 * cs + x1 * sn;
+            }
+          }
+      }
+      // ---- stage the 32 x 128 tile of this wavefront and write whole rows
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          u32x2 w;
+          w.x = pack2(acc[tt][nt][rg * 4 + 0], acc[tt][nt][rg * 4 + 1]);
+          w.y = pack2(acc[tt][nt][rg * 4 + 2], acc[tt][nt][rg * 4 + 3]);
+          *reinterpret_cast<u32x2 *>(sOut + l32 * OUT_ROW + (nt * 32 + rg * 8 + half * 4) * 2) = w;
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int cidx = 0; cidx < 8; ++cidx) {
+        const int id = lane + cidx * 64, r = id >> 4, ch = id & 15;
+        const long long row = wrow0 + tt * 32 + r;
+        const u32x4 val = *reinterpret_cast<const u32x4 *>(sOut + r * OUT_ROW + ch * 16);
+        if (row < a.rows) *reinterpret_cast<u32x4 *>(dst + row * dst_stride + ch * 8) = val;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+  }
+}
+
+template <int D>
+hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, const float2 *ropeA, const float2 *ropeB,
+                       const float *temp, void *q, void *k, void *v, int grid, hipStream_t s) {
+  constexpr size_t smem = (size_t)DH * D * 16 * 16 + 4 * 32 * OUT_ROW;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  prologue_fused_kernel<D><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const u32x4 *)wc, ropeA, ropeB, temp,
+                                                  (bf16_t *)q, (bf16_t *)k, (bf16_t *)v);
+  return hipGetLastError();
+}
+
+int taps(const Dims &d) { return ((d.flags & CCA_CONV_SEQ) ? d.k_seq : 1) + d.k_ch - 1; }
+
+}  // namespace
+
+bool prologue_fused_supported(const Dims &d) {
+  return d.bf16 && d.dh == DH && (d.flags & CCA_CONV_CH) && !(d.flags & CCA_ROPE_INTERLEAVED) && taps(d) <= 3 &&
+         d.v_half % 8 == 0;
+}
+
+size_t prologue_fused_scratch_bytes(const Dims &d) {
+  if (!prologue_fused_supported(d)) return 0;
+  const size_t wc = (size_t)(d.Hq + d.Hk) * DH * taps(d) * DH * 2;
+  const size_t ra = (size_t)((d.T + 127) / 128) * (DH / 2) * 8, rb = (size_t)(DH / 2) * 128 * 8;
+  return (wc + 255) / 256 * 256 + (ra + 255) / 256 * 256 + rb;
+}
+
+hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
+                               void *scratch, hipStream_t s) {
+  const int D = taps(d);
+  const int NH = d.Hq + d.Hk;
+  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, d.rope_base};
+  const int n_thi = (d.T + 127) / 128;
+  const size_t wc_bytes = ((size_t)NH * DH * D * DH * 2 + 255) / 256 * 256;
+  const size_t ra_bytes = ((size_t)n_thi * (DH / 2) * 8 + 255) / 256 * 256;
+  char *base = static_cast<char *>(scratch);
+  bf16_t *wc = reinterpret_cast<bf16_t *>(base);
+  float2 *ropeA = reinterpret_cast<float2 *>(base + wc_bytes);
+  float2 *ropeB = reinterpret_cast<float2 *>(base + wc_bytes + ra_bytes);
+
+  const int n_fold = (NH * DH * DH + 255) / 256;
+  const int n_rope = (n_thi * (DH / 2) + (DH / 2) * 128 + 255) / 256;
+  prologue_setup_kernel<<<n_fold + n_rope, 256, 0, s>>>(a, D, (const bf16_t *)w.w_conv_seq, (const bf16_t *)w.w_conv_ch,
+                                                        wc, ropeA, ropeB, n_fold, n_thi);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  const long long tok_blocks = (d.rows() + TOK_PER_WG - 1) / TOK_PER_WG;
+  a.n_conv_blocks = (int)(tok_blocks * NH);
+  const long long v_chunks = d.rows() * (d.e_kv / 8);
+  const int v_blocks = (int)((v_chunks + NT * 8 - 1) / (NT * 8));
+  const int grid = a.n_conv_blocks + v_blocks;
+  switch (D) {
+    case 1: return launch_main<1>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
+    case 2: return launch_main<2>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
+    default: return launch_main<3>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
+  }
+}
+
+}  // namespace cca
