@@ -92,7 +92,9 @@ static cca_status project(const Dims &d, const void *A, const void *W, void *C, 
 static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *lat, void *q, void *k, void *v,
                                void *scratch, size_t scratch_bytes, hipStream_t s) {
   hipError_t e;
-  if (prologue_fused_supported(d)) {
+  if (prologue_is_split_copy(d)) {
+    e = prologue_split_copy(d, lat, q, k, v, s);
+  } else if (prologue_fused_supported(d)) {
     if (!scratch || scratch_bytes < prologue_fused_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
     e = prologue_fused_bf16(d, *w, lat, q, k, v, scratch, s);
   } else {

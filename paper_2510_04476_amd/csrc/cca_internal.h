@@ -56,6 +56,10 @@ bool attention_mfma_supported(const Dims &d);
 hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
                                hipStream_t s);
 
+// no transform selected: q, k, v are slices of the latent rows (plus the optional value-shift)
+bool prologue_is_split_copy(const Dims &d);
+hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, hipStream_t s);
+
 bool prologue_fused_supported(const Dims &d);
 size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE tables; 0 if unsupported
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,

@@ -299,6 +299,34 @@ __global__ __launch_bounds__(NT) void prologue_fused_kernel(FusedArgs a, const b
   }
 }
 
+// ---------------------------------------------------------------------------
+// No transform selected (plain MHA / GQA, Sec. 2.1): q, k, v are column slices
+// of the latent rows; only the optional value-shift moves data in time.
+// 16 bytes per thread, storage-type agnostic (`es` = bytes per element).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void split_copy_kernel(const unsigned char *__restrict__ lat,
+                                                        unsigned char *__restrict__ q, unsigned char *__restrict__ k,
+                                                        unsigned char *__restrict__ v, long long rows, int T, int e_q,
+                                                        int e_kv, int v_half, int es, int v_shift) {
+  const int n_lat = e_q + 2 * e_kv;
+  const int cpr = n_lat * es / 16;  // chunks per latent row
+  const long long total = rows * cpr;
+  for (long long id = (long long)blockIdx.x * 256 + threadIdx.x; id < total; id += (long long)gridDim.x * 256) {
+    const long long row = id / cpr;
+    const int col = (int)(id % cpr) * (16 / es);  // first element of the chunk
+    const int t = (int)(row % T);
+    u32x4 val = {0, 0, 0, 0};
+    const bool shifted = v_shift && col >= e_q + e_kv + v_half;
+    if (!shifted || t > 0)
+      val = *reinterpret_cast<const u32x4 *>(lat + ((row - (shifted ? 1 : 0)) * n_lat + col) * es);
+    unsigned char *dstp;
+    if (col < e_q) dstp = q + (row * e_q + col) * es;
+    else if (col < e_q + e_kv) dstp = k + (row * e_kv + (col - e_q)) * es;
+    else dstp = v + (row * e_kv + (col - e_q - e_kv)) * es;
+    *reinterpret_cast<u32x4 *>(dstp) = val;
+  }
+}
+
 template <int D>
 hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, const float2 *ropeA, const float2 *ropeB,
                        const float *temp, void *q, void *k, void *v, int grid, hipStream_t s) {
@@ -318,6 +346,21 @@ hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, cons
 int taps(const Dims &d) { return ((d.flags & CCA_CONV_SEQ) ? d.k_seq : 1) + d.k_ch - 1; }
 
 }  // namespace
+
+bool prologue_is_split_copy(const Dims &d) {
+  const uint32_t transforms = CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_QK_NORM | CCA_KEY_TEMP | CCA_ROPE;
+  const int per16 = d.bf16 ? 8 : 4;
+  return !(d.flags & transforms) && d.e_q % per16 == 0 && d.e_kv % per16 == 0 && d.v_half % per16 == 0;
+}
+
+hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, hipStream_t s) {
+  const long long total = d.rows() * ((long long)d.n_lat * d.esize() / 16);
+  const int grid = (int)((total + 255) / 256 < 256 * 64 ? (total + 255) / 256 : 256 * 64);
+  split_copy_kernel<<<grid, 256, 0, s>>>((const unsigned char *)lat, (unsigned char *)q, (unsigned char *)k,
+                                         (unsigned char *)v, d.rows(), d.T, d.e_q, d.e_kv, d.v_half, (int)d.esize(),
+                                         (d.flags & CCA_V_SHIFT) ? 1 : 0);
+  return hipGetLastError();
+}
 
 bool prologue_fused_supported(const Dims &d) {
   return d.bf16 && d.dh == DH && (d.flags & CCA_CONV_CH) && !(d.flags & CCA_ROPE_INTERLEAVED) && taps(d) <= 3 &&
