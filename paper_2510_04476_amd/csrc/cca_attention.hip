@@ -15,236 +15,280 @@
 // row, so (a) the row max / sum are in-lane reductions plus a single exchange
 // between the two half-waves, and (b) the exponentiated scores, packed to
 // bf16 in place, are already the second operand of O^T += V^T P^T: P never
-// goes through LDS.  V is transposed on its way into LDS (4 keys x 8 channels
-// per lane, in registers) into the key order that accumulator layout dictates.
+// goes through LDS.  V sits in LDS row-major like K; the PV operand (8 keys of
+// one channel per lane) is fetched with the gfx950 transposing LDS read
+// (ds_read_b64_tr_b16), in the key order that accumulator layout dictates.
+//
+// Vector-ALU work per score is what bounds this kernel next to the MFMAs, so
+// it is pared down to exp2 + convert + half a dot2:
+//   - Q is multiplied by scale*log2(e) once, so scores are in log2 units;
+//   - the MFMA accumulator starts from -m (the row's reference max, kept as a
+//     16-register vector) instead of 0, so the scores come out max-subtracted;
+//   - the reference max is raised only when a score exceeds it by more than
+//     2^8 (always on the first tile), so rescaling the accumulator is rare;
+//   - the row sum adds the bf16-rounded probabilities pairwise with
+//     v_dot2_f32_bf16 (the same numbers the PV product uses).
+#include <type_traits>
+
 #include "cca_internal.h"
 
 namespace cca {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
 
 namespace {
 
 constexpr int BQ = 128;   // query rows per workgroup (4 wavefronts x 32 rows)
 constexpr int BKV = 64;   // keys per LDS tile
 constexpr int NT = 256;   // threads
-constexpr float RESCALE_LOG2 = 8.f;  // the running max is only raised when it would grow by more than 2^8
+constexpr float RESCALE_LOG2 = 8.f;
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-  // round-to-nearest-even pair; inputs are finite and non-negative
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};  // round to nearest even
   return __builtin_bit_cast(uint32_t, v);
 }
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
-    float *__restrict__ LSE, int T, int Hq, int Hk, int BH, int nqb, float scale) {
-  constexpr int KK = DH / 16;   // MFMA k-steps over the head width
-  constexpr int DT = DH / 32;   // 32-wide output tiles over the head width
-  constexpr int KCH = DH / 8;   // 16-byte chunks per key row
+    float *__restrict__ LSE, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale) {
+  constexpr int KK = DH / 16;          // MFMA k-steps over the head width
+  constexpr int DT = DH / 32;          // 32-wide output tiles over the head width
+  constexpr int KCH = DH / 8;          // 16-byte chunks per key row
+  constexpr int KROW = DH * 2 + 16;    // padded key row in LDS: conflict-free 16-byte reads down a column of rows
+  constexpr int KBUF = BKV * KROW;     // bytes per K buffer
+  constexpr int VROW = DH * 2 + 64;    // padded value row: the 4 rows x 32 bytes a transposing read touches per
+                                       // 16 lanes fall into disjoint banks
+  constexpr int VBUF = BKV * VROW;     // bytes per V buffer
   constexpr int K_PER_THREAD = BKV * KCH / NT;
-  constexpr int V_UNITS = (BKV / 4) * (DH / 8);  // 4-key x 8-channel units per tile
-  static_assert(V_UNITS <= NT, "one V unit per thread at most");
-  __shared__ u32x4 sK[2][BKV * KCH];
-  __shared__ u32x4 sV[2][DH * 8];  // V^T: d_h rows of 64 keys
+  constexpr int K_ROWS_PER_PASS = NT / KCH;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * KBUF + 2 * VBUF];
+  unsigned char *const sKb = smem;
+  unsigned char *const sVb = smem + 2 * KBUF;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  // heaviest (latest) query blocks first; the head index is the fast one, so with
-  // B*Hq a multiple of 8 every XCD keeps working on the K/V of the same head
   const int idx = blockIdx.x;
-  const int bh = idx % BH, qb = nqb - 1 - idx / BH;
+  const int bh = idx % BH;  // head index fastest: with B*Hq a multiple of 8 an XCD keeps one head's K/V in its L2
   const int b = bh / Hq, h = bh % Hq, g = h / (Hq / Hk);
-  const int q0 = qb * BQ, qw0 = q0 + wave * 32;
   const float c = scale * 1.44269504088896340736f;  // exp(x * scale) = exp2(x * c)
+  const int row_bytes = Hk * DH * 2;                 // one token of K or V, all KV heads
+  const unsigned char *const Kg = reinterpret_cast<const unsigned char *>(K + ((long long)b * T * Hk + g) * DH);
+  const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
 
-  // ---- query fragments: row qw0 + l32, all of d_h, straight from HBM
-  bf16x8 qf[KK];
-  {
-    int row = qw0 + l32;
-    row = row < T ? row : T - 1;
-    const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p + kk * 16));
-  }
+  // ---- per-thread constants of the K/V staging
+  const int k_r0 = tid / KCH, k_ch = tid % KCH;                 // K chunk i of this thread: row k_r0 + i*K_ROWS_PER_PASS
+  const uint32_t k_goff = (uint32_t)k_r0 * row_bytes + k_ch * 16;
+  const uint32_t k_soff = (uint32_t)k_r0 * KROW + k_ch * 16;
+  const uint32_t v_soff = (uint32_t)k_r0 * VROW + k_ch * 16;    // V is staged with the same thread -> chunk map
+  // ---- per-lane constants of the MFMA operand reads
+  const uint32_t kr_off = (uint32_t)l32 * KROW + half * 16;  // + ks*32*KROW + kk*32
+  // Transposing read: in each block of 16 lanes, lane i supplies the address of 4 channels of one key and
+  // receives element (i & 3) of the vectors addressed by lanes (i >> 2) + 4*j, j = 0..3.  With lane i pointing
+  // at key 4*half + (i >> 2) + ..., channels dblock*16 + 4*(i & 3)..+3, lane L of the block receives channel
+  // dblock*16 + L of keys 4*half + 0..3: exactly the MFMA fragment of lane (d = l32, half).
+  const uint32_t vr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * VROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
 
-  f32x16 oacc[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-  float m_run = -INFINITY;  // reference max of the raw scores of this lane's query row
-  float l_run = 0.f;        // running sum; each half-wave keeps its own part
-
-  const int kv_end = CAUSAL ? min(q0 + BQ, T) : T;  // keys [0, kv_end) matter to this workgroup
-  const int ntiles = (kv_end + BKV - 1) / BKV;
-  const int wave_last = min(qw0 + 31, T - 1);
-  const bool wave_live = qw0 < T;
-
-  // ---- global -> register staging of one K/V tile
   u32x4 rk[K_PER_THREAD];
-  u32x4 rv[4];
-  const int v_kg = tid / (DH / 8), v_dg = tid % (DH / 8);  // V unit of this thread: keys 4*v_kg.., channels 8*v_dg..
+  u32x4 rv[K_PER_THREAD];
   auto load_tile = [&](int kv0) {
+    if (kv0 + BKV <= T) {  // whole tile in range: uniform bases + one per-thread offset
+      const unsigned char *kb = Kg + (long long)kv0 * row_bytes;
+      const unsigned char *vb = Vg + (long long)kv0 * row_bytes;
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int id = tid + i * NT, r = id / KCH, ch = id % KCH;
-      int s = kv0 + r;
-      s = s < T ? s : T - 1;
-      rk[i] = *reinterpret_cast<const u32x4 *>(K + (((long long)b * T + s) * Hk + g) * DH + ch * 8);
-    }
-    if (tid < V_UNITS) {
+      for (int i = 0; i < K_PER_THREAD; ++i)
+        rk[i] = *reinterpret_cast<const u32x4 *>(kb + (long long)i * K_ROWS_PER_PASS * row_bytes + k_goff);
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        int s = kv0 + v_kg * 4 + rr;
-        s = s < T ? s : T - 1;
-        rv[rr] = *reinterpret_cast<const u32x4 *>(V + (((long long)b * T + s) * Hk + g) * DH + v_dg * 8);
+      for (int i = 0; i < K_PER_THREAD; ++i)
+        rv[i] = *reinterpret_cast<const u32x4 *>(vb + (long long)i * K_ROWS_PER_PASS * row_bytes + k_goff);
+    } else {  // ragged last tile: clamp the key index (clamped keys are masked out below)
+#pragma unroll
+      for (int i = 0; i < K_PER_THREAD; ++i) {
+        const int s = min(kv0 + k_r0 + i * K_ROWS_PER_PASS, T - 1);
+        rk[i] = *reinterpret_cast<const u32x4 *>(Kg + (long long)s * row_bytes + k_ch * 16);
+        rv[i] = *reinterpret_cast<const u32x4 *>(Vg + (long long)s * row_bytes + k_ch * 16);
       }
     }
   };
-  auto kswz = [](int r, int ch) {
-    return KCH == 16 ? (ch ^ (r & 15)) : (ch ^ ((r & 7) ^ ((r >> 3) & 1)));
-  };
-  auto vswz = [](int d, int ch) { return ch ^ ((d & 7) ^ ((d >> 3) & 7)); };
   auto store_tile = [&](int buf) {
+    unsigned char *kd = sKb + buf * KBUF + k_soff;
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int id = tid + i * NT, r = id / KCH, ch = id % KCH;
-      sK[buf][r * KCH + kswz(r, ch)] = rk[i];
-    }
-    if (tid < V_UNITS) {
-      // position of key group v_kg inside a V^T row: chunk = ks*4 + j*2 + hf, 8-byte slot blk
-      const int ks = v_kg >> 3, k8 = v_kg & 7;
-      const int chunk = ks * 4 + (k8 >> 2) * 2 + (k8 & 1), blk = (k8 & 3) >> 1;
-      unsigned char *base = reinterpret_cast<unsigned char *>(sV[buf]);
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(kd + i * K_ROWS_PER_PASS * KROW) = rk[i];
+    unsigned char *vd = sVb + buf * VBUF + v_soff;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {  // channel d = 8*v_dg + e: gather its 4 keys
-        const int d = v_dg * 8 + e;
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 p;
-        p.x = __builtin_amdgcn_perm(rv[1][e >> 1], rv[0][e >> 1], sel);
-        p.y = __builtin_amdgcn_perm(rv[3][e >> 1], rv[2][e >> 1], sel);
-        *reinterpret_cast<u32x2 *>(base + d * 128 + vswz(d, chunk) * 16 + blk * 8) = p;
-      }
-    }
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(vd + i * K_ROWS_PER_PASS * VROW) = rv[i];
   };
 
-  load_tile(0);
-  store_tile(0);
-  __syncthreads();
-  for (int j = 0; j < ntiles; ++j) {
-    const int kv0 = j * BKV, buf = j & 1;
-    const bool more = j + 1 < ntiles;
-    if (more) load_tile(kv0 + BKV);  // in flight while this tile is multiplied
-    if (wave_live && !(CAUSAL && kv0 > wave_last)) {
-      // ---- S^T = K Q^T for 64 keys x 32 query rows
-      f32x16 sacc[2];
+  const int npass = paired ? 2 : 1;
+  for (int pass = 0; pass < npass; ++pass) {
+    // causal work per query block grows with its index: heavy blocks are issued first (unpaired),
+    // or each workgroup takes one heavy and one light block (paired) so all workgroups do equal work
+    const int slot = idx / BH;
+    const int qb = (paired && pass == 1) ? slot : nqb - 1 - slot;
+    if (pass == 1 && slot >= nqb - 1 - slot) break;  // odd count: the middle block was done in pass 0
+    const int q0 = qb * BQ, qw0 = q0 + wave * 32;
+    const bool wave_live = qw0 < T;
+    const int wave_last = min(qw0 + 31, T - 1);
+
+    // ---- query fragment of row qw0 + l32, scaled to log2 units and rounded back to bf16
+    bf16x8 qf[KK];
+    {
+      const int row = min(qw0 + l32, T - 1);
+      const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+      for (int kk = 0; kk < KK; ++kk) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+        w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+        w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+        w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+        w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+        qf[kk] = __builtin_bit_cast(bf16x8, w);
+      }
+    }
+
+    f32x16 oacc[DT];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[ks][r] = 0.f;
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+      for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    f32x16 negm;  // minus the reference max (log2 units) of this lane's query row, replicated: MFMA start value
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+    float l_run = 0.f;  // running sum of probabilities; each half-wave keeps its own part
+
+    const int kv_end = CAUSAL ? min(q0 + BQ, T) : T;  // keys [0, kv_end) matter to this workgroup
+    const int ntiles = (kv_end + BKV - 1) / BKV;
+
+    auto tile = [&](int j, auto buf_c) {
+      constexpr int BUF = decltype(buf_c)::value;
+      const int kv0 = j * BKV;
+      const bool more = j + 1 < ntiles;
+      if (more) load_tile(kv0 + BKV);  // in flight while this tile is multiplied
+      if (wave_live && !(CAUSAL && kv0 > wave_last)) {
+        const unsigned char *kp = sKb + BUF * KBUF + kr_off;
+        // ---- S^T - m = K Q^T - m for 64 keys x 32 query rows (log2 units)
+        f32x16 sacc[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-          const int r = ks * 32 + l32;
-          const bf16x8 kf = __builtin_bit_cast(bf16x8, sK[buf][r * KCH + kswz(r, kk * 2 + half)]);
-          sacc[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[ks], 0, 0, 0);
+          const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + ks * 32 * KROW));
+          sacc[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], negm, 0, 0, 0);
         }
+#pragma unroll
+        for (int kk = 1; kk < KK; ++kk)
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            const bf16x8 kf =
+                __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + ks * 32 * KROW + kk * 32));
+            sacc[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[ks], 0, 0, 0);
+          }
 
-      // ---- online softmax; lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of row l32
-      if ((CAUSAL && kv0 + BKV - 1 > qw0) || (kv0 + BKV > T)) {
-        const int t = qw0 + l32;
-        const int lim = CAUSAL ? min(t, T - 1) : T - 1;  // last visible key
+        // ---- lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of row qw0 + l32
+        if ((CAUSAL && kv0 + BKV - 1 > qw0) || (kv0 + BKV > T)) {
+          const int t = qw0 + l32;
+          const int lim = (CAUSAL ? min(t, T - 1) : T - 1) - kv0 - 4 * half;  // last visible key, tile-relative
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              if (ks * 32 + 8 * (r >> 2) + (r & 3) > lim) sacc[ks][r] = -INFINITY;
+        }
+        float mx = max3(sacc[0][0], sacc[0][1], sacc[1][0]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = max3(mx, sacc[0][r], sacc[0][r + 1]);
+#pragma unroll
+        for (int r = 1; r < 16; r += 2) mx = max3(mx, sacc[1][r], sacc[1][(r + 1) & 15]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // Move the reference max only on the first tile (to the tile's own max) or when a score
+        // exceeds it by more than 2^RESCALE_LOG2; exp2 arguments stay <= RESCALE_LOG2.
+        if (j == 0 || __any(mx > RESCALE_LOG2)) {
+          const float delta = (j == 0) ? mx : fmaxf(mx, 0.f);  // finite: key 0 is visible to every row
+          const float alpha = __builtin_amdgcn_exp2f(-delta);
+          l_run *= alpha;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) negm[r] -= delta;
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[ks][r] -= delta;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        }
+        bf16x8 pf[2][2];
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int s = kv0 + ks * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (s > lim) sacc[ks][r] = -INFINITY;
+          for (int jj = 0; jj < 2; ++jj) {
+            u32x4 w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const uint32_t pk = pack2(__builtin_amdgcn_exp2f(sacc[ks][8 * jj + 2 * e]),
+                                        __builtin_amdgcn_exp2f(sacc[ks][8 * jj + 2 * e + 1]));
+              l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, l_run, false);
+              w[e] = pk;
+            }
+            pf[ks][jj] = __builtin_bit_cast(bf16x8, w);
           }
+
+        // ---- O^T += V^T P^T
+        const unsigned char *vp = sVb + BUF * VBUF + vr_off;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+              const unsigned char *a = vp + (ks * 32 + jj * 16) * VROW + dt * 64;
+              const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)a);
+              const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + 8 * VROW));
+              const v8i16 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+              oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[ks][jj], oacc[dt],
+                                                                 0, 0, 0);
+            }
       }
-      float mx = max3(sacc[0][0], sacc[0][1], sacc[1][0]);
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = max3(mx, sacc[0][r], sacc[0][r + 1]);
-#pragma unroll
-      for (int r = 1; r < 16; r += 2) mx = max3(mx, sacc[1][r], sacc[1][(r + 1) & 15]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      // Raise the reference max only when it would grow by more than 2^RESCALE_LOG2:
-      // exp2 arguments stay <= RESCALE_LOG2, far from fp32 / bf16 overflow, and the
-      // accumulator is rescaled on few tiles only.
-      if (__any((mx - m_run) * c > RESCALE_LOG2)) {
-        const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every row in tile 0
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c);  // 0 on the first tile
-        m_run = m_new;
-        l_run *= alpha;
+      if (more) store_tile(BUF ^ 1);  // that buffer was last read before the barrier ending the previous tile
+      __syncthreads();
+    };
+
+    load_tile(0);
+    store_tile(0);
+    __syncthreads();
+    for (int j = 0; j < ntiles; j += 2) {
+      tile(j, std::integral_constant<int, 0>{});
+      if (j + 1 < ntiles) tile(j + 1, std::integral_constant<int, 1>{});
+    }
+
+    // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
+    if (wave_live) {
+      const int t = qw0 + l32;
+      const float l = l_run + __shfl_xor(l_run, 32);
+      if (t < T) {
+        const float inv = 1.f / l;
+        bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
-      }
-      const float mc = m_run * c;
-      bf16x8 pf[2][2];
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        float p[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          p[r] = __builtin_amdgcn_exp2f(fmaf(sacc[ks][r], c, -mc));
-          l_run += p[r];
-        }
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          u32x4 w;
-          w.x = pack2(p[8 * jj + 0], p[8 * jj + 1]);
-          w.y = pack2(p[8 * jj + 2], p[8 * jj + 3]);
-          w.z = pack2(p[8 * jj + 4], p[8 * jj + 5]);
-          w.w = pack2(p[8 * jj + 6], p[8 * jj + 7]);
-          pf[ks][jj] = __builtin_bit_cast(bf16x8, w);
-        }
-      }
-
-      // ---- O^T += V^T P^T
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            const int d = dt * 32 + l32;
-            const bf16x8 vf = __builtin_bit_cast(bf16x8, sV[buf][d * 8 + vswz(d, ks * 4 + jj * 2 + half)]);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[ks][jj], oacc[dt], 0, 0, 0);
+          for (int rg = 0; rg < 4; ++rg) {
+            u32x2 w;
+            w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
+            w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
+            *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
           }
-    }
-    if (more) store_tile(buf ^ 1);  // last read before the barrier that ended the previous iteration
-    __syncthreads();
-  }
-
-  // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
-  if (!wave_live) return;
-  {
-    const int t = qw0 + l32;
-    const float l = l_run + __shfl_xor(l_run, 32);
-    if (t < T) {
-      const float inv = 1.f / l;
-      bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          u32x2 w;
-          w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
-          w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
-          *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
-        }
-      if (LSE && half == 0) LSE[((long long)b * Hq + h) * T + t] = m_run * scale + logf(l);
+        if (LSE && half == 0)
+          LSE[((long long)b * Hq + h) * T + t] = (log2f(l) - negm[0]) * 0.69314718055994530942f;
+      }
     }
   }
 }
@@ -253,20 +297,25 @@ template <int DH>
 hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse, hipStream_t s) {
   const int nqb = (d.T + BQ - 1) / BQ;
   const int BH = d.B * d.Hq;
-  const long long blocks = (long long)nqb * BH;
-  if (d.flags & CCA_CAUSAL)
+  const bool causal = d.flags & CCA_CAUSAL;
+  // pair a heavy with a light query block once that still leaves >= 2 workgroups for each of the 256 CUs
+  const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 512 ? 1 : 0;
+  const long long blocks = (long long)BH * (paired ? (nqb + 1) / 2 : nqb);
+  if (causal)
     attn_fwd_kernel<DH, true><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                                                            (bf16_t *)o, lse, d.T, d.Hq, d.Hk, BH, nqb, d.scale);
+                                                            (bf16_t *)o, lse, d.T, d.Hq, d.Hk, BH, nqb, paired, d.scale);
   else
-    attn_fwd_kernel<DH, false><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                                                             (bf16_t *)o, lse, d.T, d.Hq, d.Hk, BH, nqb, d.scale);
+    attn_fwd_kernel<DH, false><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k,
+                                                             (const bf16_t *)v, (bf16_t *)o, lse, d.T, d.Hq, d.Hk, BH,
+                                                             nqb, paired, d.scale);
   return hipGetLastError();
 }
 
 }  // namespace
 
 bool attention_mfma_supported(const Dims &d) {
-  return d.bf16 && (d.dh == 128 || d.dh == 64) && (long long)d.B * d.Hq * ((d.T + BQ - 1) / BQ) < (1ll << 31);
+  return d.bf16 && (d.dh == 128 || d.dh == 64) && (long long)d.B * d.Hq * ((d.T + BQ - 1) / BQ) < (1ll << 31) &&
+         (long long)d.T * d.Hk * d.dh * 2 < (1ll << 31);
 }
 
 hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,

@@ -141,7 +141,8 @@ def test_attention_stage(T, Hq, Hk, dh, causal):
     o_ref, lse_ref = O.attention(q, k, v, 1.0 / np.sqrt(dh), causal=causal)
     say("o", check_tap(to_np(o).reshape(o_ref.shape), o_ref, "bf16", "o"))
     rel, mx = errors(to_np(lse), lse_ref)
-    assert mx <= 2e-3, ("lse", rel, mx)
+    # scores carry one extra bf16 rounding (q is pre-multiplied by scale*log2 e): |d lse| ~ |s| 2^-9
+    assert mx <= 5e-3, ("lse", rel, mx)
 
 
 # ---- config 2: CCA prefill bf16, T = 4096, literal and conv-visible ----------
