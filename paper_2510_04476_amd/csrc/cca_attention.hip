@@ -7,8 +7,8 @@
 // statistics of a row never leave a wavefront.  Two workgroups share a CU
 // (2 wavefronts per SIMD): while one wavefront does softmax arithmetic on
 // the vector ALU, the other keeps the matrix core busy.  Keys / values arrive
-// in tiles of 64 through double-buffered LDS; the next tile travels HBM ->
-// registers while the current one is multiplied.
+// in tiles of 64 through double-buffered LDS: tile j+2 travels HBM -> registers
+// and tile j+1 registers -> LDS while tile j is multiplied.
 //
 // The scores are produced transposed, S^T = K Q^T, with the 32x32x16 bf16
 // MFMA.  Its accumulator layout then gives every lane 16 keys of ONE query
@@ -45,9 +45,9 @@ typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
 
 namespace {
 
-constexpr int BQ = 128;   // query rows per workgroup (4 wavefronts x 32 rows)
+constexpr int BQ = 256;   // query rows per workgroup (8 wavefronts x 32 rows)
 constexpr int BKV = 64;   // keys per LDS tile
-constexpr int NT = 256;   // threads
+constexpr int NT = 512;   // threads
 constexpr float RESCALE_LOG2 = 8.f;
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -172,8 +172,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     auto tile = [&](int j, auto buf_c) {
       constexpr int BUF = decltype(buf_c)::value;
       const int kv0 = j * BKV;
-      const bool more = j + 1 < ntiles;
-      if (more) load_tile(kv0 + BKV);  // in flight while this tile is multiplied
+      // Tile j+1 is already in registers (loaded while tile j-1 was multiplied): put it into the other LDS
+      // buffer right away, so that its stores drain under this tile's MFMAs instead of in front of the
+      // barrier, then start the loads of tile j+2 into the same registers.
+      if (j + 1 < ntiles) store_tile(BUF ^ 1);  // that buffer was last read before the barrier ending tile j-1
+      if (j + 2 < ntiles) load_tile(kv0 + 2 * BKV);
       if (wave_live && !(CAUSAL && kv0 > wave_last)) {
         const unsigned char *kp = sKb + BUF * KBUF + kr_off;
         // ---- S^T - m = K Q^T - m for 64 keys x 32 query rows (log2 units)
@@ -258,12 +261,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                                                                  0, 0, 0);
             }
       }
-      if (more) store_tile(BUF ^ 1);  // that buffer was last read before the barrier ending the previous tile
       __syncthreads();
     };
 
     load_tile(0);
     store_tile(0);
+    if (ntiles > 1) load_tile(BKV);
     __syncthreads();
     for (int j = 0; j < ntiles; j += 2) {
       tile(j, std::integral_constant<int, 0>{});
@@ -298,8 +301,10 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
   const int nqb = (d.T + BQ - 1) / BQ;
   const int BH = d.B * d.Hq;
   const bool causal = d.flags & CCA_CAUSAL;
-  // pair a heavy with a light query block once that still leaves >= 2 workgroups for each of the 256 CUs
-  const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 512 ? 1 : 0;
+  // Pairing a heavy with a light causal query block in one workgroup equalises the work per workgroup, but
+  // measured slower than issuing the heavy blocks first (two diagonals per workgroup, no overlap of one
+  // workgroup's tail with another's start): kept switchable, off.
+  const int paired = 0;
   const long long blocks = (long long)BH * (paired ? (nqb + 1) / 2 : nqb);
   if (causal)
     attn_fwd_kernel<DH, true><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
