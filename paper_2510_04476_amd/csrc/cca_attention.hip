@@ -301,10 +301,10 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
   const int nqb = (d.T + BQ - 1) / BQ;
   const int BH = d.B * d.Hq;
   const bool causal = d.flags & CCA_CAUSAL;
-  // Pairing a heavy with a light causal query block in one workgroup equalises the work per workgroup, but
-  // measured slower than issuing the heavy blocks first (two diagonals per workgroup, no overlap of one
-  // workgroup's tail with another's start): kept switchable, off.
-  const int paired = 0;
+  // Causal work per query block grows with its index.  With one 8-wavefront workgroup per CU, giving every
+  // workgroup one heavy and one light block (equal work for all) measured ~20% faster at B*Hq = 8 than issuing
+  // the heavy blocks first; only worth it while it still leaves a workgroup for each of the 256 CUs.
+  const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 256 ? 1 : 0;
   const long long blocks = (long long)BH * (paired ? (nqb + 1) / 2 : nqb);
   if (causal)
     attn_fwd_kernel<DH, true><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
