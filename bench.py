@@ -36,7 +36,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="ccgqa_16k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-prefix", type=int, default=8192, help="tokens of the causal prefix the oracle is timed on")
+    ap.add_argument("--no-mha", action="store_true", help="skip the same-kernel MHA comparison run")
+    ap.add_argument("--only", choices=["attention", "prologue", "down_project", "up_project"],
+                    help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
+    ap.add_argument("--cpu-prefix", type=int, default=16384, help="tokens of the causal prefix the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
@@ -64,6 +67,20 @@ def main() -> int:
 
     def step():
         P.cca_forward(cfg, wt, x, out=out, saved=None, workspace=ws)
+
+    if args.only:
+        P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
+        stage = {
+            "attention": lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None),
+            "prologue": lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws),
+            "down_project": lambda: P.cca_down_project(cfg, x, wt.w_down, lat=saved.lat, workspace=ws),
+            "up_project": lambda: P.cca_up_project(cfg, saved.o, wt.w_out, out=out, workspace=ws),
+        }[args.only]
+        for _ in range(args.steps):
+            stage()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "launches": args.steps, "workload": args.workload}))
+        return 0
 
     for _ in range(args.warmup):
         step()
@@ -98,7 +115,7 @@ def main() -> int:
 
     # ---- same-kernel MHA baseline (compression 1, 16 x 128 heads, no transforms) ------------
     mha = None
-    if args.workload == "ccgqa_16k":
+    if args.workload == "ccgqa_16k" and not args.no_mha:
         wm = WORKLOADS["mha_16k"]
         cm = P.config_from_workload(wm)
         im = make_inputs(wm, seed=0)
