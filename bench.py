@@ -71,7 +71,7 @@ def main() -> int:
     if args.only:
         P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
         stage = {
-            "attention": lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None),
+            "attention": lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None, temp=wt.temp),
             "prologue": lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws),
             "down_project": lambda: P.cca_down_project(cfg, x, wt.w_down, lat=saved.lat, workspace=ws),
             "up_project": lambda: P.cca_up_project(cfg, saved.o, wt.w_out, out=out, workspace=ws),
@@ -107,7 +107,7 @@ def main() -> int:
         return sum(a.elapsed_time(b) for a, b in evs) / n
 
     n_ev = max(10, min(args.steps, 50))
-    attn_ms = timed(lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None), n_ev)
+    attn_ms = timed(lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None, temp=wt.temp), n_ev)
     down_ms = timed(lambda: P.cca_down_project(cfg, x, wt.w_down, lat=saved.lat, workspace=ws), n_ev)
     pro_ms = timed(lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws), n_ev)
     up_ms = timed(lambda: P.cca_up_project(cfg, saved.o, wt.w_out, out=out, workspace=ws), n_ev)

@@ -132,9 +132,16 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
                         void *v, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* o (B,T,H_q*d_h) = softmax(scale * q k^T [causal]) v per latent head, query
- * head h reading KV head h / R.  lse may be NULL. */
+ * head h reading KV head h / R.  lse may be NULL.
+ * If cfg->flags has CCA_QK_NORM the caller PROMISES that q and k are what
+ * cca_prologue writes under that flag: |q[t,h]| = sqrt(d_h) and |k[t,g]| =
+ * sqrt(d_h) * exp(temp[g]) (temp: H_k fp32 log-temperatures on the device,
+ * required with CCA_KEY_TEMP, else ignored and may be NULL).  The kernel uses
+ * the resulting bound on the scores in place of the running row max; q / k
+ * that break the promise give undefined results.  Clear CCA_QK_NORM in cfg to
+ * attend over arbitrary q, k. */
 cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o,
-                         float *lse, void *hip_stream);
+                         float *lse, const float *temp, void *hip_stream);
 
 /* out (B*T, E) = o (B*T, e_q) * w_out (e_q, E).  Last line of the final eq. block. */
 cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_out, void *out,

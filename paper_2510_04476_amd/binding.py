@@ -72,7 +72,7 @@ def load_library() -> C.CDLL:
     lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, sz, vp]
-    lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp]
+    lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
     lib.cca_strerror.argtypes = [C.c_int]
@@ -246,13 +246,13 @@ def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None, wor
     return q, k, v
 
 
-def cca_attention(cfg: CCAConfig, q, k, v, o=None, lse=None, want_lse=False):
+def cca_attention(cfg: CCAConfig, q, k, v, o=None, lse=None, want_lse=False, temp=None):
     lib = load_library()
     if o is None:
         o = torch.empty(cfg.B, cfg.T, cfg.e_q, dtype=cfg.torch_dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty(cfg.B, cfg.n_q_heads, cfg.T, dtype=torch.float32, device=q.device)
     cc = cfg.c()
-    _check(lib.cca_attention(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _stream()),
+    _check(lib.cca_attention(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(temp), _stream()),
            "cca_attention")
     return (o, lse) if want_lse else o

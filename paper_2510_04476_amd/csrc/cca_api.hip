@@ -104,8 +104,8 @@ static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *
 }
 
 static cca_status run_attention(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                                hipStream_t s) {
-  hipError_t e = attention_mfma_supported(d) ? attention_mfma_bf16(d, q, k, v, o, lse, s)
+                                const float *temp, hipStream_t s) {
+  hipError_t e = attention_mfma_supported(d) ? attention_mfma_bf16(d, q, k, v, o, lse, temp, s)
                                              : attention_generic(d, q, k, v, o, lse, s);
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
@@ -169,14 +169,16 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
 }
 
 cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o, float *lse,
-                         void *hip_stream) {
+                         const float *temp, void *hip_stream) {
   Dims d;
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
   if (!q || !k || !v || !o) return CCA_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3u))
     return CCA_ERR_ALIGN;
-  return run_attention(d, q, k, v, o, lse, (hipStream_t)hip_stream);
+  if ((d.flags & CCA_KEY_TEMP) && !temp) return CCA_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(temp) & 3u) return CCA_ERR_ALIGN;
+  return run_attention(d, q, k, v, o, lse, temp, (hipStream_t)hip_stream);
 }
 
 cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *x, void *out, const cca_saved *saved,
@@ -210,7 +212,7 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   if (st != CCA_OK) return st;
   st = run_prologue(d, w, lat, q, k, v, ws + L.pro, L.lat - L.pro, s);
   if (st != CCA_OK) return st;
-  st = run_attention(d, q, k, v, o, lse, s);
+  st = run_attention(d, q, k, v, o, lse, w->temp, s);
   if (st != CCA_OK) return st;
   return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s);
 }

@@ -26,6 +26,8 @@
 //     16-register vector) instead of 0, so the scores come out max-subtracted;
 //   - the reference max is raised only when a score exceeds it by more than
 //     2^8 (always on the first tile), so rescaling the accumulator is rare;
+//     with the QK L2-norm of the method the scores are bounded by d_h * beta *
+//     scale, that bound is the reference max and the row max is never formed;
 //   - the row sum adds the bf16-rounded probabilities pairwise with
 //     v_dot2_f32_bf16 (the same numbers the PV product uses).
 #include <type_traits>
@@ -58,10 +60,14 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(
-    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
-    float *__restrict__ LSE, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale) {
+// BOUNDED: the caller guarantees |score| <= bound (log2 units) for every query / key pair, as the QK L2-norm
+// of Sec. 2.2 does (|q| = sqrt(d_h), |k| = sqrt(d_h) * beta).  Then `bound` itself serves as the reference max
+// of every row: no row max, no rescaling, and exp2 arguments lie in [-2*bound, 0].
+template <int DH, bool CAUSAL, bool BOUNDED>
+__device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                              const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
+                                              float *__restrict__ LSE, int T, int Hq, int Hk, int BH, int nqb,
+                                              int paired, float scale, float bound) {
   constexpr int KK = DH / 16;          // MFMA k-steps over the head width
   constexpr int DT = DH / 32;          // 32-wide output tiles over the head width
   constexpr int KCH = DH / 8;          // 16-byte chunks per key row
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     f32x16 negm;  // minus the reference max (log2 units) of this lane's query row, replicated: MFMA start value
 #pragma unroll
-    for (int r = 0; r < 16; ++r) negm[r] = 0.f;
+    for (int r = 0; r < 16; ++r) negm[r] = BOUNDED ? -bound : 0.f;
     float l_run = 0.f;  // running sum of probabilities; each half-wave keeps its own part
 
     const int kv_end = CAUSAL ? min(q0 + BQ, T) : T;  // keys [0, kv_end) matter to this workgroup
@@ -205,28 +211,35 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             for (int r = 0; r < 16; ++r)
               if (ks * 32 + 8 * (r >> 2) + (r & 3) > lim) sacc[ks][r] = -INFINITY;
         }
-        float mx = max3(sacc[0][0], sacc[0][1], sacc[1][0]);
-#pragma unroll
-        for (int r = 2; r < 16; r += 2) mx = max3(mx, sacc[0][r], sacc[0][r + 1]);
-#pragma unroll
-        for (int r = 1; r < 16; r += 2) mx = max3(mx, sacc[1][r], sacc[1][(r + 1) & 15]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // Move the reference max only on the first tile (to the tile's own max) or when a score
-        // exceeds it by more than 2^RESCALE_LOG2; exp2 arguments stay <= RESCALE_LOG2.
-        if (j == 0 || __any(mx > RESCALE_LOG2)) {
-          const float delta = (j == 0) ? mx : fmaxf(mx, 0.f);  // finite: key 0 is visible to every row
-          const float alpha = __builtin_amdgcn_exp2f(-delta);
-          l_run *= alpha;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) negm[r] -= delta;
-#pragma unroll
-          for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[ks][r] -= delta;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+        if (!BOUNDED) {
+          float mx0 = max3(sacc[0][0], sacc[0][1], sacc[0][2]), mx1 = max3(sacc[1][0], sacc[1][1], sacc[1][2]);
+  #pragma unroll
+          for (int r = 3; r < 15; r += 2) {  // two independent chains
+            mx0 = max3(mx0, sacc[0][r], sacc[0][r + 1]);
+            mx1 = max3(mx1, sacc[1][r], sacc[1][r + 1]);
+          }
+          float mx = max3(mx0, mx1, fmaxf(sacc[0][15], sacc[1][15]));
+          {  // the other half-wave holds the other 32 keys of the same row: exchange on the vector ALU, not through LDS
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          }
+          // Move the reference max only on the first tile (to the tile's own max) or when a score
+          // exceeds it by more than 2^RESCALE_LOG2; exp2 arguments stay <= RESCALE_LOG2.
+          if (j == 0 || __any(mx > RESCALE_LOG2)) {
+            const float delta = (j == 0) ? mx : fmaxf(mx, 0.f);  // finite: key 0 is visible to every row
+            const float alpha = __builtin_amdgcn_exp2f(-delta);
+            l_run *= alpha;
+  #pragma unroll
+            for (int r = 0; r < 16; ++r) negm[r] -= delta;
+  #pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+  #pragma unroll
+              for (int r = 0; r < 16; ++r) sacc[ks][r] -= delta;
+  #pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+  #pragma unroll
+              for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+          }
         }
         bf16x8 pf[2][2];
         const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
@@ -296,8 +309,28 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   }
 }
 
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
+    float *__restrict__ LSE, const float *__restrict__ temp, int qk_normed, int T, int Hq, int Hk, int BH, int nqb,
+    int paired, float scale) {
+  float bound = INFINITY;
+  if (qk_normed) {
+    // |q.k| <= d_h * beta; 2 % head-room for the bf16 rounding of the stored q and k
+    const int g = ((int)blockIdx.x % BH % Hq) / (Hq / Hk);
+    const float beta = temp ? expf(temp[g]) : 1.f;
+    bound = 1.02f * (float)DH * beta * scale * 1.44269504088896340736f;
+  }
+  // exp2 arguments reach -2*bound: keep them inside the fp32 exponent range
+  if (bound <= 60.f)
+    attn_fwd_body<DH, CAUSAL, true>(Q, K, V, O, LSE, T, Hq, Hk, BH, nqb, paired, scale, bound);
+  else
+    attn_fwd_body<DH, CAUSAL, false>(Q, K, V, O, LSE, T, Hq, Hk, BH, nqb, paired, scale, 0.f);
+}
+
 template <int DH>
-hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse, hipStream_t s) {
+hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse, const float *temp,
+                  hipStream_t s) {
   const int nqb = (d.T + BQ - 1) / BQ;
   const int BH = d.B * d.Hq;
   const bool causal = d.flags & CCA_CAUSAL;
@@ -306,13 +339,16 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
   // the heavy blocks first; only worth it while it still leaves a workgroup for each of the 256 CUs.
   const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 256 ? 1 : 0;
   const long long blocks = (long long)BH * (paired ? (nqb + 1) / 2 : nqb);
+  const int qk_normed = (d.flags & CCA_QK_NORM) ? 1 : 0;
+  if (!(d.flags & CCA_KEY_TEMP)) temp = nullptr;
   if (causal)
     attn_fwd_kernel<DH, true><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                                                            (bf16_t *)o, lse, d.T, d.Hq, d.Hk, BH, nqb, paired, d.scale);
+                                                            (bf16_t *)o, lse, temp, qk_normed, d.T, d.Hq, d.Hk, BH, nqb, paired,
+                                                            d.scale);
   else
     attn_fwd_kernel<DH, false><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k,
-                                                             (const bf16_t *)v, (bf16_t *)o, lse, d.T, d.Hq, d.Hk, BH,
-                                                             nqb, paired, d.scale);
+                                                             (const bf16_t *)v, (bf16_t *)o, lse, temp, qk_normed, d.T,
+                                                             d.Hq, d.Hk, BH, nqb, paired, d.scale);
   return hipGetLastError();
 }
 
@@ -324,8 +360,8 @@ bool attention_mfma_supported(const Dims &d) {
 }
 
 hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                               hipStream_t s) {
-  return d.dh == 128 ? launch<128>(d, q, k, v, o, lse, s) : launch<64>(d, q, k, v, o, lse, s);
+                               const float *temp, hipStream_t s) {
+  return d.dh == 128 ? launch<128>(d, q, k, v, o, lse, temp, s) : launch<64>(d, q, k, v, o, lse, temp, s);
 }
 
 }  // namespace cca

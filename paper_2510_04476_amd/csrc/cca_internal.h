@@ -53,8 +53,9 @@ hipError_t gemm_mfma_bf16(const void *A, const void *Bt, void *C, long long M, i
 hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStream_t s);
 
 bool attention_mfma_supported(const Dims &d);
+// temp (H_k log-temperatures, device) is read only when d.flags has QK_NORM and KEY_TEMP: it bounds the scores
 hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                               hipStream_t s);
+                               const float *temp, hipStream_t s);
 
 // no transform selected: q, k, v are slices of the latent rows (plus the optional value-shift)
 bool prologue_is_split_copy(const Dims &d);
