@@ -16,8 +16,9 @@
 // The MFMA is issued with the filter as its first operand, so each lane ends
 // up with 64 of the 128 output channels of ONE token (the other half-wave has
 // the rest): the L2 norm is an in-lane sum plus one half-wave exchange, and
-// the rotate-half RoPE partner (o, o + d_h/2) sits in the same lane.  Results
-// are staged per wavefront in LDS and leave as whole 256-byte rows.
+// the rotate-half RoPE partner (o, o + d_h/2) sits in the same lane.  The
+// qk-mean skip branch is added by the matrix core as well (a scaled identity
+// times the pre-conv latent rows), so it needs no loads in another layout.
 //
 // RoPE angles: t * theta_i is split as (t >> 7) * 128 * theta_i + (t & 127) *
 // theta_i; both parts come from tables made in fp64, combined by the angle
@@ -36,9 +37,8 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 namespace {
 
 constexpr int DH = 128;
-constexpr int NT = 256;
+constexpr int NT = 512;
 constexpr int TOK_PER_WG = 512;
-constexpr int OUT_ROW = 272;  // bytes per staged output row (256 + pad: 8-byte column writes stay conflict-free)
 
 struct FusedArgs {
   int T, Hq, Hk, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch;
@@ -103,19 +103,16 @@ __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D,
 }
 
 // ---------------------------------------------------------------------------
-// main kernel
+// main kernel: one workgroup = one head x 512 tokens, 8 wavefronts x (2 x 32 tokens)
 // ---------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(NT) void prologue_fused_kernel(FusedArgs a, const bf16_t *__restrict__ lat,
-                                                           const u32x4 *__restrict__ wc,
-                                                           const float2 *__restrict__ ropeA,
-                                                           const float2 *__restrict__ ropeB,
-                                                           const float *__restrict__ temp, bf16_t *__restrict__ q,
-                                                           bf16_t *__restrict__ k, bf16_t *__restrict__ v) {
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_fused_kernel(
+    FusedArgs a, const bf16_t *__restrict__ lat, const u32x4 *__restrict__ wc, const float2 *__restrict__ ropeA,
+    const float2 *__restrict__ ropeB, const float *__restrict__ temp, bf16_t *__restrict__ q, bf16_t *__restrict__ k,
+    bf16_t *__restrict__ v) {
   constexpr int WROW = D * 16;  // 16-byte chunks per filter row (one output channel)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4 *sW = reinterpret_cast<u32x4 *>(smem);
-  unsigned char *sOutAll = smem + (size_t)DH * WROW * 16;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -124,8 +121,8 @@ __global__ __launch_bounds__(NT) void prologue_fused_kernel(FusedArgs a, const b
     // ---- value-shift role: v[t] = [vc[t] | vp[t-1]], 16 bytes per thread, whole rows per wavefront
     const int cpr = a.e_kv / 8;  // chunks per row
     const long long total = a.rows * cpr;
-    const long long first = ((long long)blockIdx.x - a.n_conv_blocks) * (NT * 8);
-    for (int it = 0; it < 8; ++it) {
+    const long long first = ((long long)blockIdx.x - a.n_conv_blocks) * (NT * 4);
+    for (int it = 0; it < 4; ++it) {
       const long long id = first + it * NT + tid;
       if (id >= total) break;
       const long long row = id / cpr;
@@ -150,151 +147,156 @@ __global__ __launch_bounds__(NT) void prologue_fused_kernel(FusedArgs a, const b
   // ---- filter of this head -> LDS, chunk-swizzled by output channel
   {
     const u32x4 *src = wc + (long long)head * DH * WROW;
+#pragma unroll 4
     for (int id = tid; id < DH * WROW; id += NT) {
       const int o = id / WROW, c = id % WROW;
       sW[o * WROW + ((c & ~15) | ((c ^ o) & 15))] = src[id];
     }
   }
-  __syncthreads();
+  __syncthreads();  // the only workgroup-wide synchronisation
   const float beta = (!is_q && (a.flags & CCA_KEY_TEMP)) ? expf(temp[g]) : 1.f;
-  unsigned char *sOut = sOutAll + wave * (32 * OUT_ROW);
   bf16_t *dst = is_q ? q + head * DH : k + g * DH;
   const int dst_stride = is_q ? a.e_q : a.e_kv;
 
-  for (int it = 0; it < TOK_PER_WG / 256; ++it) {
-    const long long wrow0 = row_begin + it * 256 + wave * 64;
-    if (wrow0 >= a.rows) break;  // wave-uniform; nothing below synchronises across wavefronts
-
-    long long rowc[2];
-    int tpos[2];
+  // ---- qk-mean through the matrix core: m = c * I * u adds c times a latent row, already in the
+  // accumulator layout, with no extra loads or conversions.  Fragment j of c*I for output tile nt pairs with
+  // operand fragment kk = 2*nt + j of the source row; lane (l32, half) is non-zero in fragment l32 >> 4 when
+  // (l32 >> 3) & 1 == half, element l32 & 7.
+  const bool mean = a.flags & CCA_QK_MEAN;
+  bf16x8 id_half[2], id_grp[2];  // 1/2 * I (own pre-conv latent; k for q heads), 1/(2R) * I (q rows for a k head)
+  {
+    const uint32_t hb = (uint32_t)f32_to_bf16(0.5f), gb = (uint32_t)f32_to_bf16(0.5f / (float)a.R);
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const long long row = wrow0 + tt * 32 + l32;
-      rowc[tt] = row < a.rows ? row : a.rows - 1;
-      tpos[tt] = (int)(rowc[tt] % a.T);
+    for (int j = 0; j < 2; ++j) {
+      const bool on = ((l32 >> 4) == j) && (((l32 >> 3) & 1) == half);
+      u32x4 wh = {0, 0, 0, 0}, wg = {0, 0, 0, 0};
+      const int e = l32 & 7;
+      if (on) {
+        wh[e >> 1] = hb << ((e & 1) * 16);
+        wg[e >> 1] = gb << ((e & 1) * 16);
+      }
+      id_half[j] = __builtin_bit_cast(bf16x8, wh);
+      id_grp[j] = __builtin_bit_cast(bf16x8, wg);
     }
+  }
 
-    // ---- y1^T = Wc * [u(t-D+1) .. u(t)]^T
-    f32x16 acc[2][4];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[tt][nt][r] = 0.f;
+  for (int tt = 0; tt < TOK_PER_WG / (8 * 32); ++tt) {
+    const long long trow0 = row_begin + wave * 64 + tt * 32;
+    if (trow0 >= a.rows) break;  // wave-uniform; nothing below synchronises across wavefronts
+    const long long row = trow0 + l32;
+    const long long rowc = row < a.rows ? row : a.rows - 1;
+    const int tpos = (int)(rowc % a.T);
+    // Tokens before the start of their sequence contribute zeros.  Only the first tile of a sequence has such
+    // taps: everywhere else the loads are unconditional and all in flight together.
+    const bool any_pad = __any(tpos < D - 1) != 0;
+
+    // ---- operands: latent rows of tokens t-D+1 .. t of this head (d = D-1 is the token itself)
+    bf16x8 uf[D][8];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       const int back = D - 1 - d;
+      const long long src_row = rowc - back >= 0 ? rowc - back : 0;  // in bounds; zeroed below
+      const bf16_t *p = lat + src_row * a.n_lat + ch0 + half * 8;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
-        bf16x8 uf[2];
+        u32x4 raw = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+        if (any_pad && tpos < back) raw = u32x4{0, 0, 0, 0};
+        uf[d][kk] = __builtin_bit_cast(bf16x8, raw);
+      }
+    }
+
+    // ---- y1^T = Wc * [u(t-D+1) .. u(t)]^T
+    f32x16 acc[4];
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          u32x4 raw = {0, 0, 0, 0};
-          if (tpos[tt] >= back)  // tokens before the start of the sequence are zero
-            raw = *reinterpret_cast<const u32x4 *>(lat + (rowc[tt] - back) * a.n_lat + ch0 + kk * 16 + half * 8);
-          uf[tt] = __builtin_bit_cast(bf16x8, raw);
-        }
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
           const int o = nt * 32 + l32;
           const int c = d * 16 + kk * 2 + half;
           const bf16x8 wf = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~15) | ((c ^ o) & 15))]);
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt)
-            acc[tt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[tt], acc[tt][nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[d][kk], acc[nt], 0, 0, 0);
         }
+
+    // ---- qk-mean.  q head: + (q0 + k0[g]) / 2.  k head: + (mean_r q0[gR + r] + k0) / 2.
+    if (mean) {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_half[j], uf[D - 1][2 * nt + j], acc[nt], 0, 0, 0);
+      const int nsrc = is_q ? 1 : a.R;
+      for (int sidx = 0; sidx < nsrc; ++sidx) {
+        const int col = is_q ? a.e_q + g * DH : (g * a.R + sidx) * DH;
+        const bf16_t *p = lat + rowc * a.n_lat + col + half * 8;
+        bf16x8 mf[8];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+          mf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p + kk * 16));
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(is_q ? id_half[j] : id_grp[j], mf[2 * nt + j], acc[nt], 0,
+                                                              0, 0);
       }
     }
 
-    // ---- per token: qk-mean, norm, temperature, RoPE.  Lane (l32, half) holds
-    //      channels o = 32*nt + 8*rg + 4*half + e of token l32 in acc[tt][nt][4*rg + e].
+    // ---- per token: norm, temperature, RoPE.  Lane (l32, half) holds channels
+    //      o = 32*nt + 8*rg + 4*half + e of token l32 in acc[nt][4*rg + e].
+    if (a.flags & CCA_QK_NORM) {
+      float ssq = 0.f;
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const bf16_t *lrow = lat + rowc[tt] * a.n_lat;
-      if (a.flags & CCA_QK_MEAN) {
+      for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int r = 0; r < 16; ++r) ssq = fmaf(acc[nt][r], acc[nt][r], ssq);
+      ssq += __shfl_xor(ssq, 32);
+      const float mul = sqrtf((float)DH) / sqrtf(ssq) * beta;
 #pragma unroll
-          for (int rg = 0; rg < 4; ++rg) {
-            const int o0 = nt * 32 + rg * 8 + half * 4;
-            const u32x2 kk0 = *reinterpret_cast<const u32x2 *>(lrow + a.e_q + g * DH + o0);
-            float m[4] = {lo_f(kk0.x), hi_f(kk0.x), lo_f(kk0.y), hi_f(kk0.y)};
-            if (is_q) {
-              const u32x2 q0 = *reinterpret_cast<const u32x2 *>(lrow + head * DH + o0);
-              m[0] += lo_f(q0.x); m[1] += hi_f(q0.x); m[2] += lo_f(q0.y); m[3] += hi_f(q0.y);
-            } else {
-              float s[4] = {0.f, 0.f, 0.f, 0.f};
-              for (int r = 0; r < a.R; ++r) {
-                const u32x2 q0 = *reinterpret_cast<const u32x2 *>(lrow + (g * a.R + r) * DH + o0);
-                s[0] += lo_f(q0.x); s[1] += hi_f(q0.x); s[2] += lo_f(q0.y); s[3] += hi_f(q0.y);
-              }
-              const float invR = 1.f / (float)a.R;
+      for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-              for (int e = 0; e < 4; ++e) m[e] = fmaf(s[e], invR, m[e]);
-            }
+        for (int r = 0; r < 16; ++r) acc[nt][r] *= mul;
+    }
+    if (a.flags & CCA_ROPE) {
+      const int thi = tpos >> 7, tlo = tpos & 127;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[tt][nt][rg * 4 + e] = fmaf(0.5f, m[e], acc[tt][nt][rg * 4 + e]);
+      for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int i0 = nt * 32 + rg * 8 + half * 4;  // 4 consecutive pair indices
+          const f32x4 *pa = reinterpret_cast<const f32x4 *>(ropeA + thi * (DH / 2) + i0);
+          const f32x4 *pb = reinterpret_cast<const f32x4 *>(ropeB + ((i0 >> 2) * 128 + tlo) * 4);
+          const f32x4 a01 = pa[0], a23 = pa[1], b01 = pb[0], b23 = pb[1];
+          const float ca[4] = {a01.x, a01.z, a23.x, a23.z}, sa[4] = {a01.y, a01.w, a23.y, a23.w};
+          const float cb[4] = {b01.x, b01.z, b23.x, b23.z}, sb[4] = {b01.y, b01.w, b23.y, b23.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float cs = ca[e] * cb[e] - sa[e] * sb[e];
+            const float sn = sa[e] * cb[e] + ca[e] * sb[e];
+            const float x1 = acc[nt][rg * 4 + e], x2 = acc[nt + 2][rg * 4 + e];
+            acc[nt][rg * 4 + e] = x1 * cs - x2 * sn;
+            acc[nt + 2][rg * 4 + e] = x2 * cs + x1 * sn;
           }
-      }
-      if (a.flags & CCA_QK_NORM) {
-        float ssq = 0.f;
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) ssq = fmaf(acc[tt][nt][r], acc[tt][nt][r], ssq);
-        ssq += __shfl_xor(ssq, 32);
-        const float mul = sqrtf((float)DH) / sqrtf(ssq) * beta;
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[tt][nt][r] *= mul;
-      }
-      if (a.flags & CCA_ROPE) {
-        const int thi = tpos[tt] >> 7, tlo = tpos[tt] & 127;
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg) {
-            const int i0 = nt * 32 + rg * 8 + half * 4;  // 4 consecutive pair indices
-            const f32x4 *pa = reinterpret_cast<const f32x4 *>(ropeA + thi * (DH / 2) + i0);
-            const f32x4 *pb = reinterpret_cast<const f32x4 *>(ropeB + ((i0 >> 2) * 128 + tlo) * 4);
-            const f32x4 a01 = pa[0], a23 = pa[1], b01 = pb[0], b23 = pb[1];
-            const float ca[4] = {a01.x, a01.z, a23.x, a23.z}, sa[4] = {a01.y, a01.w, a23.y, a23.w};
-            const float cb[4] = {b01.x, b01.z, b23.x, b23.z}, sb[4] = {b01.y, b01.w, b23.y, b23.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float cs = ca[e] * cb[e] - sa[e] * sb[e];
-              const float sn = sa[e] * cb[e] + ca[e] * sb[e];
-              const float x1 = acc[tt][nt][rg * 4 + e], x2 = acc[tt][nt + 2][rg * 4 + e];
-              acc[tt][nt][rg * 4 + e] = x1 * cs - x2 * sn;
-              acc[tt][nt + 2][rg * 4 + e] = x2 * cs + x1 * sn;
-            }
-          }
-      }
-      // ---- stage the 32 x 128 tile of this wavefront and write whole rows
+        }
+    }
+    // ---- round once to bf16 and store: 4 consecutive channels (8 bytes) per lane and store, the two
+    //      half-waves side by side; the 16 stores of a wavefront fill whole 256-byte rows in L2
+    if (row < a.rows) {
+      bf16_t *orow = dst + row * dst_stride;
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
           u32x2 w;
-          w.x = pack2(acc[tt][nt][rg * 4 + 0], acc[tt][nt][rg * 4 + 1]);
-          w.y = pack2(acc[tt][nt][rg * 4 + 2], acc[tt][nt][rg * 4 + 3]);
-          *reinterpret_cast<u32x2 *>(sOut + l32 * OUT_ROW + (nt * 32 + rg * 8 + half * 4) * 2) = w;
+          w.x = pack2(acc[nt][rg * 4 + 0], acc[nt][rg * 4 + 1]);
+          w.y = pack2(acc[nt][rg * 4 + 2], acc[nt][rg * 4 + 3]);
+          *reinterpret_cast<u32x2 *>(orow + nt * 32 + rg * 8 + half * 4) = w;
         }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-#pragma unroll
-      for (int cidx = 0; cidx < 8; ++cidx) {
-        const int id = lane + cidx * 64, r = id >> 4, ch = id & 15;
-        const long long row = wrow0 + tt * 32 + r;
-        const u32x4 val = *reinterpret_cast<const u32x4 *>(sOut + r * OUT_ROW + ch * 16);
-        if (row < a.rows) *reinterpret_cast<u32x4 *>(dst + row * dst_stride + ch * 8) = val;
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
   }
 }
@@ -330,7 +332,7 @@ __global__ __launch_bounds__(256) void split_copy_kernel(const unsigned char *__
 template <int D>
 hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, const float2 *ropeA, const float2 *ropeB,
                        const float *temp, void *q, void *k, void *v, int grid, hipStream_t s) {
-  constexpr size_t smem = (size_t)DH * D * 16 * 16 + 4 * 32 * OUT_ROW;
+  constexpr size_t smem = (size_t)DH * D * 16 * 16;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<D>),
@@ -397,7 +399,7 @@ hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *
   const long long tok_blocks = (d.rows() + TOK_PER_WG - 1) / TOK_PER_WG;
   a.n_conv_blocks = (int)(tok_blocks * NH);
   const long long v_chunks = d.rows() * (d.e_kv / 8);
-  const int v_blocks = (int)((v_chunks + NT * 8 - 1) / (NT * 8));
+  const int v_blocks = (int)((v_chunks + NT * 4 - 1) / (NT * 4));
   const int grid = a.n_conv_blocks + v_blocks;
   switch (D) {
     case 1: return launch_main<1>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
