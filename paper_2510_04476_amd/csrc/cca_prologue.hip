@@ -38,13 +38,14 @@ namespace {
 
 constexpr int DH = 128;
 constexpr int NT = 512;
-constexpr int TOK_PER_WG = 512;
+constexpr int MAX_TILES_PER_WAVE = 3;  // a workgroup takes 256 * tiles_per_wave tokens, tiles dealt round-robin
 
 struct FusedArgs {
   int T, Hq, Hk, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch;
   long long rows;
   uint32_t flags;
   int n_conv_blocks;
+  int tiles_per_wave;
   float rope_base;
 };
 
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D,
 }
 
 // ---------------------------------------------------------------------------
-// main kernel: one workgroup = one head x 512 tokens, 8 wavefronts x (2 x 32 tokens)
+// main kernel: one workgroup = one head x (256 * tiles_per_wave) tokens, 8 wavefronts x 32-token tiles
 // ---------------------------------------------------------------------------
 template <int D>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_fused_kernel(
@@ -139,7 +140,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 
   const int NH = a.Hq + a.Hk;
   const int head = blockIdx.x % NH;
-  const long long row_begin = (long long)(blockIdx.x / NH) * TOK_PER_WG;
+  const long long row_begin = (long long)(blockIdx.x / NH) * (256 * a.tiles_per_wave);
   const bool is_q = head < a.Hq;
   const int g = is_q ? head / a.R : head - a.Hq;
   const int ch0 = is_q ? head * DH : a.e_q + g * DH;
@@ -180,8 +181,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
   }
 
-  for (int tt = 0; tt < TOK_PER_WG / (8 * 32); ++tt) {
-    const long long trow0 = row_begin + wave * 64 + tt * 32;
+  for (int tt = 0; tt < a.tiles_per_wave; ++tt) {
+    const long long trow0 = row_begin + (tt * 8 + wave) * 32;
     if (trow0 >= a.rows) break;  // wave-uniform; nothing below synchronises across wavefronts
     const long long row = trow0 + l32;
     const long long rowc = row < a.rows ? row : a.rows - 1;
@@ -380,7 +381,7 @@ hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *
                                void *scratch, hipStream_t s) {
   const int D = taps(d);
   const int NH = d.Hq + d.Hk;
-  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, d.rope_base};
+  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1, d.rope_base};
   const int n_thi = (d.T + 127) / 128;
   const size_t wc_bytes = ((size_t)NH * DH * D * DH * 2 + 255) / 256 * 256;
   const size_t ra_bytes = ((size_t)n_thi * (DH / 2) * 8 + 255) / 256 * 256;
@@ -396,7 +397,18 @@ hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
-  const long long tok_blocks = (d.rows() + TOK_PER_WG - 1) / TOK_PER_WG;
+  // Tokens per workgroup: each workgroup first loads its head's filter (about one tile's worth of time), and
+  // one workgroup fits per CU, so minimise rounds-on-256-CUs x (1 + tiles per wavefront).
+  long long best_cost = -1, tok_blocks = 0;
+  for (int tpw = 1; tpw <= MAX_TILES_PER_WAVE; ++tpw) {
+    const long long blocks = (d.rows() + 256 * tpw - 1) / (256 * tpw);
+    const long long cost = ((blocks * NH + 255) / 256) * (1 + tpw);
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      a.tiles_per_wave = tpw;
+      tok_blocks = blocks;
+    }
+  }
   a.n_conv_blocks = (int)(tok_blocks * NH);
   const long long v_chunks = d.rows() * (d.e_kv / 8);
   const int v_blocks = (int)((v_chunks + NT * 4 - 1) / (NT * 4));
