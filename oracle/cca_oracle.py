@@ -39,7 +39,7 @@ import numpy as np
 
 __all__ = [
     "down_project", "conv_seq", "conv_ch", "qk_mean", "value_shift",
-    "qk_norm_temp", "rope", "attention", "up_project", "cca_forward",
+    "qk_norm_temp", "rope", "attention", "up_project", "cca_forward", "cca_backward",
 ]
 
 
@@ -249,3 +249,218 @@ def cca_forward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, *,
     o, lse = attention(q, k, v, scale, causal=causal, rows=rows)
     out = up_project(o, w_out)
     return dict(out=out, q0=q0, k0=k0, vc=vc, vp=vp, q=q, k=k, v=v, o=o, lse=lse)
+
+
+# ===========================================================================
+# Backward (adjoint) of steps 9 -> 1.  The paper gives no backward equations;
+# each function below is the hand-derived transpose of the forward step of the
+# same name, in fp64.  Pinned by central finite differences of cca_forward and
+# by the <dOut, J d> = <J^T dOut, d> identity (tests/test_oracle_backward.py).
+# ===========================================================================
+def _unshift_time(a, s):
+    """Adjoint of _shift_time: out[:, t] = a[:, t + s], zeros entering at the end."""
+    if s == 0:
+        return a
+    out = np.zeros_like(a)
+    if s < a.shape[1]:
+        out[:, : a.shape[1] - s] = a[:, s:]
+    return out
+
+
+def conv_seq_bwd(dy, u, w0):
+    """y[t,c] = sum_j w0[c,j] u[t-(k-1-j), c]  ->  du, dw0."""
+    dy, u, w0 = _f64(dy), _f64(u), _f64(w0)
+    k = w0.shape[1]
+    du = np.zeros_like(u)
+    dw0 = np.zeros_like(w0)
+    for j in range(k):
+        s = k - 1 - j
+        du += w0[:, j] * _unshift_time(dy, s)
+        dw0[:, j] = (dy * _shift_time(u, s)).sum(axis=(0, 1))
+    return du, dw0
+
+
+def conv_ch_bwd(dy, u, w1):
+    """y[t,h,o] = sum_j sum_i w1[h,o,i,j] u[t-(k-1-j), h, i]  ->  du, dw1."""
+    dy, u, w1 = _f64(dy), _f64(u), _f64(w1)
+    H, d_out, d_in, k = w1.shape
+    du = np.zeros_like(u)
+    dw1 = np.zeros_like(w1)
+    for j in range(k):
+        s = k - 1 - j
+        dys = _unshift_time(dy, s)         # dy[t + s]
+        us = _shift_time(u, s)             # u[t - s]
+        for h in range(H):
+            du[:, :, h, :] += dys[:, :, h, :] @ w1[h, :, :, j]
+            dw1[h, :, :, j] = np.einsum("bto,bti->oi", dy[:, :, h, :], us[:, :, h, :])
+    return du, dw1
+
+
+def qk_mean_bwd(dq3, dk3):
+    """q3 = q2 + m_q, k3 = k2 + m_k with m_q = (q0 + rep(k0))/2, m_k = mean_r m_q.
+    Returns (dq2, dk2, dq0_part, dk0_part)."""
+    Hq, Hk = dq3.shape[2], dk3.shape[2]
+    R = Hq // Hk
+    dm_q = dq3 + np.repeat(dk3, R, axis=2) / R
+    dq0 = 0.5 * dm_q
+    dk0 = 0.5 * dm_q.reshape(dm_q.shape[0], dm_q.shape[1], Hk, R, -1).sum(axis=3)
+    return dq3, dk3, dq0, dk0
+
+
+def value_shift_bwd(dv, shift=True):
+    """v = [vc | shift(vp)]  ->  dvc, dvp."""
+    B, T = dv.shape[:2]
+    dv = dv.reshape(B, T, -1)
+    half = dv.shape[-1] // 2
+    dvc, dvp = dv[..., :half], dv[..., half:]
+    if shift:
+        dvp = _unshift_time(dvp, 1)
+    return dvc, dvp
+
+
+def qk_norm_temp_bwd(dq4, dk4, q3, k3, temp=None):
+    """y = x sqrt(d) / |x| (* exp(temp_g) for keys)  ->  dx (and dtemp)."""
+    d = q3.shape[-1]
+
+    def one(dy, x, mul):
+        n = np.sqrt((x * x).sum(-1, keepdims=True))
+        xh = x / n
+        return mul * np.sqrt(d) / n * (dy - xh * (xh * dy).sum(-1, keepdims=True))
+
+    dq3 = one(dq4, q3, 1.0)
+    if temp is None:
+        return dq3, one(dk4, k3, 1.0), None
+    beta = np.exp(_f64(temp))[None, None, :, None]
+    dk3 = one(dk4, k3, beta)
+    k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True)) * beta
+    dtemp = (dk4 * k4).sum(axis=(0, 1, 3))
+    return dq3, dk3, dtemp
+
+
+def rope_bwd(dy, base=10000.0, interleaved=False):
+    """RoPE is a rotation: its adjoint rotates by the opposite angle."""
+    dy = _f64(dy)
+    B, T, H, d = dy.shape
+    half = d // 2
+    theta = base ** (-2.0 * np.arange(half, dtype=np.float64) / d)
+    ang = np.arange(T, dtype=np.float64)[:, None] * theta[None, :]
+    c, s = np.cos(ang)[None, :, None, :], np.sin(ang)[None, :, None, :]
+    out = np.empty_like(dy)
+    if interleaved:
+        a, b = dy[..., 0::2], dy[..., 1::2]
+        out[..., 0::2] = a * c + b * s
+        out[..., 1::2] = b * c - a * s
+    else:
+        a, b = dy[..., :half], dy[..., half:]
+        out[..., :half] = a * c + b * s
+        out[..., half:] = b * c - a * s
+    return out
+
+
+def attention_bwd(do, q, k, v, scale, causal=True):
+    """Adjoint of attention(): with P = softmax(scale q k^T) row-wise,
+    dV = P^T dO, dP = dO V^T, dS = P * (dP - rowsum(dP * P)),
+    dQ = scale dS K, dK = scale dS^T Q; dK, dV summed over the query heads of a group."""
+    do, q, k, v = _f64(do), _f64(q), _f64(k), _f64(v)
+    B, T, Hq, d = q.shape
+    Hk = k.shape[2]
+    R = Hq // Hk
+    do = do.reshape(B, T, Hq, -1)
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    chunk = 256
+    for b in range(B):
+        for h in range(Hq):
+            g = h // R
+            for c0 in range(0, T, chunk):
+                r = np.arange(c0, min(T, c0 + chunk))
+                s_max = int(r.max()) + 1 if causal else T
+                s = scale * (q[b, r, h, :] @ k[b, :s_max, g, :].T)
+                if causal:
+                    s = np.where(np.arange(s_max)[None, :] <= r[:, None], s, -np.inf)
+                p = np.exp(s - s.max(axis=1, keepdims=True))
+                p /= p.sum(axis=1, keepdims=True)
+                dp = do[b, r, h, :] @ v[b, :s_max, g, :].T
+                ds = p * (dp - (dp * p).sum(axis=1, keepdims=True))
+                dv[b, :s_max, g, :] += p.T @ do[b, r, h, :]
+                dq[b, r, h, :] = scale * (ds @ k[b, :s_max, g, :])
+                dk[b, :s_max, g, :] += scale * (ds.T @ q[b, r, h, :])
+    return dq, dk, dv
+
+
+def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
+                 n_q_heads, n_kv_heads, head_dim,
+                 causal=True, use_conv_seq=True, use_conv_ch=True,
+                 use_qk_mean=True, use_v_shift=True, use_qk_norm=True,
+                 use_key_temp=True, use_rope=True, rope_interleaved=False,
+                 rope_base=10000.0, softmax_scale=None):
+    """Gradients of sum(out * d_out) with respect to x and every weight.
+    Recomputes the forward intermediates it needs.  Returns a dict:
+    d_x, d_w_down, d_w_conv_seq, d_w_conv_ch, d_temp, d_w_out plus the
+    intermediate gradients d_o, d_q, d_k, d_v (as they leave attention) and d_lat."""
+    Hq, Hk, dh = n_q_heads, n_kv_heads, head_dim
+    e_q, e_kv = Hq * dh, Hk * dh
+    x, d_out = _f64(x), _f64(d_out)
+    B, T, _ = x.shape
+    w_down, w_out = _f64(w_down), _f64(w_out)
+    # ---- forward, keeping what the adjoint needs
+    q0, k0, vc, vp = down_project(x, w_down, Hq, Hk, dh)
+    q1, k1 = q0, k0
+    if use_conv_seq:
+        w0 = _f64(w_conv_seq)
+        q1 = conv_seq(q0.reshape(B, T, -1), w0[:e_q]).reshape(q0.shape)
+        k1 = conv_seq(k0.reshape(B, T, -1), w0[e_q:]).reshape(k0.shape)
+    q2, k2 = q1, k1
+    if use_conv_ch:
+        w1 = _f64(w_conv_ch)
+        q2, k2 = conv_ch(q1, w1[:Hq]), conv_ch(k1, w1[Hq:])
+    q3, k3 = qk_mean(q2, k2, q0, k0) if use_qk_mean else (q2, k2)
+    v = value_shift(vc, vp, Hk, dh, shift=use_v_shift)
+    q4, k4 = qk_norm_temp(q3, k3, temp if use_key_temp else None) if use_qk_norm else (q3, k3)
+    q5, k5 = (rope(q4, rope_base, rope_interleaved), rope(k4, rope_base, rope_interleaved)) if use_rope else (q4, k4)
+    scale = 1.0 / np.sqrt(dh) if not softmax_scale else float(softmax_scale)
+    o, _ = attention(q5, k5, v, scale, causal=causal)
+    # ---- adjoint, last step first
+    o_flat = o.reshape(B, T, -1)
+    d_w_out = np.einsum("bte,btf->ef", o_flat, d_out)
+    d_o = d_out @ w_out.T
+    d_q5, d_k5, d_v = attention_bwd(d_o, q5, k5, v, scale, causal=causal)
+    d_q4, d_k4 = (rope_bwd(d_q5, rope_base, rope_interleaved), rope_bwd(d_k5, rope_base, rope_interleaved)) \
+        if use_rope else (d_q5, d_k5)
+    d_temp = np.zeros(Hk)
+    if use_qk_norm:
+        d_q3, d_k3, dt = qk_norm_temp_bwd(d_q4, d_k4, q3, k3, temp if use_key_temp else None)
+        if dt is not None:
+            d_temp = dt
+    else:
+        d_q3, d_k3 = d_q4, d_k4
+    d_q0 = np.zeros_like(q0)
+    d_k0 = np.zeros_like(k0)
+    if use_qk_mean:
+        d_q2, d_k2, dq0m, dk0m = qk_mean_bwd(d_q3, d_k3)
+        d_q0 += dq0m
+        d_k0 += dk0m
+    else:
+        d_q2, d_k2 = d_q3, d_k3
+    d_w1 = np.zeros_like(_f64(w_conv_ch)) if w_conv_ch is not None else None
+    if use_conv_ch:
+        d_q1, dw1q = conv_ch_bwd(d_q2, q1, w1[:Hq])
+        d_k1, dw1k = conv_ch_bwd(d_k2, k1, w1[Hq:])
+        d_w1 = np.concatenate([dw1q, dw1k], axis=0)
+    else:
+        d_q1, d_k1 = d_q2, d_k2
+    d_w0 = np.zeros_like(_f64(w_conv_seq)) if w_conv_seq is not None else None
+    if use_conv_seq:
+        dq, dw0q = conv_seq_bwd(d_q1.reshape(B, T, -1), q0.reshape(B, T, -1), w0[:e_q])
+        dk, dw0k = conv_seq_bwd(d_k1.reshape(B, T, -1), k0.reshape(B, T, -1), w0[e_q:])
+        d_q0 += dq.reshape(q0.shape)
+        d_k0 += dk.reshape(k0.shape)
+        d_w0 = np.concatenate([dw0q, dw0k], axis=0)
+    else:
+        d_q0 += d_q1
+        d_k0 += d_k1
+    d_vc, d_vp = value_shift_bwd(d_v, shift=use_v_shift)
+    d_lat = np.concatenate([d_q0.reshape(B, T, -1), d_k0.reshape(B, T, -1), d_vc, d_vp], axis=-1)
+    d_x = d_lat @ w_down.T
+    d_w_down = np.einsum("bte,btf->ef", x, d_lat)
+    return dict(d_x=d_x, d_w_down=d_w_down, d_w_conv_seq=d_w0, d_w_conv_ch=d_w1, d_temp=d_temp, d_w_out=d_w_out,
+                d_o=d_o, d_q=d_q5, d_k=d_k5, d_v=d_v, d_lat=d_lat)
