@@ -143,6 +143,16 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
 cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o,
                          float *lse, const float *temp, void *hip_stream);
 
+/* Backward of cca_attention (the paper gives no backward equations; this is
+ * the adjoint of the attention line of the final eq. block): from q, k, v, o,
+ * lse of the forward pass and d_o (B,T,H_q*d_h) computes d_q (B,T,H_q,d_h),
+ * d_k, d_v (B,T,H_k,d_h), overwritten; d_k, d_v are summed over the query
+ * heads sharing a KV head.  Probabilities are recomputed from lse.  bf16 and
+ * d_h = 128 only (else CCA_ERR_UNSUPPORTED).  workspace: B*H_q*T*4 bytes. */
+cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v,
+                                  const void *o, const float *lse, const void *d_o, void *d_q, void *d_k,
+                                  void *d_v, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* out (B*T, E) = o (B*T, e_q) * w_out (e_q, E).  Last line of the final eq. block. */
 cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_out, void *out,
                           void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -28,7 +28,7 @@ CCA_FLAGS_PAPER = (CCA_CAUSAL | CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_V
 CCA_FLAGS_MHA = CCA_CAUSAL
 
 EXPORTS = ("cca_workspace_size", "cca_forward", "cca_down_project", "cca_prologue", "cca_attention",
-           "cca_up_project", "cca_strerror", "cca_version")
+           "cca_attention_backward", "cca_up_project", "cca_strerror", "cca_version")
 
 
 class cca_config(C.Structure):
@@ -73,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, sz, vp]
     lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
+    lib.cca_attention_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
     lib.cca_strerror.argtypes = [C.c_int]
@@ -256,3 +257,17 @@ def cca_attention(cfg: CCAConfig, q, k, v, o=None, lse=None, want_lse=False, tem
     _check(lib.cca_attention(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(temp), _stream()),
            "cca_attention")
     return (o, lse) if want_lse else o
+
+
+def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=None, d_v=None, workspace=None):
+    lib = load_library()
+    d_q = torch.empty_like(q) if d_q is None else d_q
+    d_k = torch.empty_like(k) if d_k is None else d_k
+    d_v = torch.empty_like(v) if d_v is None else d_v
+    if workspace is None:
+        workspace = torch.empty(cfg.B * cfg.n_q_heads * cfg.T * 4, dtype=torch.uint8, device=q.device)
+    cc = cfg.c()
+    _check(lib.cca_attention_backward(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(d_q),
+                                      _ptr(d_k), _ptr(d_v), _ptr(workspace), workspace.numel(), _stream()),
+           "cca_attention_backward")
+    return d_q, d_k, d_v

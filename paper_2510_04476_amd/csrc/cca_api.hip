@@ -181,6 +181,23 @@ cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, co
   return run_attention(d, q, k, v, o, lse, temp, (hipStream_t)hip_stream);
 }
 
+cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v, const void *o,
+                                  const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!q || !k || !v || !o || !lse || !d_o || !d_q || !d_k || !d_v) return CCA_ERR_NULL;
+  if (!attention_bwd_supported(d)) return CCA_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(d_q) ||
+      !aligned16(d_k) || !aligned16(d_v) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+    return CCA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < attention_bwd_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
+  hipError_t e = attention_bwd_bf16(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, static_cast<float *>(workspace),
+                                    (hipStream_t)hip_stream);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
 cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *x, void *out, const cca_saved *saved,
                        void *workspace, size_t workspace_bytes, void *hip_stream) {
   Dims d;

@@ -1,0 +1,431 @@
+// Backward of the latent softmax attention on the gfx950 matrix cores (flash
+// style: probabilities are recomputed from the saved log-sum-exp, nothing of
+// size T x T is stored).  The paper gives no backward equations; with
+// P = softmax(scale * Q K^T) per row and Delta_t = <dO_t, O_t>:
+//     dV = P^T dO,  dP = dO V^T,  dS = P * (dP - Delta),  dQ = scale * dS K,  dK = scale * dS^T Q,
+// dK and dV summed over the query heads that share a KV head (CCGQA paragraph).
+//
+// Three kernels, no atomics, deterministic:
+//   delta_kernel      Delta (B,H_q,T) fp32.
+//   attn_bwd_dq       one workgroup = 256 query rows of one head (8 wavefronts x 32 rows), loops over key
+//                     tiles like the forward kernel; S^T and dP^T come out with one query row per lane, dS^T
+//                     packed to bf16 is the second MFMA operand of dQ^T += K^T dS^T, K^T fetched with the
+//                     transposing LDS read.
+//   attn_bwd_dkdv     one workgroup = 128 keys of one KV head (4 wavefronts x 32 keys), loops over the query
+//                     heads of the group and their query tiles; S and dP come out with one key per lane, P and
+//                     dS packed to bf16 are the second operands of dV^T += dO^T P and dK^T += Q^T dS, with
+//                     dO^T and Q^T fetched by transposing LDS reads.
+// S is recomputed in both kernels (7 contractions instead of 5) in exchange for having no atomics.
+#include <type_traits>
+
+#include "cca_internal.h"
+
+namespace cca {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef short v8i16 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+
+namespace {
+
+constexpr int DH = 128;
+constexpr int KK = DH / 16, DT = DH / 32, KCH = DH / 8;
+constexpr int ROW = DH * 2 + 16;  // padded LDS row of one token: conflict-free 16-byte reads down a column of rows
+constexpr float LOG2E = 1.44269504088896340736f;
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// MFMA first-operand fragment of the TRANSPOSE of a row-major LDS tile: lane (c = l32, half) receives
+// tile[r0 + 4*half + {0..3}][c0 + c] and tile[r0 + 8 + 4*half + {0..3}][c0 + c].  `base` already holds the
+// per-lane part  (4*half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2.
+__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int c0) {
+  const unsigned char *a = base + r0 * ROW + c0 * 2;
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)a);
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + 8 * ROW));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+// ---------------------------------------------------------------------------
+// Delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d]; one wavefront per 4 (t,h) rows (16 lanes x 16 bytes each)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ dO, const bf16_t *__restrict__ O,
+                                                   float *__restrict__ delta, long long n_rows, int T, int Hq) {
+  const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);  // row = (b*T + t)*Hq + h
+  const int sub = threadIdx.x & 15;
+  float acc = 0.f;
+  if (row < n_rows) {
+    const u32x4 a = *reinterpret_cast<const u32x4 *>(dO + row * DH + sub * 8);
+    const u32x4 b = *reinterpret_cast<const u32x4 *>(O + row * DH + sub * 8);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc += bf_lo(a[i]) * bf_lo(b[i]) + bf_hi(a[i]) * bf_hi(b[i]);
+  }
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if (sub == 0 && row < n_rows) {
+    const long long bt = row / Hq;
+    const int h = (int)(row % Hq);
+    const long long b = bt / T;
+    const int t = (int)(bt % T);
+    delta[(b * Hq + h) * T + t] = acc;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// dQ
+// ---------------------------------------------------------------------------
+constexpr int DQ_BQ = 256, DQ_NT = 512, BKV = 64;
+
+template <bool CAUSAL>
+__global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+    const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
+    bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, float scale) {
+  constexpr int TILE = BKV * ROW;
+  constexpr int PER_THREAD = BKV * KCH / DQ_NT;  // 16-byte chunks of K (and of V) per thread per tile
+  constexpr int ROWS_PER_PASS = DQ_NT / KCH;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];  // K0 K1 V0 V1
+  unsigned char *const sK = smem, *const sV = smem + 2 * TILE;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int idx = blockIdx.x;
+  const int bh = idx % BH, qb = nqb - 1 - idx / BH;  // heavy (late) query blocks first
+  const int b = bh / Hq, h = bh % Hq, g = h / (Hq / Hk);
+  const int q0 = qb * DQ_BQ, qw0 = q0 + wave * 32;
+  const float c = scale * LOG2E;
+  const int row_bytes = Hk * DH * 2;
+  const unsigned char *const Kg = reinterpret_cast<const unsigned char *>(K + ((long long)b * T * Hk + g) * DH);
+  const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
+
+  const int s_r0 = tid / KCH, s_ch = tid % KCH;
+  const uint32_t s_off = (uint32_t)s_r0 * ROW + s_ch * 16;
+  const uint32_t rd_off = (uint32_t)l32 * ROW + half * 16;
+  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+
+  u32x4 rk[PER_THREAD], rv[PER_THREAD];
+  auto load_tile = [&](int kv0) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int s = min(kv0 + s_r0 + i * ROWS_PER_PASS, T - 1);  // clamped keys are masked below
+      rk[i] = *reinterpret_cast<const u32x4 *>(Kg + (long long)s * row_bytes + s_ch * 16);
+      rv[i] = *reinterpret_cast<const u32x4 *>(Vg + (long long)s * row_bytes + s_ch * 16);
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      *reinterpret_cast<u32x4 *>(sK + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rk[i];
+      *reinterpret_cast<u32x4 *>(sV + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rv[i];
+    }
+  };
+
+  const bool wave_live = qw0 < T;
+  const int wave_last = min(qw0 + 31, T - 1);
+  const int trow = min(qw0 + l32, T - 1);
+  bf16x8 qf[KK], dof[KK];
+  {
+    const bf16_t *pq = Q + (((long long)b * T + trow) * Hq + h) * DH + half * 8;
+    const bf16_t *pd = dO + (((long long)b * T + trow) * Hq + h) * DH + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pq + kk * 16));
+      dof[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pd + kk * 16));
+    }
+  }
+  const float lse2 = LSE[((long long)b * Hq + h) * T + trow] * LOG2E;  // exp(s*scale - lse) = exp2(s*c - lse2)
+  const float delta = DELTA[((long long)b * Hq + h) * T + trow];
+
+  f32x16 acc[DT];  // dQ^T: lane = query row, registers = channels
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+
+  const int kv_end = CAUSAL ? min(q0 + DQ_BQ, T) : T;
+  const int ntiles = (kv_end + BKV - 1) / BKV;
+  load_tile(0);
+  store_tile(0);
+  if (ntiles > 1) load_tile(BKV);
+  __syncthreads();
+  for (int j = 0; j < ntiles; ++j) {
+    const int kv0 = j * BKV, buf = j & 1;
+    if (j + 1 < ntiles) store_tile(buf ^ 1);
+    if (j + 2 < ntiles) load_tile(kv0 + 2 * BKV);
+    if (wave_live && !(CAUSAL && kv0 > wave_last)) {
+      const unsigned char *kp = sK + buf * TILE, *vp = sV + buf * TILE;
+      const bool need_mask = (CAUSAL && kv0 + BKV - 1 > qw0) || (kv0 + BKV > T);
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {  // 32 keys at a time
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 kf = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const u32x4 *>(kp + rd_off + ks * 32 * ROW + kk * 32));
+          const bf16x8 vf = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const u32x4 *>(vp + rd_off + ks * 32 * ROW + kk * 32));
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
+        }
+        // lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of query row qw0 + l32
+        float ds[16];
+        const int lim = (CAUSAL ? min(qw0 + l32, T - 1) : T - 1) - kv0 - ks * 32 - 4 * half;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -lse2));
+          if (need_mask && (8 * (r >> 2) + (r & 3) > lim)) p = 0.f;
+          ds[r] = p * (dp[r] - delta);
+        }
+        bf16x8 dsf[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          u32x4 w;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) w[e] = pack2(ds[8 * jj + 2 * e], ds[8 * jj + 2 * e + 1]);
+          dsf[jj] = __builtin_bit_cast(bf16x8, w);
+        }
+        // dQ^T += K^T dS^T
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(kp + tr_off, ks * 32 + jj * 16, dt * 32), dsf[jj],
+                                                              acc[dt], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  if (wave_live && qw0 + l32 < T) {
+    bf16_t *row = dQ + (((long long)b * T + qw0 + l32) * Hq + h) * DH;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        u32x2 w;
+        w.x = pack2(acc[dt][rg * 4 + 0] * scale, acc[dt][rg * 4 + 1] * scale);
+        w.y = pack2(acc[dt][rg * 4 + 2] * scale, acc[dt][rg * 4 + 3] * scale);
+        *reinterpret_cast<u32x2 *>(row + dt * 32 + rg * 8 + half * 4) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// dK, dV
+// ---------------------------------------------------------------------------
+constexpr int KV_BK = 128, KV_NT = 256, BQT = 64;  // keys per workgroup, threads, query rows per LDS tile
+
+template <bool CAUSAL>
+__global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+    const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
+    bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, int T, int Hq, int Hk, int BG, int nkb, float scale) {
+  constexpr int TILE = BQT * ROW;
+  constexpr int PER_THREAD = BQT * KCH / KV_NT;
+  constexpr int ROWS_PER_PASS = KV_NT / KCH;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];  // Q0 Q1 dO0 dO1
+  __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];                                      // [buf][lse2 | delta][row]
+  unsigned char *const sQ = smem, *const sD = smem + 2 * TILE;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int idx = blockIdx.x;
+  const int bg = idx % BG, kb = idx / BG;  // early key blocks (most query tiles when causal) first
+  const int b = bg / Hk, g = bg % Hk, R = Hq / Hk;
+  const int k0 = kb * KV_BK, kw0 = k0 + wave * 32;
+  const float c = scale * LOG2E;
+  const int qrow_bytes = Hq * DH * 2;
+
+  const int s_r0 = tid / KCH, s_ch = tid % KCH;
+  const uint32_t s_off = (uint32_t)s_r0 * ROW + s_ch * 16;
+  const uint32_t rd_off = (uint32_t)l32 * ROW + half * 16;
+  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+
+  // this wavefront's 32 keys: K and V rows as second MFMA operands, resident in registers
+  bf16x8 kf[KK], vf[KK];
+  {
+    const int s = min(kw0 + l32, T - 1);
+    const bf16_t *pk = K + (((long long)b * T + s) * Hk + g) * DH + half * 8;
+    const bf16_t *pv = V + (((long long)b * T + s) * Hk + g) * DH + half * 8;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pk + kk * 16));
+      vf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pv + kk * 16));
+    }
+  }
+  f32x16 dk[DT], dv[DT];  // dK^T, dV^T: lane = key, registers = channels
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dk[dt][r] = 0.f, dv[dt][r] = 0.f;
+
+  // query tiles that see keys of this block
+  const int qt_first = CAUSAL ? k0 / BQT : 0;
+  const int nqt = (T + BQT - 1) / BQT;
+  const int per_head = nqt - qt_first;
+  const int steps = per_head * R;
+
+  u32x4 rq[PER_THREAD], rd[PER_THREAD];
+  float rstat = 0.f;
+  auto load_tile = [&](int step) {
+    const int h = g * R + step / per_head, t0 = (qt_first + step % per_head) * BQT;
+    const unsigned char *Qg = reinterpret_cast<const unsigned char *>(Q + ((long long)b * T * Hq + h) * DH);
+    const unsigned char *Dg = reinterpret_cast<const unsigned char *>(dO + ((long long)b * T * Hq + h) * DH);
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      const int t = min(t0 + s_r0 + i * ROWS_PER_PASS, T - 1);  // clamped rows get probability 0 below
+      rq[i] = *reinterpret_cast<const u32x4 *>(Qg + (long long)t * qrow_bytes + s_ch * 16);
+      rd[i] = *reinterpret_cast<const u32x4 *>(Dg + (long long)t * qrow_bytes + s_ch * 16);
+    }
+    if (tid < 2 * BQT) {
+      const int t = min(t0 + (tid & (BQT - 1)), T - 1);
+      const long long o = ((long long)b * Hq + h) * T + t;
+      rstat = tid < BQT ? LSE[o] * LOG2E : DELTA[o];
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < PER_THREAD; ++i) {
+      *reinterpret_cast<u32x4 *>(sQ + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rq[i];
+      *reinterpret_cast<u32x4 *>(sD + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rd[i];
+    }
+    if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = rstat;
+  };
+
+  const bool wave_live = kw0 < T;
+  if (steps > 0) {
+    load_tile(0);
+    store_tile(0);
+    if (steps > 1) load_tile(1);
+    __syncthreads();
+  }
+  for (int step = 0; step < steps; ++step) {
+    const int buf = step & 1;
+    const int t0 = (qt_first + step % per_head) * BQT;
+    if (step + 1 < steps) store_tile(buf ^ 1);
+    if (step + 2 < steps) load_tile(step + 2);
+    if (wave_live && !(CAUSAL && t0 + BQT - 1 < kw0)) {
+      const unsigned char *qp = sQ + buf * TILE, *dp_ = sD + buf * TILE;
+      const bool need_mask = (CAUSAL && t0 < kw0 + 31) || (t0 + BQT > T) || (kw0 + 32 > T);
+#pragma unroll
+      for (int qs = 0; qs < 2; ++qs) {  // 32 query rows at a time
+        f32x16 s, dp;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const bf16x8 qa = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const u32x4 *>(qp + rd_off + qs * 32 * ROW + kk * 32));
+          const bf16x8 da = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + rd_off + qs * 32 * ROW + kk * 32));
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);    // S[t, key]
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);  // dP[t, key]
+        }
+        // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4
+        float pr[16], ds[16];
+        const int key = kw0 + l32;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
+          const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = rg * 4 + e;
+            const int t = t0 + qs * 32 + rg * 8 + half * 4 + e;
+            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -l4[e]));
+            if (need_mask && ((CAUSAL && key > t) || t >= T || key >= T)) p = 0.f;
+            pr[r] = p;
+            ds[r] = p * (dp[r] - d4[e]);
+          }
+        }
+        bf16x8 pf[2], dsf[2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+          u32x4 w, x;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            w[e] = pack2(pr[8 * jj + 2 * e], pr[8 * jj + 2 * e + 1]);
+            x[e] = pack2(ds[8 * jj + 2 * e], ds[8 * jj + 2 * e + 1]);
+          }
+          pf[jj] = __builtin_bit_cast(bf16x8, w);
+          dsf[jj] = __builtin_bit_cast(bf16x8, x);
+        }
+        // dV^T += dO^T P,  dK^T += Q^T dS
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dp_ + tr_off, qs * 32 + jj * 16, dt * 32), pf[jj],
+                                                             dv[dt], 0, 0, 0);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qp + tr_off, qs * 32 + jj * 16, dt * 32), dsf[jj],
+                                                             dk[dt], 0, 0, 0);
+          }
+      }
+    }
+    __syncthreads();
+  }
+  if (wave_live && kw0 + l32 < T) {
+    bf16_t *rk_ = dK + (((long long)b * T + kw0 + l32) * Hk + g) * DH;
+    bf16_t *rv_ = dV + (((long long)b * T + kw0 + l32) * Hk + g) * DH;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        u32x2 w, x;
+        w.x = pack2(dk[dt][rg * 4 + 0] * scale, dk[dt][rg * 4 + 1] * scale);
+        w.y = pack2(dk[dt][rg * 4 + 2] * scale, dk[dt][rg * 4 + 3] * scale);
+        x.x = pack2(dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1]);
+        x.y = pack2(dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]);
+        *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+        *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+      }
+  }
+}
+
+}  // namespace
+
+bool attention_bwd_supported(const Dims &d) {
+  return d.bf16 && d.dh == DH && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
+}
+
+size_t attention_bwd_scratch_bytes(const Dims &d) { return (size_t)d.B * d.Hq * d.T * sizeof(float); }
+
+hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
+                              const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                              hipStream_t s) {
+  const bool causal = d.flags & CCA_CAUSAL;
+  const long long n_rows = d.rows() * d.Hq;
+  delta_kernel<<<(unsigned)((n_rows + 15) / 16), 256, 0, s>>>((const bf16_t *)d_o, (const bf16_t *)o, delta, n_rows, d.T,
+                                                             d.Hq);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int BH = d.B * d.Hq, nqb = (d.T + DQ_BQ - 1) / DQ_BQ;
+  const int BG = d.B * d.Hk, nkb = (d.T + KV_BK - 1) / KV_BK;
+#define ARGS_DQ (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_q, \
+                d.T, d.Hq, d.Hk, BH, nqb, d.scale
+#define ARGS_KV (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_k, \
+                (bf16_t *)d_v, d.T, d.Hq, d.Hk, BG, nkb, d.scale
+  if (causal) {
+    attn_bwd_dq_kernel<true><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
+    attn_bwd_dkdv_kernel<true><<<(unsigned)((long long)BG * nkb), KV_NT, 0, s>>>(ARGS_KV);
+  } else {
+    attn_bwd_dq_kernel<false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
+    attn_bwd_dkdv_kernel<false><<<(unsigned)((long long)BG * nkb), KV_NT, 0, s>>>(ARGS_KV);
+  }
+#undef ARGS_DQ
+#undef ARGS_KV
+  return hipGetLastError();
+}
+
+}  // namespace cca

@@ -61,6 +61,13 @@ hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, cons
 bool prologue_is_split_copy(const Dims &d);
 hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, hipStream_t s);
 
+// ---- backward of the attention stage (bf16, d_h = 128) ----------------------
+bool attention_bwd_supported(const Dims &d);
+size_t attention_bwd_scratch_bytes(const Dims &d);  // Delta (B,H_q,T) fp32
+hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
+                              const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                              hipStream_t s);
+
 bool prologue_fused_supported(const Dims &d);
 size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE tables; 0 if unsupported
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,

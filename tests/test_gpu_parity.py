@@ -199,3 +199,30 @@ def test_forward_is_deterministic_and_causal_on_gpu():
     _, out3, _ = run_gpu(w, dict(inp, x=x2))
     assert torch.equal(out1[:, :t0], out3[:, :t0])
     assert not torch.equal(out1[:, t0], out3[:, t0])
+
+
+# ---- backward of the attention stage against the oracle's adjoint ------------------------------
+@pytest.mark.parametrize("T,Hq,Hk,causal", [(700, 8, 2, True), (333, 4, 4, True), (520, 4, 1, False), (64, 2, 2, True)])
+def test_attention_backward_stage(T, Hq, Hk, causal):
+    say("case attention backward", T, Hq, Hk, causal)
+    dh, Bn = 128, 2
+    rng = np.random.default_rng(100 + T)
+    q = rng.standard_normal((Bn, T, Hq, dh))
+    k = rng.standard_normal((Bn, T, Hk, dh))
+    temp = np.linspace(-0.2, 0.3, Hk).astype(np.float32)
+    q *= np.sqrt(dh) / np.linalg.norm(q, axis=-1, keepdims=True)
+    k *= np.sqrt(dh) / np.linalg.norm(k, axis=-1, keepdims=True) * np.exp(temp)[None, None, :, None]
+    v = rng.standard_normal((Bn, T, Hk, dh))
+    do = rng.standard_normal((Bn, T, Hq * dh))
+    q, k, v, do = (round_to_bf16(a.astype(np.float32)) for a in (q, k, v, do))
+    flags = B.CCA_FLAGS_PAPER if causal else B.CCA_FLAGS_PAPER & ~B.CCA_CAUSAL
+    cfg = P.CCAConfig(B=Bn, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh, flags=flags)
+    dev = lambda a: torch.from_numpy(a).to("cuda", torch.bfloat16)
+    dq_, dk_, dv_, do_ = dev(q), dev(k), dev(v), dev(do)
+    o, lse = P.cca_attention(cfg, dq_, dk_, dv_, want_lse=True, temp=torch.from_numpy(temp).cuda())
+    g_q, g_k, g_v = P.cca_attention_backward(cfg, dq_, dk_, dv_, o, lse, do_)
+    torch.cuda.synchronize()
+    r_q, r_k, r_v = O.attention_bwd(do, q, k, v, 1.0 / np.sqrt(dh), causal=causal)
+    say("dq", check_tap(to_np(g_q), r_q, "bf16", "d_q"))
+    say("dk", check_tap(to_np(g_k), r_k, "bf16", "d_k"))
+    say("dv", check_tap(to_np(g_v), r_v, "bf16", "d_v"))
