@@ -103,6 +103,8 @@ typedef struct {
   void *v;    /* (B,T,H_k,d_h) value as it enters attention */
   void *o;    /* (B,T,H_q*d_h) attention output */
   float *lse; /* (B,H_q,T) natural-log sum-exp of the scaled logits */
+  float *rnorm; /* (B,T,H_q+H_k) factor the norm step multiplied each head vector by: sqrt(d_h) [* beta] / |x|;
+                   1 when CCA_QK_NORM is off.  Needed by cca_backward. */
 } cca_saved;
 
 /* Bytes of device workspace cca_forward needs for `cfg` (independent of which
@@ -129,7 +131,7 @@ cca_status cca_down_project(const cca_config *cfg, const void *x, const void *w_
  * as selected by cfg->flags.  w->w_down / w->w_out are not read.  The
  * workspace holds the folded convolution filters and the RoPE tables. */
 cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void *lat, void *q, void *k,
-                        void *v, void *workspace, size_t workspace_bytes, void *hip_stream);
+                        void *v, float *rnorm_or_null, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* o (B,T,H_q*d_h) = softmax(scale * q k^T [causal]) v per latent head, query
  * head h reading KV head h / R.  lse may be NULL.

@@ -239,6 +239,7 @@ def cca_forward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, *,
         k = conv_ch(k, w1[Hq:])
     if use_qk_mean:
         q, k = qk_mean(q, k, q0, k0)
+    q3, k3 = q, k                                      # as they enter the norm step
     v = value_shift(vc, vp, Hk, dh, shift=use_v_shift)
     if use_qk_norm:
         q, k = qk_norm_temp(q, k, temp if use_key_temp else None)
@@ -248,7 +249,7 @@ def cca_forward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, *,
     scale = 1.0 / np.sqrt(dh) if not softmax_scale else float(softmax_scale)
     o, lse = attention(q, k, v, scale, causal=causal, rows=rows)
     out = up_project(o, w_out)
-    return dict(out=out, q0=q0, k0=k0, vc=vc, vp=vp, q=q, k=k, v=v, o=o, lse=lse)
+    return dict(out=out, q0=q0, k0=k0, vc=vc, vp=vp, q3=q3, k3=k3, q=q, k=k, v=v, o=o, lse=lse)
 
 
 # ===========================================================================

@@ -45,7 +45,7 @@ class cca_weights(C.Structure):
 
 class cca_saved(C.Structure):
     _fields_ = [("lat", C.c_void_p), ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p),
-                ("o", C.c_void_p), ("lse", C.c_void_p)]
+                ("o", C.c_void_p), ("lse", C.c_void_p), ("rnorm", C.c_void_p)]
 
 
 class CCAError(RuntimeError):
@@ -71,7 +71,7 @@ def load_library() -> C.CDLL:
     lib.cca_forward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, C.POINTER(cca_saved), vp, sz, vp]
     lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
-    lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, sz, vp]
+    lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
     lib.cca_attention_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     for name in EXPORTS:
@@ -139,6 +139,7 @@ class CCASaved:
     v: torch.Tensor | None = None
     o: torch.Tensor | None = None
     lse: torch.Tensor | None = None
+    rnorm: torch.Tensor | None = None
 
     @staticmethod
     def allocate(cfg: CCAConfig, device) -> "CCASaved":
@@ -150,10 +151,12 @@ class CCASaved:
             k=torch.empty(B, T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=device),
             v=torch.empty(B, T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=device),
             o=torch.empty(B, T, cfg.e_q, dtype=dt, device=device),
-            lse=torch.empty(B, cfg.n_q_heads, T, dtype=torch.float32, device=device))
+            lse=torch.empty(B, cfg.n_q_heads, T, dtype=torch.float32, device=device),
+            rnorm=torch.empty(B, T, cfg.n_q_heads + cfg.n_kv_heads, dtype=torch.float32, device=device))
 
     def c(self) -> cca_saved:
-        return cca_saved(_ptr(self.lat), _ptr(self.q), _ptr(self.k), _ptr(self.v), _ptr(self.o), _ptr(self.lse))
+        return cca_saved(_ptr(self.lat), _ptr(self.q), _ptr(self.k), _ptr(self.v), _ptr(self.o), _ptr(self.lse),
+                         _ptr(self.rnorm))
 
 
 def _ptr(t):
@@ -230,7 +233,7 @@ def cca_up_project(cfg: CCAConfig, o, w_out, out=None, workspace=None):
     return out
 
 
-def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None, workspace=None):
+def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None, workspace=None, rnorm=None):
     lib = load_library()
     dt, dev = cfg.torch_dtype, lat.device
     if q is None:
@@ -242,8 +245,8 @@ def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None, wor
     if workspace is None:
         workspace = new_workspace(cfg, dev)
     cc, cw = cfg.c(), w.c()
-    _check(lib.cca_prologue(C.byref(cc), C.byref(cw), _ptr(lat), _ptr(q), _ptr(k), _ptr(v), _ptr(workspace),
-                            workspace.numel(), _stream()), "cca_prologue")
+    _check(lib.cca_prologue(C.byref(cc), C.byref(cw), _ptr(lat), _ptr(q), _ptr(k), _ptr(v), _ptr(rnorm),
+                            _ptr(workspace), workspace.numel(), _stream()), "cca_prologue")
     return q, k, v
 
 

@@ -90,15 +90,15 @@ static cca_status project(const Dims &d, const void *A, const void *W, void *C, 
 }
 
 static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *lat, void *q, void *k, void *v,
-                               void *scratch, size_t scratch_bytes, hipStream_t s) {
+                               float *rnorm, void *scratch, size_t scratch_bytes, hipStream_t s) {
   hipError_t e;
   if (prologue_is_split_copy(d)) {
-    e = prologue_split_copy(d, lat, q, k, v, s);
+    e = prologue_split_copy(d, lat, q, k, v, rnorm, s);
   } else if (prologue_fused_supported(d)) {
     if (!scratch || scratch_bytes < prologue_fused_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
-    e = prologue_fused_bf16(d, *w, lat, q, k, v, scratch, s);
+    e = prologue_fused_bf16(d, *w, lat, q, k, v, rnorm, scratch, s);
   } else {
-    e = prologue_generic(d, *w, lat, q, k, v, s);
+    e = prologue_generic(d, *w, lat, q, k, v, rnorm, s);
   }
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
@@ -156,7 +156,7 @@ cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_ou
 }
 
 cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void *lat, void *q, void *k, void *v,
-                        void *workspace, size_t workspace_bytes, void *hip_stream) {
+                        float *rnorm, void *workspace, size_t workspace_bytes, void *hip_stream) {
   Dims d;
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
@@ -165,7 +165,8 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
   if (st != CCA_OK) return st;
   if (!aligned16(lat) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(workspace))
     return CCA_ERR_ALIGN;
-  return run_prologue(d, w, lat, q, k, v, workspace, workspace_bytes, (hipStream_t)hip_stream);
+  if (reinterpret_cast<uintptr_t>(rnorm) & 3u) return CCA_ERR_ALIGN;
+  return run_prologue(d, w, lat, q, k, v, rnorm, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
 cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o, float *lse,
@@ -212,7 +213,7 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   if (!aligned16(workspace)) return CCA_ERR_ALIGN;
   char *ws = static_cast<char *>(workspace);
   void *lat = ws + L.lat, *q = ws + L.q, *k = ws + L.k, *v = ws + L.v, *o = ws + L.o;
-  float *lse = nullptr;
+  float *lse = nullptr, *rnorm = nullptr;
   if (saved) {
     if (!aligned16(saved->lat) || !aligned16(saved->q) || !aligned16(saved->k) || !aligned16(saved->v) ||
         !aligned16(saved->o) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u))
@@ -223,11 +224,13 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
     if (saved->v) v = saved->v;
     if (saved->o) o = saved->o;
     lse = saved->lse;
+    rnorm = saved->rnorm;
+    if (reinterpret_cast<uintptr_t>(rnorm) & 3u) return CCA_ERR_ALIGN;
   }
   hipStream_t s = (hipStream_t)hip_stream;
   st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, ws + L.wt_down, (size_t)d.E * d.n_lat * 2, s);
   if (st != CCA_OK) return st;
-  st = run_prologue(d, w, lat, q, k, v, ws + L.pro, L.lat - L.pro, s);
+  st = run_prologue(d, w, lat, q, k, v, rnorm, ws + L.pro, L.lat - L.pro, s);
   if (st != CCA_OK) return st;
   st = run_attention(d, q, k, v, o, lse, w->temp, s);
   if (st != CCA_OK) return st;

@@ -80,7 +80,8 @@ struct PrologueArgs {
 template <typename T>
 __global__ void prologue_generic_kernel(PrologueArgs a, const T *__restrict__ lat, const T *__restrict__ w0,
                                         const T *__restrict__ w1, const float *__restrict__ temp,
-                                        T *__restrict__ q, T *__restrict__ k, T *__restrict__ v) {
+                                        T *__restrict__ q, T *__restrict__ k, T *__restrict__ v,
+                                        float *__restrict__ rnorm) {
   extern __shared__ float sm[];  // y0[k_ch][dh] | red[blockDim] | yrot[dh]
   const long long row = blockIdx.x;  // b*T + t
   const int t = (int)(row % a.T);
@@ -170,6 +171,7 @@ __global__ void prologue_generic_kernel(PrologueArgs a, const T *__restrict__ la
     mul = sqrtf((float)dh) / sqrtf(red[0]);
     if (!is_q && (a.flags & CCA_KEY_TEMP)) mul *= expf(temp[head - a.Hq]);
   }
+  if (rnorm && tid == 0) rnorm[row * (a.Hq + a.Hk) + head] = mul;
   T *dst = is_q ? q + row * a.e_q + head * dh : k + row * a.e_kv + (head - a.Hq) * dh;
   for (int o = tid; o < dh; o += blockDim.x) {
     float y = yrot[o] * mul;
@@ -194,7 +196,7 @@ __global__ void prologue_generic_kernel(PrologueArgs a, const T *__restrict__ la
 }
 
 hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
-                            hipStream_t s) {
+                            float *rnorm, hipStream_t s) {
   PrologueArgs a{d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.flags, d.rope_base};
   int threads = 64;
   while (threads < d.dh && threads < 256) threads *= 2;
@@ -204,11 +206,11 @@ hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat
   if (d.bf16)
     prologue_generic_kernel<bf16_t><<<grid, threads, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)w.w_conv_seq,
                                                                (const bf16_t *)w.w_conv_ch, w.temp, (bf16_t *)q,
-                                                               (bf16_t *)k, (bf16_t *)v);
+                                                               (bf16_t *)k, (bf16_t *)v, rnorm);
   else
     prologue_generic_kernel<float><<<grid, threads, smem, s>>>(a, (const float *)lat, (const float *)w.w_conv_seq,
                                                               (const float *)w.w_conv_ch, w.temp, (float *)q,
-                                                              (float *)k, (float *)v);
+                                                              (float *)k, (float *)v, rnorm);
   return hipGetLastError();
 }
 

@@ -41,7 +41,7 @@ __device__ __forceinline__ void store_f(bf16_t *p, float v) { *p = f32_to_bf16(v
 hipError_t gemm_generic(bool bf16, const void *A, const void *Bm, void *C, long long M, int N, int K,
                         hipStream_t s);
 hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
-                            hipStream_t s);
+                            float *rnorm, hipStream_t s);
 hipError_t attention_generic(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
                              hipStream_t s);
 
@@ -59,7 +59,7 @@ hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, cons
 
 // no transform selected: q, k, v are slices of the latent rows (plus the optional value-shift)
 bool prologue_is_split_copy(const Dims &d);
-hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, hipStream_t s);
+hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, float *rnorm, hipStream_t s);
 
 // ---- backward of the attention stage (bf16, d_h = 128) ----------------------
 bool attention_bwd_supported(const Dims &d);
@@ -71,6 +71,6 @@ hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const
 bool prologue_fused_supported(const Dims &d);
 size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE tables; 0 if unsupported
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
-                               void *scratch, hipStream_t s);
+                               float *rnorm, void *scratch, hipStream_t s);
 
 }  // namespace cca

@@ -110,7 +110,7 @@ template <int D>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_fused_kernel(
     FusedArgs a, const bf16_t *__restrict__ lat, const u32x4 *__restrict__ wc, const float2 *__restrict__ ropeA,
     const float2 *__restrict__ ropeB, const float *__restrict__ temp, bf16_t *__restrict__ q, bf16_t *__restrict__ k,
-    bf16_t *__restrict__ v) {
+    bf16_t *__restrict__ v, float *__restrict__ rnorm) {
   constexpr int WROW = D * 16;  // 16-byte chunks per filter row (one output channel)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4 *sW = reinterpret_cast<u32x4 *>(smem);
@@ -262,6 +262,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[nt][r] *= mul;
+      if (rnorm && half == 0 && row < a.rows) rnorm[row * NH + head] = mul;
+    } else if (rnorm && half == 0 && row < a.rows) {
+      rnorm[row * NH + head] = 1.f;
     }
     if (a.flags & CCA_ROPE) {
       const int thi = tpos >> 7, tlo = tpos & 127;
@@ -332,7 +335,7 @@ __global__ __launch_bounds__(256) void split_copy_kernel(const unsigned char *__
 
 template <int D>
 hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, const float2 *ropeA, const float2 *ropeB,
-                       const float *temp, void *q, void *k, void *v, int grid, hipStream_t s) {
+                       const float *temp, void *q, void *k, void *v, float *rnorm, int grid, hipStream_t s) {
   constexpr size_t smem = (size_t)DH * D * 16 * 16;
   static bool attr_set = false;
   if (!attr_set) {
@@ -342,7 +345,7 @@ hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, cons
     attr_set = true;
   }
   prologue_fused_kernel<D><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const u32x4 *)wc, ropeA, ropeB, temp,
-                                                  (bf16_t *)q, (bf16_t *)k, (bf16_t *)v);
+                                                  (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
   return hipGetLastError();
 }
 
@@ -356,7 +359,13 @@ bool prologue_is_split_copy(const Dims &d) {
   return !(d.flags & transforms) && d.e_q % per16 == 0 && d.e_kv % per16 == 0 && d.v_half % per16 == 0;
 }
 
-hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, hipStream_t s) {
+__global__ void fill_f32_kernel(float *p, long long n, float val) {
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long long)gridDim.x * blockDim.x)
+    p[i] = val;
+}
+
+hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, float *rnorm, hipStream_t s) {
+  if (rnorm) fill_f32_kernel<<<256, 256, 0, s>>>(rnorm, d.rows() * (d.Hq + d.Hk), 1.f);
   const long long total = d.rows() * ((long long)d.n_lat * d.esize() / 16);
   const int grid = (int)((total + 255) / 256 < 256 * 64 ? (total + 255) / 256 : 256 * 64);
   split_copy_kernel<<<grid, 256, 0, s>>>((const unsigned char *)lat, (unsigned char *)q, (unsigned char *)k,
@@ -378,7 +387,7 @@ size_t prologue_fused_scratch_bytes(const Dims &d) {
 }
 
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
-                               void *scratch, hipStream_t s) {
+                               float *rnorm, void *scratch, hipStream_t s) {
   const int D = taps(d);
   const int NH = d.Hq + d.Hk;
   FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1, d.rope_base};
@@ -414,9 +423,9 @@ hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *
   const int v_blocks = (int)((v_chunks + NT * 4 - 1) / (NT * 4));
   const int grid = a.n_conv_blocks + v_blocks;
   switch (D) {
-    case 1: return launch_main<1>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
-    case 2: return launch_main<2>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
-    default: return launch_main<3>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, grid, s);
+    case 1: return launch_main<1>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, rnorm, grid, s);
+    case 2: return launch_main<2>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, rnorm, grid, s);
+    default: return launch_main<3>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, rnorm, grid, s);
   }
 }
 

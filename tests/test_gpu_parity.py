@@ -45,6 +45,11 @@ def compare_all(w, inp, ref, out, saved, rows=None):
     lse = lse if rows is None else lse[:, :, rows]
     res["lse"] = check_tap(lse, ref["lse"], dt, "lse")
     res["out"] = check_out(sel(to_np(out)), ref["out"], dt)
+    # factor applied by the norm step: |y| / |x| per head vector (1 when the norm is off)
+    rn_ref = np.concatenate([np.linalg.norm(ref["q"], axis=-1) / np.linalg.norm(ref["q3"], axis=-1),
+                             np.linalg.norm(ref["k"], axis=-1) / np.linalg.norm(ref["k3"], axis=-1)], axis=-1)
+    rel, _ = errors(to_np(saved.rnorm), rn_ref)
+    assert rel <= (1e-2 if dt == "bf16" else 1e-5), ("rnorm", rel)
     return res
 
 
