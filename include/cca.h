@@ -107,15 +107,44 @@ typedef struct {
                    1 when CCA_QK_NORM is off.  Needed by cca_backward. */
 } cca_saved;
 
+/* Gradients of the weights (device pointers, caller-owned, same shapes and
+ * storage type as cca_weights; temp fp32).  cca_backward OVERWRITES each
+ * non-NULL member (it does not accumulate); a NULL member is not computed. */
+typedef struct {
+  void *w_down;     /* (E, N_lat) */
+  void *w_conv_seq; /* (e_q + e_kv, k_seq); ignored when CCA_CONV_SEQ is off */
+  void *w_conv_ch;  /* (H_q + H_k, d_h, d_h, k_ch); ignored when CCA_CONV_CH is off */
+  float *temp;      /* (H_k) fp32; ignored when CCA_KEY_TEMP is off */
+  void *w_out;      /* (e_q, E) */
+} cca_grads;
+
 /* Bytes of device workspace cca_forward needs for `cfg` (independent of which
  * cca_saved members are given).  Returns CCA_OK or a validation error. */
 cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes);
+
+/* Bytes of device workspace cca_backward needs for `cfg`. */
+cca_status cca_backward_workspace_size(const cca_config *cfg, size_t *bwd_bytes);
 
 /* Whole block.  x: (B,T,E) in, out: (B,T,E) overwritten.  `saved` may be NULL.
  * `workspace` is scratch of at least cca_workspace_size() bytes whose
  * contents are undefined afterwards. */
 cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *x, void *out,
                        const cca_saved *saved, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Gradient of the whole block (the paper gives no backward equations: this is
+ * the adjoint of the steps of Sec. 2.2, last step first).  Given d_out =
+ * dLoss/d out (B,T,E) and the intermediates `saved` that cca_forward wrote for
+ * the SAME cfg, weights and x (all seven members required), computes
+ *   d_x (B,T,E)            overwritten; may be NULL (then not computed)
+ *   grads->...             see cca_grads; `grads` itself may be NULL.
+ * Attention probabilities are recomputed from saved->lse (nothing of size
+ * T x T is stored); the convolution inputs are re-read from saved->lat.
+ * Deterministic: no floating-point atomics, a repeated call gives the same
+ * bits.  `workspace`: at least cca_backward_workspace_size() bytes, contents
+ * undefined afterwards. */
+cca_status cca_backward(const cca_config *cfg, const cca_weights *w, const void *x, const cca_saved *saved,
+                        const void *d_out, void *d_x, const cca_grads *grads, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
 
 /* ---- the four stages of cca_forward, callable on their own ---------------
  * Same validation and conventions.  They exist so that each stage can be
@@ -149,11 +178,22 @@ cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, co
  * the adjoint of the attention line of the final eq. block): from q, k, v, o,
  * lse of the forward pass and d_o (B,T,H_q*d_h) computes d_q (B,T,H_q,d_h),
  * d_k, d_v (B,T,H_k,d_h), overwritten; d_k, d_v are summed over the query
- * heads sharing a KV head.  Probabilities are recomputed from lse.  bf16 and
- * d_h = 128 only (else CCA_ERR_UNSUPPORTED).  workspace: B*H_q*T*4 bytes. */
+ * heads sharing a KV head.  Probabilities are recomputed from lse.
+ * workspace: B*H_q*T*4 bytes. */
 cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v,
                                   const void *o, const float *lse, const void *d_o, void *d_q, void *d_k,
                                   void *d_v, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Backward of cca_prologue: from d_q (B,T,H_q,d_h), d_k, d_v (B,T,H_k,d_h)
+ * (gradients of what cca_prologue wrote), the saved lat, q, k and rnorm of the
+ * forward pass, computes d_lat (B,T,N_lat) and, where the pointer is non-NULL
+ * and the flag is on, grads->w_conv_seq, grads->w_conv_ch, grads->temp
+ * (grads->w_down / w_out are not touched).  workspace:
+ * cca_backward_workspace_size() bytes always suffice. */
+cca_status cca_prologue_backward(const cca_config *cfg, const cca_weights *w, const void *lat, const void *q,
+                                 const void *k, const float *rnorm, const void *d_q, const void *d_k,
+                                 const void *d_v, void *d_lat, const cca_grads *grads, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
 
 /* out (B*T, E) = o (B*T, e_q) * w_out (e_q, E).  Last line of the final eq. block. */
 cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_out, void *out,

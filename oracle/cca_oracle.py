@@ -320,7 +320,8 @@ def value_shift_bwd(dv, shift=True):
 
 
 def qk_norm_temp_bwd(dq4, dk4, q3, k3, temp=None):
-    """y = x sqrt(d) / |x| (* exp(temp_g) for keys)  ->  dx (and dtemp)."""
+    """y = x sqrt(d) / |x| (* exp(temp_g) for keys)  ->  dx, dtemp and sum_t |<dk4_t, k4_t>| (the magnitude
+    the signed sum dtemp cancels down from: the natural error scale for a reduced-precision dtemp)."""
     d = q3.shape[-1]
 
     def one(dy, x, mul):
@@ -330,12 +331,12 @@ def qk_norm_temp_bwd(dq4, dk4, q3, k3, temp=None):
 
     dq3 = one(dq4, q3, 1.0)
     if temp is None:
-        return dq3, one(dk4, k3, 1.0), None
+        return dq3, one(dk4, k3, 1.0), None, None
     beta = np.exp(_f64(temp))[None, None, :, None]
     dk3 = one(dk4, k3, beta)
     k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True)) * beta
-    dtemp = (dk4 * k4).sum(axis=(0, 1, 3))
-    return dq3, dk3, dtemp
+    per_token = (dk4 * k4).sum(axis=3)                 # (B,T,Hk): d temp_g is the sum of these signed terms
+    return dq3, dk3, per_token.sum(axis=(0, 1)), np.abs(per_token).sum(axis=(0, 1))
 
 
 def rope_bwd(dy, base=10000.0, interleaved=False):
@@ -358,22 +359,27 @@ def rope_bwd(dy, base=10000.0, interleaved=False):
     return out
 
 
-def attention_bwd(do, q, k, v, scale, causal=True):
+def attention_bwd(do, q, k, v, scale, causal=True, rows=None):
     """Adjoint of attention(): with P = softmax(scale q k^T) row-wise,
     dV = P^T dO, dP = dO V^T, dS = P * (dP - rowsum(dP * P)),
-    dQ = scale dS K, dK = scale dS^T Q; dK, dV summed over the query heads of a group."""
+    dQ = scale dS K, dK = scale dS^T Q; dK, dV summed over the query heads of a group.
+
+    ``rows`` (1-D int array): the caller states that ``do`` is zero at every
+    other query position; those rows have dS = 0 and add nothing to dV, so
+    they are skipped (their dQ stays zero)."""
     do, q, k, v = _f64(do), _f64(q), _f64(k), _f64(v)
     B, T, Hq, d = q.shape
     Hk = k.shape[2]
     R = Hq // Hk
     do = do.reshape(B, T, Hq, -1)
     dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    rows = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
     chunk = 256
     for b in range(B):
         for h in range(Hq):
             g = h // R
-            for c0 in range(0, T, chunk):
-                r = np.arange(c0, min(T, c0 + chunk))
+            for c0 in range(0, len(rows), chunk):
+                r = rows[c0:c0 + chunk]
                 s_max = int(r.max()) + 1 if causal else T
                 s = scale * (q[b, r, h, :] @ k[b, :s_max, g, :].T)
                 if causal:
@@ -393,11 +399,16 @@ def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
                  causal=True, use_conv_seq=True, use_conv_ch=True,
                  use_qk_mean=True, use_v_shift=True, use_qk_norm=True,
                  use_key_temp=True, use_rope=True, rope_interleaved=False,
-                 rope_base=10000.0, softmax_scale=None):
+                 rope_base=10000.0, softmax_scale=None, rows=None):
     """Gradients of sum(out * d_out) with respect to x and every weight.
     Recomputes the forward intermediates it needs.  Returns a dict:
     d_x, d_w_down, d_w_conv_seq, d_w_conv_ch, d_temp, d_w_out plus the
-    intermediate gradients d_o, d_q, d_k, d_v (as they leave attention) and d_lat."""
+    intermediate gradients d_o, d_q, d_k, d_v (as they leave attention) and d_lat.
+
+    ``rows`` (1-D int array): the caller states that ``d_out`` is zero at
+    every other position; the attention forward / backward then visit only
+    those query rows (everything is linear in d_out, so the result is the
+    same as with rows=None)."""
     Hq, Hk, dh = n_q_heads, n_kv_heads, head_dim
     e_q, e_kv = Hq * dh, Hk * dh
     x, d_out = _f64(x), _f64(d_out)
@@ -419,19 +430,21 @@ def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
     q4, k4 = qk_norm_temp(q3, k3, temp if use_key_temp else None) if use_qk_norm else (q3, k3)
     q5, k5 = (rope(q4, rope_base, rope_interleaved), rope(k4, rope_base, rope_interleaved)) if use_rope else (q4, k4)
     scale = 1.0 / np.sqrt(dh) if not softmax_scale else float(softmax_scale)
-    o, _ = attention(q5, k5, v, scale, causal=causal)
+    ridx = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
+    o, _ = attention(q5, k5, v, scale, causal=causal, rows=rows)       # (B, len(ridx), Hq, dh)
     # ---- adjoint, last step first
-    o_flat = o.reshape(B, T, -1)
-    d_w_out = np.einsum("bte,btf->ef", o_flat, d_out)
-    d_o = d_out @ w_out.T
-    d_q5, d_k5, d_v = attention_bwd(d_o, q5, k5, v, scale, causal=causal)
+    o_flat = o.reshape(B, len(ridx), -1)
+    d_w_out = np.einsum("bte,btf->ef", o_flat, d_out[:, ridx])
+    d_o = np.zeros((B, T, e_q))
+    d_o[:, ridx] = d_out[:, ridx] @ w_out.T
+    d_q5, d_k5, d_v = attention_bwd(d_o, q5, k5, v, scale, causal=causal, rows=rows)
     d_q4, d_k4 = (rope_bwd(d_q5, rope_base, rope_interleaved), rope_bwd(d_k5, rope_base, rope_interleaved)) \
         if use_rope else (d_q5, d_k5)
-    d_temp = np.zeros(Hk)
+    d_temp, d_temp_abs = np.zeros(Hk), np.zeros(Hk)
     if use_qk_norm:
-        d_q3, d_k3, dt = qk_norm_temp_bwd(d_q4, d_k4, q3, k3, temp if use_key_temp else None)
+        d_q3, d_k3, dt, dt_abs = qk_norm_temp_bwd(d_q4, d_k4, q3, k3, temp if use_key_temp else None)
         if dt is not None:
-            d_temp = dt
+            d_temp, d_temp_abs = dt, dt_abs
     else:
         d_q3, d_k3 = d_q4, d_k4
     d_q0 = np.zeros_like(q0)
@@ -464,4 +477,4 @@ def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
     d_x = d_lat @ w_down.T
     d_w_down = np.einsum("bte,btf->ef", x, d_lat)
     return dict(d_x=d_x, d_w_down=d_w_down, d_w_conv_seq=d_w0, d_w_conv_ch=d_w1, d_temp=d_temp, d_w_out=d_w_out,
-                d_o=d_o, d_q=d_q5, d_k=d_k5, d_v=d_v, d_lat=d_lat)
+                d_temp_abs=d_temp_abs, d_o=d_o, d_q=d_q5, d_k=d_k5, d_v=d_v, d_lat=d_lat)

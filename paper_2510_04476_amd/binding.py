@@ -27,8 +27,9 @@ CCA_FLAGS_PAPER = (CCA_CAUSAL | CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_V
                    | CCA_KEY_TEMP | CCA_ROPE)
 CCA_FLAGS_MHA = CCA_CAUSAL
 
-EXPORTS = ("cca_workspace_size", "cca_forward", "cca_down_project", "cca_prologue", "cca_attention",
-           "cca_attention_backward", "cca_up_project", "cca_strerror", "cca_version")
+EXPORTS = ("cca_workspace_size", "cca_backward_workspace_size", "cca_forward", "cca_backward", "cca_down_project",
+           "cca_prologue", "cca_attention", "cca_attention_backward", "cca_prologue_backward", "cca_up_project",
+           "cca_strerror", "cca_version")
 
 
 class cca_config(C.Structure):
@@ -46,6 +47,11 @@ class cca_weights(C.Structure):
 class cca_saved(C.Structure):
     _fields_ = [("lat", C.c_void_p), ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p),
                 ("o", C.c_void_p), ("lse", C.c_void_p), ("rnorm", C.c_void_p)]
+
+
+class cca_grads(C.Structure):
+    _fields_ = [("w_down", C.c_void_p), ("w_conv_seq", C.c_void_p), ("w_conv_ch", C.c_void_p),
+                ("temp", C.c_void_p), ("w_out", C.c_void_p)]
 
 
 class CCAError(RuntimeError):
@@ -74,6 +80,11 @@ def load_library() -> C.CDLL:
     lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
     lib.cca_attention_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cca_backward_workspace_size.argtypes = [cfgp, C.POINTER(sz)]
+    lib.cca_backward.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_saved), vp, vp,
+                                 C.POINTER(cca_grads), vp, sz, vp]
+    lib.cca_prologue_backward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, vp, vp, vp,
+                                          C.POINTER(cca_grads), vp, sz, vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
     lib.cca_strerror.argtypes = [C.c_int]
@@ -157,6 +168,26 @@ class CCASaved:
     def c(self) -> cca_saved:
         return cca_saved(_ptr(self.lat), _ptr(self.q), _ptr(self.k), _ptr(self.v), _ptr(self.o), _ptr(self.lse),
                          _ptr(self.rnorm))
+
+
+@dataclass
+class CCAGrads:
+    """Gradients of the weights, same shapes / storage type as CCAWeights (temp fp32)."""
+    w_down: torch.Tensor | None = None
+    w_out: torch.Tensor | None = None
+    w_conv_seq: torch.Tensor | None = None
+    w_conv_ch: torch.Tensor | None = None
+    temp: torch.Tensor | None = None
+
+    @staticmethod
+    def allocate_like(w: CCAWeights) -> "CCAGrads":
+        e = lambda t: None if t is None else torch.empty_like(t)
+        return CCAGrads(w_down=e(w.w_down), w_out=e(w.w_out), w_conv_seq=e(w.w_conv_seq), w_conv_ch=e(w.w_conv_ch),
+                        temp=e(w.temp))
+
+    def c(self) -> cca_grads:
+        return cca_grads(_ptr(self.w_down), _ptr(self.w_conv_seq), _ptr(self.w_conv_ch), _ptr(self.temp),
+                         _ptr(self.w_out))
 
 
 def _ptr(t):
@@ -274,3 +305,48 @@ def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=N
                                       _ptr(d_k), _ptr(d_v), _ptr(workspace), workspace.numel(), _stream()),
            "cca_attention_backward")
     return d_q, d_k, d_v
+
+
+def cca_backward_workspace_size(cfg: CCAConfig) -> int:
+    n = C.c_size_t(0)
+    cc = cfg.c()
+    _check(load_library().cca_backward_workspace_size(C.byref(cc), C.byref(n)), "cca_backward_workspace_size")
+    return n.value
+
+
+def new_backward_workspace(cfg: CCAConfig, device) -> torch.Tensor:
+    return torch.empty(max(cca_backward_workspace_size(cfg), 256), dtype=torch.uint8, device=device)
+
+
+def cca_backward(cfg: CCAConfig, w: CCAWeights, x, saved: CCASaved, d_out, d_x=None, grads: CCAGrads | None = None,
+                 workspace=None, want_d_x=True):
+    """Returns (d_x, grads).  grads=None allocates gradients for every weight of `w`."""
+    lib = load_library()
+    if d_x is None and want_d_x:
+        d_x = torch.empty_like(x)
+    if grads is None:
+        grads = CCAGrads.allocate_like(w)
+    if workspace is None:
+        workspace = new_backward_workspace(cfg, x.device)
+    cc, cw, cs, cg = cfg.c(), w.c(), saved.c(), grads.c()
+    _check(lib.cca_backward(C.byref(cc), C.byref(cw), _ptr(x), C.byref(cs), _ptr(d_out), _ptr(d_x), C.byref(cg),
+                            _ptr(workspace), workspace.numel(), _stream()), "cca_backward")
+    return d_x, grads
+
+
+def cca_prologue_backward(cfg: CCAConfig, w: CCAWeights, lat, q, k, rnorm, d_q, d_k, d_v, d_lat=None,
+                          grads: CCAGrads | None = None, workspace=None):
+    lib = load_library()
+    if d_lat is None:
+        d_lat = torch.empty_like(lat)
+    if grads is None:
+        grads = CCAGrads(w_conv_seq=None if w.w_conv_seq is None else torch.empty_like(w.w_conv_seq),
+                         w_conv_ch=None if w.w_conv_ch is None else torch.empty_like(w.w_conv_ch),
+                         temp=None if w.temp is None else torch.empty_like(w.temp))
+    if workspace is None:
+        workspace = new_backward_workspace(cfg, lat.device)
+    cc, cw, cg = cfg.c(), w.c(), grads.c()
+    _check(lib.cca_prologue_backward(C.byref(cc), C.byref(cw), _ptr(lat), _ptr(q), _ptr(k), _ptr(rnorm), _ptr(d_q),
+                                     _ptr(d_k), _ptr(d_v), _ptr(d_lat), C.byref(cg), _ptr(workspace),
+                                     workspace.numel(), _stream()), "cca_prologue_backward")
+    return d_lat, grads

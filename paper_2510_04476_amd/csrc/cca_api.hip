@@ -110,6 +110,82 @@ static cca_status run_attention(const Dims &d, const void *q, const void *k, con
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
+struct BwdLayout {
+  size_t d_o, d_q, d_k, d_v, delta, d_lat, pro, gemm, total;  // byte offsets
+  size_t pro_bytes, gemm_bytes;
+};
+
+static size_t prologue_bwd_scratch_bytes(const Dims &d) {
+  return prologue_bwd_fused_supported(d) ? prologue_bwd_fused_scratch_bytes(d) : prologue_bwd_generic_scratch_bytes(d);
+}
+
+static bool tn_mfma(const Dims &d, int Mo, int No) { return d.bf16 && gemm_tn_mfma_supported(Mo, No, d.rows()); }
+
+static BwdLayout bwd_layout(const Dims &d) {
+  BwdLayout L;
+  const size_t es = d.esize();
+  const size_t rows = (size_t)d.rows();
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  L.d_o = take(rows * d.e_q * es);
+  L.d_q = take(rows * d.e_q * es);
+  L.d_k = take(rows * d.e_kv * es);
+  L.d_v = take(rows * d.e_kv * es);
+  L.delta = take((size_t)d.B * d.Hq * d.T * sizeof(float));
+  L.d_lat = take(rows * d.n_lat * es);
+  L.pro_bytes = prologue_bwd_scratch_bytes(d);
+  L.pro = take(L.pro_bytes);
+  size_t g1 = tn_mfma(d, d.e_q, d.E) ? gemm_tn_scratch_bytes(d.e_q, d.E, d.rows()) : 0;
+  size_t g2 = tn_mfma(d, d.E, d.n_lat) ? gemm_tn_scratch_bytes(d.E, d.n_lat, d.rows()) : 0;
+  L.gemm_bytes = g1 > g2 ? g1 : g2;
+  L.gemm = take(L.gemm_bytes);
+  L.total = off;
+  return L;
+}
+
+// C (M,N) = A (M,K) * W (N,K)^T with W as stored (no transpose pass): d_o = d_out W_O^T, d_x = d_lat W_down^T
+static cca_status project_t(const Dims &d, const void *A, const void *W, void *C, long long M, int N, int K,
+                            hipStream_t s) {
+  hipError_t e = (d.bf16 && gemm_mfma_supported(M, N, K)) ? gemm_mfma_bf16(A, W, C, M, N, K, s)
+                                                          : gemm_generic_ex(d.bf16, A, K, false, W, K, true, C, N, M, N, K, s);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+// dW (Mo,No) = A (rows,Mo)^T * Bm (rows,No)
+static cca_status weight_grad(const Dims &d, const void *A, const void *Bm, void *dW, int Mo, int No, void *scratch,
+                              hipStream_t s) {
+  hipError_t e = tn_mfma(d, Mo, No)
+                     ? gemm_tn_mfma_bf16(A, Mo, Bm, No, dW, Mo, No, d.rows(), static_cast<float *>(scratch), s)
+                     : gemm_generic_ex(d.bf16, A, Mo, true, Bm, No, false, dW, No, Mo, No, d.rows(), s);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+static cca_status run_attention_bwd(const Dims &d, const void *q, const void *k, const void *v, const void *o,
+                                    const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                                    hipStream_t s) {
+  hipError_t e = attention_bwd_supported(d) ? attention_bwd_bf16(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, delta, s)
+                                            : attention_bwd_generic(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, delta, s);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+static cca_status run_prologue_bwd(const Dims &d, const cca_weights *w, const void *lat, const void *q, const void *k,
+                                   const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                   const cca_grads *gr, void *scratch, size_t scratch_bytes, hipStream_t s) {
+  if (!scratch || scratch_bytes < prologue_bwd_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
+  hipError_t e = prologue_bwd_fused_supported(d)
+                     ? prologue_bwd_fused_bf16(d, *w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s)
+                     : prologue_bwd_generic(d, *w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s);
+  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+}
+
+static cca_status check_grads(const cca_grads *g) {
+  if (!g) return CCA_OK;
+  if (!aligned16(g->w_down) || !aligned16(g->w_conv_seq) || !aligned16(g->w_conv_ch) || !aligned16(g->w_out) ||
+      (reinterpret_cast<uintptr_t>(g->temp) & 3u))
+    return CCA_ERR_ALIGN;
+  return CCA_OK;
+}
+
 static cca_status check_prologue_weights(const Dims &d, const cca_weights *w) {
   if (!w) return CCA_ERR_NULL;
   if ((d.flags & CCA_CONV_SEQ) && !w->w_conv_seq) return CCA_ERR_NULL;
@@ -132,6 +208,15 @@ cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes) {
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
   *fwd_bytes = fwd_layout(d).total;
+  return CCA_OK;
+}
+
+cca_status cca_backward_workspace_size(const cca_config *cfg, size_t *bwd_bytes) {
+  if (!bwd_bytes) return CCA_ERR_NULL;
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  *bwd_bytes = bwd_layout(d).total;
   return CCA_OK;
 }
 
@@ -189,14 +274,79 @@ cca_status cca_attention_backward(const cca_config *cfg, const void *q, const vo
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
   if (!q || !k || !v || !o || !lse || !d_o || !d_q || !d_k || !d_v) return CCA_ERR_NULL;
-  if (!attention_bwd_supported(d)) return CCA_ERR_UNSUPPORTED;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(d_q) ||
       !aligned16(d_k) || !aligned16(d_v) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
     return CCA_ERR_ALIGN;
   if (!workspace || workspace_bytes < attention_bwd_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
-  hipError_t e = attention_bwd_bf16(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, static_cast<float *>(workspace),
-                                    (hipStream_t)hip_stream);
-  return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
+  return run_attention_bwd(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, static_cast<float *>(workspace),
+                           (hipStream_t)hip_stream);
+}
+
+cca_status cca_prologue_backward(const cca_config *cfg, const cca_weights *w, const void *lat, const void *q,
+                                 const void *k, const float *rnorm, const void *d_q, const void *d_k, const void *d_v,
+                                 void *d_lat, const cca_grads *grads, void *workspace, size_t workspace_bytes,
+                                 void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!lat || !q || !k || !rnorm || !d_q || !d_k || !d_v || !d_lat) return CCA_ERR_NULL;
+  st = check_prologue_weights(d, w);
+  if (st != CCA_OK) return st;
+  st = check_grads(grads);
+  if (st != CCA_OK) return st;
+  if (!aligned16(lat) || !aligned16(q) || !aligned16(k) || !aligned16(d_q) || !aligned16(d_k) || !aligned16(d_v) ||
+      !aligned16(d_lat) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(rnorm) & 3u))
+    return CCA_ERR_ALIGN;
+  return run_prologue_bwd(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, grads, workspace, workspace_bytes,
+                          (hipStream_t)hip_stream);
+}
+
+cca_status cca_backward(const cca_config *cfg, const cca_weights *w, const void *x, const cca_saved *saved,
+                        const void *d_out, void *d_x, const cca_grads *grads, void *workspace, size_t workspace_bytes,
+                        void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!w || !x || !saved || !d_out || !w->w_down || !w->w_out) return CCA_ERR_NULL;
+  if (!saved->lat || !saved->q || !saved->k || !saved->v || !saved->o || !saved->lse || !saved->rnorm)
+    return CCA_ERR_NULL;
+  st = check_prologue_weights(d, w);
+  if (st != CCA_OK) return st;
+  st = check_grads(grads);
+  if (st != CCA_OK) return st;
+  if (!aligned16(x) || !aligned16(d_out) || !aligned16(d_x) || !aligned16(w->w_down) || !aligned16(w->w_out) ||
+      !aligned16(saved->lat) || !aligned16(saved->q) || !aligned16(saved->k) || !aligned16(saved->v) ||
+      !aligned16(saved->o) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u) ||
+      (reinterpret_cast<uintptr_t>(saved->rnorm) & 3u))
+    return CCA_ERR_ALIGN;
+  const BwdLayout L = bwd_layout(d);
+  if (!workspace || workspace_bytes < L.total) return CCA_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return CCA_ERR_ALIGN;
+  char *ws = static_cast<char *>(workspace);
+  void *d_o = ws + L.d_o, *d_q = ws + L.d_q, *d_k = ws + L.d_k, *d_v = ws + L.d_v, *d_lat = ws + L.d_lat;
+  hipStream_t s = (hipStream_t)hip_stream;
+  // last step first: out = o W_O
+  if (grads && grads->w_out) {
+    st = weight_grad(d, saved->o, d_out, grads->w_out, d.e_q, d.E, ws + L.gemm, s);
+    if (st != CCA_OK) return st;
+  }
+  st = project_t(d, d_out, w->w_out, d_o, d.rows(), d.e_q, d.E, s);
+  if (st != CCA_OK) return st;
+  st = run_attention_bwd(d, saved->q, saved->k, saved->v, saved->o, saved->lse, d_o, d_q, d_k, d_v,
+                         reinterpret_cast<float *>(ws + L.delta), s);
+  if (st != CCA_OK) return st;
+  st = run_prologue_bwd(d, w, saved->lat, saved->q, saved->k, saved->rnorm, d_q, d_k, d_v, d_lat, grads, ws + L.pro,
+                        L.pro_bytes, s);
+  if (st != CCA_OK) return st;
+  if (d_x) {
+    st = project_t(d, d_lat, w->w_down, d_x, d.rows(), d.E, d.n_lat, s);
+    if (st != CCA_OK) return st;
+  }
+  if (grads && grads->w_down) {
+    st = weight_grad(d, x, d_lat, grads->w_down, d.E, d.n_lat, ws + L.gemm, s);
+    if (st != CCA_OK) return st;
+  }
+  return CCA_OK;
 }
 
 cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *x, void *out, const cca_saved *saved,
@@ -252,6 +402,6 @@ const char *cca_strerror(cca_status s) {
   return "unknown status";
 }
 
-int cca_version(void) { return 100; }
+int cca_version(void) { return 200; }
 
 }  // extern "C"

@@ -68,6 +68,32 @@ hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const
                               const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                               hipStream_t s);
 
+// C (Mo,No) = A (K,Mo)^T * B (K,No): weight gradients, contraction over token rows, split over K into fp32
+// partial sums in `part` (gemm_tn_scratch_bytes), added in a fixed order.
+bool gemm_tn_mfma_supported(int Mo, int No, long long K);
+size_t gemm_tn_scratch_bytes(int Mo, int No, long long K);
+hipError_t gemm_tn_mfma_bf16(const void *A, long long lda, const void *Bm, long long ldb, void *C, int Mo, int No,
+                             long long K, float *part, hipStream_t s);
+
+// ---- generic backward kernels (any supported shape, fp32 or bf16 storage) ----
+// C (M,N) = op(A) op(B); ta: A is stored (K,M); tb: B is stored (N,K)
+hipError_t gemm_generic_ex(bool bf16, const void *A, long long lda, bool ta, const void *Bm, long long ldb, bool tb,
+                           void *C, long long ldc, long long M, int N, long long K, hipStream_t s);
+hipError_t attention_bwd_generic(const Dims &d, const void *q, const void *k, const void *v, const void *o,
+                                 const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                                 hipStream_t s);
+size_t prologue_bwd_generic_scratch_bytes(const Dims &d);
+hipError_t prologue_bwd_generic(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
+                                const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                const cca_grads *gr, void *scratch, hipStream_t s);
+
+// ---- backward of the fused prologue (bf16, d_h = 128, same shapes as the fused forward) ----
+bool prologue_bwd_fused_supported(const Dims &d);
+size_t prologue_bwd_fused_scratch_bytes(const Dims &d);
+hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
+                                   const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                   const cca_grads *gr, void *scratch, hipStream_t s);
+
 bool prologue_fused_supported(const Dims &d);
 size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE tables; 0 if unsupported
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,

@@ -47,6 +47,13 @@ struct FusedArgs {
   int n_conv_blocks;
   int tiles_per_wave;
   float rope_base;
+  // Row strides (elements).  Forward: the source is the latent (n_lat), q / k / v are dense.  Backward: the source
+  // is the gradient entering the convolutions (e_q + e_kv wide), q / k destinations are column ranges of d_lat,
+  // the value role reads d_v (e_kv) and writes the value columns of d_lat.
+  int src_stride, q_stride, k_stride, vsrc_stride, vdst_stride;
+  // qk-mean weights of the other stream: a q head adds mean_q_other * (k row of its group), a k head adds
+  // mean_k_other * (each q row of its group).  Forward 1/2 and 1/(2R); the adjoint swaps them.
+  float mean_q_other, mean_k_other;
 };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -65,14 +72,14 @@ __device__ __forceinline__ float hi_f(uint32_t w) { return __uint_as_float(w & 0
 __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D, const bf16_t *__restrict__ w0,
                                                             const bf16_t *__restrict__ w1, bf16_t *__restrict__ wc,
                                                             float2 *__restrict__ ropeA, float2 *__restrict__ ropeB,
-                                                            int n_fold_blocks, int n_thi) {
+                                                            int n_fold_blocks, int n_thi, int transposed) {
   const int NH = a.Hq + a.Hk;
   if ((int)blockIdx.x < n_fold_blocks) {
     const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (h, o, i)
     if (id >= (long long)NH * DH * DH) return;
     const int i = (int)(id % DH), o = (int)((id / DH) % DH), h = (int)(id / (DH * DH));
     const int ch = h * DH + i;  // packed q|k channel: q heads first, then k heads
-    const int ks = (a.flags & CCA_CONV_SEQ) ? a.k_seq : 1, kc = a.k_ch;
+    const int ks = (a.flags & CCA_CONV_SEQ) ? a.k_seq : 1, kc = (a.flags & CCA_CONV_CH) ? a.k_ch : 1;
     for (int d = 0; d < D; ++d) {
       float acc = 0.f;
       for (int j = 0; j < kc; ++j) {
@@ -81,7 +88,9 @@ __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D,
         const float f0 = (a.flags & CCA_CONV_SEQ) ? bf16_to_f32(w0[(long long)ch * ks + jj]) : 1.f;
         acc = fmaf(bf16_to_f32(w1[(((long long)h * DH + o) * DH + i) * kc + j]), f0, acc);
       }
-      wc[(((long long)h * DH + o) * D + d) * DH + i] = f32_to_bf16(acc);
+      // the adjoint convolution contracts over the output channel: filter stored [h][i][d][o]
+      if (transposed) wc[(((long long)h * DH + i) * D + d) * DH + o] = f32_to_bf16(acc);
+      else wc[(((long long)h * DH + o) * D + d) * DH + i] = f32_to_bf16(acc);
     }
     return;
   }
@@ -104,13 +113,17 @@ __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D,
 }
 
 // ---------------------------------------------------------------------------
-// main kernel: one workgroup = one head x (256 * tiles_per_wave) tokens, 8 wavefronts x 32-token tiles
+// main kernel: one workgroup = one head x (256 * tiles_per_wave) tokens, 8 wavefronts x 32-token tiles.
+// BWD = false: the forward prologue.  BWD = true: its adjoint from the gradient d3 of the conv2 output to
+// d_lat: the same contraction with the transposed filter and the taps reaching FORWARD in time (token t reads
+// rows t .. t+D-1, zero past the end of its sequence), the qk-mean adjoint through the same identity MFMAs, no
+// norm / RoPE (those are undone by a pointwise kernel before), and the value role running the shift backwards.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int D, bool BWD>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_fused_kernel(
-    FusedArgs a, const bf16_t *__restrict__ lat, const u32x4 *__restrict__ wc, const float2 *__restrict__ ropeA,
-    const float2 *__restrict__ ropeB, const float *__restrict__ temp, bf16_t *__restrict__ q, bf16_t *__restrict__ k,
-    bf16_t *__restrict__ v, float *__restrict__ rnorm) {
+    FusedArgs a, const bf16_t *__restrict__ lat, const bf16_t *__restrict__ vsrc, const u32x4 *__restrict__ wc,
+    const float2 *__restrict__ ropeA, const float2 *__restrict__ ropeB, const float *__restrict__ temp,
+    bf16_t *__restrict__ q, bf16_t *__restrict__ k, bf16_t *__restrict__ v, float *__restrict__ rnorm) {
   constexpr int WROW = D * 16;  // 16-byte chunks per filter row (one output channel)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4 *sW = reinterpret_cast<u32x4 *>(smem);
@@ -131,9 +144,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       const int t = (int)(row % a.T);
       u32x4 val = {0, 0, 0, 0};
       const bool shifted = (a.flags & CCA_V_SHIFT) && ch >= a.v_half;
-      if (!shifted || t > 0)
-        val = *reinterpret_cast<const u32x4 *>(lat + (row - (shifted ? 1 : 0)) * a.n_lat + a.e_q + a.e_kv + ch);
-      *reinterpret_cast<u32x4 *>(v + row * a.e_kv + ch) = val;
+      // forward: the shifted half comes from token t-1; adjoint: its gradient goes back to token t, read at t+1
+      const bool live = !shifted || (BWD ? t + 1 < a.T : t > 0);
+      if (live) val = *reinterpret_cast<const u32x4 *>(vsrc + (row + (shifted ? (BWD ? 1 : -1) : 0)) * a.vsrc_stride + ch);
+      *reinterpret_cast<u32x4 *>(v + row * a.vdst_stride + ch) = val;
     }
     return;
   }
@@ -157,16 +171,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   __syncthreads();  // the only workgroup-wide synchronisation
   const float beta = (!is_q && (a.flags & CCA_KEY_TEMP)) ? expf(temp[g]) : 1.f;
   bf16_t *dst = is_q ? q + head * DH : k + g * DH;
-  const int dst_stride = is_q ? a.e_q : a.e_kv;
+  const int dst_stride = is_q ? a.q_stride : a.k_stride;
 
   // ---- qk-mean through the matrix core: m = c * I * u adds c times a latent row, already in the
   // accumulator layout, with no extra loads or conversions.  Fragment j of c*I for output tile nt pairs with
   // operand fragment kk = 2*nt + j of the source row; lane (l32, half) is non-zero in fragment l32 >> 4 when
   // (l32 >> 3) & 1 == half, element l32 & 7.
   const bool mean = a.flags & CCA_QK_MEAN;
-  bf16x8 id_half[2], id_grp[2];  // 1/2 * I (own pre-conv latent; k for q heads), 1/(2R) * I (q rows for a k head)
+  bf16x8 id_half[2], id_grp[2];  // 1/2 * I (own stream), weight of the other stream * I
   {
-    const uint32_t hb = (uint32_t)f32_to_bf16(0.5f), gb = (uint32_t)f32_to_bf16(0.5f / (float)a.R);
+    const uint32_t hb = (uint32_t)f32_to_bf16(0.5f),
+                   gb = (uint32_t)f32_to_bf16(is_q ? a.mean_q_other : a.mean_k_other);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const bool on = ((l32 >> 4) == j) && (((l32 >> 3) & 1) == half);
@@ -187,21 +202,22 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const long long row = trow0 + l32;
     const long long rowc = row < a.rows ? row : a.rows - 1;
     const int tpos = (int)(rowc % a.T);
-    // Tokens before the start of their sequence contribute zeros.  Only the first tile of a sequence has such
-    // taps: everywhere else the loads are unconditional and all in flight together.
-    const bool any_pad = __any(tpos < D - 1) != 0;
+    // Taps outside the token's sequence contribute zeros.  Only the first (adjoint: last) tile of a sequence
+    // has such taps: everywhere else the loads are unconditional and all in flight together.
+    const bool any_pad = __any(BWD ? tpos + D - 1 >= a.T : tpos < D - 1) != 0;
 
-    // ---- operands: latent rows of tokens t-D+1 .. t of this head (d = D-1 is the token itself)
+    // ---- operands: source rows of tokens t-D+1 .. t (adjoint: t+D-1 .. t) of this head; d = D-1 is the token itself
     bf16x8 uf[D][8];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       const int back = D - 1 - d;
-      const long long src_row = rowc - back >= 0 ? rowc - back : 0;  // in bounds; zeroed below
-      const bf16_t *p = lat + src_row * a.n_lat + ch0 + half * 8;
+      long long src_row = BWD ? rowc + back : rowc - back;  // clamped in bounds; zeroed below
+      src_row = src_row < 0 ? 0 : (src_row >= a.rows ? a.rows - 1 : src_row);
+      const bf16_t *p = lat + src_row * a.src_stride + ch0 + half * 8;
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         u32x4 raw = *reinterpret_cast<const u32x4 *>(p + kk * 16);
-        if (any_pad && tpos < back) raw = u32x4{0, 0, 0, 0};
+        if (any_pad && (BWD ? tpos + back >= a.T : tpos < back)) raw = u32x4{0, 0, 0, 0};
         uf[d][kk] = __builtin_bit_cast(bf16x8, raw);
       }
     }
@@ -225,6 +241,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         }
 
     // ---- qk-mean.  q head: + (q0 + k0[g]) / 2.  k head: + (mean_r q0[gR + r] + k0) / 2.
+    //      Adjoint: q head + d3_q / 2 + d3_k[g] / (2R);  k head: + (sum_r d3_q[gR + r] + d3_k) / 2.
     if (mean) {
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
@@ -234,7 +251,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       const int nsrc = is_q ? 1 : a.R;
       for (int sidx = 0; sidx < nsrc; ++sidx) {
         const int col = is_q ? a.e_q + g * DH : (g * a.R + sidx) * DH;
-        const bf16_t *p = lat + rowc * a.n_lat + col + half * 8;
+        const bf16_t *p = lat + rowc * a.src_stride + col + half * 8;
         bf16x8 mf[8];
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk)
@@ -243,14 +260,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
-            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(is_q ? id_half[j] : id_grp[j], mf[2 * nt + j], acc[nt], 0,
-                                                              0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp[j], mf[2 * nt + j], acc[nt], 0, 0, 0);
       }
     }
 
     // ---- per token: norm, temperature, RoPE.  Lane (l32, half) holds channels
     //      o = 32*nt + 8*rg + 4*half + e of token l32 in acc[nt][4*rg + e].
-    if (a.flags & CCA_QK_NORM) {
+    if (!BWD && (a.flags & CCA_QK_NORM)) {
       float ssq = 0.f;
 #pragma unroll
       for (int nt = 0; nt < 4; ++nt)
@@ -263,10 +279,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[nt][r] *= mul;
       if (rnorm && half == 0 && row < a.rows) rnorm[row * NH + head] = mul;
-    } else if (rnorm && half == 0 && row < a.rows) {
+    } else if (!BWD && rnorm && half == 0 && row < a.rows) {
       rnorm[row * NH + head] = 1.f;
     }
-    if (a.flags & CCA_ROPE) {
+    if (!BWD && (a.flags & CCA_ROPE)) {
       const int thi = tpos >> 7, tlo = tpos & 127;
 #pragma unroll
       for (int nt = 0; nt < 2; ++nt)
@@ -333,19 +349,65 @@ __global__ __launch_bounds__(256) void split_copy_kernel(const unsigned char *__
   }
 }
 
-template <int D>
-hipError_t launch_main(const FusedArgs &a, const void *lat, const void *wc, const float2 *ropeA, const float2 *ropeB,
-                       const float *temp, void *q, void *k, void *v, float *rnorm, int grid, hipStream_t s) {
+template <int D, bool BWD>
+hipError_t launch_main(const FusedArgs &a, const void *lat, const void *vsrc, const void *wc, const float2 *ropeA,
+                       const float2 *ropeB, const float *temp, void *q, void *k, void *v, float *rnorm, int grid,
+                       hipStream_t s) {
   constexpr size_t smem = (size_t)DH * D * 16 * 16;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<D>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<D, BWD>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  prologue_fused_kernel<D><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const u32x4 *)wc, ropeA, ropeB, temp,
-                                                  (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
+  prologue_fused_kernel<D, BWD><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc, (const u32x4 *)wc,
+                                                       ropeA, ropeB, temp, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
+  return hipGetLastError();
+}
+
+// Tokens per workgroup: each workgroup first loads its head's filter (about one tile's worth of time), and one
+// workgroup fits per CU, so minimise rounds-on-256-CUs x (1 + tiles per wavefront).  Returns the grid size.
+int plan_grid(const Dims &d, FusedArgs &a) {
+  const int NH = d.Hq + d.Hk;
+  long long best_cost = -1, tok_blocks = 0;
+  for (int tpw = 1; tpw <= MAX_TILES_PER_WAVE; ++tpw) {
+    const long long blocks = (d.rows() + 256 * tpw - 1) / (256 * tpw);
+    const long long cost = ((blocks * NH + 255) / 256) * (1 + tpw);
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      a.tiles_per_wave = tpw;
+      tok_blocks = blocks;
+    }
+  }
+  a.n_conv_blocks = (int)(tok_blocks * NH);
+  const long long v_chunks = d.rows() * (d.e_kv / 8);
+  const int v_blocks = (int)((v_chunks + NT * 4 - 1) / (NT * 4));
+  return a.n_conv_blocks + v_blocks;
+}
+
+struct FusedScratch {
+  bf16_t *wc;
+  float2 *ropeA, *ropeB;
+  size_t bytes;
+};
+FusedScratch carve(const Dims &d, void *scratch, int D) {
+  const int NH = d.Hq + d.Hk, n_thi = (d.T + 127) / 128;
+  const size_t wc_bytes = ((size_t)NH * DH * D * DH * 2 + 255) / 256 * 256;
+  const size_t ra_bytes = ((size_t)n_thi * (DH / 2) * 8 + 255) / 256 * 256;
+  const size_t rb_bytes = (size_t)(DH / 2) * 128 * 8;
+  char *base = static_cast<char *>(scratch);
+  return FusedScratch{reinterpret_cast<bf16_t *>(base), reinterpret_cast<float2 *>(base + wc_bytes),
+                      reinterpret_cast<float2 *>(base + wc_bytes + ra_bytes), wc_bytes + ra_bytes + rb_bytes};
+}
+
+hipError_t run_setup(const Dims &d, const FusedArgs &a, const cca_weights &w, const FusedScratch &fs, int D,
+                     bool transposed, hipStream_t s) {
+  const int NH = d.Hq + d.Hk, n_thi = (d.T + 127) / 128;
+  const int n_fold = (NH * DH * DH + 255) / 256;
+  const int n_rope = (n_thi * (DH / 2) + (DH / 2) * 128 + 255) / 256;
+  prologue_setup_kernel<<<n_fold + n_rope, 256, 0, s>>>(a, D, (const bf16_t *)w.w_conv_seq, (const bf16_t *)w.w_conv_ch,
+                                                        fs.wc, fs.ropeA, fs.ropeB, n_fold, n_thi, transposed ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -381,51 +443,54 @@ bool prologue_fused_supported(const Dims &d) {
 
 size_t prologue_fused_scratch_bytes(const Dims &d) {
   if (!prologue_fused_supported(d)) return 0;
-  const size_t wc = (size_t)(d.Hq + d.Hk) * DH * taps(d) * DH * 2;
-  const size_t ra = (size_t)((d.T + 127) / 128) * (DH / 2) * 8, rb = (size_t)(DH / 2) * 128 * 8;
-  return (wc + 255) / 256 * 256 + (ra + 255) / 256 * 256 + rb;
+  return carve(d, nullptr, taps(d)).bytes;
 }
 
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
                                float *rnorm, void *scratch, hipStream_t s) {
   const int D = taps(d);
-  const int NH = d.Hq + d.Hk;
-  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1, d.rope_base};
-  const int n_thi = (d.T + 127) / 128;
-  const size_t wc_bytes = ((size_t)NH * DH * D * DH * 2 + 255) / 256 * 256;
-  const size_t ra_bytes = ((size_t)n_thi * (DH / 2) * 8 + 255) / 256 * 256;
-  char *base = static_cast<char *>(scratch);
-  bf16_t *wc = reinterpret_cast<bf16_t *>(base);
-  float2 *ropeA = reinterpret_cast<float2 *>(base + wc_bytes);
-  float2 *ropeB = reinterpret_cast<float2 *>(base + wc_bytes + ra_bytes);
-
-  const int n_fold = (NH * DH * DH + 255) / 256;
-  const int n_rope = (n_thi * (DH / 2) + (DH / 2) * 128 + 255) / 256;
-  prologue_setup_kernel<<<n_fold + n_rope, 256, 0, s>>>(a, D, (const bf16_t *)w.w_conv_seq, (const bf16_t *)w.w_conv_ch,
-                                                        wc, ropeA, ropeB, n_fold, n_thi);
-  hipError_t e = hipGetLastError();
+  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1,
+              d.rope_base, d.n_lat, d.e_q, d.e_kv, d.n_lat, d.e_kv, 0.5f, 0.5f / (float)d.R};
+  const FusedScratch fs = carve(d, scratch, D);
+  hipError_t e = run_setup(d, a, w, fs, D, false, s);
   if (e != hipSuccess) return e;
-
-  // Tokens per workgroup: each workgroup first loads its head's filter (about one tile's worth of time), and
-  // one workgroup fits per CU, so minimise rounds-on-256-CUs x (1 + tiles per wavefront).
-  long long best_cost = -1, tok_blocks = 0;
-  for (int tpw = 1; tpw <= MAX_TILES_PER_WAVE; ++tpw) {
-    const long long blocks = (d.rows() + 256 * tpw - 1) / (256 * tpw);
-    const long long cost = ((blocks * NH + 255) / 256) * (1 + tpw);
-    if (best_cost < 0 || cost < best_cost) {
-      best_cost = cost;
-      a.tiles_per_wave = tpw;
-      tok_blocks = blocks;
-    }
-  }
-  a.n_conv_blocks = (int)(tok_blocks * NH);
-  const long long v_chunks = d.rows() * (d.e_kv / 8);
-  const int v_blocks = (int)((v_chunks + NT * 4 - 1) / (NT * 4));
-  const int grid = a.n_conv_blocks + v_blocks;
+  const int grid = plan_grid(d, a);
+  const bf16_t *vsrc = (const bf16_t *)lat + d.e_q + d.e_kv;
   switch (D) {
-    case 1: return launch_main<1>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, rnorm, grid, s);
-    case 2: return launch_main<2>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, rnorm, grid, s);
-    default: return launch_main<3>(a, lat, wc, ropeA, ropeB, w.temp, q, k, v, rnorm, grid, s);
+    case 1: return launch_main<1, false>(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
+    case 2: return launch_main<2, false>(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
+    default: return launch_main<3, false>(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
+  }
+}
+
+// ---- adjoint: d3 (B*T, e_q+e_kv), d_v -> d_lat.  `scratch` as for the forward; the RoPE tables it leaves
+// behind are the ones the pointwise backward kernel reads, so this runs its set-up first (see fused_bwd_setup).
+hipError_t prologue_fused_bwd_setup(const Dims &d, const cca_weights &w, void *scratch, const float2 **ropeA,
+                                    const float2 **ropeB, hipStream_t s) {
+  const int D = taps(d);
+  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1,
+              d.rope_base, 0, 0, 0, 0, 0, 0.f, 0.f};
+  const FusedScratch fs = carve(d, scratch, D);
+  *ropeA = fs.ropeA;
+  *ropeB = fs.ropeB;
+  return run_setup(d, a, w, fs, D, true, s);
+}
+
+hipError_t prologue_fused_bwd_dlat(const Dims &d, const void *d3, const void *d_v, void *d_lat, void *scratch,
+                                   hipStream_t s) {
+  const int D = taps(d);
+  const int ld = d.e_q + d.e_kv;
+  // only the qk-mean and value-shift flags matter to the adjoint kernel
+  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(),
+              d.flags & (CCA_QK_MEAN | CCA_V_SHIFT), 0, 1, d.rope_base, ld, d.n_lat, d.n_lat, d.e_kv, d.n_lat,
+              0.5f / (float)d.R, 0.5f};
+  const FusedScratch fs = carve(d, scratch, D);
+  const int grid = plan_grid(d, a);
+  bf16_t *dl = (bf16_t *)d_lat;
+  switch (D) {
+    case 1: return launch_main<1, true>(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
+    case 2: return launch_main<2, true>(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
+    default: return launch_main<3, true>(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
   }
 }
 

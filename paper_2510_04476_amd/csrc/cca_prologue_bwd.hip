@@ -1,0 +1,397 @@
+// Backward of the fused latent-space prologue for gfx950, bf16 storage,
+// d_h = 128 (adjoint of the convolution, qk-mean and value-shift equations
+// and of the first two lines of the final equation block of Sec. 2.2; the
+// paper states these steps forward only).
+//
+//   1. pointwise kernel: undoes RoPE (a rotation: rotate back) and the norm /
+//      temperature step on the gradients of q and k.  With y = x * mul,
+//      mul = sqrt(d_h) beta / |x|:   dx = mul * (dy - y <y,dy> / (d_h beta^2)),
+//      where y is the saved q / k (the dot product is invariant under RoPE, so
+//      it is taken on the rotated vectors), mul the saved norm factor.  Result
+//      d3 (B*T, e_q + e_kv) bf16 = gradient of the conv2 output; also
+//      <dk,k> per (token, KV head), whose sum over tokens is d temp.
+//   2. d_lat: the forward kernel run as its own adjoint (cca_prologue.hip).
+//   3. filter gradients: dWc[h,o,d,i] = sum_t d3[t,h,o] * u[t-(D-1-d),h,i] for
+//      the folded filter Wc of width D = k_seq + k_ch - 1, as an MFMA
+//      contraction over tokens (both operands fetched from row-major LDS tiles
+//      with the transposing read), split over chunks of tokens into fp32
+//      partial sums that a second kernel adds in a fixed order; Wc is bilinear
+//      in (w0, w1), so d w1[h,o,i,j] = sum_jj dWc[h,o,j+jj,i] w0[c,jj] and
+//      d w0[c,jj] = sum_o sum_j dWc[h,o,j+jj,i] w1[h,o,i,j].
+// No atomics anywhere: a repeated call gives the same bits.
+#include "cca_internal.h"
+
+namespace cca {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+
+// from cca_prologue.hip
+bool prologue_fused_supported(const Dims &d);
+size_t prologue_fused_scratch_bytes(const Dims &d);
+hipError_t prologue_fused_bwd_setup(const Dims &d, const cca_weights &w, void *scratch, const float2 **ropeA,
+                                    const float2 **ropeB, hipStream_t s);
+hipError_t prologue_fused_bwd_dlat(const Dims &d, const void *d3, const void *d_v, void *d_lat, void *scratch,
+                                   hipStream_t s);
+
+namespace {
+
+constexpr int DH = 128;
+constexpr int ROW = DH * 2 + 16;  // padded LDS row of one token
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+struct PointArgs {
+  int T, Hq, Hk, e_q, e_kv;
+  long long rows;
+  uint32_t flags;
+};
+
+// ---------------------------------------------------------------------------
+// 1. pointwise: 16 lanes per (token, head); lane j holds channels 4j..4j+3 and 64+4j..64+4j+3, so the
+//    rotate-half partner sits in the same lane and the row dot product is a 16-lane butterfly.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pro_bwd_point_kernel(PointArgs a, const bf16_t *__restrict__ q,
+                                                           const bf16_t *__restrict__ k,
+                                                           const float *__restrict__ rnorm,
+                                                           const float *__restrict__ temp,
+                                                           const bf16_t *__restrict__ dq, const bf16_t *__restrict__ dk,
+                                                           const float2 *__restrict__ ropeA,
+                                                           const float2 *__restrict__ ropeB, bf16_t *__restrict__ d3,
+                                                           float *__restrict__ rowdot) {
+  const int NH = a.Hq + a.Hk;
+  const long long item = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);  // row * NH + head
+  const int j = threadIdx.x & 15;
+  const bool live = item < a.rows * NH;
+  const long long it = live ? item : 0;
+  const long long row = it / NH;
+  const int head = (int)(it % NH);
+  const int tpos = (int)(row % a.T);
+  const bool is_q = head < a.Hq;
+  const int g = head - a.Hq;
+  const bf16_t *y5 = is_q ? q + (row * a.Hq + head) * DH : k + (row * a.Hk + g) * DH;
+  const bf16_t *dy5 = is_q ? dq + (row * a.Hq + head) * DH : dk + (row * a.Hk + g) * DH;
+  const u32x2 ya = *reinterpret_cast<const u32x2 *>(y5 + 4 * j), yb = *reinterpret_cast<const u32x2 *>(y5 + 64 + 4 * j);
+  const u32x2 da = *reinterpret_cast<const u32x2 *>(dy5 + 4 * j), db = *reinterpret_cast<const u32x2 *>(dy5 + 64 + 4 * j);
+  float y[8] = {bf_lo(ya.x), bf_hi(ya.x), bf_lo(ya.y), bf_hi(ya.y), bf_lo(yb.x), bf_hi(yb.x), bf_lo(yb.y), bf_hi(yb.y)};
+  float dy[8] = {bf_lo(da.x), bf_hi(da.x), bf_lo(da.y), bf_hi(da.y), bf_lo(db.x), bf_hi(db.x), bf_lo(db.y), bf_hi(db.y)};
+  float dot = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) dot = fmaf(y[e], dy[e], dot);
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+  float mul = 1.f, c = 0.f;
+  if (a.flags & CCA_QK_NORM) {
+    mul = rnorm[row * NH + head];
+    const float beta2 = (!is_q && (a.flags & CCA_KEY_TEMP)) ? expf(2.f * temp[g]) : 1.f;
+    c = dot / ((float)DH * beta2);
+  }
+  if (live && !is_q && rowdot && j == 0) rowdot[row * a.Hk + g] = dot;
+  float r[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = dy[e] - y[e] * c;
+  if (a.flags & CCA_ROPE) {
+    const int thi = tpos >> 7, tlo = tpos & 127;
+    const f32x4 *pa = reinterpret_cast<const f32x4 *>(ropeA + thi * (DH / 2) + 4 * j);
+    const f32x4 *pb = reinterpret_cast<const f32x4 *>(ropeB + (j * 128 + tlo) * 4);
+    const f32x4 a01 = pa[0], a23 = pa[1], b01 = pb[0], b23 = pb[1];
+    const float ca[4] = {a01.x, a01.z, a23.x, a23.z}, sa[4] = {a01.y, a01.w, a23.y, a23.w};
+    const float cb[4] = {b01.x, b01.z, b23.x, b23.z}, sb[4] = {b01.y, b01.w, b23.y, b23.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float cs = ca[e] * cb[e] - sa[e] * sb[e];
+      const float sn = sa[e] * cb[e] + ca[e] * sb[e];
+      // forward: (x1, x2) -> (x1 c - x2 s, x2 c + x1 s); the adjoint rotates back
+      const float g1 = r[e], g2 = r[e + 4];
+      r[e] = g1 * cs + g2 * sn;
+      r[e + 4] = g2 * cs - g1 * sn;
+    }
+  }
+  if (live) {
+    bf16_t *dst = d3 + row * (a.e_q + a.e_kv) + (is_q ? head * DH : a.e_q + g * DH);
+    u32x2 lo, hi;
+    lo.x = pack2(r[0] * mul, r[1] * mul);
+    lo.y = pack2(r[2] * mul, r[3] * mul);
+    hi.x = pack2(r[4] * mul, r[5] * mul);
+    hi.y = pack2(r[6] * mul, r[7] * mul);
+    *reinterpret_cast<u32x2 *>(dst + 4 * j) = lo;
+    *reinterpret_cast<u32x2 *>(dst + 64 + 4 * j) = hi;
+  }
+}
+
+// out[col] = sum over rows of src[row*ncol + col]; one workgroup per column, fixed summation order
+__global__ __launch_bounds__(256) void column_sum_f32_kernel(const float *__restrict__ src, long long rows, int ncol,
+                                                            float *__restrict__ out) {
+  __shared__ float red[256];
+  const int col = blockIdx.x, tid = threadIdx.x;
+  float acc = 0.f;
+  for (long long r = tid; r < rows; r += 256) acc += src[r * ncol + col];
+  red[tid] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (tid < s) red[tid] += red[tid + s];
+    __syncthreads();
+  }
+  if (tid == 0) out[col] = red[0];
+}
+
+// ---------------------------------------------------------------------------
+// 3. folded-filter gradient, partial sums per chunk of tokens.
+//    Workgroup = (head, chunk of `chunk` tokens of one sequence), 8 wavefronts; wavefront w owns output-channel
+//    tiles 2*(w&1), 2*(w&1)+1 and input-channel tile w>>1, for all D taps.
+// ---------------------------------------------------------------------------
+// MFMA operand fragment of the TRANSPOSE of a row-major LDS tile: lane (c = lane & 31, half) receives
+// tile[r0 + 4*half + {0..3}][c0 + c] and tile[r0 + 8 + 4*half + {0..3}][c0 + c].  `base` already holds the
+// per-lane part  (4*half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2.
+__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int c0) {
+  const unsigned char *p = base + r0 * ROW + c0 * 2;
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)p);
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(p + 8 * ROW));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+constexpr int DW_NT = 512, DW_BT = 64;  // threads, tokens per LDS tile
+
+template <int D>
+__global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__restrict__ d3, const bf16_t *__restrict__ lat,
+                                                           float *__restrict__ part, int T, int Hq, int Hk, int e_q,
+                                                           int e_kv, int n_lat, int chunk, int chunks_per_seq) {
+  constexpr int UROWS = DW_BT + D - 1;
+  constexpr int DY_TILE = DW_BT * ROW, U_TILE = UROWS * ROW;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (DY_TILE + U_TILE)];
+  unsigned char *const sDy = smem, *const sU = smem + 2 * DY_TILE;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int NH = Hq + Hk;
+  const int head = blockIdx.x % NH, cid = blockIdx.x / NH;  // cid = b * chunks_per_seq + chunk index
+  const int b = cid / chunks_per_seq, t_begin = (cid % chunks_per_seq) * chunk;
+  const int t_end = min(T, t_begin + chunk);
+  const int ch0 = head < Hq ? head * DH : e_q + (head - Hq) * DH;
+  const int ld3 = e_q + e_kv;
+  const bf16_t *const d3b = d3 + (long long)b * T * ld3 + ch0;
+  const bf16_t *const ub = lat + (long long)b * T * n_lat + ch0;
+
+  constexpr int DY_CHUNKS = DW_BT * 16, U_CHUNKS = UROWS * 16;  // 16-byte chunks per tile
+  constexpr int DY_PER = DY_CHUNKS / DW_NT, U_PER = (U_CHUNKS + DW_NT - 1) / DW_NT;
+  u32x4 rdy[DY_PER], ru[U_PER];
+  auto load_tile = [&](int t0) {
+#pragma unroll
+    for (int i = 0; i < DY_PER; ++i) {
+      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      const int t = t0 + r;
+      u32x4 val = {0, 0, 0, 0};
+      if (t < t_end) val = *reinterpret_cast<const u32x4 *>(d3b + (long long)t * ld3 + c * 8);
+      rdy[i] = val;
+    }
+#pragma unroll
+    for (int i = 0; i < U_PER; ++i) {
+      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      const int t = t0 - (D - 1) + r;  // row r of the tile holds token t0 - (D-1) + r
+      u32x4 val = {0, 0, 0, 0};
+      if (id < U_CHUNKS && t >= 0 && t < t_end) val = *reinterpret_cast<const u32x4 *>(ub + (long long)t * n_lat + c * 8);
+      ru[i] = val;
+    }
+  };
+  auto store_tile = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < DY_PER; ++i) {
+      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      *reinterpret_cast<u32x4 *>(sDy + buf * DY_TILE + r * ROW + c * 16) = rdy[i];
+    }
+#pragma unroll
+    for (int i = 0; i < U_PER; ++i) {
+      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      if (id < U_CHUNKS) *reinterpret_cast<u32x4 *>(sU + buf * U_TILE + r * ROW + c * 16) = ru[i];
+    }
+  };
+
+  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+  const int o_tile0 = 2 * (wave & 1), i_tile = wave >> 1;
+
+  f32x16 acc[2][D];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[x][d][r] = 0.f;
+
+  const int ntiles = (t_end - t_begin + DW_BT - 1) / DW_BT;
+  load_tile(t_begin);
+  store_tile(0);
+  if (ntiles > 1) load_tile(t_begin + DW_BT);
+  __syncthreads();
+  for (int it = 0; it < ntiles; ++it) {
+    const int buf = it & 1;
+    if (it + 1 < ntiles) store_tile(buf ^ 1);
+    if (it + 2 < ntiles) load_tile(t_begin + (it + 2) * DW_BT);
+    const unsigned char *dyp = sDy + buf * DY_TILE + tr_off, *up = sU + buf * U_TILE + tr_off;
+#pragma unroll
+    for (int kk = 0; kk < DW_BT / 16; ++kk) {
+      bf16x8 fo[2], fu[D];
+#pragma unroll
+      for (int x = 0; x < 2; ++x) fo[x] = tr_frag(dyp, kk * 16, (o_tile0 + x) * 32);
+#pragma unroll
+      for (int d = 0; d < D; ++d) fu[d] = tr_frag(up, kk * 16 + d, i_tile * 32);  // token t - (D-1-d)
+#pragma unroll
+      for (int x = 0; x < 2; ++x)
+#pragma unroll
+        for (int d = 0; d < D; ++d) acc[x][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[x], fu[d], acc[x][d], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  // acc[x][d][r]: o = (o_tile0 + x)*32 + 8*(r/4) + 4*half + r%4,  i = i_tile*32 + l32
+  float *out = part + (long long)blockIdx.x * DH * D * DH;  // [o][d][i] of (cid, head); blockIdx.x = cid*NH + head
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int o = (o_tile0 + x) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        out[(o * D + d) * DH + i_tile * 32 + l32] = acc[x][d][r];
+      }
+}
+
+// dwc[h][o][d][i] = sum over chunks (fixed order); then d w1[h,o,i,j] = sum_jj dwc[h,o,j+jj,i] * w0[c(h,i),jj]
+__global__ __launch_bounds__(256) void pro_bwd_unfold_w1_kernel(const float *__restrict__ part, int n_chunks, int NH,
+                                                               int D, int ks, int kc, int use_w0,
+                                                               const bf16_t *__restrict__ w0, float *__restrict__ dwc,
+                                                               bf16_t *__restrict__ dw1) {
+  const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (h*DH + o)*DH + i
+  if (id >= (long long)NH * DH * DH) return;
+  const int i = (int)(id % DH), o = (int)((id / DH) % DH), h = (int)(id / (DH * DH));
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};  // D <= 4
+  for (int c = 0; c < n_chunks; ++c) {
+    const float *p = part + (((long long)c * NH + h) * DH + o) * D * DH + i;
+    for (int d = 0; d < D; ++d) sum[d] += p[d * DH];
+  }
+  for (int d = 0; d < D; ++d) dwc[(((long long)h * DH + o) * D + d) * DH + i] = sum[d];
+  if (!dw1) return;
+  for (int j = 0; j < kc; ++j) {
+    float acc = 0.f;
+    for (int jj = 0; jj < ks; ++jj) {
+      const float f0 = use_w0 ? bf16_to_f32(w0[(long long)(h * DH + i) * ks + jj]) : 1.f;
+      acc = fmaf(sum[j + jj], f0, acc);
+    }
+    dw1[(((long long)h * DH + o) * DH + i) * kc + j] = f32_to_bf16(acc);
+  }
+}
+
+// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j]
+__global__ __launch_bounds__(128) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
+                                                               const bf16_t *__restrict__ w1, bf16_t *__restrict__ dw0) {
+  const int h = blockIdx.x, i = threadIdx.x;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int o = 0; o < DH; ++o) {
+    const float *p = dwc + (((long long)h * DH + o) * D) * DH + i;
+    const bf16_t *wp = w1 + (((long long)h * DH + o) * DH + i) * kc;
+    for (int j = 0; j < kc; ++j) {
+      const float f1 = bf16_to_f32(wp[j]);
+      for (int jj = 0; jj < ks; ++jj) acc[jj] = fmaf(p[(j + jj) * DH], f1, acc[jj]);
+    }
+  }
+  for (int jj = 0; jj < ks; ++jj) dw0[(long long)(h * DH + i) * ks + jj] = f32_to_bf16(acc[jj]);
+}
+
+int taps(const Dims &d) { return ((d.flags & CCA_CONV_SEQ) ? d.k_seq : 1) + d.k_ch - 1; }
+
+// tokens per chunk of the filter-gradient kernel: the largest of 512..64 that still gives >= 256 workgroups
+int dwc_chunk(const Dims &d) {
+  const int NH = d.Hq + d.Hk;
+  for (int c = 512; c > 64; c >>= 1)
+    if ((long long)d.B * ((d.T + c - 1) / c) * NH >= 256) return c;
+  return 64;
+}
+
+struct BwdScratch {
+  size_t fused, d3, rowdot, part, dwc, total;  // byte offsets
+};
+BwdScratch bwd_layout(const Dims &d) {
+  BwdScratch L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
+  const int D = taps(d), NH = d.Hq + d.Hk, chunk = dwc_chunk(d);
+  const size_t n_chunks = (size_t)d.B * ((d.T + chunk - 1) / chunk);
+  L.fused = take(prologue_fused_scratch_bytes(d));
+  L.d3 = take((size_t)d.rows() * (d.e_q + d.e_kv) * 2);
+  L.rowdot = take((size_t)d.rows() * d.Hk * 4);
+  L.part = take(n_chunks * NH * DH * D * DH * 4);
+  L.dwc = take((size_t)NH * DH * D * DH * 4);
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d); }
+
+size_t prologue_bwd_fused_scratch_bytes(const Dims &d) {
+  return prologue_bwd_fused_supported(d) ? bwd_layout(d).total : 0;
+}
+
+hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
+                                   const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                   const cca_grads *gr, void *scratch, hipStream_t s) {
+  const BwdScratch L = bwd_layout(d);
+  char *base = static_cast<char *>(scratch);
+  bf16_t *d3 = reinterpret_cast<bf16_t *>(base + L.d3);
+  float *rowdot = reinterpret_cast<float *>(base + L.rowdot);
+  float *part = reinterpret_cast<float *>(base + L.part);
+  float *dwc = reinterpret_cast<float *>(base + L.dwc);
+  const int D = taps(d), NH = d.Hq + d.Hk;
+
+  const float2 *ropeA, *ropeB;
+  hipError_t e = prologue_fused_bwd_setup(d, w, base + L.fused, &ropeA, &ropeB, s);
+  if (e != hipSuccess) return e;
+
+  const bool want_temp = (d.flags & CCA_KEY_TEMP) && gr && gr->temp;
+  PointArgs pa{d.T, d.Hq, d.Hk, d.e_q, d.e_kv, d.rows(), d.flags};
+  const long long items = d.rows() * NH;
+  pro_bwd_point_kernel<<<(unsigned)((items + 15) / 16), 256, 0, s>>>(pa, (const bf16_t *)q, (const bf16_t *)k, rnorm,
+                                                                    w.temp, (const bf16_t *)d_q, (const bf16_t *)d_k,
+                                                                    ropeA, ropeB, d3, want_temp ? rowdot : nullptr);
+  if (want_temp) column_sum_f32_kernel<<<d.Hk, 256, 0, s>>>(rowdot, d.rows(), d.Hk, gr->temp);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  e = prologue_fused_bwd_dlat(d, d3, d_v, d_lat, base + L.fused, s);
+  if (e != hipSuccess) return e;
+
+  const bool want_w1 = gr && gr->w_conv_ch;  // CONV_CH is on whenever this path runs
+  const bool want_w0 = (d.flags & CCA_CONV_SEQ) && gr && gr->w_conv_seq;
+  if (!want_w1 && !want_w0) return hipSuccess;
+  const int chunk = dwc_chunk(d), cps = (d.T + chunk - 1) / chunk, n_chunks = d.B * cps;
+#define DWC(DD)                                                                                                     \
+  pro_bwd_dwc_kernel<DD><<<n_chunks * NH, DW_NT, 0, s>>>(d3, (const bf16_t *)lat, part, d.T, d.Hq, d.Hk, d.e_q, d.e_kv, \
+                                                         d.n_lat, chunk, cps)
+  switch (D) {
+    case 1: DWC(1); break;
+    case 2: DWC(2); break;
+    default: DWC(3); break;
+  }
+#undef DWC
+  const int ks = (d.flags & CCA_CONV_SEQ) ? d.k_seq : 1;
+  pro_bwd_unfold_w1_kernel<<<(NH * DH * DH + 255) / 256, 256, 0, s>>>(part, n_chunks, NH, D, ks, d.k_ch,
+                                                                     (d.flags & CCA_CONV_SEQ) ? 1 : 0,
+                                                                     (const bf16_t *)w.w_conv_seq, dwc,
+                                                                     want_w1 ? (bf16_t *)gr->w_conv_ch : nullptr);
+  if (want_w0)
+    pro_bwd_unfold_w0_kernel<<<NH, DH, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
+                                               (bf16_t *)gr->w_conv_seq);
+  return hipGetLastError();
+}
+
+}  // namespace cca

@@ -1,0 +1,185 @@
+"""GPU parity of cca_backward (through the C ABI) against the fp64 oracle's hand-derived adjoint on the same
+seeded inputs.  The oracle recomputes its own forward in fp64; the HIP path runs cca_forward then cca_backward.
+
+Tolerances.  fp32 storage: 1e-5 relative (rel-L2, and max-abs against the largest reference magnitude).  bf16
+storage: the benchmark spec's 1e-2 rel-L2; every gradient passes through up to six tensors stored in bf16 (d_o, d_q /
+d_k / d_v, the gradient entering the convolutions, d_lat, the result; P and dS inside attention), each adding
+about 1e-3 rms relative error, so ~3e-3 is expected.  max-abs is bounded relative to the largest reference
+magnitude (gradients are not O(1) quantities): 2e-2 * max|ref|."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_04476_amd as P
+from paper_2510_04476_amd import binding as B
+from oracle import cca_oracle as O
+from synth_inputs import WORKLOADS, make_inputs, make_upstream_grad, round_to_bf16, sample_rows
+from util import errors, to_np
+
+pytestmark = pytest.mark.gpu
+
+GRADS = ("d_x", "d_w_down", "d_w_conv_seq", "d_w_conv_ch", "d_temp", "d_w_out")
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def oracle_backward(w, inp, d_out, rows=None, **kw):
+    flags = {}
+    if not w.get("paper_flags", True):
+        flags = dict(use_conv_seq=False, use_conv_ch=False, use_qk_mean=False, use_v_shift=False,
+                     use_qk_norm=False, use_key_temp=False, use_rope=False)
+    flags.update(kw)
+    return O.cca_backward(inp["x"], inp["w_down"], inp["w_conv_seq"], inp["w_conv_ch"], inp["temp"], inp["w_out"],
+                          d_out, n_q_heads=w["Hq"], n_kv_heads=w["Hk"], head_dim=w["dh"], rows=rows, **flags)
+
+
+def gpu_backward(w, inp, d_out, **override):
+    cfg = P.config_from_workload(w, **override)
+    x, wt = P.weights_to_device(cfg, inp)
+    saved = P.CCASaved.allocate(cfg, x.device)
+    P.cca_forward(cfg, wt, x, saved=saved)
+    g = torch.from_numpy(d_out).to("cuda", cfg.torch_dtype)
+    d_x, grads = P.cca_backward(cfg, wt, x, saved, g)
+    torch.cuda.synchronize()
+    return dict(d_x=d_x, d_w_down=grads.w_down, d_w_conv_seq=grads.w_conv_seq, d_w_conv_ch=grads.w_conv_ch,
+                d_temp=grads.temp, d_w_out=grads.w_out), (cfg, x, wt, saved, g)
+
+
+def compare(got, ref, dtype, skip=()):
+    rtol, arel = (1e-2, 2e-2) if dtype == "bf16" else (1e-5, 1e-5)
+    res = {}
+    for key in GRADS:
+        if key in skip:
+            continue
+        rel, mx = errors(to_np(got[key]), ref[key])
+        scale = float(np.abs(ref[key]).max())
+        if key == "d_temp":
+            # one number per KV head, a signed sum over all tokens that cancels heavily: its error is measured
+            # against the sum of the magnitudes of its terms, not against the cancelled result
+            err = np.abs(to_np(got[key]) - ref[key])
+            res[key] = (rel, float((err / np.maximum(ref["d_temp_abs"], 1e-300)).max()))
+            floor = 1e-6 if dtype == "bf16" else 1e-9  # T = 1: every term is zero by construction (see below)
+            assert (err <= rtol * ref["d_temp_abs"] + floor).all(), f"d_temp: err={err}, scale={ref['d_temp_abs']}"
+            continue
+        if scale == 0.0:
+            # a gradient that is exactly zero by construction (T = 1: the softmax over one key is constant, so
+            # nothing reaches q and k); the HIP path may leave rounding residue of o = bf16(v) there
+            res[key] = (0.0, mx)
+            assert mx <= (1e-6 if dtype == "bf16" else 1e-9), f"{key}: reference is zero, max_abs={mx:.3e}"
+            continue
+        res[key] = (rel, mx / scale)
+        assert rel <= rtol and mx <= arel * scale, f"{key}: rel_l2={rel:.3e} (<= {rtol}), max_abs={mx:.3e} (<= {arel * scale:.3e})"
+    return res
+
+
+SMALL = [
+    dict(B=2, T=333, E=256, Hq=4, Hk=2, dh=32, k_seq=2, k_ch=2, dtype="f32", paper_flags=True),
+    dict(B=1, T=257, E=256, Hq=2, Hk=1, dh=64, k_seq=3, k_ch=2, dtype="f32", paper_flags=True),
+    dict(B=2, T=2, E=256, Hq=2, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="f32", paper_flags=True),
+    dict(B=2, T=777, E=1024, Hq=4, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=515, E=1024, Hq=8, Hk=2, dh=128, k_seq=2, k_ch=1, dtype="bf16", paper_flags=True),
+    dict(B=3, T=130, E=384, Hq=3, Hk=3, dh=128, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=1, E=256, Hq=2, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    # bf16 shapes off the MFMA paths (generic kernels with bf16 storage)
+    dict(B=2, T=200, E=512, Hq=4, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=150, E=1024, Hq=4, Hk=2, dh=128, k_seq=3, k_ch=4, dtype="bf16", paper_flags=True),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL)))
+def test_backward_small_shapes(i):
+    w = SMALL[i]
+    say("case backward small", i, w)
+    inp = make_inputs(w, seed=40 + i, conv_visible=True)
+    d_out = make_upstream_grad(w, seed=1)
+    got, _ = gpu_backward(w, inp, d_out)
+    ref = oracle_backward(w, inp, d_out)
+    say(compare(got, ref, w["dtype"]))
+
+
+def test_backward_tiny_fp32_literal():
+    w = WORKLOADS["tiny_fp32"]
+    say("case backward tiny_fp32")
+    inp = make_inputs(w, seed=0)
+    d_out = make_upstream_grad(w, seed=1)
+    got, _ = gpu_backward(w, inp, d_out)
+    say(compare(got, oracle_backward(w, inp, d_out), "f32"))
+
+
+FLAG_CASES = {
+    "no_qk_mean": (B.CCA_FLAGS_PAPER & ~B.CCA_QK_MEAN, dict(use_qk_mean=False), ()),
+    "no_conv_seq": (B.CCA_FLAGS_PAPER & ~B.CCA_CONV_SEQ, dict(use_conv_seq=False), ("d_w_conv_seq",)),
+    "no_conv_ch": (B.CCA_FLAGS_PAPER & ~B.CCA_CONV_CH, dict(use_conv_ch=False), ("d_w_conv_ch",)),
+    "no_v_shift": (B.CCA_FLAGS_PAPER & ~B.CCA_V_SHIFT, dict(use_v_shift=False), ()),
+    "no_norm": (B.CCA_FLAGS_PAPER & ~(B.CCA_QK_NORM | B.CCA_KEY_TEMP), dict(use_qk_norm=False, use_key_temp=False),
+                ("d_temp",)),
+    "no_temp": (B.CCA_FLAGS_PAPER & ~B.CCA_KEY_TEMP, dict(use_key_temp=False), ("d_temp",)),
+    "no_rope": (B.CCA_FLAGS_PAPER & ~B.CCA_ROPE, dict(use_rope=False), ()),
+    "rope_interleaved": (B.CCA_FLAGS_PAPER | B.CCA_ROPE_INTERLEAVED, dict(rope_interleaved=True), ()),
+    "non_causal": (B.CCA_FLAGS_PAPER & ~B.CCA_CAUSAL, dict(causal=False), ()),
+}
+
+
+@pytest.mark.parametrize("name", sorted(FLAG_CASES))
+@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128)])
+def test_backward_each_flag(name, dtype, dh):
+    flags, okw, skip = FLAG_CASES[name]
+    w = dict(B=2, T=200, E=4 * dh * 2, Hq=4, Hk=2, dh=dh, k_seq=2, k_ch=2, dtype=dtype, paper_flags=True)
+    say("case backward flag", name, w)
+    inp = make_inputs(w, seed=21, conv_visible=True)
+    d_out = make_upstream_grad(w, seed=2)
+    got, _ = gpu_backward(w, inp, d_out, flags=flags)
+    say(compare(got, oracle_backward(w, inp, d_out, **okw), dtype, skip=skip))
+
+
+def test_backward_mha_flags():
+    """Compression 1, no transforms: backward of plain GQA through the same entry point."""
+    w = dict(B=2, T=300, E=512, Hq=4, Hk=2, dh=128, k_seq=1, k_ch=1, dtype="bf16", paper_flags=False)
+    say("case backward mha", w)
+    inp = make_inputs(w, seed=5)
+    d_out = make_upstream_grad(w, seed=3)
+    got, _ = gpu_backward(w, inp, d_out)
+    say(compare(got, oracle_backward(w, inp, d_out), "bf16", skip=("d_w_conv_seq", "d_w_conv_ch", "d_temp")))
+
+
+def test_backward_is_deterministic():
+    w = SMALL[3]
+    inp = make_inputs(w, seed=43, conv_visible=True)
+    d_out = make_upstream_grad(w, seed=1)
+    got1, (cfg, x, wt, saved, g) = gpu_backward(w, inp, d_out)
+    d_x2, grads2 = P.cca_backward(cfg, wt, x, saved, g)
+    torch.cuda.synchronize()
+    assert torch.equal(got1["d_x"], d_x2)
+    for a, b in [(got1["d_w_down"], grads2.w_down), (got1["d_w_out"], grads2.w_out), (got1["d_temp"], grads2.temp),
+                 (got1["d_w_conv_seq"], grads2.w_conv_seq), (got1["d_w_conv_ch"], grads2.w_conv_ch)]:
+        assert torch.equal(a, b)
+
+
+# ---- CCGQA layout at T = 4096, dense upstream gradient, every gradient against the full oracle adjoint -------
+def test_backward_ccgqa_4k_dense():
+    w = dict(WORKLOADS["ccgqa_16k"], T=4096)
+    say("case backward ccgqa T=4096 dense d_out")
+    inp = make_inputs(w, seed=0)
+    d_out = make_upstream_grad(w, seed=1)
+    got, _ = gpu_backward(w, inp, d_out)
+    say(compare(got, oracle_backward(w, inp, d_out), "bf16"))
+
+
+# ---- config 5 at full size (T = 16384): the backward is linear in d_out, so an upstream gradient supported on a
+#      sample of rows is checked exactly: the oracle visits only those query rows, the HIP path runs its
+#      ordinary full-size launch configuration ------------------------------------------------------------------
+@pytest.mark.parametrize("conv_visible", [False, True])
+def test_backward_ccgqa_16k_sampled_rows(conv_visible):
+    w = WORKLOADS["ccgqa_16k"]
+    say("case backward ccgqa_16k, d_out on sampled rows, conv_visible", conv_visible)
+    inp = make_inputs(w, seed=0, conv_visible=conv_visible)
+    rows = sample_rows(w["T"], 96)
+    d_out = np.zeros((w["B"], w["T"], w["E"]), np.float32)
+    d_out[:, rows] = make_upstream_grad(w, seed=1)[:, rows]
+    got, _ = gpu_backward(w, inp, d_out)
+    say(compare(got, oracle_backward(w, inp, d_out, rows=rows), "bf16"))

@@ -90,3 +90,19 @@ def test_attention_backward_against_autograd():
     np.testing.assert_allclose(dq, tq.grad.numpy(), atol=1e-12)
     np.testing.assert_allclose(dk, tk.grad.numpy(), atol=1e-12)
     np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_backward_restricted_to_rows_equals_full_backward(causal):
+    """With d_out zero outside a set of rows, the rows= shortcut (skip the other query rows) must give the same
+    gradients as the full adjoint: it is what the full-size GPU parity test relies on."""
+    w = dict(B=2, T=300, E=64, Hq=4, Hk=2, dh=8, k_seq=2, k_ch=2, dtype="f32")
+    inp = make(w, seed=8)
+    rng = np.random.default_rng(4)
+    rows = np.array(sorted(rng.choice(w["T"], size=37, replace=False)))
+    d_out = np.zeros((w["B"], w["T"], w["E"]))
+    d_out[:, rows] = rng.standard_normal((w["B"], len(rows), w["E"]))
+    full = bwd(inp, w, d_out, causal=causal)
+    part = bwd(inp, w, d_out, causal=causal, rows=rows)
+    for key in ("d_x", "d_w_down", "d_w_conv_seq", "d_w_conv_ch", "d_temp", "d_w_out", "d_q", "d_k", "d_v", "d_lat"):
+        np.testing.assert_allclose(part[key], full[key], rtol=1e-11, atol=1e-13, err_msg=key)
