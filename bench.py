@@ -37,7 +37,9 @@ def main() -> int:
     ap.add_argument("--workload", default="ccgqa_16k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mha", action="store_true", help="skip the same-kernel MHA comparison run")
-    ap.add_argument("--only", choices=["attention", "prologue", "down_project", "up_project"],
+    ap.add_argument("--no-backward", action="store_true", help="skip the forward+backward measurement")
+    ap.add_argument("--only", choices=["attention", "prologue", "down_project", "up_project", "backward",
+                                       "attention_backward", "prologue_backward"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
     ap.add_argument("--cpu-prefix", type=int, default=16384, help="tokens of the causal prefix the oracle is timed on")
     args = ap.parse_args()
@@ -68,9 +70,29 @@ def main() -> int:
     def step():
         P.cca_forward(cfg, wt, x, out=out, saved=None, workspace=ws)
 
+    def backward_buffers():
+        from synth_inputs import make_upstream_grad
+        g = torch.from_numpy(make_upstream_grad(w, seed=1)).to(x.device, cfg.torch_dtype)
+        return dict(d_out=g, d_x=torch.empty_like(x), grads=P.CCAGrads.allocate_like(wt),
+                    ws=P.new_backward_workspace(cfg, x.device),
+                    d_o=torch.randn_like(saved.o), d_q=torch.empty_like(saved.q), d_k=torch.empty_like(saved.k),
+                    d_v=torch.empty_like(saved.v), d_lat=torch.empty_like(saved.lat))
+
     if args.only:
         P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
+        bb = backward_buffers() if "backward" in args.only else None
+        if bb is not None:  # d_q, d_k, d_v of a real attention backward as inputs of the prologue stage call
+            P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse, bb["d_o"], bb["d_q"],
+                                     bb["d_k"], bb["d_v"], workspace=bb["ws"])
         stage = {
+            "backward": lambda: P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"],
+                                               workspace=bb["ws"]),
+            "attention_backward": lambda: P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse,
+                                                                   bb["d_o"], bb["d_q"], bb["d_k"], bb["d_v"],
+                                                                   workspace=bb["ws"]),
+            "prologue_backward": lambda: P.cca_prologue_backward(cfg, wt, saved.lat, saved.q, saved.k, saved.rnorm,
+                                                                 bb["d_q"], bb["d_k"], bb["d_v"], d_lat=bb["d_lat"],
+                                                                 grads=bb["grads"], workspace=bb["ws"]),
             "attention": lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None, temp=wt.temp),
             "prologue": lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws),
             "down_project": lambda: P.cca_down_project(cfg, x, wt.w_down, lat=saved.lat, workspace=ws),
@@ -112,6 +134,42 @@ def main() -> int:
     pro_ms = timed(lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws), n_ev)
     up_ms = timed(lambda: P.cca_up_project(cfg, saved.o, wt.w_out, out=out, workspace=ws), n_ev)
     attn_tflops = fl["attn"] / attn_ms / 1e9
+
+    # ---- forward + backward (training step of the block): cca_forward saving intermediates, then cca_backward ----
+    bwd = None
+    if not args.no_backward:
+        bb = backward_buffers()
+
+        def train_step():
+            P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
+            P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"], workspace=bb["ws"])
+
+        n_b = max(5, args.steps // 2)
+        for _ in range(3):
+            train_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_b):
+            train_step()
+        torch.cuda.synchronize()
+        fb_ms = (time.perf_counter() - t0) * 1e3 / n_b
+        b_ms = timed(lambda: P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"],
+                                            workspace=bb["ws"]), n_ev)
+        ab_ms = timed(lambda: P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse, bb["d_o"],
+                                                       bb["d_q"], bb["d_k"], bb["d_v"], workspace=bb["ws"]), n_ev)
+        pb_ms = timed(lambda: P.cca_prologue_backward(cfg, wt, saved.lat, saved.q, saved.k, saved.rnorm, bb["d_q"],
+                                                      bb["d_k"], bb["d_v"], d_lat=bb["d_lat"], grads=bb["grads"],
+                                                      workspace=bb["ws"]), n_ev)
+        # adjoint work: every projection twice (input and weight gradient), the convolutions twice, attention
+        # five contractions instead of two (recomputed scores are extra work and not counted)
+        bwd_flops = 2.0 * fl["proj"] + 2.0 * fl["conv"] + 2.5 * fl["attn"]
+        bwd = {"fwd_bwd_ms": round(fb_ms, 4), "backward_ms": round(b_ms, 4),
+               "fwd_bwd_tflops": round((fl["total"] + bwd_flops) / fb_ms / 1e9, 1),
+               "backward_tflops": round(bwd_flops / b_ms / 1e9, 1), "backward_flops": bwd_flops,
+               "attention_backward_ms": round(ab_ms, 4),
+               "attention_backward_tflops": round(2.5 * fl["attn"] / ab_ms / 1e9, 1),
+               "prologue_backward_ms": round(pb_ms, 4)}
+        del bb
 
     # ---- same-kernel MHA baseline (compression 1, 16 x 128 heads, no transforms) ------------
     mha = None
@@ -180,6 +238,7 @@ def main() -> int:
                           "attention": round(attn_tflops, 1),
                           "up_project": round(2.0 * cfg.B * cfg.T * cfg.e_q * cfg.d_model / up_ms / 1e9, 1)},
         "prologue_gbps": round((cfg.B * cfg.T * (cfg.n_lat + cfg.e_q + 2 * cfg.e_kv) * 2) / pro_ms / 1e6, 1),
+        "backward": bwd,
         "mha_same_kernel": mha,
         "roofline": {"kernel": "attn_fwd_kernel (latent attention)", "bound": "mfma",
                      "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

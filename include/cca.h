@@ -179,7 +179,9 @@ cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, co
  * lse of the forward pass and d_o (B,T,H_q*d_h) computes d_q (B,T,H_q,d_h),
  * d_k, d_v (B,T,H_k,d_h), overwritten; d_k, d_v are summed over the query
  * heads sharing a KV head.  Probabilities are recomputed from lse.
- * workspace: B*H_q*T*4 bytes. */
+ * workspace: B*H_q*T*4 bytes (rounded up to 256) plus, when H_q > H_k,
+ * 2*B*T*H_q*d_h*4 bytes for the per-query-head partial sums of d_k and d_v;
+ * cca_backward_workspace_size() bytes always suffice. */
 cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v,
                                   const void *o, const float *lse, const void *d_o, void *d_q, void *d_k,
                                   void *d_v, void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -299,7 +299,8 @@ def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=N
     d_k = torch.empty_like(k) if d_k is None else d_k
     d_v = torch.empty_like(v) if d_v is None else d_v
     if workspace is None:
-        workspace = torch.empty(cfg.B * cfg.n_q_heads * cfg.T * 4, dtype=torch.uint8, device=q.device)
+        n = cfg.B * cfg.n_q_heads * cfg.T * 4 + 256 + 2 * cfg.B * cfg.T * cfg.e_q * 4
+        workspace = torch.empty(n, dtype=torch.uint8, device=q.device)
     cc = cfg.c()
     _check(lib.cca_attention_backward(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(d_q),
                                       _ptr(d_k), _ptr(d_v), _ptr(workspace), workspace.numel(), _stream()),

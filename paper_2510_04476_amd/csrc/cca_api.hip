@@ -131,7 +131,7 @@ static BwdLayout bwd_layout(const Dims &d) {
   L.d_q = take(rows * d.e_q * es);
   L.d_k = take(rows * d.e_kv * es);
   L.d_v = take(rows * d.e_kv * es);
-  L.delta = take((size_t)d.B * d.Hq * d.T * sizeof(float));
+  L.delta = take(attention_bwd_scratch_bytes(d));  // Delta and the attention backward's per-head partial sums
   L.d_lat = take(rows * d.n_lat * es);
   L.pro_bytes = prologue_bwd_scratch_bytes(d);
   L.pro = take(L.pro_bytes);

@@ -11,10 +11,13 @@
 //                     tiles like the forward kernel; S^T and dP^T come out with one query row per lane, dS^T
 //                     packed to bf16 is the second MFMA operand of dQ^T += K^T dS^T, K^T fetched with the
 //                     transposing LDS read.
-//   attn_bwd_dkdv     one workgroup = 128 keys of one KV head (4 wavefronts x 32 keys), loops over the query
-//                     heads of the group and their query tiles; S and dP come out with one key per lane, P and
-//                     dS packed to bf16 are the second operands of dV^T += dO^T P and dK^T += Q^T dS, with
-//                     dO^T and Q^T fetched by transposing LDS reads.
+//   attn_bwd_dkdv     one workgroup = 256 keys x one QUERY head (8 wavefronts x 32 keys), loops over the query
+//                     tiles of that head; S and dP come out with one key per lane, P and dS packed to bf16 are
+//                     the second operands of dV^T += dO^T P and dK^T += Q^T dS, with dO^T and Q^T fetched by
+//                     transposing LDS reads.  With R > 1 query heads per KV head each workgroup writes its
+//                     head's fp32 contribution and group_sum_kernel adds the R of them in a fixed order
+//                     (one workgroup looping over the whole group leaves a causal grid of only B*H_k*T/128
+//                     unequal workgroups: measured 4.2 ms against 0.86 ms for dQ at the 16k CCGQA shape).
 // S is recomputed in both kernels (7 contractions instead of 5) in exchange for having no atomics.
 #include <type_traits>
 
@@ -224,13 +227,19 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 // ---------------------------------------------------------------------------
 // dK, dV
 // ---------------------------------------------------------------------------
-constexpr int KV_BK = 128, KV_NT = 256, BQT = 64;  // keys per workgroup, threads, query rows per LDS tile
+constexpr int KV_BK = 256, KV_NT = 512, BQT = 64;  // keys per workgroup, threads, query rows per LDS tile
 
-template <bool CAUSAL>
-__global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
+// PARTIAL = false (one query head per KV head): dK, dV written as bf16 (B,T,H_k,d_h).
+// PARTIAL = true: this head's contribution written as fp32 to dKp, dVp (B,T,H_q,d_h).
+// MODE 0: dK and dV in one pass (4 contractions; needs more than the 256 registers two wavefronts per SIMD leave
+// each lane, so it spills); MODE 1: dV only (S, dV); MODE 2: dK only (S, dP, dK).  Modes 1 + 2 together are 5
+// contractions without spills.
+template <bool CAUSAL, bool PARTIAL, int MODE>
+__global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
-    bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, int T, int Hq, int Hk, int BG, int nkb, float scale) {
+    bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
+    int Hk, int BH, int nkb, float scale) {
   constexpr int TILE = BQT * ROW;
   constexpr int PER_THREAD = BQT * KCH / KV_NT;
   constexpr int ROWS_PER_PASS = KV_NT / KCH;
@@ -241,8 +250,8 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
   const int idx = blockIdx.x;
-  const int bg = idx % BG, kb = idx / BG;  // early key blocks (most query tiles when causal) first
-  const int b = bg / Hk, g = bg % Hk, R = Hq / Hk;
+  const int bh = idx % BH, kb = idx / BH;  // early key blocks (most query tiles when causal) first
+  const int b = bh / Hq, h = bh % Hq, g = h / (Hq / Hk);
   const int k0 = kb * KV_BK, kw0 = k0 + wave * 32;
   const float c = scale * LOG2E;
   const int qrow_bytes = Hq * DH * 2;
@@ -261,7 +270,7 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pk + kk * 16));
-      vf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pv + kk * 16));
+      if (MODE != 1) vf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pv + kk * 16));
     }
   }
   f32x16 dk[DT], dv[DT];  // dK^T, dV^T: lane = key, registers = channels
@@ -273,13 +282,12 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
   // query tiles that see keys of this block
   const int qt_first = CAUSAL ? k0 / BQT : 0;
   const int nqt = (T + BQT - 1) / BQT;
-  const int per_head = nqt - qt_first;
-  const int steps = per_head * R;
+  const int steps = nqt - qt_first;
 
   u32x4 rq[PER_THREAD], rd[PER_THREAD];
   float rstat = 0.f;
   auto load_tile = [&](int step) {
-    const int h = g * R + step / per_head, t0 = (qt_first + step % per_head) * BQT;
+    const int t0 = (qt_first + step) * BQT;
     const unsigned char *Qg = reinterpret_cast<const unsigned char *>(Q + ((long long)b * T * Hq + h) * DH);
     const unsigned char *Dg = reinterpret_cast<const unsigned char *>(dO + ((long long)b * T * Hq + h) * DH);
 #pragma unroll
@@ -312,7 +320,7 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
   }
   for (int step = 0; step < steps; ++step) {
     const int buf = step & 1;
-    const int t0 = (qt_first + step % per_head) * BQT;
+    const int t0 = (qt_first + step) * BQT;
     if (step + 1 < steps) store_tile(buf ^ 1);
     if (step + 2 < steps) load_tile(step + 2);
     if (wave_live && !(CAUSAL && t0 + BQT - 1 < kw0)) {
@@ -329,8 +337,8 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
               bf16x8, *reinterpret_cast<const u32x4 *>(qp + rd_off + qs * 32 * ROW + kk * 32));
           const bf16x8 da = __builtin_bit_cast(
               bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + rd_off + qs * 32 * ROW + kk * 32));
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);    // S[t, key]
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);  // dP[t, key]
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);                   // S[t, key]
+          if (MODE != 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);  // dP[t, key]
         }
         // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4
         float pr[16], ds[16];
@@ -366,14 +374,33 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) {
-            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dp_ + tr_off, qs * 32 + jj * 16, dt * 32), pf[jj],
-                                                             dv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qp + tr_off, qs * 32 + jj * 16, dt * 32), dsf[jj],
-                                                             dk[dt], 0, 0, 0);
+            if (MODE != 2)
+              dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dp_ + tr_off, qs * 32 + jj * 16, dt * 32),
+                                                               pf[jj], dv[dt], 0, 0, 0);
+            if (MODE != 1)
+              dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qp + tr_off, qs * 32 + jj * 16, dt * 32),
+                                                               dsf[jj], dk[dt], 0, 0, 0);
           }
       }
     }
     __syncthreads();
+  }
+  if (PARTIAL) {
+    if (wave_live && kw0 + l32 < T) {
+      float *rk_ = dKp + (((long long)b * T + kw0 + l32) * Hq + h) * DH;
+      float *rv_ = dVp + (((long long)b * T + kw0 + l32) * Hq + h) * DH;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const f32x4 w = {dk[dt][rg * 4 + 0] * scale, dk[dt][rg * 4 + 1] * scale, dk[dt][rg * 4 + 2] * scale,
+                           dk[dt][rg * 4 + 3] * scale};
+          const f32x4 x = {dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1], dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]};
+          if (MODE != 1) *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+          if (MODE != 2) *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+        }
+    }
+    return;
   }
   if (wave_live && kw0 + l32 < T) {
     bf16_t *rk_ = dK + (((long long)b * T + kw0 + l32) * Hk + g) * DH;
@@ -387,10 +414,32 @@ __global__ __launch_bounds__(KV_NT) void attn_bwd_dkdv_kernel(
         w.y = pack2(dk[dt][rg * 4 + 2] * scale, dk[dt][rg * 4 + 3] * scale);
         x.x = pack2(dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1]);
         x.y = pack2(dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]);
-        *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-        *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+        if (MODE != 1) *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+        if (MODE != 2) *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
       }
   }
+}
+
+// out[(row, g), :] = bf16(sum_r part[(row, g*R + r), :]) for dK and dV, 4 channels per thread, fixed order
+__global__ __launch_bounds__(256) void group_sum_kernel(const float *__restrict__ pk, const float *__restrict__ pv,
+                                                       bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
+                                                       long long n_out, int R) {
+  const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (row*Hk + g) * (DH/4) + c4
+  if (id >= n_out) return;
+  const long long rg = id / (DH / 4);
+  const int c = (int)(id % (DH / 4)) * 4;
+  f32x4 ak = {0.f, 0.f, 0.f, 0.f}, av = {0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < R; ++r) {
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(pk + (rg * R + r) * DH + c);
+    const f32x4 b = *reinterpret_cast<const f32x4 *>(pv + (rg * R + r) * DH + c);
+    ak.x += a.x; ak.y += a.y; ak.z += a.z; ak.w += a.w;
+    av.x += b.x; av.y += b.y; av.z += b.z; av.w += b.w;
+  }
+  u32x2 w, x;
+  w.x = pack2(ak.x, ak.y); w.y = pack2(ak.z, ak.w);
+  x.x = pack2(av.x, av.y); x.y = pack2(av.z, av.w);
+  *reinterpret_cast<u32x2 *>(dK + rg * DH + c) = w;
+  *reinterpret_cast<u32x2 *>(dV + rg * DH + c) = x;
 }
 
 }  // namespace
@@ -399,7 +448,12 @@ bool attention_bwd_supported(const Dims &d) {
   return d.bf16 && d.dh == DH && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
 }
 
-size_t attention_bwd_scratch_bytes(const Dims &d) { return (size_t)d.B * d.Hq * d.T * sizeof(float); }
+// Delta (B,H_q,T) fp32, then (R > 1 only) the per-query-head fp32 contributions to dK and dV, (B,T,H_q,d_h) each
+static size_t delta_bytes(const Dims &d) { return ((size_t)d.B * d.Hq * d.T * sizeof(float) + 255) / 256 * 256; }
+size_t attention_bwd_scratch_bytes(const Dims &d) {
+  if (!attention_bwd_supported(d)) return (size_t)d.B * d.Hq * d.T * sizeof(float);
+  return delta_bytes(d) + (d.R > 1 ? 2 * (size_t)d.rows() * d.e_q * sizeof(float) : 0);
+}
 
 hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
                               const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
@@ -411,20 +465,40 @@ hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int BH = d.B * d.Hq, nqb = (d.T + DQ_BQ - 1) / DQ_BQ;
-  const int BG = d.B * d.Hk, nkb = (d.T + KV_BK - 1) / KV_BK;
+  const int nkb = (d.T + KV_BK - 1) / KV_BK;
+  float *pk = reinterpret_cast<float *>(reinterpret_cast<char *>(delta) + delta_bytes(d));
+  float *pv = pk + (size_t)d.rows() * d.e_q;
 #define ARGS_DQ (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_q, \
                 d.T, d.Hq, d.Hk, BH, nqb, d.scale
 #define ARGS_KV (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_k, \
-                (bf16_t *)d_v, d.T, d.Hq, d.Hk, BG, nkb, d.scale
+                (bf16_t *)d_v, pk, pv, d.T, d.Hq, d.Hk, BH, nkb, d.scale
+  const unsigned gkv = (unsigned)((long long)BH * nkb);
+  const bool partial = d.R > 1;
   if (causal) {
     attn_bwd_dq_kernel<true><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
-    attn_bwd_dkdv_kernel<true><<<(unsigned)((long long)BG * nkb), KV_NT, 0, s>>>(ARGS_KV);
+    if (partial) {
+      attn_bwd_dkdv_kernel<true, true, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<true, true, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+    } else {
+      attn_bwd_dkdv_kernel<true, false, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<true, false, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+    }
   } else {
     attn_bwd_dq_kernel<false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
-    attn_bwd_dkdv_kernel<false><<<(unsigned)((long long)BG * nkb), KV_NT, 0, s>>>(ARGS_KV);
+    if (partial) {
+      attn_bwd_dkdv_kernel<false, true, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<false, true, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+    } else {
+      attn_bwd_dkdv_kernel<false, false, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<false, false, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+    }
   }
 #undef ARGS_DQ
 #undef ARGS_KV
+  if (partial) {
+    const long long n_out = d.rows() * d.Hk * (DH / 4);
+    group_sum_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(pk, pv, (bf16_t *)d_k, (bf16_t *)d_v, n_out, d.R);
+  }
   return hipGetLastError();
 }
 

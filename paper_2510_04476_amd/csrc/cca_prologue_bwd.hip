@@ -290,12 +290,14 @@ __global__ __launch_bounds__(256) void pro_bwd_unfold_w1_kernel(const float *__r
   }
 }
 
-// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j]
-__global__ __launch_bounds__(128) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
-                                                               const bf16_t *__restrict__ w1, bf16_t *__restrict__ dw0) {
-  const int h = blockIdx.x, i = threadIdx.x;
+// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j].  One workgroup per head, 8 groups of 16 output
+// channels x 128 input channels; the 8 partial sums are added through LDS in a fixed order.
+__global__ __launch_bounds__(1024) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
+                                                                const bf16_t *__restrict__ w1, bf16_t *__restrict__ dw0) {
+  __shared__ float red[8][4][DH];
+  const int h = blockIdx.x, i = threadIdx.x & (DH - 1), og = threadIdx.x >> 7;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int o = 0; o < DH; ++o) {
+  for (int o = og * 16; o < og * 16 + 16; ++o) {
     const float *p = dwc + (((long long)h * DH + o) * D) * DH + i;
     const bf16_t *wp = w1 + (((long long)h * DH + o) * DH + i) * kc;
     for (int j = 0; j < kc; ++j) {
@@ -303,7 +305,14 @@ __global__ __launch_bounds__(128) void pro_bwd_unfold_w0_kernel(const float *__r
       for (int jj = 0; jj < ks; ++jj) acc[jj] = fmaf(p[(j + jj) * DH], f1, acc[jj]);
     }
   }
-  for (int jj = 0; jj < ks; ++jj) dw0[(long long)(h * DH + i) * ks + jj] = f32_to_bf16(acc[jj]);
+  for (int jj = 0; jj < 4; ++jj) red[og][jj][i] = acc[jj];
+  __syncthreads();
+  if (og == 0)
+    for (int jj = 0; jj < ks; ++jj) {
+      float sum = 0.f;
+      for (int x = 0; x < 8; ++x) sum += red[x][jj][i];
+      dw0[(long long)(h * DH + i) * ks + jj] = f32_to_bf16(sum);
+    }
 }
 
 int taps(const Dims &d) { return ((d.flags & CCA_CONV_SEQ) ? d.k_seq : 1) + d.k_ch - 1; }
@@ -389,7 +398,7 @@ hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const vo
                                                                      (const bf16_t *)w.w_conv_seq, dwc,
                                                                      want_w1 ? (bf16_t *)gr->w_conv_ch : nullptr);
   if (want_w0)
-    pro_bwd_unfold_w0_kernel<<<NH, DH, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
+    pro_bwd_unfold_w0_kernel<<<NH, 1024, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
                                                (bf16_t *)gr->w_conv_seq);
   return hipGetLastError();
 }
