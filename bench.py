@@ -25,8 +25,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured
-ATTN_TRAFFIC_BYTES = None
+# HBM bytes per attn_fwd_kernel launch on the ccgqa_16k workload, from two rocprofv3 --pmc runs (FETCH_SIZE
+# 148.36 MiB after scaling by 2.000, WRITE_SIZE 32.08 MiB after scaling by 1.000, the factors a 256 MiB
+# device-to-device copy gives for the same counters); summary in profiles/ccgqa_16k_hbm_traffic_pmc.txt.
+# Algorithmic bytes of the kernel: 80 MiB (Q 32 + K,V 16 read, O 32 written).
+ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((148.36 + 32.08) * 2 ** 20)}
 
 
 def main() -> int:
@@ -38,7 +41,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mha", action="store_true", help="skip the same-kernel MHA comparison run")
     ap.add_argument("--no-backward", action="store_true", help="skip the forward+backward measurement")
-    ap.add_argument("--only", choices=["attention", "prologue", "down_project", "up_project", "backward",
+    ap.add_argument("--only", choices=["forward", "attention", "prologue", "down_project", "up_project", "backward",
                                        "attention_backward", "prologue_backward"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
     ap.add_argument("--cpu-prefix", type=int, default=16384, help="tokens of the causal prefix the oracle is timed on")
@@ -85,6 +88,7 @@ def main() -> int:
             P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse, bb["d_o"], bb["d_q"],
                                      bb["d_k"], bb["d_v"], workspace=bb["ws"])
         stage = {
+            "forward": lambda: P.cca_forward(cfg, wt, x, out=out, saved=None, workspace=ws),
             "backward": lambda: P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"],
                                                workspace=bb["ws"]),
             "attention_backward": lambda: P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse,
@@ -101,7 +105,15 @@ def main() -> int:
         for _ in range(args.steps):
             stage()
         torch.cuda.synchronize()
-        print(json.dumps({"only": args.only, "launches": args.steps, "workload": args.workload}))
+        # calibration for hardware byte counters: a plain device-to-device copy of known size
+        # (reads 256 MiB, writes 256 MiB per launch), three launches
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=x.device).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "launches": args.steps, "workload": args.workload,
+                          "calibration_copy_bytes_each_way": 256 << 20}))
         return 0
 
     for _ in range(args.warmup):
@@ -242,7 +254,8 @@ def main() -> int:
         "mha_same_kernel": mha,
         "roofline": {"kernel": "attn_fwd_kernel (latent attention)", "bound": "mfma",
                      "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_TRAFFIC_BYTES,
+                     "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": ATTN_TRAFFIC_BYTES.get(args.workload),
                      "flops_per_launch": fl["attn"], "avg_launch_ms": round(attn_ms, 4)},
         "cpu_baseline": cpu,
         "paper_context": "H100 bf16, S=16k: fused CCA kernel ~1.7x prefill vs MHA (CCA-4x); decoupled C1=2/C2=8 layout 1.3-1.4x",
