@@ -86,14 +86,14 @@ def main() -> int:
         bb = backward_buffers() if "backward" in args.only else None
         if bb is not None:  # d_q, d_k, d_v of a real attention backward as inputs of the prologue stage call
             P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse, bb["d_o"], bb["d_q"],
-                                     bb["d_k"], bb["d_v"], workspace=bb["ws"])
+                                     bb["d_k"], bb["d_v"], workspace=bb["ws"], o_lo=saved.o_lo)
         stage = {
             "forward": lambda: P.cca_forward(cfg, wt, x, out=out, saved=None, workspace=ws),
             "backward": lambda: P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"],
                                                workspace=bb["ws"]),
             "attention_backward": lambda: P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse,
                                                                    bb["d_o"], bb["d_q"], bb["d_k"], bb["d_v"],
-                                                                   workspace=bb["ws"]),
+                                                                   workspace=bb["ws"], o_lo=saved.o_lo),
             "prologue_backward": lambda: P.cca_prologue_backward(cfg, wt, saved.lat, saved.q, saved.k, saved.rnorm,
                                                                  bb["d_q"], bb["d_k"], bb["d_v"], d_lat=bb["d_lat"],
                                                                  grads=bb["grads"], workspace=bb["ws"]),
@@ -168,7 +168,8 @@ def main() -> int:
         b_ms = timed(lambda: P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"],
                                             workspace=bb["ws"]), n_ev)
         ab_ms = timed(lambda: P.cca_attention_backward(cfg, saved.q, saved.k, saved.v, saved.o, saved.lse, bb["d_o"],
-                                                       bb["d_q"], bb["d_k"], bb["d_v"], workspace=bb["ws"]), n_ev)
+                                                       bb["d_q"], bb["d_k"], bb["d_v"], workspace=bb["ws"],
+                                                       o_lo=saved.o_lo), n_ev)
         pb_ms = timed(lambda: P.cca_prologue_backward(cfg, wt, saved.lat, saved.q, saved.k, saved.rnorm, bb["d_q"],
                                                       bb["d_k"], bb["d_v"], d_lat=bb["d_lat"], grads=bb["grads"],
                                                       workspace=bb["ws"]), n_ev)

@@ -105,6 +105,10 @@ typedef struct {
   float *lse; /* (B,H_q,T) natural-log sum-exp of the scaled logits */
   float *rnorm; /* (B,T,H_q+H_k) factor the norm step multiplied each head vector by: sqrt(d_h) [* beta] / |x|;
                    1 when CCA_QK_NORM is off.  Needed by cca_backward. */
+  void *o_lo;   /* (B,T,H_q*d_h), bf16 storage only (not written with CCA_F32): the part of the fp32 attention
+                   result that rounding `o` to bf16 dropped, itself rounded to bf16.  Optional for
+                   cca_backward: with it <d_o, o> is formed from o + o_lo; without it the rounding error of o
+                   can dominate d_q and d_k when the softmax is flat. */
 } cca_saved;
 
 /* Gradients of the weights (device pointers, caller-owned, same shapes and
@@ -134,7 +138,7 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
 /* Gradient of the whole block (the paper gives no backward equations: this is
  * the adjoint of the steps of Sec. 2.2, last step first).  Given d_out =
  * dLoss/d out (B,T,E) and the intermediates `saved` that cca_forward wrote for
- * the SAME cfg, weights and x (all seven members required), computes
+ * the SAME cfg, weights and x (every member required except o_lo), computes
  *   d_x (B,T,E)            overwritten; may be NULL (then not computed)
  *   grads->...             see cca_grads; `grads` itself may be NULL.
  * Attention probabilities are recomputed from saved->lse (nothing of size
@@ -163,7 +167,7 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
                         void *v, float *rnorm_or_null, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* o (B,T,H_q*d_h) = softmax(scale * q k^T [causal]) v per latent head, query
- * head h reading KV head h / R.  lse may be NULL.
+ * head h reading KV head h / R.  lse and o_lo (see cca_saved) may be NULL.
  * If cfg->flags has CCA_QK_NORM the caller PROMISES that q and k are what
  * cca_prologue writes under that flag: |q[t,h]| = sqrt(d_h) and |k[t,g]| =
  * sqrt(d_h) * exp(temp[g]) (temp: H_k fp32 log-temperatures on the device,
@@ -172,7 +176,7 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
  * that break the promise give undefined results.  Clear CCA_QK_NORM in cfg to
  * attend over arbitrary q, k. */
 cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o,
-                         float *lse, const float *temp, void *hip_stream);
+                         void *o_lo, float *lse, const float *temp, void *hip_stream);
 
 /* Backward of cca_attention (the paper gives no backward equations; this is
  * the adjoint of the attention line of the final eq. block): from q, k, v, o,
@@ -183,7 +187,7 @@ cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, co
  * 2*B*T*H_q*d_h*4 bytes for the per-query-head partial sums of d_k and d_v;
  * cca_backward_workspace_size() bytes always suffice. */
 cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v,
-                                  const void *o, const float *lse, const void *d_o, void *d_q, void *d_k,
+                                  const void *o, const void *o_lo_or_null, const float *lse, const void *d_o, void *d_q, void *d_k,
                                   void *d_v, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Backward of cca_prologue: from d_q (B,T,H_q,d_h), d_k, d_v (B,T,H_k,d_h)

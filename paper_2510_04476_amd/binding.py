@@ -46,7 +46,7 @@ class cca_weights(C.Structure):
 
 class cca_saved(C.Structure):
     _fields_ = [("lat", C.c_void_p), ("q", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p),
-                ("o", C.c_void_p), ("lse", C.c_void_p), ("rnorm", C.c_void_p)]
+                ("o", C.c_void_p), ("lse", C.c_void_p), ("rnorm", C.c_void_p), ("o_lo", C.c_void_p)]
 
 
 class cca_grads(C.Structure):
@@ -78,8 +78,8 @@ def load_library() -> C.CDLL:
     lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_prologue.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, vp, sz, vp]
-    lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp]
-    lib.cca_attention_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.cca_attention.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.cca_attention_backward.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.cca_backward_workspace_size.argtypes = [cfgp, C.POINTER(sz)]
     lib.cca_backward.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_saved), vp, vp,
                                  C.POINTER(cca_grads), vp, sz, vp]
@@ -151,6 +151,7 @@ class CCASaved:
     o: torch.Tensor | None = None
     lse: torch.Tensor | None = None
     rnorm: torch.Tensor | None = None
+    o_lo: torch.Tensor | None = None
 
     @staticmethod
     def allocate(cfg: CCAConfig, device) -> "CCASaved":
@@ -163,11 +164,12 @@ class CCASaved:
             v=torch.empty(B, T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=device),
             o=torch.empty(B, T, cfg.e_q, dtype=dt, device=device),
             lse=torch.empty(B, cfg.n_q_heads, T, dtype=torch.float32, device=device),
-            rnorm=torch.empty(B, T, cfg.n_q_heads + cfg.n_kv_heads, dtype=torch.float32, device=device))
+            rnorm=torch.empty(B, T, cfg.n_q_heads + cfg.n_kv_heads, dtype=torch.float32, device=device),
+            o_lo=torch.empty(B, T, cfg.e_q, dtype=dt, device=device) if cfg.dtype == CCA_BF16 else None)
 
     def c(self) -> cca_saved:
         return cca_saved(_ptr(self.lat), _ptr(self.q), _ptr(self.k), _ptr(self.v), _ptr(self.o), _ptr(self.lse),
-                         _ptr(self.rnorm))
+                         _ptr(self.rnorm), _ptr(self.o_lo))
 
 
 @dataclass
@@ -281,19 +283,20 @@ def cca_prologue(cfg: CCAConfig, w: CCAWeights, lat, q=None, k=None, v=None, wor
     return q, k, v
 
 
-def cca_attention(cfg: CCAConfig, q, k, v, o=None, lse=None, want_lse=False, temp=None):
+def cca_attention(cfg: CCAConfig, q, k, v, o=None, lse=None, want_lse=False, temp=None, o_lo=None):
     lib = load_library()
     if o is None:
         o = torch.empty(cfg.B, cfg.T, cfg.e_q, dtype=cfg.torch_dtype, device=q.device)
     if lse is None and want_lse:
         lse = torch.empty(cfg.B, cfg.n_q_heads, cfg.T, dtype=torch.float32, device=q.device)
     cc = cfg.c()
-    _check(lib.cca_attention(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(temp), _stream()),
-           "cca_attention")
+    _check(lib.cca_attention(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(o_lo), _ptr(lse), _ptr(temp),
+                             _stream()), "cca_attention")
     return (o, lse) if want_lse else o
 
 
-def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=None, d_v=None, workspace=None):
+def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=None, d_v=None, workspace=None,
+                           o_lo=None):
     lib = load_library()
     d_q = torch.empty_like(q) if d_q is None else d_q
     d_k = torch.empty_like(k) if d_k is None else d_k
@@ -302,7 +305,8 @@ def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=N
         n = cfg.B * cfg.n_q_heads * cfg.T * 4 + 256 + 2 * cfg.B * cfg.T * cfg.e_q * 4
         workspace = torch.empty(n, dtype=torch.uint8, device=q.device)
     cc = cfg.c()
-    _check(lib.cca_attention_backward(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(d_q),
+    _check(lib.cca_attention_backward(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(o_lo), _ptr(lse), _ptr(d_o),
+                                      _ptr(d_q),
                                       _ptr(d_k), _ptr(d_v), _ptr(workspace), workspace.numel(), _stream()),
            "cca_attention_backward")
     return d_q, d_k, d_v

@@ -103,10 +103,10 @@ static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
-static cca_status run_attention(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                                const float *temp, hipStream_t s) {
-  hipError_t e = attention_mfma_supported(d) ? attention_mfma_bf16(d, q, k, v, o, lse, temp, s)
-                                             : attention_generic(d, q, k, v, o, lse, s);
+static cca_status run_attention(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo,
+                                float *lse, const float *temp, hipStream_t s) {
+  hipError_t e = attention_mfma_supported(d) ? attention_mfma_bf16(d, q, k, v, o, o_lo, lse, temp, s)
+                                             : attention_generic(d, q, k, v, o, o_lo, lse, s);
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
@@ -161,10 +161,10 @@ static cca_status weight_grad(const Dims &d, const void *A, const void *Bm, void
 }
 
 static cca_status run_attention_bwd(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                                    const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                                    const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                                     hipStream_t s) {
-  hipError_t e = attention_bwd_supported(d) ? attention_bwd_bf16(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, delta, s)
-                                            : attention_bwd_generic(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, delta, s);
+  hipError_t e = attention_bwd_supported(d) ? attention_bwd_bf16(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s)
+                                            : attention_bwd_generic(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s);
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
@@ -254,31 +254,33 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
   return run_prologue(d, w, lat, q, k, v, rnorm, workspace, workspace_bytes, (hipStream_t)hip_stream);
 }
 
-cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o, float *lse,
-                         const float *temp, void *hip_stream) {
+cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, const void *v, void *o, void *o_lo,
+                         float *lse, const float *temp, void *hip_stream) {
   Dims d;
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
   if (!q || !k || !v || !o) return CCA_ERR_NULL;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_lo) ||
+      (reinterpret_cast<uintptr_t>(lse) & 3u))
     return CCA_ERR_ALIGN;
   if ((d.flags & CCA_KEY_TEMP) && !temp) return CCA_ERR_NULL;
   if (reinterpret_cast<uintptr_t>(temp) & 3u) return CCA_ERR_ALIGN;
-  return run_attention(d, q, k, v, o, lse, temp, (hipStream_t)hip_stream);
+  return run_attention(d, q, k, v, o, o_lo, lse, temp, (hipStream_t)hip_stream);
 }
 
 cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v, const void *o,
-                                  const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, void *workspace,
+                                  const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, void *workspace,
                                   size_t workspace_bytes, void *hip_stream) {
   Dims d;
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
   if (!q || !k || !v || !o || !lse || !d_o || !d_q || !d_k || !d_v) return CCA_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(d_q) ||
-      !aligned16(d_k) || !aligned16(d_v) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+      !aligned16(d_k) || !aligned16(d_v) || !aligned16(workspace) || !aligned16(o_lo) ||
+      (reinterpret_cast<uintptr_t>(lse) & 3u))
     return CCA_ERR_ALIGN;
   if (!workspace || workspace_bytes < attention_bwd_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
-  return run_attention_bwd(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, static_cast<float *>(workspace),
+  return run_attention_bwd(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, static_cast<float *>(workspace),
                            (hipStream_t)hip_stream);
 }
 
@@ -316,7 +318,7 @@ cca_status cca_backward(const cca_config *cfg, const cca_weights *w, const void 
   if (st != CCA_OK) return st;
   if (!aligned16(x) || !aligned16(d_out) || !aligned16(d_x) || !aligned16(w->w_down) || !aligned16(w->w_out) ||
       !aligned16(saved->lat) || !aligned16(saved->q) || !aligned16(saved->k) || !aligned16(saved->v) ||
-      !aligned16(saved->o) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u) ||
+      !aligned16(saved->o) || !aligned16(saved->o_lo) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u) ||
       (reinterpret_cast<uintptr_t>(saved->rnorm) & 3u))
     return CCA_ERR_ALIGN;
   const BwdLayout L = bwd_layout(d);
@@ -332,7 +334,7 @@ cca_status cca_backward(const cca_config *cfg, const cca_weights *w, const void 
   }
   st = project_t(d, d_out, w->w_out, d_o, d.rows(), d.e_q, d.E, s);
   if (st != CCA_OK) return st;
-  st = run_attention_bwd(d, saved->q, saved->k, saved->v, saved->o, saved->lse, d_o, d_q, d_k, d_v,
+  st = run_attention_bwd(d, saved->q, saved->k, saved->v, saved->o, saved->o_lo, saved->lse, d_o, d_q, d_k, d_v,
                          reinterpret_cast<float *>(ws + L.delta), s);
   if (st != CCA_OK) return st;
   st = run_prologue_bwd(d, w, saved->lat, saved->q, saved->k, saved->rnorm, d_q, d_k, d_v, d_lat, grads, ws + L.pro,
@@ -364,9 +366,10 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   char *ws = static_cast<char *>(workspace);
   void *lat = ws + L.lat, *q = ws + L.q, *k = ws + L.k, *v = ws + L.v, *o = ws + L.o;
   float *lse = nullptr, *rnorm = nullptr;
+  void *o_lo = nullptr;
   if (saved) {
     if (!aligned16(saved->lat) || !aligned16(saved->q) || !aligned16(saved->k) || !aligned16(saved->v) ||
-        !aligned16(saved->o) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u))
+        !aligned16(saved->o) || !aligned16(saved->o_lo) || (reinterpret_cast<uintptr_t>(saved->lse) & 3u))
       return CCA_ERR_ALIGN;
     if (saved->lat) lat = saved->lat;
     if (saved->q) q = saved->q;
@@ -375,6 +378,7 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
     if (saved->o) o = saved->o;
     lse = saved->lse;
     rnorm = saved->rnorm;
+    o_lo = saved->o_lo;
     if (reinterpret_cast<uintptr_t>(rnorm) & 3u) return CCA_ERR_ALIGN;
   }
   hipStream_t s = (hipStream_t)hip_stream;
@@ -382,7 +386,7 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   if (st != CCA_OK) return st;
   st = run_prologue(d, w, lat, q, k, v, rnorm, ws + L.pro, L.lat - L.pro, s);
   if (st != CCA_OK) return st;
-  st = run_attention(d, q, k, v, o, lse, w->temp, s);
+  st = run_attention(d, q, k, v, o, o_lo, lse, w->temp, s);
   if (st != CCA_OK) return st;
   return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s);
 }

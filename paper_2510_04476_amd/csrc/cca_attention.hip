@@ -66,7 +66,8 @@ __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 
 template <int DH, bool CAUSAL, bool BOUNDED>
 __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                               const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
-                                              float *__restrict__ LSE, int T, int Hq, int Hk, int BH, int nqb,
+                                              bf16_t *__restrict__ OLO, float *__restrict__ LSE, int T, int Hq, int Hk,
+                                              int BH, int nqb,
                                               int paired, float scale, float bound) {
   constexpr int KK = DH / 16;          // MFMA k-steps over the head width
   constexpr int DT = DH / 32;          // 32-wide output tiles over the head width
@@ -301,6 +302,12 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
             w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
             w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
             *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
+            if (OLO) {  // what the rounding dropped: the backward pass forms <dO, O> from o + o_lo
+              u32x2 x;
+              x.x = pack2(oacc[dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[dt][rg * 4 + 1] * inv - bf_hi(w.x));
+              x.y = pack2(oacc[dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[dt][rg * 4 + 3] * inv - bf_hi(w.y));
+              *reinterpret_cast<u32x2 *>(OLO + (orow - O) + dt * 32 + rg * 8 + half * 4) = x;
+            }
           }
         if (LSE && half == 0)
           LSE[((long long)b * Hq + h) * T + t] = (log2f(l) - negm[0]) * 0.69314718055994530942f;
@@ -312,7 +319,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
 template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
-    float *__restrict__ LSE, const float *__restrict__ temp, int qk_normed, int T, int Hq, int Hk, int BH, int nqb,
+    bf16_t *__restrict__ OLO, float *__restrict__ LSE, const float *__restrict__ temp, int qk_normed, int T, int Hq, int Hk, int BH, int nqb,
     int paired, float scale) {
   float bound = INFINITY;
   if (qk_normed) {
@@ -323,14 +330,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   }
   // exp2 arguments reach -2*bound: keep them inside the fp32 exponent range
   if (bound <= 60.f)
-    attn_fwd_body<DH, CAUSAL, true>(Q, K, V, O, LSE, T, Hq, Hk, BH, nqb, paired, scale, bound);
+    attn_fwd_body<DH, CAUSAL, true>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, bound);
   else
-    attn_fwd_body<DH, CAUSAL, false>(Q, K, V, O, LSE, T, Hq, Hk, BH, nqb, paired, scale, 0.f);
+    attn_fwd_body<DH, CAUSAL, false>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, 0.f);
 }
 
 template <int DH>
-hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse, const float *temp,
-                  hipStream_t s) {
+hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo, float *lse,
+                  const float *temp, hipStream_t s) {
   const int nqb = (d.T + BQ - 1) / BQ;
   const int BH = d.B * d.Hq;
   const bool causal = d.flags & CCA_CAUSAL;
@@ -343,11 +350,11 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
   if (!(d.flags & CCA_KEY_TEMP)) temp = nullptr;
   if (causal)
     attn_fwd_kernel<DH, true><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                                                            (bf16_t *)o, lse, temp, qk_normed, d.T, d.Hq, d.Hk, BH, nqb, paired,
+                                                            (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T, d.Hq, d.Hk, BH, nqb, paired,
                                                             d.scale);
   else
     attn_fwd_kernel<DH, false><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k,
-                                                             (const bf16_t *)v, (bf16_t *)o, lse, temp, qk_normed, d.T,
+                                                             (const bf16_t *)v, (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T,
                                                              d.Hq, d.Hk, BH, nqb, paired, d.scale);
   return hipGetLastError();
 }
@@ -359,9 +366,9 @@ bool attention_mfma_supported(const Dims &d) {
          (long long)d.T * d.Hk * d.dh * 2 < (1ll << 31);
 }
 
-hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                               const float *temp, hipStream_t s) {
-  return d.dh == 128 ? launch<128>(d, q, k, v, o, lse, temp, s) : launch<64>(d, q, k, v, o, lse, temp, s);
+hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo,
+                               float *lse, const float *temp, hipStream_t s) {
+  return d.dh == 128 ? launch<128>(d, q, k, v, o, o_lo, lse, temp, s) : launch<64>(d, q, k, v, o, o_lo, lse, temp, s);
 }
 
 }  // namespace cca

@@ -19,6 +19,12 @@
 //                     (one workgroup looping over the whole group leaves a causal grid of only B*H_k*T/128
 //                     unequal workgroups: measured 4.2 ms against 0.86 ms for dQ at the 16k CCGQA shape).
 // S is recomputed in both kernels (7 contractions instead of 5) in exchange for having no atomics.
+//
+// The probabilities must be the forward kernel's own: that kernel multiplies q by scale*log2(e) and rounds it
+// to bf16 before the score MFMAs, and lse is the log-sum-exp of THOSE scores.  Recomputing the scores from
+// the unrounded q against that lse leaves every row of P off by a common factor exp(lse_exact - lse) (about
+// 1 % where logits reach ~10: measured 0.8 % on d_q, d_k).  So q is scaled and rounded here exactly as there;
+// d_k then contracts dS with the scaled q and is multiplied by ln 2 instead of scale.
 #include <type_traits>
 
 #include "cca_internal.h"
@@ -41,6 +47,7 @@ constexpr int DH = 128;
 constexpr int KK = DH / 16, DT = DH / 32, KCH = DH / 8;
 constexpr int ROW = DH * 2 + 16;  // padded LDS row of one token: conflict-free 16-byte reads down a column of rows
 constexpr float LOG2E = 1.44269504088896340736f;
+constexpr float LN2 = 0.69314718055994530942f;  // the scaled q carries scale * log2(e): scale * q = ln 2 * q_scaled
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   bf16x2 v = {(__bf16)lo, (__bf16)hi};
@@ -63,7 +70,8 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int
 // Delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d]; one wavefront per 4 (t,h) rows (16 lanes x 16 bytes each)
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ dO, const bf16_t *__restrict__ O,
-                                                   float *__restrict__ delta, long long n_rows, int T, int Hq) {
+                                                   const bf16_t *__restrict__ OLO, float *__restrict__ delta,
+                                                   long long n_rows, int T, int Hq) {
   const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);  // row = (b*T + t)*Hq + h
   const int sub = threadIdx.x & 15;
   float acc = 0.f;
@@ -72,6 +80,12 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ d
     const u32x4 b = *reinterpret_cast<const u32x4 *>(O + row * DH + sub * 8);
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc += bf_lo(a[i]) * bf_lo(b[i]) + bf_hi(a[i]) * bf_hi(b[i]);
+    if (OLO) {  // O to ~16 mantissa bits: with O rounded to bf16 alone, the error of Delta dominates dQ and dK
+                // whenever the softmax is flat (measured 2 % at T = 700 with 0.02-scaled weights)
+      const u32x4 c = *reinterpret_cast<const u32x4 *>(OLO + row * DH + sub * 8);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc += bf_lo(a[i]) * bf_lo(c[i]) + bf_hi(a[i]) * bf_hi(c[i]);
+    }
   }
 #pragma unroll
   for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
@@ -142,7 +156,12 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     const bf16_t *pd = dO + (((long long)b * T + trow) * Hq + h) * DH + half * 8;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pq + kk * 16));
+      u32x4 w = *reinterpret_cast<const u32x4 *>(pq + kk * 16);
+      w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+      w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+      w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+      w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+      qf[kk] = __builtin_bit_cast(bf16x8, w);  // log2 units, rounded as in the forward kernel
       dof[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pd + kk * 16));
     }
   }
@@ -187,7 +206,7 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         const int lim = (CAUSAL ? min(qw0 + l32, T - 1) : T - 1) - kv0 - ks * 32 - 4 * half;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -lse2));
+          float p = __builtin_amdgcn_exp2f(s[r] - lse2);
           if (need_mask && (8 * (r >> 2) + (r & 3) > lim)) p = 0.f;
           ds[r] = p * (dp[r] - delta);
         }
@@ -305,7 +324,12 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
-      *reinterpret_cast<u32x4 *>(sQ + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rq[i];
+      u32x4 w = rq[i];  // q in log2 units, rounded as in the forward kernel
+      w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+      w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+      w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+      w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+      *reinterpret_cast<u32x4 *>(sQ + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = w;
       *reinterpret_cast<u32x4 *>(sD + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rd[i];
     }
     if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = rstat;
@@ -351,7 +375,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
           for (int e = 0; e < 4; ++e) {
             const int r = rg * 4 + e;
             const int t = t0 + qs * 32 + rg * 8 + half * 4 + e;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[r], c, -l4[e]));
+            float p = __builtin_amdgcn_exp2f(s[r] - l4[e]);
             if (need_mask && ((CAUSAL && key > t) || t >= T || key >= T)) p = 0.f;
             pr[r] = p;
             ds[r] = p * (dp[r] - d4[e]);
@@ -393,8 +417,8 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-          const f32x4 w = {dk[dt][rg * 4 + 0] * scale, dk[dt][rg * 4 + 1] * scale, dk[dt][rg * 4 + 2] * scale,
-                           dk[dt][rg * 4 + 3] * scale};
+          const f32x4 w = {dk[dt][rg * 4 + 0] * LN2, dk[dt][rg * 4 + 1] * LN2, dk[dt][rg * 4 + 2] * LN2,
+                           dk[dt][rg * 4 + 3] * LN2};
           const f32x4 x = {dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1], dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]};
           if (MODE != 1) *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
           if (MODE != 2) *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
@@ -410,8 +434,8 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         u32x2 w, x;
-        w.x = pack2(dk[dt][rg * 4 + 0] * scale, dk[dt][rg * 4 + 1] * scale);
-        w.y = pack2(dk[dt][rg * 4 + 2] * scale, dk[dt][rg * 4 + 3] * scale);
+        w.x = pack2(dk[dt][rg * 4 + 0] * LN2, dk[dt][rg * 4 + 1] * LN2);
+        w.y = pack2(dk[dt][rg * 4 + 2] * LN2, dk[dt][rg * 4 + 3] * LN2);
         x.x = pack2(dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1]);
         x.y = pack2(dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]);
         if (MODE != 1) *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
@@ -456,11 +480,12 @@ size_t attention_bwd_scratch_bytes(const Dims &d) {
 }
 
 hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                              const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                              const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                               hipStream_t s) {
   const bool causal = d.flags & CCA_CAUSAL;
   const long long n_rows = d.rows() * d.Hq;
-  delta_kernel<<<(unsigned)((n_rows + 15) / 16), 256, 0, s>>>((const bf16_t *)d_o, (const bf16_t *)o, delta, n_rows, d.T,
+  delta_kernel<<<(unsigned)((n_rows + 15) / 16), 256, 0, s>>>((const bf16_t *)d_o, (const bf16_t *)o, (const bf16_t *)o_lo, delta,
+                                                             n_rows, d.T,
                                                              d.Hq);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

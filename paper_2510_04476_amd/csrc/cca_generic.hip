@@ -222,7 +222,8 @@ hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat
 template <typename T, int DH_MAX>
 __global__ __launch_bounds__(64) void attention_generic_kernel(const T *__restrict__ q, const T *__restrict__ k,
                                                               const T *__restrict__ v, T *__restrict__ o,
-                                                              float *__restrict__ lse, int Tn, int Hq, int Hk, int dh,
+                                                              T *__restrict__ o_lo, float *__restrict__ lse, int Tn,
+                                                              int Hq, int Hk, int dh,
                                                               float scale, int causal) {
   __shared__ float qs[DH_MAX];
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -263,7 +264,10 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(const T *__restri
     if (i < dh) {
       float a = acc[i] * f;
       for (int off = 32; off > 0; off >>= 1) a += __shfl_xor(a, off);
-      if (lane == 0) store_f(o + qrow * dh + i, a * inv);
+      if (lane == 0) {
+        store_f(o + qrow * dh + i, a * inv);
+        if (o_lo) store_f(o_lo + qrow * dh + i, a * inv - load_f(o + qrow * dh + i));  // what the rounding dropped
+      }
     }
   }
   if (lse && lane == 0) lse[((long long)b * Hq + h) * Tn + t] = M + logf(Z);
@@ -271,11 +275,11 @@ __global__ __launch_bounds__(64) void attention_generic_kernel(const T *__restri
 
 template <typename T>
 static hipError_t attention_generic_t(const Dims &d, const void *q, const void *k, const void *v, void *o,
-                                      float *lse, hipStream_t s) {
+                                      void *o_lo, float *lse, hipStream_t s) {
   dim3 grid(d.T, d.Hq, d.B);
   const int causal = (d.flags & CCA_CAUSAL) ? 1 : 0;
 #define LAUNCH(DH)                                                                                      \
-  attention_generic_kernel<T, DH><<<grid, 64, 0, s>>>((const T *)q, (const T *)k, (const T *)v, (T *)o, lse, d.T, \
+  attention_generic_kernel<T, DH><<<grid, 64, 0, s>>>((const T *)q, (const T *)k, (const T *)v, (T *)o, (T *)o_lo, lse, d.T, \
                                                       d.Hq, d.Hk, d.dh, d.scale, causal)
   if (d.dh <= 32) LAUNCH(32);
   else if (d.dh <= 64) LAUNCH(64);
@@ -285,9 +289,11 @@ static hipError_t attention_generic_t(const Dims &d, const void *q, const void *
   return hipGetLastError();
 }
 
-hipError_t attention_generic(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                             hipStream_t s) {
-  return d.bf16 ? attention_generic_t<bf16_t>(d, q, k, v, o, lse, s) : attention_generic_t<float>(d, q, k, v, o, lse, s);
+hipError_t attention_generic(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo,
+                             float *lse, hipStream_t s) {
+  // fp32 storage rounds nothing away: no low part
+  return d.bf16 ? attention_generic_t<bf16_t>(d, q, k, v, o, o_lo, lse, s)
+                : attention_generic_t<float>(d, q, k, v, o, nullptr, lse, s);
 }
 
 }  // namespace cca

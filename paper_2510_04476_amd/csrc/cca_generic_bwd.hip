@@ -81,16 +81,22 @@ hipError_t gemm_generic_ex(bool bf16, const void *A, long long lda, bool ta, con
 // ---------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void delta_generic_kernel(const T *__restrict__ dO, const T *__restrict__ O,
-                                                           float *__restrict__ delta, long long n_rows, int Tn, int Hq,
-                                                           int dh) {
+                                                           const T *__restrict__ OLO, float *__restrict__ delta,
+                                                           long long n_rows, int Tn, int Hq, int dh) {
   const long long row = (long long)blockIdx.x * 256 + threadIdx.x;  // (b*T + t)*Hq + h
   if (row >= n_rows) return;
   float acc = 0.f;
-  for (int i = 0; i < dh; ++i) acc = fmaf(load_f(dO + row * dh + i), load_f(O + row * dh + i), acc);
+  for (int i = 0; i < dh; ++i)
+    acc = fmaf(load_f(dO + row * dh + i), load_f(O + row * dh + i) + (OLO ? load_f(OLO + row * dh + i) : 0.f), acc);
   const long long bt = row / Hq;
   const int h = (int)(row % Hq);
   delta[((bt / Tn) * Hq + h) * Tn + (bt % Tn)] = acc;
 }
+
+// log2-unit score against the forward MFMA kernel's own rounding of q (q * scale * log2(e) rounded to bf16):
+// used when that kernel produced lse, so that the recomputed probabilities are exactly its probabilities
+__device__ __forceinline__ float q_log2_rounded(float q, float c) { return bf16_to_f32(f32_to_bf16(q * c)); }
+constexpr float kLog2e = 1.44269504088896340736f;
 
 // one wavefront per query row (b, h, t); lane l walks keys l, l + 64, ...
 template <typename T, int DH_MAX>
@@ -99,18 +105,20 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_generic_kernel(const T *__rest
                                                                 const float *__restrict__ lse,
                                                                 const float *__restrict__ delta, T *__restrict__ dq,
                                                                 int Tn, int Hq, int Hk, int dh, float scale,
-                                                                int causal) {
+                                                                int causal, int q_rounded) {
   __shared__ float qs[DH_MAX], ds_[DH_MAX];
   const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
   const int g = h / (Hq / Hk);
   const int lane = threadIdx.x;
   const long long qrow = ((long long)b * Tn + t) * Hq + h;
   for (int i = lane; i < dh; i += 64) {
-    qs[i] = load_f(q + qrow * dh + i) * scale;
+    const float qv = load_f(q + qrow * dh + i);
+    qs[i] = q_rounded ? q_log2_rounded(qv, scale * kLog2e) : qv * scale;
     ds_[i] = load_f(dO + qrow * dh + i);
   }
   __syncthreads();
-  const float L = lse[((long long)b * Hq + h) * Tn + t], Dl = delta[((long long)b * Hq + h) * Tn + t];
+  const float L = lse[((long long)b * Hq + h) * Tn + t] * (q_rounded ? kLog2e : 1.f);
+  const float Dl = delta[((long long)b * Hq + h) * Tn + t];
   float acc[DH_MAX];
 #pragma unroll
   for (int i = 0; i < DH_MAX; ++i) acc[i] = 0.f;
@@ -123,7 +131,7 @@ __global__ __launch_bounds__(64) void attn_bwd_dq_generic_kernel(const T *__rest
       dot = fmaf(qs[i], load_f(kp + i), dot);
       dp = fmaf(ds_[i], load_f(vp + i), dp);
     }
-    const float dsv = expf(dot - L) * (dp - Dl);
+    const float dsv = (q_rounded ? exp2f(dot - L) : expf(dot - L)) * (dp - Dl);
 #pragma unroll
     for (int i = 0; i < DH_MAX; ++i)
       if (i < dh) acc[i] = fmaf(dsv, load_f(kp + i), acc[i]);
@@ -146,14 +154,14 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_generic_kernel(const T *__res
                                                                  const float *__restrict__ lse,
                                                                  const float *__restrict__ delta, T *__restrict__ out,
                                                                  int Tn, int Hq, int Hk, int dh, float scale,
-                                                                 int causal) {
+                                                                 int causal, int q_rounded) {
   __shared__ float ks[DH_MAX], vs[DH_MAX];
   const int s = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int R = Hq / Hk;
   const int lane = threadIdx.x;
   const long long krow = ((long long)b * Tn + s) * Hk + g;
   for (int i = lane; i < dh; i += 64) {
-    ks[i] = load_f(k + krow * dh + i) * scale;
+    ks[i] = load_f(k + krow * dh + i) * (q_rounded ? 1.f : scale);
     vs[i] = load_f(v + krow * dh + i);
   }
   __syncthreads();
@@ -168,11 +176,12 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_generic_kernel(const T *__res
     const T *qp = q + qrow * dh, *dp_ = dO + qrow * dh;
     float dot = 0.f, dp = 0.f;
     for (int i = 0; i < dh; ++i) {
-      dot = fmaf(ks[i], load_f(qp + i), dot);
+      const float qv = load_f(qp + i);
+      dot = fmaf(ks[i], q_rounded ? q_log2_rounded(qv, scale * kLog2e) : qv, dot);
       dp = fmaf(vs[i], load_f(dp_ + i), dp);
     }
     const long long st = ((long long)b * Hq + h) * Tn + t;
-    const float p = expf(dot - lse[st]);
+    const float p = q_rounded ? exp2f(dot - lse[st] * kLog2e) : expf(dot - lse[st]);
     const float w = WHICH == 0 ? p * (dp - delta[st]) * scale : p;
     const T *src = WHICH == 0 ? qp : dp_;
 #pragma unroll
@@ -191,23 +200,25 @@ __global__ __launch_bounds__(64) void attn_bwd_dkv_generic_kernel(const T *__res
 
 template <typename T>
 static hipError_t attention_bwd_generic_t(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                                          const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v,
+                                          const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v,
                                           float *delta, hipStream_t s) {
   const long long n_rows = d.rows() * d.Hq;
-  delta_generic_kernel<T><<<(unsigned)((n_rows + 255) / 256), 256, 0, s>>>((const T *)d_o, (const T *)o, delta, n_rows,
+  delta_generic_kernel<T><<<(unsigned)((n_rows + 255) / 256), 256, 0, s>>>((const T *)d_o, (const T *)o, (const T *)o_lo, delta, n_rows,
                                                                           d.T, d.Hq, d.dh);
   const int causal = (d.flags & CCA_CAUSAL) ? 1 : 0;
+  const int q_rounded = attention_mfma_supported(d) ? 1 : 0;  // lse then comes from the MFMA forward kernel
   dim3 gq(d.T, d.Hq, d.B), gk(d.T, d.Hk, d.B);
 #define LAUNCH(DH)                                                                                                    \
   do {                                                                                                                \
     attn_bwd_dq_generic_kernel<T, DH><<<gq, 64, 0, s>>>((const T *)q, (const T *)k, (const T *)v, (const T *)d_o, lse, \
-                                                        delta, (T *)d_q, d.T, d.Hq, d.Hk, d.dh, d.scale, causal);     \
+                                                        delta, (T *)d_q, d.T, d.Hq, d.Hk, d.dh, d.scale, causal,      \
+                                                        q_rounded);                                                   \
     attn_bwd_dkv_generic_kernel<T, DH, 0><<<gk, 64, 0, s>>>((const T *)q, (const T *)k, (const T *)v, (const T *)d_o,  \
                                                             lse, delta, (T *)d_k, d.T, d.Hq, d.Hk, d.dh, d.scale,     \
-                                                            causal);                                                  \
+                                                            causal, q_rounded);                                       \
     attn_bwd_dkv_generic_kernel<T, DH, 1><<<gk, 64, 0, s>>>((const T *)q, (const T *)k, (const T *)v, (const T *)d_o,  \
                                                             lse, delta, (T *)d_v, d.T, d.Hq, d.Hk, d.dh, d.scale,     \
-                                                            causal);                                                  \
+                                                            causal, q_rounded);                                       \
   } while (0)
   if (d.dh <= 32) LAUNCH(32);
   else if (d.dh <= 64) LAUNCH(64);
@@ -218,10 +229,10 @@ static hipError_t attention_bwd_generic_t(const Dims &d, const void *q, const vo
 }
 
 hipError_t attention_bwd_generic(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                                 const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                                 const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                                  hipStream_t s) {
-  return d.bf16 ? attention_bwd_generic_t<bf16_t>(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, delta, s)
-                : attention_bwd_generic_t<float>(d, q, k, v, o, lse, d_o, d_q, d_k, d_v, delta, s);
+  return d.bf16 ? attention_bwd_generic_t<bf16_t>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s)
+                : attention_bwd_generic_t<float>(d, q, k, v, o, nullptr, lse, d_o, d_q, d_k, d_v, delta, s);
 }
 
 // ---------------------------------------------------------------------------

@@ -42,8 +42,9 @@ hipError_t gemm_generic(bool bf16, const void *A, const void *Bm, void *C, long 
                         hipStream_t s);
 hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
                             float *rnorm, hipStream_t s);
-hipError_t attention_generic(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                             hipStream_t s);
+// o_lo (may be NULL): bf16 storage only, receives the part of the fp32 result that rounding o to bf16 dropped
+hipError_t attention_generic(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo,
+                             float *lse, hipStream_t s);
 
 // ---- gfx950 MFMA kernels (bf16 storage) -----------------------------------
 // C (M,N) = A (M,K) * Bt (N,K)^T; Bt is the K-contiguous ("transposed") weight.
@@ -54,8 +55,8 @@ hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStr
 
 bool attention_mfma_supported(const Dims &d);
 // temp (H_k log-temperatures, device) is read only when d.flags has QK_NORM and KEY_TEMP: it bounds the scores
-hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, float *lse,
-                               const float *temp, hipStream_t s);
+hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo,
+                               float *lse, const float *temp, hipStream_t s);
 
 // no transform selected: q, k, v are slices of the latent rows (plus the optional value-shift)
 bool prologue_is_split_copy(const Dims &d);
@@ -65,7 +66,7 @@ hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k,
 bool attention_bwd_supported(const Dims &d);
 size_t attention_bwd_scratch_bytes(const Dims &d);  // Delta (B,H_q,T) fp32
 hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                              const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                              const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                               hipStream_t s);
 
 // C (Mo,No) = A (K,Mo)^T * B (K,No): weight gradients, contraction over token rows, split over K into fp32
@@ -80,7 +81,7 @@ hipError_t gemm_tn_mfma_bf16(const void *A, long long lda, const void *Bm, long 
 hipError_t gemm_generic_ex(bool bf16, const void *A, long long lda, bool ta, const void *Bm, long long ldb, bool tb,
                            void *C, long long ldc, long long M, int N, long long K, hipStream_t s);
 hipError_t attention_bwd_generic(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                                 const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                                 const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                                  hipStream_t s);
 size_t prologue_bwd_generic_scratch_bytes(const Dims &d);
 hipError_t prologue_bwd_generic(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,

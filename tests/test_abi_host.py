@@ -78,7 +78,7 @@ def test_forward_rejects_null_misaligned_and_small_workspace():
     assert call(w, C.c_void_p(0x10008), p, p, need) == B.CCA_ERR_ALIGN
     assert call(w, p, p, p, need - 1) == B.CCA_ERR_WORKSPACE
     assert call(w, p, p, None, need) == B.CCA_ERR_WORKSPACE
-    assert lib.cca_attention(C.byref(cc), p, p, None, p, None, p, None) == B.CCA_ERR_NULL
+    assert lib.cca_attention(C.byref(cc), p, p, None, p, None, None, p, None) == B.CCA_ERR_NULL
     assert lib.cca_prologue(C.byref(cc), None, p, p, p, p, None, p, 0, None) == B.CCA_ERR_NULL
     assert lib.cca_down_project(C.byref(cc), p, None, p, p, 0, None) == B.CCA_ERR_NULL
     assert lib.cca_up_project(C.byref(cc), p, p, None, p, 0, None) == B.CCA_ERR_NULL

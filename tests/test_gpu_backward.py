@@ -102,6 +102,18 @@ def test_backward_small_shapes(i):
     say(compare(got, ref, w["dtype"]))
 
 
+@pytest.mark.parametrize("i", [3, 4, 7])
+def test_backward_small_shapes_literal_weights(i):
+    """0.02-scaled weights: the softmax is nearly flat, the regime in which <d_o, o> taken from the bf16-rounded o
+    alone would put a 2 % error on d_q / d_k and, through them, on the convolution filter gradients."""
+    w = SMALL[i]
+    say("case backward small, literal weights", i, w)
+    inp = make_inputs(w, seed=60 + i)
+    d_out = make_upstream_grad(w, seed=1)
+    got, _ = gpu_backward(w, inp, d_out)
+    say(compare(got, oracle_backward(w, inp, d_out), w["dtype"]))
+
+
 def test_backward_tiny_fp32_literal():
     w = WORKLOADS["tiny_fp32"]
     say("case backward tiny_fp32")

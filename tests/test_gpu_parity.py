@@ -50,6 +50,15 @@ def compare_all(w, inp, ref, out, saved, rows=None):
                              np.linalg.norm(ref["k"], axis=-1) / np.linalg.norm(ref["k3"], axis=-1)], axis=-1)
     rel, _ = errors(to_np(saved.rnorm), rn_ref)
     assert rel <= (1e-2 if dt == "bf16" else 1e-5), ("rnorm", rel)
+    if saved.o_lo is not None:
+        # o + o_lo carries the attention output to ~16 mantissa bits; what is left is the kernel's own error
+        # (bf16 probabilities), far below the rounding of o alone at every element
+        o_ref = ref["o"].reshape(B_, -1, w["Hq"] * w["dh"])
+        rel_hi, _ = errors(sel(to_np(saved.o)), o_ref)
+        rel_sum, _ = errors(sel(to_np(saved.o) + to_np(saved.o_lo)), o_ref)
+        assert rel_sum <= rel_hi, ("o + o_lo", rel_sum, rel_hi)
+        assert float(np.abs(sel(to_np(saved.o_lo))).max()) <= 2.0 ** -8 * max(1.0, float(np.abs(o_ref).max()))
+        res["o+o_lo"] = (rel_sum, rel_hi)
     return res
 
 
@@ -224,8 +233,9 @@ def test_attention_backward_stage(T, Hq, Hk, causal):
     cfg = P.CCAConfig(B=Bn, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh, flags=flags)
     dev = lambda a: torch.from_numpy(a).to("cuda", torch.bfloat16)
     dq_, dk_, dv_, do_ = dev(q), dev(k), dev(v), dev(do)
-    o, lse = P.cca_attention(cfg, dq_, dk_, dv_, want_lse=True, temp=torch.from_numpy(temp).cuda())
-    g_q, g_k, g_v = P.cca_attention_backward(cfg, dq_, dk_, dv_, o, lse, do_)
+    o_lo = torch.empty(Bn, T, Hq * dh, dtype=torch.bfloat16, device="cuda")
+    o, lse = P.cca_attention(cfg, dq_, dk_, dv_, want_lse=True, temp=torch.from_numpy(temp).cuda(), o_lo=o_lo)
+    g_q, g_k, g_v = P.cca_attention_backward(cfg, dq_, dk_, dv_, o, lse, do_, o_lo=o_lo)
     torch.cuda.synchronize()
     r_q, r_k, r_v = O.attention_bwd(do, q, k, v, 1.0 / np.sqrt(dh), causal=causal)
     say("dq", check_tap(to_np(g_q), r_q, "bf16", "d_q"))
