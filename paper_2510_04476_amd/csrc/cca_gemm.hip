@@ -4,8 +4,13 @@
 //
 // Both operands are K-contiguous, so a lane's 8-element MFMA fragment is one
 // 16-byte LDS read.  Workgroup tile 256 x BN x 64 with 8 wavefronts; LDS is
-// double-buffered and XOR-swizzled per 16-byte chunk; K-slab k+2 travels HBM ->
-// registers and slab k+1 registers -> LDS while slab k is multiplied.  The MFMA is issued with the weight rows as its first operand,
+// double-buffered and XOR-swizzled per 16-byte chunk; K-slab k+1 travels HBM ->
+// LDS directly (global_load_lds, no staging registers, no ds_write) while slab k
+// is multiplied, its loads spread over the slab's four 16-wide MFMA steps so
+// that the LDS writes trickle in between the fragment reads instead of
+// arriving in one burst (the LDS write port, ~75 B/clk against ~230 B/clk for
+// reads, is what this kernel feels first: without the stores it runs a third
+// faster).  The MFMA is issued with the weight rows as its first operand,
 // which leaves every lane with 4 consecutive output columns of one row, so
 // the epilogue packs them to bf16, stages the tile in LDS and writes whole
 // rows with 16-byte stores.
@@ -39,8 +44,6 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
   constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
   constexpr int MI = WM / 32, NI = WN / 32;            // 32x32 MFMA tiles per wave
   static_assert(MI * 32 == WM && NI * 32 == WN, "wave tile must be a multiple of 32");
-  constexpr int A_CHUNKS = BM * 8 / NTHREADS;  // 16-byte chunks per thread per slab
-  constexpr int B_CHUNKS = BN * 8 / NTHREADS;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int STAGE = (BM + BN) * 8;  // 16-byte chunks per pipeline stage
   u32x4 *const sbase = reinterpret_cast<u32x4 *>(smem);
@@ -60,26 +63,39 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int l32 = lane & 31, half = lane >> 5;
 
-  // global source rows of this thread's chunks (clamped: rows past the edge are loaded but never stored)
-  const bf16_t *a_src[A_CHUNKS];
-  const bf16_t *b_src[B_CHUNKS];
-  int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
+  // Direct global -> LDS loads: wave instruction i deposits 64 x 16 bytes at LDS chunks [i*64, i*64+64) of the
+  // stage (A rows first, then B rows; 8 chunks per row), so lane L fetches the chunk that the XOR swizzle puts
+  // at that position.  No staging registers, no ds_write.
+  constexpr int N_INSTR = (BM + BN) * 8 / 64;
+  constexpr int PER_WAVE = N_INSTR / (NTHREADS / 64);
+  static_assert(N_INSTR % (NTHREADS / 64) == 0, "instructions must divide evenly over the wavefronts");
+  const bf16_t *g_src[PER_WAVE];
 #pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) {
-    const int id = tid + i * NTHREADS, r = id >> 3, c = id & 7;
-    long long gr = m0 + r;
-    gr = gr < M ? gr : M - 1;
-    a_src[i] = A + gr * K + c * 8;
-    a_dst[i] = swz(r, c);
+  for (int u = 0; u < PER_WAVE; ++u) {
+    const int i = wave + u * (NTHREADS / 64);
+    const int pos = i * 64 + lane;            // chunk position inside the stage
+    const bool isb = pos >= BM * 8;
+    const int r = (isb ? pos - BM * 8 : pos) >> 3, cs = pos & 7;
+    const int c = cs ^ ((r & 7) ^ ((r >> 3) & 1));  // inverse of swz(): the chunk stored at this position
+    if (!isb) {
+      long long gr = m0 + r;
+      gr = gr < M ? gr : M - 1;
+      g_src[u] = A + gr * K + c * 8;
+    } else {
+      int gr = n0 + r;
+      gr = gr < N ? gr : N - 1;
+      g_src[u] = Bt + (long long)gr * K + c * 8;
+    }
   }
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef __attribute__((address_space(1))) void glb_void;
+  auto issue_slab = [&](int k0, int buf) {
 #pragma unroll
-  for (int i = 0; i < B_CHUNKS; ++i) {
-    const int id = tid + i * NTHREADS, r = id >> 3, c = id & 7;
-    int gr = n0 + r;
-    gr = gr < N ? gr : N - 1;
-    b_src[i] = Bt + (long long)gr * K + c * 8;
-    b_dst[i] = swz(r, c);
-  }
+    for (int u = 0; u < PER_WAVE; ++u) {
+      const int i = wave + u * (NTHREADS / 64);
+      __builtin_amdgcn_global_load_lds((glb_void *)(g_src[u] + k0), (lds_void *)(sbase + buf * STAGE + i * 64), 16, 0, 0);
+    }
+  };
 
   f32x16 acc[NI][MI];
 #pragma unroll
@@ -89,33 +105,22 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
 
-  u32x4 ra[A_CHUNKS], rb[B_CHUNKS];
-  auto load_slab = [&](int k0) {
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) ra[i] = *reinterpret_cast<const u32x4 *>(a_src[i] + k0);
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) rb[i] = *reinterpret_cast<const u32x4 *>(b_src[i] + k0);
-  };
-  auto store_slab = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) sbase[buf * STAGE + a_dst[i]] = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; ++i) sbase[buf * STAGE + BM * 8 + b_dst[i]] = rb[i];
-  };
-
-  // Slab kt+1 is in registers when iteration kt starts (loaded during kt-1): it goes to the other LDS buffer
-  // first, so its stores drain under this slab's MFMAs, then the loads of slab kt+2 are issued.
   const int nk = K / BK;
-  load_slab(0);
-  store_slab(0);
-  if (nk > 1) load_slab(BK);
+  issue_slab(0, 0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) store_slab(buf ^ 1);  // last read before the barrier that ended iteration kt-1
-    if (kt + 2 < nk) load_slab((kt + 2) * BK);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
+      // the loads of slab kt+1 trickle in between this slab's fragment reads instead of arriving in one burst
+      if (kt + 1 < nk) {
+#pragma unroll
+        for (int u = kk * PER_WAVE / 4; u < (kk + 1) * PER_WAVE / 4; ++u) {
+          const int i = wave + u * (NTHREADS / 64);
+          __builtin_amdgcn_global_load_lds((glb_void *)(g_src[u] + (kt + 1) * BK), (lds_void *)(sbase + (buf ^ 1) * STAGE + i * 64), 16, 0, 0);
+        }
+      }
       bf16x8 fa[MI], fb[NI];
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi) {
@@ -135,6 +140,7 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
         for (int mi = 0; mi < MI; ++mi)
           acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[ni][mi], 0, 0, 0);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
