@@ -207,6 +207,35 @@ def main() -> int:
                "speedup_ccgqa_vs_mha": round(mha_ms / ms, 3), "flop_ratio": round(flm["total"] / fl["total"], 3)}
         del xm, wtm, wsm, outm
 
+    # ---- head-to-head at B = 4 (timing only: tensors of the same distributions drawn on the device) ----------
+    h2h = None
+    if args.workload == "ccgqa_16k" and not args.no_mha:
+        def time_b4(name):
+            wb = WORKLOADS[name]
+            cb = P.config_from_workload(wb)
+            g = torch.Generator(device=x.device).manual_seed(0)
+            rn = lambda *sh, sc=1.0: (torch.randn(*sh, device=x.device, generator=g) * sc).to(cb.torch_dtype)
+            xb = rn(cb.B, cb.T, cb.d_model)
+            wtb = P.CCAWeights(w_down=rn(cb.d_model, cb.n_lat, sc=0.02), w_out=rn(cb.e_q, cb.d_model, sc=0.02),
+                               w_conv_seq=rn(cb.e_q + cb.e_kv, cb.k_seq, sc=0.02),
+                               w_conv_ch=rn(cb.n_q_heads + cb.n_kv_heads, cb.head_dim, cb.head_dim, cb.k_ch, sc=0.02),
+                               temp=torch.randn(cb.n_kv_heads, device=x.device, generator=g) * 0.02)
+            wsb = P.new_workspace(cb, x.device)
+            ob = torch.empty_like(xb)
+            for _ in range(2):
+                P.cca_forward(cb, wtb, xb, out=ob, workspace=wsb)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(5):
+                P.cca_forward(cb, wtb, xb, out=ob, workspace=wsb)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / 5, P.forward_flops(cb)["total"]
+        c_ms, c_fl = time_b4("ccgqa_16k_b4")
+        m_ms, m_fl = time_b4("mha_16k_b4")
+        h2h = {"ccgqa_ms": round(c_ms, 4), "ccgqa_tflops": round(c_fl / c_ms / 1e9, 1), "mha_ms": round(m_ms, 4),
+               "mha_tflops": round(m_fl / m_ms / 1e9, 1), "speedup_ccgqa_vs_mha": round(m_ms / c_ms, 3),
+               "flop_ratio": round(m_fl / c_fl, 3)}
+
     # ---- CPU oracle on a causal prefix of the same inputs -----------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -253,6 +282,7 @@ def main() -> int:
         "prologue_gbps": round((cfg.B * cfg.T * (cfg.n_lat + cfg.e_q + 2 * cfg.e_kv) * 2) / pro_ms / 1e6, 1),
         "backward": bwd,
         "mha_same_kernel": mha,
+        "head_to_head_b4": h2h,
         "roofline": {"kernel": "attn_fwd_kernel (latent attention)", "bound": "mfma",
                      "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),

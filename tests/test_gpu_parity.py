@@ -241,3 +241,22 @@ def test_attention_backward_stage(T, Hq, Hk, causal):
     say("dq", check_tap(to_np(g_q), r_q, "bf16", "d_q"))
     say("dk", check_tap(to_np(g_k), r_k, "bf16", "d_k"))
     say("dv", check_tap(to_np(g_v), r_v, "bf16", "d_v"))
+
+
+# ---- config 4: CCGQA vs MHA head-to-head at B = 4, T = 16384, both through the same kernels.  The HIP path runs
+#      the full batch; the oracle (batch items are independent) checks the first and the last item on sampled rows.
+@pytest.mark.parametrize("name", ["ccgqa_16k_b4", "mha_16k_b4"])
+def test_head_to_head_b4_sampled_rows(name):
+    w = WORKLOADS[name]
+    say("case head-to-head", name)
+    inp = make_inputs(w, seed=0)
+    cfg, out, saved = run_gpu(w, inp)
+    rows = sample_rows(w["T"], 48)
+    items = [0, w["B"] - 1]
+    w2 = dict(w, B=len(items))
+    ref = oracle_forward(w2, dict(inp, x=inp["x"][items]), rows=rows)
+    pick = lambda t: t[items]
+    sub = B.CCASaved(lat=pick(saved.lat), q=pick(saved.q), k=pick(saved.k), v=pick(saved.v), o=pick(saved.o),
+                     lse=pick(saved.lse), rnorm=pick(saved.rnorm), o_lo=pick(saved.o_lo))
+    res = compare_all(w2, inp, ref, pick(out), sub, rows=rows)
+    say(res)
