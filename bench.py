@@ -32,6 +32,73 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((148.36 + 32.08) * 2 ** 20)}
 
 
+# Layouts of the grid, all at E = 2048 and d_h = 128 through the same entry points.  "gqa8" reads the paper's GQA-8 as
+# 8x fewer KV heads than MHA (16 query heads, 2 KV heads: the KV-cache size of the C2 = 8 layouts).
+GRID_LAYOUTS = {
+    "mha": dict(Hq=16, Hk=16, paper_flags=False),
+    "gqa8": dict(Hq=16, Hk=2, paper_flags=False),
+    "cca4x": dict(Hq=4, Hk=4, paper_flags=True),
+    "ccgqa": dict(Hq=8, Hk=2, paper_flags=True),
+}
+
+
+def run_grid(P, torch) -> int:
+    from paper_2510_04476_amd import binding as b
+    dev = "cuda"
+    rows = []
+    for causal in (True, False):
+        for S in (512, 1024, 2048, 4096, 8192, 16384):
+            base = {}
+            for name, lay in GRID_LAYOUTS.items():
+                w = dict(B=1, T=S, E=2048, dh=128, k_seq=2, k_ch=2, dtype="bf16", **lay)
+                cfg = P.config_from_workload(w)
+                if not causal:
+                    cfg.flags &= ~b.CCA_CAUSAL
+                g = torch.Generator(device=dev).manual_seed(0)
+                rn = lambda *sh, sc=1.0: (torch.randn(*sh, device=dev, generator=g) * sc).to(cfg.torch_dtype)
+                x = rn(cfg.B, cfg.T, cfg.d_model)
+                wt = P.CCAWeights(w_down=rn(cfg.d_model, cfg.n_lat, sc=0.02), w_out=rn(cfg.e_q, cfg.d_model, sc=0.02),
+                                  w_conv_seq=rn(cfg.e_q + cfg.e_kv, cfg.k_seq, sc=0.02),
+                                  w_conv_ch=rn(cfg.n_q_heads + cfg.n_kv_heads, cfg.head_dim, cfg.head_dim, cfg.k_ch, sc=0.02),
+                                  temp=torch.randn(cfg.n_kv_heads, device=dev, generator=g) * 0.02)
+                d_out = rn(cfg.B, cfg.T, cfg.d_model)
+                out, d_x = torch.empty_like(x), torch.empty_like(x)
+                saved = P.CCASaved.allocate(cfg, dev)
+                grads = P.CCAGrads.allocate_like(wt)
+                ws, wsb = P.new_workspace(cfg, dev), P.new_backward_workspace(cfg, dev)
+                fwd = lambda: P.cca_forward(cfg, wt, x, out=out, saved=None, workspace=ws)
+
+                def fwd_bwd():
+                    P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
+                    P.cca_backward(cfg, wt, x, saved, d_out, d_x=d_x, grads=grads, workspace=wsb)
+
+                def timeit(fn, n):
+                    for _ in range(2):
+                        fn()
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(n):
+                        fn()
+                    torch.cuda.synchronize()
+                    return (time.perf_counter() - t0) * 1e3 / n
+
+                n = 30 if S <= 4096 else 10
+                f_ms, fb_ms = timeit(fwd, n), timeit(fwd_bwd, max(3, n // 3))
+                base.setdefault("f", f_ms if name == "mha" else None)
+                base.setdefault("fb", fb_ms if name == "mha" else None)
+                r = {"layout": name, "S": S, "causal": causal, "fwd_ms": round(f_ms, 4), "fwd_bwd_ms": round(fb_ms, 4),
+                     "bwd_ms": round(fb_ms - f_ms, 4), "fwd_speedup_vs_mha": round(base["f"] / f_ms, 3),
+                     "bwd_speedup_vs_mha": round((base["fb"] - base["f"]) / (fb_ms - f_ms), 3)}
+                rows.append(r)
+                print(json.dumps(r), flush=True)
+                del x, wt, d_out, out, d_x, saved, grads, ws, wsb
+    print(f"{'layout':8s} {'S':>6s} {'causal':>6s} {'fwd ms':>9s} {'bwd ms':>9s} {'fwd x MHA':>10s} {'bwd x MHA':>10s}")
+    for r in rows:
+        print(f"{r['layout']:8s} {r['S']:6d} {str(r['causal']):>6s} {r['fwd_ms']:9.4f} {r['bwd_ms']:9.4f} "
+              f"{r['fwd_speedup_vs_mha']:10.3f} {r['bwd_speedup_vs_mha']:10.3f}")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -44,6 +111,10 @@ def main() -> int:
     ap.add_argument("--only", choices=["forward", "attention", "prologue", "down_project", "up_project", "backward",
                                        "attention_backward", "prologue_backward"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
+    ap.add_argument("--grid", action="store_true",
+                    help="latency grid on the axes of the paper's kernel figures (App. D.1: E = 2048, bf16, S = 512..16384, "
+                         "causal and non-causal, forward and forward+backward) for four layouts at d_h = 128, instead "
+                         "of the one-line benchmark; prints one JSON line per point and a table")
     ap.add_argument("--cpu-prefix", type=int, default=16384, help="tokens of the causal prefix the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -61,6 +132,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     P.load_library()  # raises if the HIP library is not built: there is no fallback
+    if args.grid:
+        return run_grid(P, torch)
     w = WORKLOADS[args.workload]
     cfg = P.config_from_workload(w)
     inp = make_inputs(w, seed=0)

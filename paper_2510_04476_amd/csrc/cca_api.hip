@@ -116,6 +116,7 @@ struct BwdLayout {
 };
 
 static size_t prologue_bwd_scratch_bytes(const Dims &d) {
+  if (prologue_is_split_copy(d)) return 0;
   return prologue_bwd_fused_supported(d) ? prologue_bwd_fused_scratch_bytes(d) : prologue_bwd_generic_scratch_bytes(d);
 }
 
@@ -171,6 +172,8 @@ static cca_status run_attention_bwd(const Dims &d, const void *q, const void *k,
 static cca_status run_prologue_bwd(const Dims &d, const cca_weights *w, const void *lat, const void *q, const void *k,
                                    const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
                                    const cca_grads *gr, void *scratch, size_t scratch_bytes, hipStream_t s) {
+  if (prologue_is_split_copy(d))  // plain MHA / GQA: nothing to differentiate but the column split
+    return prologue_split_copy_bwd(d, d_q, d_k, d_v, d_lat, s) == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
   if (!scratch || scratch_bytes < prologue_bwd_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
   hipError_t e = prologue_bwd_fused_supported(d)
                      ? prologue_bwd_fused_bf16(d, *w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s)

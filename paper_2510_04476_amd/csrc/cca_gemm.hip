@@ -364,12 +364,10 @@ hipError_t launch_gemm(const void *A, const void *Bt, void *C, long long M, int 
   constexpr size_t main_bytes = 2ull * (BM + BN) * BK * 2;
   constexpr size_t epi_bytes = (size_t)BM * (BN * 2 + 16);
   constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
-  static bool attr_set = false;  // idempotent; a race only repeats the call
-  if (!attr_set) {
+  {  // per launch: the attribute belongs to the current device, and the library keeps no state
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N><<<per_xcd * 8, WAVES_M * WAVES_N * 64, smem, s>>>((const bf16_t *)A, (const bf16_t *)Bt, (bf16_t *)C, M, N,
                                                              K, tiles_n, total);
@@ -407,12 +405,10 @@ hipError_t gemm_tn_mfma_bf16(const void *A, long long lda, const void *Bm, long 
   const long long nk = (K + BK - 1) / BK;
   const int per = (int)((nk + splits - 1) / splits);
   constexpr size_t smem = 2ull * 2 * BK * TN_ROW;
-  static bool attr_set = false;
-  if (!attr_set) {
+  {  // per launch: the attribute belongs to the current device, and the library keeps no state
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_tn_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   gemm_bf16_tn_kernel<<<dim3(per_xcd * 8, splits), 512, smem, s>>>((const bf16_t *)A, lda, (const bf16_t *)Bm, ldb, part,
                                                                   Mo, No, K, tiles_n, total, per);

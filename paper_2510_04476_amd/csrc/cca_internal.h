@@ -61,6 +61,9 @@ hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, cons
 // no transform selected: q, k, v are slices of the latent rows (plus the optional value-shift)
 bool prologue_is_split_copy(const Dims &d);
 hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k, void *v, float *rnorm, hipStream_t s);
+// its adjoint: no weights, no scratch
+hipError_t prologue_split_copy_bwd(const Dims &d, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                   hipStream_t s);
 
 // ---- backward of the attention stage (bf16, d_h = 128) ----------------------
 bool attention_bwd_supported(const Dims &d);

@@ -349,17 +349,43 @@ __global__ __launch_bounds__(256) void split_copy_kernel(const unsigned char *__
   }
 }
 
+// Adjoint of split_copy_kernel: d_lat is d_q | d_k | d_v side by side, the shifted half of d_v read one token later
+// (zero for the last token of a sequence).
+__global__ __launch_bounds__(256) void split_copy_bwd_kernel(const unsigned char *__restrict__ dq,
+                                                            const unsigned char *__restrict__ dk,
+                                                            const unsigned char *__restrict__ dv,
+                                                            unsigned char *__restrict__ d_lat, long long rows, int T,
+                                                            int e_q, int e_kv, int v_half, int es, int v_shift) {
+  const int n_lat = e_q + 2 * e_kv;
+  const int cpr = n_lat * es / 16;
+  const long long total = rows * cpr;
+  for (long long id = (long long)blockIdx.x * 256 + threadIdx.x; id < total; id += (long long)gridDim.x * 256) {
+    const long long row = id / cpr;
+    const int col = (int)(id % cpr) * (16 / es);
+    const int t = (int)(row % T);
+    u32x4 val = {0, 0, 0, 0};
+    if (col < e_q) {
+      val = *reinterpret_cast<const u32x4 *>(dq + (row * e_q + col) * es);
+    } else if (col < e_q + e_kv) {
+      val = *reinterpret_cast<const u32x4 *>(dk + (row * e_kv + (col - e_q)) * es);
+    } else {
+      const int cc = col - e_q - e_kv;
+      const bool shifted = v_shift && cc >= v_half;
+      if (!shifted || t + 1 < T) val = *reinterpret_cast<const u32x4 *>(dv + ((row + (shifted ? 1 : 0)) * e_kv + cc) * es);
+    }
+    *reinterpret_cast<u32x4 *>(d_lat + (row * n_lat + col) * es) = val;
+  }
+}
+
 template <int D, bool BWD>
 hipError_t launch_main(const FusedArgs &a, const void *lat, const void *vsrc, const void *wc, const float2 *ropeA,
                        const float2 *ropeB, const float *temp, void *q, void *k, void *v, float *rnorm, int grid,
                        hipStream_t s) {
   constexpr size_t smem = (size_t)DH * D * 16 * 16;
-  static bool attr_set = false;
-  if (!attr_set) {
+  {  // per launch: the attribute belongs to the current device, and the library keeps no state
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<D, BWD>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   prologue_fused_kernel<D, BWD><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc, (const u32x4 *)wc,
                                                        ropeA, ropeB, temp, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
@@ -433,6 +459,16 @@ hipError_t prologue_split_copy(const Dims &d, const void *lat, void *q, void *k,
   split_copy_kernel<<<grid, 256, 0, s>>>((const unsigned char *)lat, (unsigned char *)q, (unsigned char *)k,
                                          (unsigned char *)v, d.rows(), d.T, d.e_q, d.e_kv, d.v_half, (int)d.esize(),
                                          (d.flags & CCA_V_SHIFT) ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t prologue_split_copy_bwd(const Dims &d, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                   hipStream_t s) {
+  const long long total = d.rows() * ((long long)d.n_lat * d.esize() / 16);
+  const int grid = (int)((total + 255) / 256 < 256 * 64 ? (total + 255) / 256 : 256 * 64);
+  split_copy_bwd_kernel<<<grid, 256, 0, s>>>((const unsigned char *)d_q, (const unsigned char *)d_k,
+                                             (const unsigned char *)d_v, (unsigned char *)d_lat, d.rows(), d.T, d.e_q,
+                                             d.e_kv, d.v_half, (int)d.esize(), (d.flags & CCA_V_SHIFT) ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -84,6 +84,39 @@ def test_forward_rejects_null_misaligned_and_small_workspace():
     assert lib.cca_up_project(C.byref(cc), p, p, None, p, 0, None) == B.CCA_ERR_NULL
 
 
+def test_backward_rejects_null_misaligned_and_small_workspace():
+    lib = P.load_library()
+    cfg = good()
+    cc = cfg.c()
+    p = C.c_void_p(0x10000)  # fake device addresses: validation fails before anything is dereferenced or enqueued
+    w = B.cca_weights(p, p, p, p, p)
+    sv = B.cca_saved(p, p, p, p, p, p, p, None)
+    gr = B.cca_grads(p, p, p, p, p)
+    n = C.c_size_t(0)
+    assert lib.cca_backward_workspace_size(C.byref(cc), C.byref(n)) == B.CCA_OK and n.value > 0
+    assert lib.cca_backward_workspace_size(C.byref(cc), None) == B.CCA_ERR_NULL
+    need = n.value
+    call = lambda w_, x, sv_, d_out, d_x, gr_, wsp, nb: lib.cca_backward(
+        C.byref(cc), C.byref(w_), x, C.byref(sv_) if sv_ is not None else None, d_out, d_x,
+        C.byref(gr_) if gr_ is not None else None, wsp, nb, None)
+    assert call(w, None, sv, p, p, gr, p, need) == B.CCA_ERR_NULL
+    assert call(w, p, None, p, p, gr, p, need) == B.CCA_ERR_NULL
+    assert call(w, p, sv, None, p, gr, p, need) == B.CCA_ERR_NULL
+    assert call(w, p, B.cca_saved(p, p, p, p, p, None, p, None), p, p, gr, p, need) == B.CCA_ERR_NULL  # lse missing
+    assert call(w, p, B.cca_saved(p, p, p, p, p, p, None, None), p, p, gr, p, need) == B.CCA_ERR_NULL  # rnorm missing
+    assert call(w, p, sv, p, C.c_void_p(0x10004), gr, p, need) == B.CCA_ERR_ALIGN
+    assert call(w, p, sv, p, p, B.cca_grads(C.c_void_p(0x10002), p, p, p, p), p, need) == B.CCA_ERR_ALIGN
+    assert call(w, p, sv, p, p, gr, p, need - 1) == B.CCA_ERR_WORKSPACE
+    assert call(w, p, sv, p, p, gr, None, need) == B.CCA_ERR_WORKSPACE
+    # the stage entry points
+    assert lib.cca_attention_backward(C.byref(cc), p, p, p, p, None, None, p, p, p, p, p, 1 << 30, None) == B.CCA_ERR_NULL
+    assert lib.cca_attention_backward(C.byref(cc), p, p, p, p, None, p, p, p, p, p, p, 16, None) == B.CCA_ERR_WORKSPACE
+    assert lib.cca_prologue_backward(C.byref(cc), C.byref(w), p, p, p, None, p, p, p, p, None, p, 1 << 30,
+                                     None) == B.CCA_ERR_NULL
+    assert lib.cca_prologue_backward(C.byref(cc), C.byref(w), p, p, p, p, p, p, p, p, None, p, 16,
+                                     None) == B.CCA_ERR_WORKSPACE
+
+
 def test_flop_counter_matches_cost_table():
     """Forward FLOPs of the cost table: (1/C1 + 1/C2) 4BSE^2 + 4BES^2/C1 + Conv
     (dense attention term; the grouped-conv term counted per actual MAC)."""
