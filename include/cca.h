@@ -184,7 +184,8 @@ cca_status cca_attention(const cca_config *cfg, const void *q, const void *k, co
  * d_k, d_v (B,T,H_k,d_h), overwritten; d_k, d_v are summed over the query
  * heads sharing a KV head.  Probabilities are recomputed from lse.
  * workspace: B*H_q*T*4 bytes (rounded up to 256) plus, when H_q > H_k,
- * 2*B*T*H_q*d_h*4 bytes for the per-query-head partial sums of d_k and d_v;
+ * 2*B*T*H_q*d_h*4 bytes for the per-query-head partial sums of d_k and d_v,
+ * plus B*T*H_q*d_h*2 bytes for the rescaled q;
  * cca_backward_workspace_size() bytes always suffice. */
 cca_status cca_attention_backward(const cca_config *cfg, const void *q, const void *k, const void *v,
                                   const void *o, const void *o_lo_or_null, const float *lse, const void *d_o, void *d_q, void *d_k,

@@ -302,7 +302,7 @@ def cca_attention_backward(cfg: CCAConfig, q, k, v, o, lse, d_o, d_q=None, d_k=N
     d_k = torch.empty_like(k) if d_k is None else d_k
     d_v = torch.empty_like(v) if d_v is None else d_v
     if workspace is None:
-        n = cfg.B * cfg.n_q_heads * cfg.T * 4 + 256 + 2 * cfg.B * cfg.T * cfg.e_q * 4
+        n = cfg.B * cfg.n_q_heads * cfg.T * 4 + 256 + 2 * cfg.B * cfg.T * cfg.e_q * 4 + cfg.B * cfg.T * cfg.e_q * 2
         workspace = torch.empty(n, dtype=torch.uint8, device=q.device)
     cc = cfg.c()
     _check(lib.cca_attention_backward(C.byref(cc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(o_lo), _ptr(lse), _ptr(d_o),

@@ -11,6 +11,7 @@
 //                     tiles like the forward kernel; S^T and dP^T come out with one query row per lane, dS^T
 //                     packed to bf16 is the second MFMA operand of dQ^T += K^T dS^T, K^T fetched with the
 //                     transposing LDS read.
+//   scale_q           q * scale * log2(e) rounded to bf16 (what the forward kernel multiplies), once, for the next kernel.
 //   attn_bwd_dkdv     one workgroup = 256 keys x one QUERY head (8 wavefronts x 32 keys), loops over the query
 //                     tiles of that head; S and dP come out with one key per lane, P and dS packed to bf16 are
 //                     the second operands of dV^T += dO^T P and dK^T += Q^T dS, with dO^T and Q^T fetched by
@@ -18,7 +19,7 @@
 //                     head's fp32 contribution and group_sum_kernel adds the R of them in a fixed order
 //                     (one workgroup looping over the whole group leaves a causal grid of only B*H_k*T/128
 //                     unequal workgroups: measured 4.2 ms against 0.86 ms for dQ at the 16k CCGQA shape).
-// S is recomputed in both kernels (7 contractions instead of 5) in exchange for having no atomics.
+// S and dP are recomputed in both kernels (7 contractions instead of 5) in exchange for having no atomics.
 //
 // The probabilities must be the forward kernel's own: that kernel multiplies q by scale*log2(e) and rounds it
 // to bf16 before the score MFMAs, and lse is the log-sum-exp of THOSE scores.  Recomputing the scores from
@@ -243,6 +244,20 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   }
 }
 
+// q in log2 units, rounded to bf16 exactly as the forward kernel rounds it (see the note at the top): written once
+// so that the dK / dV kernel can move its Q tiles global -> LDS directly
+__global__ __launch_bounds__(256) void scale_q_kernel(const bf16_t *__restrict__ Q, bf16_t *__restrict__ Qs, long long n8,
+                                                     float c) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n8) return;
+  u32x4 w = *reinterpret_cast<const u32x4 *>(Q + i * 8);
+  w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+  w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+  w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+  w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+  *reinterpret_cast<u32x4 *>(Qs + i * 8) = w;
+}
+
 // ---------------------------------------------------------------------------
 // dK, dV
 // ---------------------------------------------------------------------------
@@ -250,10 +265,12 @@ constexpr int KV_BK = 256, KV_NT = 512, BQT = 64;  // keys per workgroup, thread
 
 // PARTIAL = false (one query head per KV head): dK, dV written as bf16 (B,T,H_k,d_h).
 // PARTIAL = true: this head's contribution written as fp32 to dKp, dVp (B,T,H_q,d_h).
-// MODE 0: dK and dV in one pass (4 contractions; needs more than the 256 registers two wavefronts per SIMD leave
-// each lane, so it spills); MODE 1: dV only (S, dV); MODE 2: dK only (S, dP, dK).  Modes 1 + 2 together are 5
-// contractions without spills.
-template <bool CAUSAL, bool PARTIAL, int MODE>
+// dK and dV in one pass (S, dP, dV, dK).  The two accumulators and the resident K / V fragments take 192 of the 256
+// registers two wavefronts per SIMD leave each lane: the Q and dO tiles therefore go global -> LDS directly (no
+// staging registers; q arrives pre-scaled from scale_q_kernel), S is turned into bf16 P before dP is formed, and
+// dS is computed from that bf16 P.  (With register staging and fp32 P the pass spilled 98 registers; split into a
+// dV pass and a dK pass it cost a fifth contraction.)
+template <bool CAUSAL, bool PARTIAL>
 __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
@@ -289,7 +306,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pk + kk * 16));
-      if (MODE != 1) vf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pv + kk * 16));
+      vf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pv + kk * 16));
     }
   }
   f32x16 dk[DT], dv[DT];  // dK^T, dV^T: lane = key, registers = channels
@@ -303,17 +320,32 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const int nqt = (T + BQT - 1) / BQT;
   const int steps = nqt - qt_first;
 
-  u32x4 rq[PER_THREAD], rd[PER_THREAD];
+  // Q (pre-scaled) and dO tiles travel global -> LDS directly: wave instruction i deposits 64 x 16 bytes at LDS
+  // chunks [i*64, i*64+64) of a tile laid out in padded rows of 17 chunks; lanes landing on padding fetch a duplicate.
+  constexpr int CPR = ROW / 16;                 // 17
+  constexpr int T_INSTR = BQT * CPR / 64;       // 17 instructions per tile
+  static_assert(BQT * CPR % 64 == 0, "tile must be a whole number of wave instructions");
+  constexpr int PER_WAVE = (2 * T_INSTR + KV_NT / 64 - 1) / (KV_NT / 64);
+  typedef __attribute__((address_space(3))) void lds_void;
+  typedef __attribute__((address_space(1))) void glb_void;
+  const unsigned char *const Qg = reinterpret_cast<const unsigned char *>(Q + ((long long)b * T * Hq + h) * DH);
+  const unsigned char *const Dg = reinterpret_cast<const unsigned char *>(dO + ((long long)b * T * Hq + h) * DH);
   float rstat = 0.f;
-  auto load_tile = [&](int step) {
+  auto issue_tile = [&](int step, int buf) {
     const int t0 = (qt_first + step) * BQT;
-    const unsigned char *Qg = reinterpret_cast<const unsigned char *>(Q + ((long long)b * T * Hq + h) * DH);
-    const unsigned char *Dg = reinterpret_cast<const unsigned char *>(dO + ((long long)b * T * Hq + h) * DH);
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-      const int t = min(t0 + s_r0 + i * ROWS_PER_PASS, T - 1);  // clamped rows get probability 0 below
-      rq[i] = *reinterpret_cast<const u32x4 *>(Qg + (long long)t * qrow_bytes + s_ch * 16);
-      rd[i] = *reinterpret_cast<const u32x4 *>(Dg + (long long)t * qrow_bytes + s_ch * 16);
+    for (int u = 0; u < PER_WAVE; ++u) {
+      const int i = wave + u * (KV_NT / 64);
+      if (i < 2 * T_INSTR) {
+        const bool isd = i >= T_INSTR;
+        const int ii = isd ? i - T_INSTR : i;
+        const int L = ii * 64 + lane;
+        const int row = L / CPR, ch = min(L % CPR, KCH - 1);
+        const int t = min(t0 + row, T - 1);  // clamped rows get probability 0 below
+        const unsigned char *src = (isd ? Dg : Qg) + (long long)t * qrow_bytes + ch * 16;
+        unsigned char *dst = (isd ? sD : sQ) + buf * TILE + ii * 1024;
+        __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)dst, 16, 0, 0);
+      }
     }
     if (tid < 2 * BQT) {
       const int t = min(t0 + (tid & (BQT - 1)), T - 1);
@@ -321,92 +353,91 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
       rstat = tid < BQT ? LSE[o] * LOG2E : DELTA[o];
     }
   };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i) {
-      u32x4 w = rq[i];  // q in log2 units, rounded as in the forward kernel
-      w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
-      w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
-      w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
-      w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
-      *reinterpret_cast<u32x4 *>(sQ + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = w;
-      *reinterpret_cast<u32x4 *>(sD + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rd[i];
-    }
+  auto land_tile = [&](int buf) {  // before the barrier that publishes the tile
     if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = rstat;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
   const bool wave_live = kw0 < T;
   if (steps > 0) {
-    load_tile(0);
-    store_tile(0);
-    if (steps > 1) load_tile(1);
+    issue_tile(0, 0);
+    land_tile(0);
     __syncthreads();
   }
   for (int step = 0; step < steps; ++step) {
     const int buf = step & 1;
     const int t0 = (qt_first + step) * BQT;
-    if (step + 1 < steps) store_tile(buf ^ 1);
-    if (step + 2 < steps) load_tile(step + 2);
+    if (step + 1 < steps) issue_tile(step + 1, buf ^ 1);  // that buffer was last read before the previous barrier
     if (wave_live && !(CAUSAL && t0 + BQT - 1 < kw0)) {
       const unsigned char *qp = sQ + buf * TILE, *dp_ = sD + buf * TILE;
       const bool need_mask = (CAUSAL && t0 < kw0 + 31) || (t0 + BQT > T) || (kw0 + 32 > T);
 #pragma unroll
       for (int qs = 0; qs < 2; ++qs) {  // 32 query rows at a time
-        f32x16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 qa = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const u32x4 *>(qp + rd_off + qs * 32 * ROW + kk * 32));
-          const bf16x8 da = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + rd_off + qs * 32 * ROW + kk * 32));
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);                   // S[t, key]
-          if (MODE != 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);  // dP[t, key]
-        }
-        // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4
-        float pr[16], ds[16];
         const int key = kw0 + l32;
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
-          const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = rg * 4 + e;
-            const int t = t0 + qs * 32 + rg * 8 + half * 4 + e;
-            float p = __builtin_amdgcn_exp2f(s[r] - l4[e]);
-            if (need_mask && ((CAUSAL && key > t) || t >= T || key >= T)) p = 0.f;
-            pr[r] = p;
-            ds[r] = p * (dp[r] - d4[e]);
-          }
-        }
         bf16x8 pf[2], dsf[2];
+        {  // S[t, key] -> P, packed to bf16 at once
+          f32x16 s;
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          u32x4 w, x;
+          for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            w[e] = pack2(pr[8 * jj + 2 * e], pr[8 * jj + 2 * e + 1]);
-            x[e] = pack2(ds[8 * jj + 2 * e], ds[8 * jj + 2 * e + 1]);
+          for (int kk = 0; kk < KK; ++kk) {
+            const bf16x8 qa = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4 *>(qp + rd_off + qs * 32 * ROW + kk * 32));
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
           }
-          pf[jj] = __builtin_bit_cast(bf16x8, w);
-          dsf[jj] = __builtin_bit_cast(bf16x8, x);
+          // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4
+          u32x4 w[2];
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
+            float p[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const int t = t0 + qs * 32 + rg * 8 + half * 4 + e;
+              p[e] = __builtin_amdgcn_exp2f(s[rg * 4 + e] - l4[e]);
+              if (need_mask && ((CAUSAL && key > t) || t >= T || key >= T)) p[e] = 0.f;
+            }
+            w[rg >> 1][(rg & 1) * 2 + 0] = pack2(p[0], p[1]);
+            w[rg >> 1][(rg & 1) * 2 + 1] = pack2(p[2], p[3]);
+          }
+          pf[0] = __builtin_bit_cast(bf16x8, w[0]);
+          pf[1] = __builtin_bit_cast(bf16x8, w[1]);
+        }
+        {  // dP[t, key] -> dS = P (dP - Delta), P taken back from its bf16 form
+          f32x16 dp;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+#pragma unroll
+          for (int kk = 0; kk < KK; ++kk) {
+            const bf16x8 da = __builtin_bit_cast(
+                bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + rd_off + qs * 32 * ROW + kk * 32));
+            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);
+          }
+          u32x4 x[2];
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
+            const u32x4 w = __builtin_bit_cast(u32x4, pf[rg >> 1]);
+            const uint32_t p01 = w[(rg & 1) * 2 + 0], p23 = w[(rg & 1) * 2 + 1];
+            x[rg >> 1][(rg & 1) * 2 + 0] = pack2(bf_lo(p01) * (dp[rg * 4 + 0] - d4[0]), bf_hi(p01) * (dp[rg * 4 + 1] - d4[1]));
+            x[rg >> 1][(rg & 1) * 2 + 1] = pack2(bf_lo(p23) * (dp[rg * 4 + 2] - d4[2]), bf_hi(p23) * (dp[rg * 4 + 3] - d4[3]));
+          }
+          dsf[0] = __builtin_bit_cast(bf16x8, x[0]);
+          dsf[1] = __builtin_bit_cast(bf16x8, x[1]);
         }
         // dV^T += dO^T P,  dK^T += Q^T dS
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) {
-            if (MODE != 2)
-              dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dp_ + tr_off, qs * 32 + jj * 16, dt * 32),
+            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dp_ + tr_off, qs * 32 + jj * 16, dt * 32),
                                                                pf[jj], dv[dt], 0, 0, 0);
-            if (MODE != 1)
-              dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qp + tr_off, qs * 32 + jj * 16, dt * 32),
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qp + tr_off, qs * 32 + jj * 16, dt * 32),
                                                                dsf[jj], dk[dt], 0, 0, 0);
           }
       }
     }
+    if (step + 1 < steps) land_tile(buf ^ 1);
     __syncthreads();
   }
   if (PARTIAL) {
@@ -420,8 +451,8 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
           const f32x4 w = {dk[dt][rg * 4 + 0] * LN2, dk[dt][rg * 4 + 1] * LN2, dk[dt][rg * 4 + 2] * LN2,
                            dk[dt][rg * 4 + 3] * LN2};
           const f32x4 x = {dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1], dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]};
-          if (MODE != 1) *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-          if (MODE != 2) *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+          *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+          *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
         }
     }
     return;
@@ -438,8 +469,8 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         w.y = pack2(dk[dt][rg * 4 + 2] * LN2, dk[dt][rg * 4 + 3] * LN2);
         x.x = pack2(dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1]);
         x.y = pack2(dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]);
-        if (MODE != 1) *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-        if (MODE != 2) *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+        *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+        *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
       }
   }
 }
@@ -472,11 +503,12 @@ bool attention_bwd_supported(const Dims &d) {
   return d.bf16 && d.dh == DH && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
 }
 
-// Delta (B,H_q,T) fp32, then (R > 1 only) the per-query-head fp32 contributions to dK and dV, (B,T,H_q,d_h) each
+// Delta (B,H_q,T) fp32, then (R > 1 only) the per-query-head fp32 contributions to dK and dV, (B,T,H_q,d_h) each,
+// then the scaled q (B,T,H_q,d_h) bf16
 static size_t delta_bytes(const Dims &d) { return ((size_t)d.B * d.Hq * d.T * sizeof(float) + 255) / 256 * 256; }
 size_t attention_bwd_scratch_bytes(const Dims &d) {
   if (!attention_bwd_supported(d)) return (size_t)d.B * d.Hq * d.T * sizeof(float);
-  return delta_bytes(d) + (d.R > 1 ? 2 * (size_t)d.rows() * d.e_q * sizeof(float) : 0);
+  return delta_bytes(d) + (d.R > 1 ? 2 * (size_t)d.rows() * d.e_q * sizeof(float) : 0) + (size_t)d.rows() * d.e_q * 2;
 }
 
 hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
@@ -493,29 +525,31 @@ hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const
   const int nkb = (d.T + KV_BK - 1) / KV_BK;
   float *pk = reinterpret_cast<float *>(reinterpret_cast<char *>(delta) + delta_bytes(d));
   float *pv = pk + (size_t)d.rows() * d.e_q;
+  bf16_t *qs = reinterpret_cast<bf16_t *>(reinterpret_cast<char *>(delta) + delta_bytes(d) +
+                                          (d.R > 1 ? 2 * (size_t)d.rows() * d.e_q * sizeof(float) : 0));
+  {
+    const long long n8 = d.rows() * d.e_q / 8;
+    scale_q_kernel<<<(unsigned)((n8 + 255) / 256), 256, 0, s>>>((const bf16_t *)q, qs, n8, d.scale * LOG2E);
+  }
 #define ARGS_DQ (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_q, \
                 d.T, d.Hq, d.Hk, BH, nqb, d.scale
-#define ARGS_KV (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_k, \
+#define ARGS_KV (const bf16_t *)qs, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_k, \
                 (bf16_t *)d_v, pk, pv, d.T, d.Hq, d.Hk, BH, nkb, d.scale
   const unsigned gkv = (unsigned)((long long)BH * nkb);
   const bool partial = d.R > 1;
   if (causal) {
     attn_bwd_dq_kernel<true><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
     if (partial) {
-      attn_bwd_dkdv_kernel<true, true, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
-      attn_bwd_dkdv_kernel<true, true, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<true, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     } else {
-      attn_bwd_dkdv_kernel<true, false, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
-      attn_bwd_dkdv_kernel<true, false, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<true, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     }
   } else {
     attn_bwd_dq_kernel<false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
     if (partial) {
-      attn_bwd_dkdv_kernel<false, true, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
-      attn_bwd_dkdv_kernel<false, true, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<false, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     } else {
-      attn_bwd_dkdv_kernel<false, false, 1><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
-      attn_bwd_dkdv_kernel<false, false, 2><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<false, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     }
   }
 #undef ARGS_DQ
