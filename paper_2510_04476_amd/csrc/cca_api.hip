@@ -74,14 +74,16 @@ static FwdLayout fwd_layout(const Dims &d) {
   return L;
 }
 
-// C (M,N) = A (M,K) * W (K,N); the MFMA path first writes W^T into `wt`.
+// C (M,N) = A (M,K) * W (K,N); the MFMA path first writes W^T into `wt` (unless the caller already has).
 static cca_status project(const Dims &d, const void *A, const void *W, void *C, long long M, int N, int K, void *wt,
-                          size_t wt_bytes, hipStream_t s) {
+                          size_t wt_bytes, hipStream_t s, bool wt_ready = false) {
   hipError_t e;
   if (d.bf16 && gemm_mfma_supported(M, N, K)) {
     if (!wt || wt_bytes < (size_t)N * K * 2) return CCA_ERR_WORKSPACE;
-    e = transpose_bf16(W, wt, K, N, s);
-    if (e != hipSuccess) return CCA_ERR_LAUNCH;
+    if (!wt_ready) {
+      e = transpose_bf16(W, wt, K, N, s);
+      if (e != hipSuccess) return CCA_ERR_LAUNCH;
+    }
     e = gemm_mfma_bf16(A, wt, C, M, N, K, s);
   } else {
     e = gemm_generic(d.bf16, A, W, C, M, N, K, s);
@@ -385,13 +387,17 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
     if (reinterpret_cast<uintptr_t>(rnorm) & 3u) return CCA_ERR_ALIGN;
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, ws + L.wt_down, (size_t)d.E * d.n_lat * 2, s);
+  // both weight transposes in one launch when both projections run on the MFMA GEMM
+  const bool both = d.bf16 && gemm_mfma_supported(d.rows(), d.n_lat, d.E) && gemm_mfma_supported(d.rows(), d.E, d.e_q);
+  if (both && transpose2_bf16(w->w_down, ws + L.wt_down, d.E, d.n_lat, w->w_out, ws + L.wt_out, d.e_q, d.E, s) != hipSuccess)
+    return CCA_ERR_LAUNCH;
+  st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, ws + L.wt_down, (size_t)d.E * d.n_lat * 2, s, both);
   if (st != CCA_OK) return st;
   st = run_prologue(d, w, lat, q, k, v, rnorm, ws + L.pro, L.lat - L.pro, s);
   if (st != CCA_OK) return st;
   st = run_attention(d, q, k, v, o, o_lo, lse, w->temp, s);
   if (st != CCA_OK) return st;
-  return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s);
+  return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s, both);
 }
 
 const char *cca_strerror(cca_status s) {

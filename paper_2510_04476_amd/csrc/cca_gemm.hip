@@ -173,10 +173,19 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
   }
 }
 
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst,
-                                                            int rows, int cols) {
+// Up to two independent transposes in one launch (both projection weights of a forward pass): workgroups
+// [0, n1) serve the first matrix, the rest the second.
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t *__restrict__ src1, bf16_t *__restrict__ dst1,
+                                                            int rows1, int cols1, int n1,
+                                                            const bf16_t *__restrict__ src2, bf16_t *__restrict__ dst2,
+                                                            int rows2, int cols2) {
   __shared__ bf16_t tile[64][66];
-  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const bool second = (int)blockIdx.x >= n1;
+  const bf16_t *src = second ? src2 : src1;
+  bf16_t *dst = second ? dst2 : dst1;
+  const int rows = second ? rows2 : rows1, cols = second ? cols2 : cols1;
+  const int id = second ? blockIdx.x - n1 : blockIdx.x, tiles_c = (cols + 63) / 64;
+  const int c0 = (id % tiles_c) * 64, r0 = (id / tiles_c) * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int i = ty; i < 64; i += 4) {
     const int r = r0 + i, c = c0 + tx;
@@ -420,8 +429,15 @@ hipError_t gemm_tn_mfma_bf16(const void *A, long long lda, const void *Bm, long 
 }
 
 hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStream_t s) {
-  dim3 grid((cols + 63) / 64, (rows + 63) / 64);
-  transpose_bf16_kernel<<<grid, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, rows, cols);
+  return transpose2_bf16(src, dst, rows, cols, nullptr, nullptr, 0, 0, s);
+}
+
+hipError_t transpose2_bf16(const void *src1, void *dst1, int rows1, int cols1, const void *src2, void *dst2, int rows2,
+                           int cols2, hipStream_t s) {
+  const int n1 = ((cols1 + 63) / 64) * ((rows1 + 63) / 64);
+  const int n2 = src2 ? ((cols2 + 63) / 64) * ((rows2 + 63) / 64) : 0;
+  transpose_bf16_kernel<<<n1 + n2, 256, 0, s>>>((const bf16_t *)src1, (bf16_t *)dst1, rows1, cols1, n1,
+                                                 (const bf16_t *)src2, (bf16_t *)dst2, rows2, cols2);
   return hipGetLastError();
 }
 

@@ -52,6 +52,9 @@ bool gemm_mfma_supported(long long M, int N, int K);
 hipError_t gemm_mfma_bf16(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s);
 // dst (cols, rows) = src (rows, cols)^T, bf16.
 hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStream_t s);
+// two independent transposes in one launch (src2 may be NULL)
+hipError_t transpose2_bf16(const void *src1, void *dst1, int rows1, int cols1, const void *src2, void *dst2, int rows2,
+                           int cols2, hipStream_t s);
 
 bool attention_mfma_supported(const Dims &d);
 // temp (H_k log-temperatures, device) is read only when d.flags has QK_NORM and KEY_TEMP: it bounds the scores
