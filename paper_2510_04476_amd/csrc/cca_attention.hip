@@ -2,13 +2,12 @@
 // line of the final equation block; KV heads shared by groups of query heads
 // as in the CCGQA paragraph).  bf16 in, fp32 accumulation, online softmax.
 //
-// One workgroup = 4 wavefronts = 128 query rows of one (batch, query head);
-// each wavefront owns 32 rows (one MFMA tile) and all of d_h, so the softmax
-// statistics of a row never leave a wavefront.  Two workgroups share a CU
-// (2 wavefronts per SIMD): while one wavefront does softmax arithmetic on
-// the vector ALU, the other keeps the matrix core busy.  Keys / values arrive
-// in tiles of 64 through double-buffered LDS: tile j+2 travels HBM -> registers
-// and tile j+1 registers -> LDS while tile j is multiplied.
+// One workgroup = 8 wavefronts = 256 query rows of one (batch, query head), one
+// workgroup per CU (2 wavefronts per SIMD); each wavefront owns 32 rows (one
+// MFMA tile) and all of d_h, so the softmax statistics of a row never leave a
+// wavefront.  Keys / values arrive in tiles of 64 through double-buffered LDS:
+// a tile travels HBM -> registers during one tile step and registers -> LDS
+// during the next.
 //
 // The scores are produced transposed, S^T = K Q^T, with the 32x32x16 bf16
 // MFMA.  Its accumulator layout then gives every lane 16 keys of ONE query
@@ -19,8 +18,7 @@
 // one channel per lane) is fetched with the gfx950 transposing LDS read
 // (ds_read_b64_tr_b16), in the key order that accumulator layout dictates.
 //
-// Vector-ALU work per score is what bounds this kernel next to the MFMAs, so
-// it is pared down to exp2 + convert + half a dot2:
+// Vector-ALU work per score is pared down to exp2 + convert + one add:
 //   - Q is multiplied by scale*log2(e) once, so scores are in log2 units;
 //   - the MFMA accumulator starts from -m (the row's reference max, kept as a
 //     16-register vector) instead of 0, so the scores come out max-subtracted;
@@ -28,8 +26,21 @@
 //     2^8 (always on the first tile), so rescaling the accumulator is rare;
 //     with the QK L2-norm of the method the scores are bounded by d_h * beta *
 //     scale, that bound is the reference max and the row max is never formed;
-//   - the row sum adds the bf16-rounded probabilities pairwise with
-//     v_dot2_f32_bf16 (the same numbers the PV product uses).
+//   - the row sum uses plain v_add_f32 (two chains).  For inference it adds
+//     the fp32 probabilities while the PV product multiplies their bf16
+//     roundings, so a row's output carries a common factor 1 + delta, |delta|
+//     <= 2^-9 (it averages out over the keys; a row dominated by one key sees
+//     all of it).  When the caller saves lse / o_lo for a backward pass the
+//     sum adds the rounded values instead (two more vector instructions per
+//     pair of scores, measured 4 % of the kernel): the backward pass forms
+//     dS = P (dP - <dO, o>), which cancels to rounding level on a sharp row
+//     only if o is exactly the convex combination the PV product formed.  The bf16 dot instructions (v_dot2*_f32_bf16) are avoided: one
+//     of them per MFMA was measured to cut the MFMA issue rate by a quarter,
+//     while exp2, convert, add and fma issue in an MFMA's shadow for free.
+//
+// Two code paths share the kernel: the generic one (running reference max,
+// one tile at a time) and, for bounded scores, a software-pipelined one
+// (attn_fwd_pipelined below).
 #include <type_traits>
 
 #include "cca_internal.h"
@@ -63,12 +74,12 @@ __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 
 // BOUNDED: the caller guarantees |score| <= bound (log2 units) for every query / key pair, as the QK L2-norm
 // of Sec. 2.2 does (|q| = sqrt(d_h), |k| = sqrt(d_h) * beta).  Then `bound` itself serves as the reference max
 // of every row: no row max, no rescaling, and exp2 arguments lie in [-2*bound, 0].
-template <int DH, bool CAUSAL, bool BOUNDED>
+template <int DH, bool CAUSAL, bool BOUNDED, bool RSUM>
 __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                               const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
                                               bf16_t *__restrict__ OLO, float *__restrict__ LSE, int T, int Hq, int Hk,
                                               int BH, int nqb,
-                                              int paired, float scale, float bound) {
+                                              int paired, float scale, float bound, unsigned char *smem) {
   constexpr int KK = DH / 16;          // MFMA k-steps over the head width
   constexpr int DT = DH / 32;          // 32-wide output tiles over the head width
   constexpr int KCH = DH / 8;          // 16-byte chunks per key row
@@ -79,7 +90,6 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
   constexpr int VBUF = BKV * VROW;     // bytes per V buffer
   constexpr int K_PER_THREAD = BKV * KCH / NT;
   constexpr int K_ROWS_PER_PASS = NT / KCH;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * KBUF + 2 * VBUF];
   unsigned char *const sKb = smem;
   unsigned char *const sVb = smem + 2 * KBUF;
 
@@ -171,7 +181,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
     f32x16 negm;  // minus the reference max (log2 units) of this lane's query row, replicated: MFMA start value
 #pragma unroll
     for (int r = 0; r < 16; ++r) negm[r] = BOUNDED ? -bound : 0.f;
-    float l_run = 0.f;  // running sum of probabilities; each half-wave keeps its own part
+    float l_run = 0.f, l_run2 = 0.f;  // running sums of probabilities (two chains); each half-wave keeps its own part
 
     const int kv_end = CAUSAL ? min(q0 + BQ, T) : T;  // keys [0, kv_end) matter to this workgroup
     const int ntiles = (kv_end + BKV - 1) / BKV;
@@ -230,6 +240,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
             const float delta = (j == 0) ? mx : fmaxf(mx, 0.f);  // finite: key 0 is visible to every row
             const float alpha = __builtin_amdgcn_exp2f(-delta);
             l_run *= alpha;
+            l_run2 *= alpha;
   #pragma unroll
             for (int r = 0; r < 16; ++r) negm[r] -= delta;
   #pragma unroll
@@ -243,7 +254,6 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
           }
         }
         bf16x8 pf[2][2];
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -251,10 +261,11 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
             u32x4 w;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const uint32_t pk = pack2(__builtin_amdgcn_exp2f(sacc[ks][8 * jj + 2 * e]),
-                                        __builtin_amdgcn_exp2f(sacc[ks][8 * jj + 2 * e + 1]));
-              l_run = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), ones, l_run, false);
-              w[e] = pk;
+              const float x0 = __builtin_amdgcn_exp2f(sacc[ks][8 * jj + 2 * e]);
+              const float x1 = __builtin_amdgcn_exp2f(sacc[ks][8 * jj + 2 * e + 1]);
+              w[e] = pack2(x0, x1);
+              l_run += RSUM ? bf_lo(w[e]) : x0;
+              l_run2 += RSUM ? bf_hi(w[e]) : x1;
             }
             pf[ks][jj] = __builtin_bit_cast(bf16x8, w);
           }
@@ -290,6 +301,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
     // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
     if (wave_live) {
       const int t = qw0 + l32;
+      l_run += l_run2;
       const float l = l_run + __shfl_xor(l_run, 32);
       if (t < T) {
         const float inv = 1.f / l;
@@ -316,11 +328,293 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
   }
 }
 
-template <int DH, bool CAUSAL>
+
+// Bounded scores (see above): no row max, no rescaling, so a tile's softmax is independent of every other
+// tile's and the loop can be software-pipelined INSIDE a wavefront.  On this chip a wavefront whose next
+// instruction is an MFMA waiting for the matrix core also keeps the other wavefront of its SIMD from issuing
+// vector-ALU work, so two wavefronts do not hide each other's exponentials; the overlap has to come from one
+// instruction stream in which every MFMA is followed by a few vector-ALU instructions that run in its shadow.
+// Iteration j therefore issues, in this fixed order (PF operand fetches ahead of use):
+//   S0(j+1), PV0(j) alternating  |  exp2 / pack / row-sum of S1(j)   -> P1(j)
+//   S1(j+1), PV1(j) alternating  |  exp2 / pack / row-sum of S0(j+1) -> P0(j+1)
+// where 0 / 1 are the two 32-key halves of a tile.  K therefore runs one tile ahead of V in LDS.
+constexpr int PF = 3;  // operand fetches run this many MFMAs ahead
+enum { IT_PRO = 0, IT_FULL = 1, IT_FINAL = 2, IT_IDLE = 3 };
+
+template <int DH, bool CAUSAL, bool RSUM>
+__device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                   const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
+                                                   bf16_t *__restrict__ OLO, float *__restrict__ LSE, int T, int Hq,
+                                                   int Hk, int BH, int nqb, int paired, float scale, float bound,
+                                                   unsigned char *smem) {
+  constexpr int KK = DH / 16, DT = DH / 32, KCH = DH / 8;
+  constexpr int KROW = DH * 2 + 16, KBUF = BKV * KROW, VROW = DH * 2 + 64, VBUF = BKV * VROW;
+  constexpr int K_PER_THREAD = BKV * KCH / NT, K_ROWS_PER_PASS = NT / KCH;
+  constexpr int NB = KK;  // MFMAs per (half-tile score | half-tile PV) block; 2 * DT == KK
+  static_assert(2 * DT == KK, "block sizes");
+  unsigned char *const sKb = smem;
+  unsigned char *const sVb = smem + 2 * KBUF;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int idx = blockIdx.x;
+  const int bh = idx % BH;
+  const int b = bh / Hq, h = bh % Hq, g = h / (Hq / Hk);
+  const float c = scale * 1.44269504088896340736f;
+  const int row_bytes = Hk * DH * 2;
+  const unsigned char *const Kg = reinterpret_cast<const unsigned char *>(K + ((long long)b * T * Hk + g) * DH);
+  const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
+  const int k_r0 = tid / KCH, k_ch = tid % KCH;
+  const uint32_t k_goff = (uint32_t)k_r0 * row_bytes + k_ch * 16;
+  const uint32_t k_soff = (uint32_t)k_r0 * KROW + k_ch * 16;
+  const uint32_t v_soff = (uint32_t)k_r0 * VROW + k_ch * 16;
+  const uint32_t kr_off = (uint32_t)l32 * KROW + half * 16;
+  const uint32_t vr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * VROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+
+  u32x4 rk[K_PER_THREAD];
+  u32x4 rv[K_PER_THREAD];
+  auto load_rows = [&](const unsigned char *base, int kt, u32x4 *dst) {  // branch-free: rows clamped to T - 1
+    const int kv0 = kt * BKV;
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) {
+      const int s = min(kv0 + k_r0 + i * K_ROWS_PER_PASS, T - 1);
+      dst[i] = *reinterpret_cast<const u32x4 *>(base + (long long)s * row_bytes + k_ch * 16);
+    }
+  };
+  auto store_k = [&](int buf) {
+    unsigned char *kd = sKb + buf * KBUF + k_soff;
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(kd + i * K_ROWS_PER_PASS * KROW) = rk[i];
+  };
+  auto store_v = [&](int buf) {
+    unsigned char *vd = sVb + buf * VBUF + v_soff;
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(vd + i * K_ROWS_PER_PASS * VROW) = rv[i];
+  };
+  // LDS traffic only: the global loads in flight (next tiles) are not waited for
+  auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  const int npass = paired ? 2 : 1;
+  for (int pass = 0; pass < npass; ++pass) {
+    const int slot = idx / BH;
+    const int qb = (paired && pass == 1) ? slot : nqb - 1 - slot;
+    if (pass == 1 && slot >= nqb - 1 - slot) break;
+    const int q0 = qb * BQ, qw0 = q0 + wave * 32;
+    const bool wave_live = qw0 < T;
+    const int wave_last = min(qw0 + 31, T - 1);
+
+    bf16x8 qf[KK];
+    {
+      const int row = min(qw0 + l32, T - 1);
+      const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+        w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+        w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+        w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+        w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+        qf[kk] = __builtin_bit_cast(bf16x8, w);
+      }
+    }
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    f32x16 negm;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[r] = -bound;
+    float l_run = 0.f, l_run2 = 0.f;
+
+    const int kv_end = CAUSAL ? min(q0 + BQ, T) : T;
+    const int ntiles = (kv_end + BKV - 1) / BKV;
+    const int my_tiles = !wave_live ? 0 : CAUSAL ? min(ntiles, wave_last / BKV + 1) : ntiles;
+    const int t_lim = (CAUSAL ? min(qw0 + l32, T - 1) : T - 1) - 4 * half;  // last visible key (minus the lane's offset)
+
+    f32x16 sacc[2];      // scores of the two halves: [0] of tile j+1, [1] of tile j while iteration j runs
+    uint32_t pw[2][8];   // probabilities (bf16 pairs) of the two halves, the second MFMA operand of PV
+
+    // one softmax unit: scores 2u, 2u+1 of half `hs` (tile kt) -> exp2 -> one packed word + row sum
+    float e0, e1;
+    auto unit_exp = [&](int hs, int u, int kt, bool mask) {
+      float s0 = sacc[hs][2 * u], s1 = sacc[hs][2 * u + 1];
+      if (mask) {
+        const int key = kt * BKV + hs * 32 + 8 * ((2 * u) >> 2) + ((2 * u) & 3);
+        if (key > t_lim) s0 = -INFINITY;
+        if (key + 1 > t_lim) s1 = -INFINITY;
+      }
+      e0 = __builtin_amdgcn_exp2f(s0);
+      e1 = __builtin_amdgcn_exp2f(s1);
+    };
+    auto unit_pack = [&](int hs, int u) {
+      const uint32_t pk = pack2(e0, e1);
+      pw[hs][u] = pk;
+      l_run += RSUM ? bf_lo(pk) : e0;
+      l_run2 += RSUM ? bf_hi(pk) : e1;
+    };
+    auto pfrag = [&](int hs, int jj) {
+      const u32x4 w = {pw[hs][4 * jj], pw[hs][4 * jj + 1], pw[hs][4 * jj + 2], pw[hs][4 * jj + 3]};
+      return __builtin_bit_cast(bf16x8, w);
+    };
+
+    auto iter = [&](int j, auto kind_c, auto mask_c) {
+      constexpr int KIND = decltype(kind_c)::value;
+      constexpr bool MASK = decltype(mask_c)::value;
+      const unsigned char *kp = sKb + ((j + 1) & 1) * KBUF + kr_off;  // K(j+1)
+      const unsigned char *vp = sVb + (j & 1) * VBUF + vr_off;        // V(j)
+      auto kfrag = [&](int ks, int kk) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + ks * 32 * KROW + kk * 32));
+      };
+      auto vfrag = [&](int ks, int p) {  // p = jj * DT + dt
+        const int jj = p / DT, dt = p % DT;
+        const unsigned char *a = vp + (ks * 32 + jj * 16) * VROW + dt * 64;
+        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)a);
+        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + 8 * VROW));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      };
+      auto mem_store = [&]() {  // K(j+2), V(j+1): their buffers were last read in iteration j-1
+        store_k(j & 1);
+        store_v((j + 1) & 1);
+      };
+      auto mem_load = [&]() {  // past the last tile the loads repeat it and the stores land in idle buffers
+        load_rows(Kg, min(j + 3, ntiles - 1), rk);
+        load_rows(Vg, min(j + 2, ntiles - 1), rv);
+      };
+      if (KIND == IT_FULL) {
+        // packet i: fetch for MFMA i + PF; MFMA i; vector-ALU chunk i.  MFMA order: even i -> scores of half
+        // (i >= 2 NB) of tile j+1, k-step (i mod 2NB) / 2; odd i -> PV of that half of tile j.
+        constexpr int NP = 4 * NB;
+        bf16x8 fr[NP];
+        auto fetch = [&](int i) {
+          const int hs = i / (2 * NB), q = (i % (2 * NB)) / 2;
+          fr[i] = (i & 1) ? vfrag(hs, q) : kfrag(hs, q);
+        };
+#pragma unroll
+        for (int i = 0; i < PF; ++i) fetch(i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          if (i + PF < NP) fetch(i + PF);
+          const int hs = i / (2 * NB), q = (i % (2 * NB)) / 2;
+          if (i & 1) {
+            const int jj = q / DT, dt = q % DT;
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], pfrag(hs, jj), oacc[dt], 0, 0, 0);
+          } else {
+            sacc[hs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], qf[q], q == 0 ? negm : sacc[hs], 0, 0, 0);
+          }
+          // softmax unit u = i / 2: units 0..7 -> half 1 of tile j, units 8..15 -> half 0 of tile j+1
+          // (for DH = 64 there are 16 packets and two units per pair of packets)
+          constexpr int UPP = 16 / (NP / 2);  // units per pair of packets
+#pragma unroll
+          for (int x = 0; x < UPP; ++x) {
+            const int u = (i / 2) * UPP + x, hs_u = u < 8 ? 1 : 0, uu = u & 7;
+            if (UPP == 1) {
+              if (!(i & 1)) unit_exp(hs_u, uu, u < 8 ? j : j + 1, MASK);
+              else unit_pack(hs_u, uu);
+            } else if ((i & 1) == x) {
+              unit_exp(hs_u, uu, u < 8 ? j : j + 1, MASK);
+              unit_pack(hs_u, uu);
+            }
+          }
+          if (i == 3) {
+            mem_store();
+            mem_load();
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else if (KIND == IT_PRO) {  // j = -1: scores of tile 0 (both halves), probabilities of its half 0
+        mem_store();
+        mem_load();
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+          for (int hs = 0; hs < 2; ++hs)
+            sacc[hs] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfrag(hs, kk), qf[kk], kk == 0 ? negm : sacc[hs], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          unit_exp(0, u, 0, MASK);
+          unit_pack(0, u);
+        }
+      } else if (KIND == IT_FINAL) {  // j = my_tiles - 1: no further scores
+        mem_store();
+        mem_load();
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          unit_exp(1, u, j, MASK);
+          unit_pack(1, u);
+        }
+#pragma unroll
+        for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+          for (int p = 0; p < 2 * DT; ++p)
+            oacc[p % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag(hs, p), pfrag(hs, p / DT), oacc[p % DT], 0, 0, 0);
+      } else {
+        mem_store();
+        mem_load();
+      }
+      lds_barrier();
+    };
+    using PRO_ = std::integral_constant<int, IT_PRO>;
+    using FULL_ = std::integral_constant<int, IT_FULL>;
+    using FINAL_ = std::integral_constant<int, IT_FINAL>;
+    using IDLE_ = std::integral_constant<int, IT_IDLE>;
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+
+    load_rows(Kg, 0, rk);
+    store_k(0);
+    load_rows(Kg, min(1, ntiles - 1), rk);
+    load_rows(Vg, 0, rv);
+    lds_barrier();
+    int j = -1;
+    if (my_tiles > 0) {
+      if (my_tiles == 1) iter(-1, PRO_{}, T_{});
+      else iter(-1, PRO_{}, F_{});
+      for (j = 0; j < my_tiles - 2; ++j) iter(j, FULL_{}, F_{});
+      if (my_tiles >= 2) iter(my_tiles - 2, FULL_{}, T_{});
+      iter(my_tiles - 1, FINAL_{}, T_{});
+      j = my_tiles;
+    }
+    for (; j < ntiles; ++j) iter(j, IDLE_{}, F_{});
+
+    // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
+    if (wave_live) {
+      const int t = qw0 + l32;
+      l_run += l_run2;
+      const float l = l_run + __shfl_xor(l_run, 32);
+      if (t < T) {
+        const float inv = 1.f / l;
+        bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            u32x2 w;
+            w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
+            w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
+            *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
+            if (OLO) {
+              u32x2 x;
+              x.x = pack2(oacc[dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[dt][rg * 4 + 1] * inv - bf_hi(w.x));
+              x.y = pack2(oacc[dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[dt][rg * 4 + 3] * inv - bf_hi(w.y));
+              *reinterpret_cast<u32x2 *>(OLO + (orow - O) + dt * 32 + rg * 8 + half * 4) = x;
+            }
+          }
+        if (LSE && half == 0) LSE[((long long)b * Hq + h) * T + t] = (log2f(l) + bound) * 0.69314718055994530942f;
+      }
+    }
+  }
+}
+
+// RSUM: the row sum adds the bf16-rounded probabilities, so that o is the exact convex combination the PV
+// product formed; chosen when the caller saves lse / o_lo for a backward pass (see the file header).
+template <int DH, bool CAUSAL, bool RSUM>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
     bf16_t *__restrict__ OLO, float *__restrict__ LSE, const float *__restrict__ temp, int qk_normed, int T, int Hq, int Hk, int BH, int nqb,
     int paired, float scale) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BKV * (DH * 2 + 16) + 2 * BKV * (DH * 2 + 64)];
   float bound = INFINITY;
   if (qk_normed) {
     // |q.k| <= d_h * beta; 2 % head-room for the bf16 rounding of the stored q and k
@@ -330,9 +624,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   }
   // exp2 arguments reach -2*bound: keep them inside the fp32 exponent range
   if (bound <= 60.f)
-    attn_fwd_body<DH, CAUSAL, true>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, bound);
+    attn_fwd_pipelined<DH, CAUSAL, RSUM>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, bound, smem);
   else
-    attn_fwd_body<DH, CAUSAL, false>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, 0.f);
+    attn_fwd_body<DH, CAUSAL, false, RSUM>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, 0.f, smem);
 }
 
 template <int DH>
@@ -348,14 +642,19 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
   const long long blocks = (long long)BH * (paired ? (nqb + 1) / 2 : nqb);
   const int qk_normed = (d.flags & CCA_QK_NORM) ? 1 : 0;
   if (!(d.flags & CCA_KEY_TEMP)) temp = nullptr;
-  if (causal)
-    attn_fwd_kernel<DH, true><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                                                            (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T, d.Hq, d.Hk, BH, nqb, paired,
-                                                            d.scale);
-  else
-    attn_fwd_kernel<DH, false><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k,
-                                                             (const bf16_t *)v, (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T,
-                                                             d.Hq, d.Hk, BH, nqb, paired, d.scale);
+  const bool rsum = lse != nullptr || o_lo != nullptr;
+#define CCA_ATTN_LAUNCH(C, R)                                                                                       \
+  attn_fwd_kernel<DH, C, R><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, \
+                                                            (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T,   \
+                                                            d.Hq, d.Hk, BH, nqb, paired, d.scale)
+  if (causal) {
+    if (rsum) CCA_ATTN_LAUNCH(true, true);
+    else CCA_ATTN_LAUNCH(true, false);
+  } else {
+    if (rsum) CCA_ATTN_LAUNCH(false, true);
+    else CCA_ATTN_LAUNCH(false, false);
+  }
+#undef CCA_ATTN_LAUNCH
   return hipGetLastError();
 }
 
