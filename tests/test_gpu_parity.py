@@ -96,6 +96,27 @@ def test_small_shapes(i, conv_visible):
     say(res)
 
 
+@pytest.mark.parametrize("i", [1, 2, 3, 5, 6])
+@pytest.mark.parametrize("causal", [True, False])
+def test_small_shapes_inference_path(i, causal):
+    """Without saved tensors the attention kernel takes its inference form (row sums of the unrounded
+    probabilities): `out` must meet the same bar, and agree with the training form to bf16 rounding."""
+    w = SMALL[i]
+    say("case small, no saved tensors", i, "causal", causal, w)
+    inp = make_inputs(w, seed=10 + i, conv_visible=True)
+    flags = B.CCA_FLAGS_PAPER if causal else B.CCA_FLAGS_PAPER & ~B.CCA_CAUSAL
+    cfg = P.config_from_workload(w, flags=flags)
+    x, wt = P.weights_to_device(cfg, inp)
+    out = P.cca_forward(cfg, wt, x)
+    saved = P.CCASaved.allocate(cfg, x.device)
+    out_t = P.cca_forward(cfg, wt, x, saved=saved)
+    torch.cuda.synchronize()
+    ref = oracle_forward(w, inp, causal=causal)
+    say(check_out(to_np(out), ref["out"], w["dtype"]))
+    scale = float(np.abs(ref["out"]).max())
+    assert float(np.abs(to_np(out) - to_np(out_t)).max()) <= 2.0 ** -6 * scale
+
+
 FLAG_CASES = {
     "no_qk_mean": (B.CCA_FLAGS_PAPER & ~B.CCA_QK_MEAN, dict(use_qk_mean=False)),
     "no_conv_seq": (B.CCA_FLAGS_PAPER & ~B.CCA_CONV_SEQ, dict(use_conv_seq=False)),
