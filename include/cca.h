@@ -168,6 +168,12 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
 
 /* o (B,T,H_q*d_h) = softmax(scale * q k^T [causal]) v per latent head, query
  * head h reading KV head h / R.  lse and o_lo (see cca_saved) may be NULL.
+ * With bf16 storage the probabilities enter the PV product rounded to bf16.
+ * When lse or o_lo is requested (a backward pass will consume o) the row is
+ * normalised by the sum of those rounded probabilities, so o is exactly the
+ * convex combination that was formed; when neither is requested it is
+ * normalised by the fp32 sum (a common factor 1 + delta per row, |delta| <=
+ * 2^-9, below the rounding of o itself) and the kernel is a few percent faster.
  * If cfg->flags has CCA_QK_NORM the caller PROMISES that q and k are what
  * cca_prologue writes under that flag: |q[t,h]| = sqrt(d_h) and |k[t,g]| =
  * sqrt(d_h) * exp(temp[g]) (temp: H_k fp32 log-temperatures on the device,
