@@ -228,6 +228,24 @@ def test_ccgqa_16k_sampled_rows():
     say("inference form", check_out(to_np(out_inf)[:, rows], ref["out"], w["dtype"]))
 
 
+def test_paired_query_blocks_odd_count_ragged():
+    """B*H_q = 32 and 15 query blocks of 256: the causal launch pairs a heavy with a light block per workgroup,
+    the middle block has no partner, and the last block is ragged (T = 3700)."""
+    w = dict(B=4, T=3700, E=1024, Hq=8, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
+    say("case paired blocks, odd count", w)
+    inp = make_inputs(w, seed=5, conv_visible=True)
+    _, out, saved = run_gpu(w, inp)
+    rows = sample_rows(w["T"], 160)
+    ref = oracle_forward(w, inp, rows=rows)
+    res = compare_all(w, inp, ref, out, saved, rows=rows)
+    say(res)
+    cfg = P.config_from_workload(w)
+    x, wt = P.weights_to_device(cfg, inp)
+    out_inf = P.cca_forward(cfg, wt, x)
+    torch.cuda.synchronize()
+    say("inference form", check_out(to_np(out_inf)[:, rows], ref["out"], w["dtype"]))
+
+
 def test_forward_is_deterministic_and_causal_on_gpu():
     w = dict(B=1, T=600, E=1024, Hq=8, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
     say("case determinism / causality")
