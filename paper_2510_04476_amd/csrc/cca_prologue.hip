@@ -54,6 +54,9 @@ struct FusedArgs {
   // qk-mean weights of the other stream: a q head adds mean_q_other * (k row of its group), a k head adds
   // mean_k_other * (each q row of its group).  Forward 1/2 and 1/(2R); the adjoint swaps them.
   float mean_q_other, mean_k_other;
+  // Key-head workgroups come first in the grid and take tiles_per_wave_k tiles per wavefront (a key-head tile
+  // costs more: its qk-mean adds the rows of all R query heads of the group); `tiles_per_wave` is the query heads'.
+  int n_k_blocks, tiles_per_wave_k;
 };
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D,
 }
 
 // ---------------------------------------------------------------------------
-// main kernel: one workgroup = one head x (256 * tiles_per_wave) tokens, 8 wavefronts x 32-token tiles.
+// main kernel: one workgroup = one head x (256 * tiles per wavefront) tokens, 8 wavefronts x 32-token tiles.
 // BWD = false: the forward prologue.  BWD = true: its adjoint from the gradient d3 of the conv2 output to
 // d_lat: the same contraction with the transposed filter and the taps reaching FORWARD in time (token t reads
 // rows t .. t+D-1, zero past the end of its sequence), the qk-mean adjoint through the same identity MFMAs, no
@@ -153,9 +156,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   }
 
   const int NH = a.Hq + a.Hk;
-  const int head = blockIdx.x % NH;
-  const long long row_begin = (long long)(blockIdx.x / NH) * (256 * a.tiles_per_wave);
-  const bool is_q = head < a.Hq;
+  const bool is_q = (int)blockIdx.x >= a.n_k_blocks;
+  const int bid = is_q ? (int)blockIdx.x - a.n_k_blocks : (int)blockIdx.x;
+  const int head = is_q ? bid % a.Hq : a.Hq + bid % a.Hk;
+  const int tiles_per_wave = is_q ? a.tiles_per_wave : a.tiles_per_wave_k;
+  const long long row_begin = (long long)(bid / (is_q ? a.Hq : a.Hk)) * (256 * tiles_per_wave);
   const int g = is_q ? head / a.R : head - a.Hq;
   const int ch0 = is_q ? head * DH : a.e_q + g * DH;
 
@@ -196,7 +201,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
   }
 
-  for (int tt = 0; tt < a.tiles_per_wave; ++tt) {
+  for (int tt = 0; tt < tiles_per_wave; ++tt) {
     const long long trow0 = row_begin + (tt * 8 + wave) * 32;
     if (trow0 >= a.rows) break;  // wave-uniform; nothing below synchronises across wavefronts
     const long long row = trow0 + l32;
@@ -395,18 +400,28 @@ hipError_t launch_main(const FusedArgs &a, const void *lat, const void *vsrc, co
 // Tokens per workgroup: each workgroup first loads its head's filter (about one tile's worth of time), and one
 // workgroup fits per CU, so minimise rounds-on-256-CUs x (1 + tiles per wavefront).  Returns the grid size.
 int plan_grid(const Dims &d, FusedArgs &a) {
-  const int NH = d.Hq + d.Hk;
-  long long best_cost = -1, tok_blocks = 0;
-  for (int tpw = 1; tpw <= MAX_TILES_PER_WAVE; ++tpw) {
-    const long long blocks = (d.rows() + 256 * tpw - 1) / (256 * tpw);
-    const long long cost = ((blocks * NH + 255) / 256) * (1 + tpw);
-    if (best_cost < 0 || cost < best_cost) {
-      best_cost = cost;
-      a.tiles_per_wave = tpw;
-      tok_blocks = blocks;
+  // One workgroup = one head x 256 * tiles tokens.  Cost of a workgroup in units of a query-head tile: about one
+  // for loading its filter, one per query-head tile, 1 + 0.11 R per key-head tile when the qk-mean is on (measured
+  // 1.43 at R = 4).  The slowest workgroup of a round sets the round's length, so key heads take fewer tiles.
+  const double ck = (a.flags & CCA_QK_MEAN) ? 1.0 + 0.11 * d.R : 1.0;
+  double best_cost = -1.0;
+  long long best_q = 0, best_k = 0;
+  for (int tq = 1; tq <= MAX_TILES_PER_WAVE; ++tq)
+    for (int tk = 1; tk <= MAX_TILES_PER_WAVE; ++tk) {
+      const long long nq = d.Hq * ((d.rows() + 256 * tq - 1) / (256 * tq));
+      const long long nk = d.Hk * ((d.rows() + 256 * tk - 1) / (256 * tk));
+      const double slowest = 1.0 + (tq > ck * tk ? (double)tq : ck * tk);
+      const double cost = (double)((nq + nk + 255) / 256) * slowest;
+      if (best_cost < 0 || cost < best_cost - 1e-9) {
+        best_cost = cost;
+        a.tiles_per_wave = tq;
+        a.tiles_per_wave_k = tk;
+        best_q = nq;
+        best_k = nk;
+      }
     }
-  }
-  a.n_conv_blocks = (int)(tok_blocks * NH);
+  a.n_k_blocks = (int)best_k;
+  a.n_conv_blocks = (int)(best_q + best_k);
   const long long v_chunks = d.rows() * (d.e_kv / 8);
   const int v_blocks = (int)((v_chunks + NT * 4 - 1) / (NT * 4));
   return a.n_conv_blocks + v_blocks;
