@@ -108,6 +108,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mha", action="store_true", help="skip the same-kernel MHA comparison run")
     ap.add_argument("--no-backward", action="store_true", help="skip the forward+backward measurement")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-step measurement")
     ap.add_argument("--only", choices=["forward", "attention", "prologue", "down_project", "up_project", "backward",
                                        "attention_backward", "prologue_backward"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
@@ -309,6 +310,32 @@ def main() -> int:
                "mha_tflops": round(m_fl / m_ms / 1e9, 1), "speedup_ccgqa_vs_mha": round(m_ms / c_ms, 3),
                "flop_ratio": round(m_fl / c_fl, 3)}
 
+    # ---- decode step against a full latent KV cache (timing only; parity is tests/test_gpu_decode.py) ----------
+    dec = None
+    if args.workload == "ccgqa_16k" and not args.no_decode:
+        Bd = 32
+        cd = P.config_from_workload(dict(w, B=Bd))
+        g = torch.Generator(device=x.device).manual_seed(1)
+        st = P.CCADecodeState.allocate(cd, x.device)
+        for t_ in (st.k_cache, st.v_cache, st.lat_ring):
+            t_.copy_(torch.randn(t_.shape, device=x.device, generator=g).to(t_.dtype))
+        xd = torch.randn(Bd, cd.d_model, device=x.device, generator=g).to(cd.torch_dtype)
+        od = torch.empty_like(xd)
+        pos = cd.T - 1
+        for _ in range(3):
+            P.cca_decode_step(cd, wt, xd, st, pos, out=od)
+        d_ms = timed(lambda: P.cca_decode_step(cd, wt, xd, st, pos, out=od), 20)
+        cache_b = 2.0 * Bd * cd.T * cd.e_kv * 2
+        weight_b = (cd.d_model * cd.n_lat + cd.e_q * cd.d_model) * 2.0
+        dec = {"batch": Bd, "cache_len": cd.T, "ms_per_step": round(d_ms, 4),
+               "tokens_per_s": round(Bd / d_ms * 1e3, 1),
+               "hbm_bytes_per_step": int(cache_b + weight_b),
+               "achieved_gbps": round((cache_b + weight_b) / d_ms / 1e6, 1), "peak_gbps": 8000.0,
+               "frac": round((cache_b + weight_b) / d_ms / 1e6 / 8000.0, 4),
+               "kv_cache_bytes_per_token": int(2 * cd.e_kv * 2),
+               "mha_kv_cache_bytes_per_token": int(2 * cd.d_model * 2)}
+        del st
+
     # ---- CPU oracle on a causal prefix of the same inputs -----------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -356,6 +383,7 @@ def main() -> int:
         "backward": bwd,
         "mha_same_kernel": mha,
         "head_to_head_b4": h2h,
+        "decode": dec,
         "roofline": {"kernel": "attn_fwd_kernel (latent attention)", "bound": "mfma",
                      "achieved": round(attn_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4),

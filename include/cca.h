@@ -212,6 +212,35 @@ cca_status cca_prologue_backward(const cca_config *cfg, const cca_weights *w, co
 cca_status cca_up_project(const cca_config *cfg, const void *o, const void *w_out, void *out,
                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* ---- decode: one new token per sequence against the latent KV cache -------
+ * Sec. 2.2 and the cost table (KV-cache and decode-FLOPs columns): what is
+ * cached per token are the latent key and value AFTER every transform, i.e.
+ * the k and v that cca_prologue / cca_forward write (cca_saved.k, .v), so a
+ * prefill leaves the cache ready.  cfg->T is the CAPACITY of the cache. */
+typedef struct {
+  void *k_cache;  /* (B, T, H_k, d_h): rows 0..pos-1 valid on entry; row pos is written */
+  void *v_cache;  /* (B, T, H_k, d_h): likewise */
+  void *lat_ring; /* (B, P, N_lat): the down-projected rows of the last P tokens, token s in slot s % P, where
+                     P = max(k_seq + k_ch - 2, 1) counting only the convolutions whose flag is on
+                     (cca_decode_workspace_size reports it).  After a prefill: copy the last P rows of
+                     cca_saved.lat.  Slots of tokens before the sequence start are never read.  The step
+                     overwrites slot pos % P with the new token's row. */
+} cca_decode_state;
+
+/* Bytes of device workspace one step needs, and (optional) the ring depth P. */
+cca_status cca_decode_workspace_size(const cca_config *cfg, size_t *bytes, int32_t *ring_rows);
+
+/* out (B, E) = the block's output for the token at position `pos` (0-based;
+ * `pos` tokens are already in the cache) given its hidden state x_new (B, E).
+ * By causality this equals row `pos` of cca_forward over tokens 0..pos.  All
+ * sequences of the batch are at the same position.  Requires d_h % 8 == 0 and
+ * CCA_CAUSAL semantics (a new token attends to everything cached).  Updates
+ * `state` in place; every pointer is device memory, 16-byte aligned.
+ * Errors as for cca_forward; CCA_ERR_SHAPE when pos is outside [0, T). */
+cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const void *x_new,
+                           const cca_decode_state *state, int32_t pos, void *out, void *workspace,
+                           size_t workspace_bytes, void *hip_stream);
+
 /* Human-readable text for a status; never NULL; static storage. */
 const char *cca_strerror(cca_status s);
 

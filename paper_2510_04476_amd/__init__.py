@@ -7,5 +7,6 @@ from .binding import *  # noqa: F401,F403
 from .binding import (CCAConfig, CCAWeights, CCASaved, CCAError, load_library, cca_forward, cca_down_project,
                       cca_prologue, cca_attention, cca_attention_backward, cca_up_project, cca_workspace_size, cca_strerror, cca_version,
                       new_workspace, EXPORTS, LIB_PATH, CCAGrads, cca_backward, cca_backward_workspace_size,
-                      cca_prologue_backward, new_backward_workspace)
+                      cca_prologue_backward, new_backward_workspace, CCADecodeState, cca_decode_step,
+                      cca_decode_workspace_size)
 from .hostutil import config_from_workload, weights_to_device, forward_flops  # noqa: F401

@@ -29,7 +29,7 @@ CCA_FLAGS_MHA = CCA_CAUSAL
 
 EXPORTS = ("cca_workspace_size", "cca_backward_workspace_size", "cca_forward", "cca_backward", "cca_down_project",
            "cca_prologue", "cca_attention", "cca_attention_backward", "cca_prologue_backward", "cca_up_project",
-           "cca_strerror", "cca_version")
+           "cca_decode_workspace_size", "cca_decode_step", "cca_strerror", "cca_version")
 
 
 class cca_config(C.Structure):
@@ -42,6 +42,10 @@ class cca_config(C.Structure):
 class cca_weights(C.Structure):
     _fields_ = [("w_down", C.c_void_p), ("w_conv_seq", C.c_void_p), ("w_conv_ch", C.c_void_p),
                 ("temp", C.c_void_p), ("w_out", C.c_void_p)]
+
+
+class cca_decode_state(C.Structure):
+    _fields_ = [("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("lat_ring", C.c_void_p)]
 
 
 class cca_saved(C.Structure):
@@ -355,3 +359,51 @@ def cca_prologue_backward(cfg: CCAConfig, w: CCAWeights, lat, q, k, rnorm, d_q, 
                                      _ptr(d_k), _ptr(d_v), _ptr(d_lat), C.byref(cg), _ptr(workspace),
                                      workspace.numel(), _stream()), "cca_prologue_backward")
     return d_lat, grads
+
+
+# ---- decode ----------------------------------------------------------------
+def cca_decode_workspace_size(cfg: CCAConfig) -> tuple[int, int]:
+    """(workspace bytes, ring depth P) of one decode step; cfg.T is the cache capacity."""
+    n, p_ = C.c_size_t(0), C.c_int32(0)
+    cc = cfg.c()
+    _check(load_library().cca_decode_workspace_size(C.byref(cc), C.byref(n), C.byref(p_)), "cca_decode_workspace_size")
+    return n.value, p_.value
+
+
+@dataclass
+class CCADecodeState:
+    """Device state of a batch of sequences being decoded (see cca_decode_state in cca.h)."""
+    k_cache: torch.Tensor   # (B, T, H_k, d_h)
+    v_cache: torch.Tensor   # (B, T, H_k, d_h)
+    lat_ring: torch.Tensor  # (B, P, N_lat)
+    workspace: torch.Tensor
+
+    @staticmethod
+    def allocate(cfg: CCAConfig, device) -> "CCADecodeState":
+        nbytes, P_ = cca_decode_workspace_size(cfg)
+        dt = cfg.torch_dtype
+        kv = lambda: torch.zeros(cfg.B, cfg.T, cfg.n_kv_heads, cfg.head_dim, dtype=dt, device=device)
+        return CCADecodeState(kv(), kv(), torch.zeros(cfg.B, P_, cfg.n_lat, dtype=dt, device=device),
+                              torch.empty(nbytes, dtype=torch.uint8, device=device))
+
+    def load_prefill(self, saved: CCASaved, n_tokens: int) -> None:
+        """Take over the first n_tokens of a prefill's saved k, v, lat (argument marshalling: tensor copies only)."""
+        self.k_cache[:, :n_tokens].copy_(saved.k[:, :n_tokens])
+        self.v_cache[:, :n_tokens].copy_(saved.v[:, :n_tokens])
+        P_ = self.lat_ring.shape[1]
+        for s in range(max(0, n_tokens - P_), n_tokens):
+            self.lat_ring[:, s % P_].copy_(saved.lat[:, s])
+
+    def c(self) -> cca_decode_state:
+        return cca_decode_state(_ptr(self.k_cache), _ptr(self.v_cache), _ptr(self.lat_ring))
+
+
+def cca_decode_step(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecodeState, pos: int, out=None):
+    """out (B, E) for the token at position `pos`; updates `state` (cache row `pos`, latent ring)."""
+    lib = load_library()
+    if out is None:
+        out = torch.empty(cfg.B, cfg.d_model, dtype=cfg.torch_dtype, device=x_new.device)
+    cc, cw, cs = cfg.c(), w.c(), state.c()
+    _check(lib.cca_decode_step(C.byref(cc), C.byref(cw), _ptr(x_new), C.byref(cs), C.c_int32(pos), _ptr(out),
+                               _ptr(state.workspace), C.c_size_t(state.workspace.numel()), _stream()), "cca_decode_step")
+    return out

@@ -400,6 +400,38 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s, both);
 }
 
+cca_status cca_decode_workspace_size(const cca_config *cfg, size_t *bytes, int32_t *ring_rows) {
+  if (!bytes) return CCA_ERR_NULL;
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (d.dh % 8 != 0) return CCA_ERR_UNSUPPORTED;
+  *bytes = decode_scratch_bytes(d);
+  if (ring_rows) *ring_rows = decode_ring_rows(d);
+  return CCA_OK;
+}
+
+cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const void *x_new, const cca_decode_state *state,
+                           int32_t pos, void *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (d.dh % 8 != 0) return CCA_ERR_UNSUPPORTED;
+  if (!w || !x_new || !state || !out || !state->k_cache || !state->v_cache || !state->lat_ring) return CCA_ERR_NULL;
+  if (!w->w_down || !w->w_out) return CCA_ERR_NULL;
+  if (pos < 0 || pos >= d.T) return CCA_ERR_SHAPE;
+  st = check_prologue_weights(d, w);
+  if (st != CCA_OK) return st;
+  if (!aligned16(x_new) || !aligned16(out) || !aligned16(state->k_cache) || !aligned16(state->v_cache) ||
+      !aligned16(state->lat_ring) || !aligned16(w->w_down) || !aligned16(w->w_out) || !aligned16(workspace))
+    return CCA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < decode_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
+  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, out, workspace,
+                     (hipStream_t)hip_stream) == hipSuccess
+             ? CCA_OK
+             : CCA_ERR_LAUNCH;
+}
+
 const char *cca_strerror(cca_status s) {
   switch (s) {
     case CCA_OK: return "ok";

@@ -1,0 +1,593 @@
+// One autoregressive decode step of the block (Sec. 2.2; the cost table's KV-cache and decode-FLOPs columns):
+// what is cached per token are the latent keys and values AFTER every transform, exactly what the prefill
+// prologue writes, so prefill and decode share one cache.  By causality the result of a step at position t is
+// row t of the whole block applied to the tokens 0..t; that identity is what the tests check.
+//
+// Per step and sequence:  lat = x W_down (small GEMM);  conv / qk-mean / value-shift / norm / temperature / RoPE
+// for the ONE new token from a ring of the last D-1 latent rows (D = k_seq + k_ch - 1 taps; one row at least, for
+// the value shift);  k, v appended to the cache;  attention of the new query against the cache;  out = o W_O.
+// The attention is bound by reading the cache (2 * len * H_k * d_h elements per sequence), so the key range is
+// split over workgroups (each serves all R query heads of one KV head: the cache is read once per group, not
+// once per query head) and a second kernel merges the partial softmax states in a fixed order.
+#include "cca_internal.h"
+
+namespace cca {
+
+namespace {
+
+constexpr int R_MAX = 8;       // query heads of a group handled per pass over the cache
+constexpr int DEC_WAVES = 4;   // wavefronts per workgroup of the attention kernel
+constexpr int MAX_SPLITS = 32;
+
+struct DecArgs {
+  int B, S, Hq, Hk, dh, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch, P, pos;
+  uint32_t flags;
+  float rope_base, scale;
+};
+
+// N consecutive elements as one vector load (N * sizeof(T) bytes, aligned by construction: head offsets and
+// channel offsets are multiples of N elements)
+template <int N>
+__device__ __forceinline__ void load_vec(const float *p, float *dst) {
+  typedef float fv __attribute__((ext_vector_type(N)));
+  if constexpr (N == 1) {
+    dst[0] = *p;
+  } else if constexpr (N == 8) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 a = *reinterpret_cast<const f4 *>(p), b = *reinterpret_cast<const f4 *>(p + 4);
+    dst[0] = a.x; dst[1] = a.y; dst[2] = a.z; dst[3] = a.w; dst[4] = b.x; dst[5] = b.y; dst[6] = b.z; dst[7] = b.w;
+  } else {
+    const fv v = *reinterpret_cast<const fv *>(p);
+#pragma unroll
+    for (int i = 0; i < N; ++i) dst[i] = v[i];
+  }
+}
+template <int N>
+__device__ __forceinline__ void load_vec(const bf16_t *p, float *dst) {
+  if constexpr (N == 1) {
+    dst[0] = bf16_to_f32(*p);
+  } else {
+    typedef uint32_t uv __attribute__((ext_vector_type(N / 2)));
+    if constexpr (N == 2) {
+      const uint32_t w = *reinterpret_cast<const uint32_t *>(p);
+      dst[0] = __uint_as_float(w << 16);
+      dst[1] = __uint_as_float(w & 0xffff0000u);
+    } else {
+      const uv v = *reinterpret_cast<const uv *>(p);
+#pragma unroll
+      for (int i = 0; i < N / 2; ++i) {
+        dst[2 * i] = __uint_as_float(v[i] << 16);
+        dst[2 * i + 1] = __uint_as_float(v[i] & 0xffff0000u);
+      }
+    }
+  }
+}
+
+// latent row of token `tok` of sequence b: the new row, a ring slot, or nothing (before the sequence start)
+template <typename T>
+__device__ __forceinline__ const T *lat_row(const DecArgs &a, const T *hist, const T *lat_new, int b, int tok) {
+  if (tok == a.pos) return lat_new + (long long)b * a.n_lat;
+  return hist + ((long long)b * a.P + tok % a.P) * a.n_lat;
+}
+
+// ---------------------------------------------------------------------------
+// Transforms of the new token: one workgroup per (sequence, head); heads 0..Hq-1 query, then Hk key, then Hk value.
+// Same arithmetic, in the same order, as the shape-generic prefill prologue.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist, const T *__restrict__ lat_new,
+                                       const T *__restrict__ w0, const T *__restrict__ w1,
+                                       const float *__restrict__ temp, float *__restrict__ q_new,
+                                       T *__restrict__ k_cache, T *__restrict__ v_cache) {
+  extern __shared__ float sm[];  // y0[dh][k_ch] | red[blockDim] | yrot[dh]
+  const int b = blockIdx.x, head = blockIdx.y, dh = a.dh, tid = threadIdx.x, t = a.pos;
+  const long long crow = (long long)b * a.S + t;  // cache row of the new token
+
+  if (head >= a.Hq + a.Hk) {  // value head: second stream delayed by one token
+    const int g = head - a.Hq - a.Hk;
+    const T *cur = lat_row(a, hist, lat_new, b, t) + a.e_q + a.e_kv;
+    const T *prev = t > 0 ? lat_row(a, hist, lat_new, b, t - 1) + a.e_q + a.e_kv : nullptr;
+    for (int i = tid; i < dh; i += blockDim.x) {
+      const int c = g * dh + i;
+      float val;
+      if (c < a.v_half || !(a.flags & CCA_V_SHIFT)) val = load_f(cur + c);
+      else val = prev ? load_f(prev + c) : 0.f;
+      store_f(v_cache + crow * a.e_kv + c, val);
+    }
+    return;
+  }
+
+  const bool is_q = head < a.Hq;
+  const int ch0 = is_q ? head * dh : a.e_q + (head - a.Hq) * dh;
+  const int kc = (a.flags & CCA_CONV_CH) ? a.k_ch : 1;
+  const int ks = (a.flags & CCA_CONV_SEQ) ? a.k_seq : 1;
+  float *y0 = sm, *red = sm + kc * dh, *yrot = red + blockDim.x;
+
+  for (int idx = tid; idx < kc * dh; idx += blockDim.x) {
+    const int j = idx / dh, i = idx % dh;
+    const int tj = t - (kc - 1) + j;
+    float acc = 0.f;
+    if (tj >= 0) {
+      if (a.flags & CCA_CONV_SEQ) {
+        for (int jj = 0; jj < ks; ++jj) {
+          const int ts = tj - (ks - 1) + jj;
+          if (ts >= 0)
+            acc = fmaf(load_f(w0 + (long long)(ch0 + i) * ks + jj), load_f(lat_row(a, hist, lat_new, b, ts) + ch0 + i), acc);
+        }
+      } else {
+        acc = load_f(lat_row(a, hist, lat_new, b, tj) + ch0 + i);
+      }
+    }
+    y0[i * kc + j] = acc;  // in the order the channel filter stores its (input channel, tap) pairs
+  }
+  __syncthreads();
+
+  const T *me = lat_new + (long long)b * a.n_lat;
+  float ssq = 0.f;
+  for (int o = tid; o < dh; o += blockDim.x) {
+    float y;
+    if (a.flags & CCA_CONV_CH) {
+      y = 0.f;
+      const T *wp = w1 + ((long long)head * dh + o) * dh * kc;  // one contiguous row of d_h * k_ch weights
+      for (int c8 = 0; c8 < dh * kc; c8 += 8) {
+        float wv[8];
+        load_vec<8>(wp + c8, wv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) y = fmaf(wv[e], y0[c8 + e], y);
+      }
+    } else {
+      y = y0[o * kc + (kc - 1)];
+    }
+    if (a.flags & CCA_QK_MEAN) {
+      float m;
+      if (is_q) {
+        m = 0.5f * (load_f(me + head * dh + o) + load_f(me + a.e_q + (head / a.R) * dh + o));
+      } else {
+        const int g = head - a.Hq;
+        float sq = 0.f;
+        for (int r = 0; r < a.R; ++r) sq += load_f(me + (g * a.R + r) * dh + o);
+        m = 0.5f * (sq / (float)a.R + load_f(me + a.e_q + g * dh + o));
+      }
+      y += m;
+    }
+    yrot[o] = y;
+    ssq = fmaf(y, y, ssq);
+  }
+  red[tid] = ssq;
+  __syncthreads();
+  for (int s = blockDim.x / 2; s > 0; s >>= 1) {
+    if (tid < s) red[tid] += red[tid + s];
+    __syncthreads();
+  }
+  float mul = 1.f;
+  if (a.flags & CCA_QK_NORM) {
+    mul = sqrtf((float)dh) / sqrtf(red[0]);
+    if (!is_q && (a.flags & CCA_KEY_TEMP)) mul *= expf(temp[head - a.Hq]);
+  }
+  for (int o = tid; o < dh; o += blockDim.x) {
+    float y = yrot[o] * mul;
+    if (a.flags & CCA_ROPE) {
+      const int half = dh / 2;
+      int pair, partner;
+      bool first;
+      if (a.flags & CCA_ROPE_INTERLEAVED) {
+        pair = o / 2; first = (o % 2) == 0; partner = first ? o + 1 : o - 1;
+      } else {
+        pair = o % half; first = o < half; partner = first ? o + half : o - half;
+      }
+      const double theta = pow((double)a.rope_base, -2.0 * (double)pair / (double)dh);
+      double sn, cs;
+      sincos((double)t * theta, &sn, &cs);
+      const float yp = yrot[partner] * mul;
+      y = first ? (y * (float)cs - yp * (float)sn) : (y * (float)cs + yp * (float)sn);
+    }
+    if (is_q) {
+      // the query goes through the storage type once, as the prefill's q does, then stays fp32 for the dot products
+      T tmp;
+      store_f(&tmp, y);
+      q_new[((long long)b * a.Hq + head) * dh + o] = load_f(&tmp);
+    } else {
+      store_f(k_cache + crow * a.e_kv + (head - a.Hq) * dh + o, y);
+    }
+  }
+}
+
+// the new latent row replaces the oldest ring slot (after every head of the step has read its taps)
+template <typename T>
+__global__ void decode_commit_kernel(DecArgs a, const T *__restrict__ lat_new, T *__restrict__ hist) {
+  const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= (long long)a.B * a.n_lat) return;
+  const int b = (int)(id / a.n_lat), c = (int)(id % a.n_lat);
+  hist[((long long)b * a.P + a.pos % a.P) * a.n_lat + c] = lat_new[id];
+}
+
+// ---------------------------------------------------------------------------
+// Attention of the new queries against the cache.  Workgroup = (sequence, KV head, split of the key range), 4
+// wavefronts, each walking its share of the split 64 keys at a time: for the scores a lane owns ONE key (its row
+// of K, 8 elements per load) and all R query heads; for P V a lane owns CPL adjacent channels and the probabilities come
+// from LDS.  Online softmax per wavefront in log2 units; the wavefronts' states are merged through LDS.
+// Partial result per (sequence, query head, split): m, l, o[d_h] in fp32.
+// ---------------------------------------------------------------------------
+// CPL = channels per lane in the P V phase (d_h <= 64 * CPL); DHC = d_h when it is one of the common widths (the
+// loops over channels then unroll and their loads are all in flight together), 0 for any other multiple of 8.
+// STAGED (needs DHC): the 64 key rows of a block are first copied HBM -> LDS with whole rows per load instruction
+// and then read one row per lane from LDS (rows padded by 16 bytes: conflict-free).  Reading a row per lane straight
+// from memory touches 64 cache lines per instruction, 16 bytes of each, and with 16 wavefronts per CU the lines
+// fall out of the 32 KB vector cache before their other chunks are wanted: the cache was re-fetched from L2
+// several times over (measured 1.8 TB/s against 4 TB/s staged).
+template <typename T, int CPL, int DHC, bool STAGED>
+__global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_kernel(DecArgs a, const float *__restrict__ q_new,
+                                                                    const T *__restrict__ k_cache,
+                                                                    const T *__restrict__ v_cache,
+                                                                    float *__restrict__ part, int nsplit, int r0) {
+  extern __shared__ float sm[];
+  const int dh = DHC ? DHC : a.dh, len = a.pos + 1;
+  const int split = blockIdx.x % nsplit, g = (blockIdx.x / nsplit) % a.Hk, b = blockIdx.x / (nsplit * a.Hk);
+  const int nr = min(R_MAX, a.R - r0);  // query heads of this pass: g*R + r0 .. + nr
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float *qs = sm;                             // [R_MAX][dh], scaled to log2 units
+  float *ps = qs + R_MAX * dh + wave * 64 * R_MAX;  // [64][R_MAX] probabilities of this wavefront's current keys
+  float *mrg = sm + R_MAX * dh + DEC_WAVES * 64 * R_MAX;  // merge area: [DEC_WAVES][R_MAX][2 + dh]
+  constexpr int ROWB = DHC * (int)sizeof(T), KROW = ROWB + 16;  // staged key rows (bytes)
+  unsigned char *sK = reinterpret_cast<unsigned char *>(mrg + DEC_WAVES * R_MAX * (2 + dh)) + wave * 64 * KROW;
+  const float c = a.scale * 1.44269504088896340736f;
+  for (int i = tid; i < R_MAX * dh; i += blockDim.x) {
+    const int r = i / dh, ch = i % dh;
+    qs[i] = r < nr ? q_new[((long long)b * a.Hq + g * a.R + r0 + r) * dh + ch] * c : 0.f;
+  }
+  __syncthreads();
+
+  // keys of this split, dealt to the wavefronts in blocks of 64
+  const int per = (len + nsplit - 1) / nsplit;
+  const int k_begin = split * per, k_end = min(len, k_begin + per);
+  float m[R_MAX], l[R_MAX], o[R_MAX][CPL];
+#pragma unroll
+  for (int r = 0; r < R_MAX; ++r) {
+    m[r] = -INFINITY;
+    l[r] = 0.f;
+#pragma unroll
+    for (int x = 0; x < CPL; ++x) o[r][x] = 0.f;
+  }
+  const long long row_elems = (long long)a.Hk * dh;
+  const T *kb = k_cache + ((long long)b * a.S * a.Hk + g) * dh;
+  const T *vb = v_cache + ((long long)b * a.S * a.Hk + g) * dh;
+  for (int k0 = k_begin + wave * 64; k0 < k_end; k0 += DEC_WAVES * 64) {
+    const int key = k0 + lane;
+    const bool live = key < k_end;
+    float s[R_MAX];
+#pragma unroll
+    for (int r = 0; r < R_MAX; ++r) s[r] = 0.f;
+    if constexpr (STAGED) {
+      typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+      constexpr int CH16 = ROWB >= 16 ? ROWB / 16 : 1, RPI = CH16 <= 64 ? 64 / CH16 : 1;  // 16-byte chunks per row, rows per load
+      const int rr = lane / CH16, cc = lane % CH16;
+      u4 tmp[64 / RPI];
+#pragma unroll
+      for (int i = 0; i < 64 / RPI; ++i) {
+        const int row = min(i * RPI + rr, k_end - 1 - k0);  // rows past the end repeat the last live one (unused)
+        tmp[i] = *reinterpret_cast<const u4 *>(reinterpret_cast<const unsigned char *>(kb + (long long)(k0 + row) * row_elems) + cc * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 64 / RPI; ++i) *reinterpret_cast<u4 *>(sK + (i * RPI + rr) * KROW + cc * 16) = tmp[i];
+    }
+    if (live) {
+      const T *kp = STAGED ? reinterpret_cast<const T *>(sK + lane * KROW) : kb + (long long)key * row_elems;
+#pragma unroll
+      for (int ch = 0; ch < dh; ch += 8) {
+        float kv[8];
+        load_vec<8>(kp + ch, kv);
+#pragma unroll
+        for (int r = 0; r < R_MAX; ++r)
+          if (r < nr) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[r] = fmaf(kv[e], qs[r * dh + ch + e], s[r]);
+          }
+      }
+    }
+    float alpha[R_MAX];
+#pragma unroll
+    for (int r = 0; r < R_MAX; ++r) {
+      float mx = live ? s[r] : -INFINITY;
+      for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+      const float mn = fmaxf(m[r], mx);  // finite: the block holds at least one live key
+      const float p = live ? exp2f(s[r] - mn) : 0.f;
+      float sum = p;
+      for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+      alpha[r] = exp2f(m[r] - mn);  // 0 on the first block
+      l[r] = l[r] * alpha[r] + sum;
+      m[r] = mn;
+      ps[lane * R_MAX + r] = p;
+    }
+#pragma unroll
+    for (int r = 0; r < R_MAX; ++r)
+#pragma unroll
+      for (int x = 0; x < CPL; ++x) o[r][x] *= alpha[r];
+    // the probabilities written above are read by the same wavefront only: LDS serves a wavefront in order
+    const int nk = min(64, k_end - k0);
+    constexpr int VB = 16;  // value rows requested together
+    for (int j0 = 0; j0 < nk; j0 += VB) {
+      float vv[VB][CPL];
+#pragma unroll
+      for (int u = 0; u < VB; ++u) {
+#pragma unroll
+        for (int x = 0; x < CPL; ++x) vv[u][x] = 0.f;
+        const int j = min(j0 + u, nk - 1);  // rows past the end repeat the last one; their probability is 0
+        if (lane * CPL < dh) load_vec<CPL>(vb + (long long)(k0 + j) * row_elems + lane * CPL, vv[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < VB; ++u) {
+#pragma unroll
+        for (int r = 0; r < R_MAX; ++r) {
+          const float p = j0 + u < nk ? ps[(j0 + u) * R_MAX + r] : 0.f;
+#pragma unroll
+          for (int x = 0; x < CPL; ++x) o[r][x] = fmaf(p, vv[u][x], o[r][x]);
+        }
+      }
+    }
+  }
+  // merge the wavefronts in a fixed order
+  const int stride = 2 + dh;
+#pragma unroll
+  for (int r = 0; r < R_MAX; ++r) {
+    float *dst = mrg + (wave * R_MAX + r) * stride;
+    if (lane == 0) {
+      dst[0] = m[r];
+      dst[1] = l[r];
+    }
+#pragma unroll
+    for (int x = 0; x < CPL; ++x) {
+      const int ch = lane * CPL + x;
+      if (ch < dh) dst[2 + ch] = o[r][x];
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < nr * dh; i += blockDim.x) {
+    const int r = i / dh, ch = i % dh;
+    float M = -INFINITY;
+    for (int w = 0; w < DEC_WAVES; ++w) M = fmaxf(M, mrg[(w * R_MAX + r) * stride]);
+    float L = 0.f, acc = 0.f;
+    for (int w = 0; w < DEC_WAVES; ++w) {
+      const float *src = mrg + (w * R_MAX + r) * stride;
+      const float f = src[0] == -INFINITY ? 0.f : exp2f(src[0] - M);
+      L += src[1] * f;
+      acc += src[2 + ch] * f;
+    }
+    float *out = part + (((long long)b * a.Hq + g * a.R + r0 + r) * nsplit + split) * stride;
+    if (ch == 0) {
+      out[0] = M;  // -inf when the split holds no key
+      out[1] = L;
+    }
+    out[2 + ch] = acc;
+  }
+}
+
+// o[b, h, :] = sum_s part_o * 2^(m_s - M) / sum_s l_s * 2^(m_s - M), splits in index order
+template <typename T>
+__global__ __launch_bounds__(128) void decode_combine_kernel(DecArgs a, const float *__restrict__ part, int nsplit,
+                                                            T *__restrict__ o) {
+  __shared__ float f[MAX_SPLITS];  // 2^(m_s - M) / L per split (0 for an empty split)
+  const int bh = blockIdx.x, dh = a.dh, stride = 2 + dh, tid = threadIdx.x;
+  const float *src = part + (long long)bh * nsplit * stride;
+  if (tid < 64) {  // one wavefront: lane s holds split s
+    const float ms = tid < nsplit ? src[tid * stride] : -INFINITY;
+    const float ls = tid < nsplit ? src[tid * stride + 1] : 0.f;
+    float M = ms;
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    const float w = ms == -INFINITY ? 0.f : exp2f(ms - M);
+    float L = 0.f;
+    for (int s = 0; s < nsplit; ++s) L += __shfl(ls * w, s);  // index order
+    if (tid < nsplit) f[tid] = w / L;
+  }
+  __syncthreads();
+  for (int ch = tid; ch < dh; ch += blockDim.x) {
+    float acc = 0.f;
+    for (int s = 0; s < nsplit; ++s) acc = fmaf(src[s * stride + 2 + ch], f[s], acc);
+    store_f(o + (long long)bh * dh + ch, acc);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Projections of a decode step: C (M, N) = A (M, K) W (K, N) with M = batch size (a handful of rows), bound by
+// reading W once.  Workgroup = 128 columns x one slice of K; a lane owns 2 adjacent columns (one 4- or 8-byte load
+// per row of W), the 4 wavefronts take quarters of the slice and are added through LDS, rows of A go through LDS
+// 16 at a time ([k][16] floats, so one 16-byte broadcast read feeds 4 rows).  K slices write fp32 partial sums
+// that a second kernel adds in index order (no atomics).
+// ---------------------------------------------------------------------------
+constexpr int SK_COLS = 128, SK_ROWS = 16, SK_MAXCHUNK = 256;
+
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(const T *__restrict__ A, const T *__restrict__ W,
+                                                         float *__restrict__ part, int M, int N, int K, int chunk) {
+  __shared__ float xs[SK_MAXCHUNK][SK_ROWS];
+  __shared__ float red[3][64][SK_ROWS * 2];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n0 = blockIdx.x * SK_COLS + lane * 2;
+  const int k_begin = blockIdx.y * chunk, k_end = min(K, k_begin + chunk);
+  const int klen = k_end - k_begin;
+  const int per_wave = (klen + 3) / 4;
+  const int kw0 = wave * per_wave, kw1 = min(klen, kw0 + per_wave);
+  for (int m0 = 0; m0 < M; m0 += SK_ROWS) {
+    __syncthreads();  // previous group's xs and red are free
+    for (int i = tid; i < klen * SK_ROWS; i += 256) {
+      const int kk = i / SK_ROWS, m = i % SK_ROWS;
+      xs[kk][m] = m0 + m < M ? load_f(A + (long long)(m0 + m) * K + k_begin + kk) : 0.f;
+    }
+    __syncthreads();
+    float acc[SK_ROWS][2];
+#pragma unroll
+    for (int m = 0; m < SK_ROWS; ++m) acc[m][0] = acc[m][1] = 0.f;
+    if (n0 < N) {
+      for (int kk = kw0; kk < kw1; ++kk) {
+        float wv[2];
+        load_vec<2>(W + (long long)(k_begin + kk) * N + n0, wv);
+#pragma unroll
+        for (int m4 = 0; m4 < SK_ROWS; m4 += 4) {
+          typedef float f4 __attribute__((ext_vector_type(4)));
+          const f4 xv = *reinterpret_cast<const f4 *>(&xs[kk][m4]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[m4 + e][0] = fmaf(xv[e], wv[0], acc[m4 + e][0]);
+            acc[m4 + e][1] = fmaf(xv[e], wv[1], acc[m4 + e][1]);
+          }
+        }
+      }
+    }
+    if (wave > 0) {
+#pragma unroll
+      for (int m = 0; m < SK_ROWS; ++m) red[wave - 1][lane][2 * m] = acc[m][0], red[wave - 1][lane][2 * m + 1] = acc[m][1];
+    }
+    __syncthreads();
+    if (wave == 0 && n0 < N) {
+#pragma unroll
+      for (int m = 0; m < SK_ROWS; ++m) {
+        if (m0 + m < M) {
+          float a0 = acc[m][0], a1 = acc[m][1];
+          for (int w = 0; w < 3; ++w) a0 += red[w][lane][2 * m], a1 += red[w][lane][2 * m + 1];
+          float *dst = part + ((long long)blockIdx.y * M + m0 + m) * N + n0;
+          dst[0] = a0;
+          dst[1] = a1;
+        }
+      }
+    }
+  }
+}
+
+template <typename T>
+__global__ void skinny_reduce_kernel(const float *__restrict__ part, T *__restrict__ C, long long mn, int splits) {
+  const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (id >= mn) return;
+  float a = 0.f;
+  for (int s = 0; s < splits; ++s) a += part[(long long)s * mn + id];
+  store_f(C + id, a);
+}
+
+int skinny_splits(int N, int K) {
+  const int col_blocks = (N + SK_COLS - 1) / SK_COLS;
+  int splits = (256 + col_blocks - 1) / col_blocks;          // about one workgroup per CU
+  const int min_splits = (K + SK_MAXCHUNK - 1) / SK_MAXCHUNK;  // a slice must fit the LDS tile
+  splits = splits < min_splits ? min_splits : splits;
+  return splits > K / 16 ? (K / 16 > min_splits ? K / 16 : min_splits) : splits;
+}
+size_t skinny_scratch_bytes(int M, int N, int K) { return (size_t)skinny_splits(N, K) * M * N * sizeof(float); }
+
+template <typename T>
+hipError_t gemm_skinny(const T *A, const T *W, T *C, float *part, int M, int N, int K, hipStream_t s) {
+  const int splits = skinny_splits(N, K);
+  int chunk = (K + splits - 1) / splits;
+  const dim3 grid((N + SK_COLS - 1) / SK_COLS, (K + chunk - 1) / chunk);
+  gemm_skinny_kernel<T><<<grid, 256, 0, s>>>(A, W, part, M, N, K, chunk);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long long mn = (long long)M * N;
+  skinny_reduce_kernel<T><<<(unsigned)((mn + 255) / 256), 256, 0, s>>>(part, C, mn, (int)grid.y);
+  return hipGetLastError();
+}
+
+int ring_rows(const Dims &d) {
+  const int ks = (d.flags & CCA_CONV_SEQ) ? d.k_seq : 1, kc = (d.flags & CCA_CONV_CH) ? d.k_ch : 1;
+  const int taps = ks + kc - 1;
+  return taps - 1 > 1 ? taps - 1 : 1;
+}
+
+size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+
+struct DecLayout {
+  size_t lat_new, q_new, o, part, gemm, total;
+};
+DecLayout layout(const Dims &d) {
+  DecLayout L;
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    const size_t at = off;
+    off += align256(n);
+    return at;
+  };
+  L.lat_new = take((size_t)d.B * d.n_lat * d.esize());
+  L.q_new = take((size_t)d.B * d.e_q * sizeof(float));
+  L.o = take((size_t)d.B * d.e_q * d.esize());
+  L.part = take((size_t)d.B * d.Hq * MAX_SPLITS * (2 + d.dh) * sizeof(float));
+  const size_t g1 = skinny_scratch_bytes(d.B, d.n_lat, d.E), g2 = skinny_scratch_bytes(d.B, d.E, d.e_q);
+  L.gemm = take(g1 > g2 ? g1 : g2);
+  L.total = off;
+  return L;
+}
+
+template <typename T>
+hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *k_cache, void *v_cache, void *hist,
+                  int pos, void *out, unsigned char *ws, hipStream_t s) {
+  const DecLayout L = layout(d);
+  const int P = ring_rows(d);
+  DecArgs a{d.B, d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, P, pos,
+            d.flags, d.rope_base, d.scale};
+  T *lat_new = reinterpret_cast<T *>(ws + L.lat_new);
+  float *q_new = reinterpret_cast<float *>(ws + L.q_new);
+  T *o = reinterpret_cast<T *>(ws + L.o);
+  float *part = reinterpret_cast<float *>(ws + L.part);
+  float *gpart = reinterpret_cast<float *>(ws + L.gemm);
+  hipError_t e = gemm_skinny<T>((const T *)x_new, (const T *)w.w_down, lat_new, gpart, d.B, d.n_lat, d.E, s);
+  if (e != hipSuccess) return e;
+  {
+    int threads = 64;
+    while (threads < d.dh && threads < 256) threads *= 2;
+    const int kc = (d.flags & CCA_CONV_CH) ? d.k_ch : 1;
+    const size_t smem = sizeof(float) * ((size_t)kc * d.dh + threads + d.dh);
+    decode_prologue_kernel<T><<<dim3(d.B, d.Hq + 2 * d.Hk), threads, smem, s>>>(
+        a, (const T *)hist, lat_new, (const T *)w.w_conv_seq, (const T *)w.w_conv_ch, w.temp, q_new, (T *)k_cache,
+        (T *)v_cache);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    decode_commit_kernel<T><<<(unsigned)(((long long)d.B * d.n_lat + 255) / 256), 256, 0, s>>>(a, lat_new, (T *)hist);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  {
+    const int len = pos + 1;
+    // enough workgroups to fill the chip, at least 256 keys each, at most MAX_SPLITS
+    int nsplit = (1024 + d.B * d.Hk - 1) / (d.B * d.Hk);
+    nsplit = nsplit < (len + 255) / 256 ? nsplit : (len + 255) / 256;
+    nsplit = nsplit < 1 ? 1 : (nsplit > MAX_SPLITS ? MAX_SPLITS : nsplit);
+    const size_t smem_base = sizeof(float) * ((size_t)R_MAX * d.dh + DEC_WAVES * 64 * R_MAX + DEC_WAVES * R_MAX * (2 + d.dh));
+    const size_t rowb = (size_t)d.dh * sizeof(T);
+    // the staging area must fit next to the rest in the 160 KB of LDS (bf16 d_h <= 128, fp32 d_h <= 64)
+    const bool staged = (d.dh == 64 || d.dh == 128 || d.dh == 256) && rowb <= 512 &&
+                        smem_base + DEC_WAVES * 64 * (rowb + 16) <= 144 * 1024 && false;  // measured slower: one workgroup per CU
+    const size_t smem = smem_base + (staged ? DEC_WAVES * 64 * (rowb + 16) : 0);
+    const unsigned grid = (unsigned)((long long)d.B * d.Hk * nsplit);
+    for (int r0 = 0; r0 < d.R; r0 += R_MAX) {
+#define CCA_DEC_ATTN(CPL, DHC, ST)                                                                              \
+  {                                                                                                             \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(decode_attn_kernel<T, CPL, DHC, ST>),                  \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                              \
+    if (e != hipSuccess) return e;                                                                              \
+    decode_attn_kernel<T, CPL, DHC, ST><<<grid, DEC_WAVES * 64, smem, s>>>(a, q_new, (const T *)k_cache,          \
+                                                                           (const T *)v_cache, part, nsplit, r0); \
+  }
+      if (staged && d.dh == 64) CCA_DEC_ATTN(1, 64, true)
+      else if (staged && d.dh == 128) CCA_DEC_ATTN(2, 128, true)
+      else if (staged) CCA_DEC_ATTN(4, 256, true)
+      else if (d.dh == 64) CCA_DEC_ATTN(1, 64, false)
+      else if (d.dh == 128) CCA_DEC_ATTN(2, 128, false)
+      else if (d.dh == 256) CCA_DEC_ATTN(4, 256, false)
+      else if (d.dh <= 64) CCA_DEC_ATTN(1, 0, false)
+      else if (d.dh <= 128) CCA_DEC_ATTN(2, 0, false)
+      else CCA_DEC_ATTN(4, 0, false)
+#undef CCA_DEC_ATTN
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    decode_combine_kernel<T><<<(unsigned)(d.B * d.Hq), 128, 0, s>>>(a, part, nsplit, o);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  return gemm_skinny<T>(o, (const T *)w.w_out, (T *)out, gpart, d.B, d.E, d.e_q, s);
+}
+
+}  // namespace
+
+int decode_ring_rows(const Dims &d) { return ring_rows(d); }
+size_t decode_scratch_bytes(const Dims &d) { return layout(d).total; }
+
+hipError_t decode_step(const Dims &d, const cca_weights &w, const void *x_new, void *k_cache, void *v_cache, void *hist,
+                       int pos, void *out, void *workspace, hipStream_t s) {
+  unsigned char *ws = static_cast<unsigned char *>(workspace);
+  return d.bf16 ? step_t<bf16_t>(d, w, x_new, k_cache, v_cache, hist, pos, out, ws, s)
+                : step_t<float>(d, w, x_new, k_cache, v_cache, hist, pos, out, ws, s);
+}
+
+}  // namespace cca

@@ -106,4 +106,10 @@ size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE ta
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
                                float *rnorm, void *scratch, hipStream_t s);
 
+// ---- decode step (one new token per sequence against the latent KV cache) ----
+int decode_ring_rows(const Dims &d);            // latent rows of history the transforms need: max(taps - 1, 1)
+size_t decode_scratch_bytes(const Dims &d);
+hipError_t decode_step(const Dims &d, const cca_weights &w, const void *x_new, void *k_cache, void *v_cache, void *hist,
+                       int pos, void *out, void *workspace, hipStream_t s);
+
 }  // namespace cca

@@ -117,6 +117,37 @@ def test_backward_rejects_null_misaligned_and_small_workspace():
                                      None) == B.CCA_ERR_WORKSPACE
 
 
+def test_decode_rejects_bad_arguments_and_reports_ring_depth():
+    lib = P.load_library()
+    cfg = good()
+    cc = cfg.c()
+    p = C.c_void_p(0x10000)  # fake device addresses: validation fails before anything is dereferenced or enqueued
+    w = B.cca_weights(p, p, p, p, p)
+    st = B.cca_decode_state(p, p, p)
+    n, ring = C.c_size_t(0), C.c_int32(0)
+    assert lib.cca_decode_workspace_size(C.byref(cc), C.byref(n), C.byref(ring)) == B.CCA_OK and n.value > 0
+    assert ring.value == max(cfg.k_seq + cfg.k_ch - 2, 1)  # both convolutions are on in the paper's flags
+    assert lib.cca_decode_workspace_size(C.byref(cc), None, None) == B.CCA_ERR_NULL
+    noconv = good()
+    noconv.flags = B.CCA_FLAGS_MHA
+    c2 = noconv.c()
+    assert lib.cca_decode_workspace_size(C.byref(c2), C.byref(n), C.byref(ring)) == B.CCA_OK and ring.value == 1
+    need = C.c_size_t(0)
+    lib.cca_decode_workspace_size(C.byref(cc), C.byref(need), None)
+    call = lambda w_, x, st_, pos, out, wsp, nb: lib.cca_decode_step(
+        C.byref(cc), C.byref(w_), x, C.byref(st_) if st_ is not None else None, C.c_int32(pos), out, wsp,
+        C.c_size_t(nb), None)
+    assert call(w, None, st, 0, p, p, need.value) == B.CCA_ERR_NULL
+    assert call(w, p, None, 0, p, p, need.value) == B.CCA_ERR_NULL
+    assert call(w, p, B.cca_decode_state(p, None, p), 0, p, p, need.value) == B.CCA_ERR_NULL
+    assert call(B.cca_weights(None, p, p, p, p), p, st, 0, p, p, need.value) == B.CCA_ERR_NULL
+    assert call(w, p, st, -1, p, p, need.value) == B.CCA_ERR_SHAPE
+    assert call(w, p, st, cfg.T, p, p, need.value) == B.CCA_ERR_SHAPE
+    assert call(w, C.c_void_p(0x10004), st, 0, p, p, need.value) == B.CCA_ERR_ALIGN
+    assert call(w, p, st, 0, p, p, need.value - 1) == B.CCA_ERR_WORKSPACE
+    assert call(w, p, st, 0, p, None, need.value) == B.CCA_ERR_WORKSPACE
+
+
 def test_flop_counter_matches_cost_table():
     """Forward FLOPs of the cost table: (1/C1 + 1/C2) 4BSE^2 + 4BES^2/C1 + Conv
     (dense attention term; the grouped-conv term counted per actual MAC)."""

@@ -1,0 +1,119 @@
+"""GPU parity of the decode step: by causality, the output for the token at position t equals row t of the whole
+block applied to tokens 0..t, so the oracle is the forward oracle (fp64) on the same seeded inputs."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_04476_amd as P
+from paper_2510_04476_amd import binding as B
+from synth_inputs import make_inputs
+from util import check_out, check_tap, oracle_forward, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def decode_all(w, inp, start=0, flags=None):
+    """Prefill tokens [0, start) with cca_forward, then decode tokens start..T-1 one by one.  Returns out
+    (B, T - start, E) and the final state."""
+    kw = {} if flags is None else dict(flags=flags)
+    cfg = P.config_from_workload(w, **kw)
+    x, wt = P.weights_to_device(cfg, inp)
+    state = P.CCADecodeState.allocate(cfg, x.device)
+    if start > 0:
+        wp = dict(w, T=start)
+        cfgp = P.config_from_workload(wp, **kw)
+        saved = P.CCASaved.allocate(cfgp, x.device)
+        P.cca_forward(cfgp, wt, x[:, :start].contiguous(), saved=saved)
+        state.load_prefill(saved, start)
+    outs = []
+    for t in range(start, w["T"]):
+        outs.append(P.cca_decode_step(cfg, wt, x[:, t].contiguous(), state, t))
+    torch.cuda.synchronize()
+    return torch.stack(outs, dim=1), state
+
+
+CASES = [
+    dict(B=2, T=37, E=256, Hq=4, Hk=2, dh=32, k_seq=2, k_ch=2, dtype="f32", paper_flags=True),
+    dict(B=1, T=70, E=256, Hq=2, Hk=1, dh=64, k_seq=3, k_ch=2, dtype="f32", paper_flags=True),
+    dict(B=2, T=90, E=1024, Hq=8, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=3, T=40, E=384, Hq=3, Hk=3, dh=128, k_seq=4, k_ch=1, dtype="bf16", paper_flags=True),
+    dict(B=1, T=33, E=512, Hq=2, Hk=1, dh=256, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=20, E=2048, Hq=16, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),  # R = 16 > 8
+]
+
+
+@pytest.mark.parametrize("i", range(len(CASES)))
+def test_decode_from_scratch_matches_forward_oracle(i):
+    w = CASES[i]
+    say("case decode from scratch", i, w)
+    inp = make_inputs(w, seed=70 + i, conv_visible=True)
+    out, state = decode_all(w, inp)
+    ref = oracle_forward(w, inp)
+    say(check_out(to_np(out), ref["out"], w["dtype"]))
+    # the cache holds what the prefill prologue would have written
+    say(check_tap(to_np(state.k_cache), ref["k"], w["dtype"], "k_cache"))
+    say(check_tap(to_np(state.v_cache), ref["v"], w["dtype"], "v_cache"))
+
+
+@pytest.mark.parametrize("i", [0, 2, 3])
+@pytest.mark.parametrize("start", [1, 17])
+def test_decode_after_prefill(i, start):
+    w = CASES[i]
+    say("case decode after prefill", i, "start", start, w)
+    inp = make_inputs(w, seed=80 + i, conv_visible=True)
+    out, _ = decode_all(w, inp, start=start)
+    ref = oracle_forward(w, inp)
+    say(check_out(to_np(out), ref["out"][:, start:], w["dtype"]))
+
+
+@pytest.mark.parametrize("name", ["no_conv", "no_v_shift", "no_norm", "rope_interleaved", "mha"])
+def test_decode_flags(name):
+    F = B.CCA_FLAGS_PAPER
+    flags, okw = {
+        "no_conv": (F & ~(B.CCA_CONV_SEQ | B.CCA_CONV_CH), dict(use_conv_seq=False, use_conv_ch=False)),
+        "no_v_shift": (F & ~B.CCA_V_SHIFT, dict(use_v_shift=False)),
+        "no_norm": (F & ~(B.CCA_QK_NORM | B.CCA_KEY_TEMP), dict(use_qk_norm=False, use_key_temp=False)),
+        "rope_interleaved": (F | B.CCA_ROPE_INTERLEAVED, dict(rope_interleaved=True)),
+        "mha": (B.CCA_FLAGS_MHA, dict(use_conv_seq=False, use_conv_ch=False, use_qk_mean=False, use_v_shift=False,
+                                       use_qk_norm=False, use_key_temp=False, use_rope=False)),
+    }[name]
+    w = dict(B=2, T=45, E=512, Hq=4, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
+    say("case decode flags", name, w)
+    inp = make_inputs(w, seed=91, conv_visible=True)
+    out, _ = decode_all(w, inp, flags=flags)
+    ref = oracle_forward(w, inp, **okw)
+    say(check_out(to_np(out), ref["out"], w["dtype"]))
+
+
+def test_decode_long_cache_split_over_workgroups():
+    """A long cache (several splits of the key range, ragged last split), decoded after a prefill."""
+    w = dict(B=2, T=3000, E=1024, Hq=8, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
+    start = 2990
+    say("case decode long cache", w)
+    inp = make_inputs(w, seed=95)
+    out, _ = decode_all(w, inp, start=start)
+    rows = np.arange(start, w["T"])
+    ref = oracle_forward(w, inp, rows=rows)
+    say(check_out(to_np(out), ref["out"], w["dtype"]))
+
+
+def test_decode_rejects_bad_arguments():
+    w = CASES[2]
+    cfg = P.config_from_workload(w)
+    inp = make_inputs(w, seed=1)
+    x, wt = P.weights_to_device(cfg, inp)
+    state = P.CCADecodeState.allocate(cfg, x.device)
+    with pytest.raises(P.CCAError):
+        P.cca_decode_step(cfg, wt, x[:, 0].contiguous(), state, w["T"])  # position outside the cache
+    with pytest.raises(P.CCAError):
+        P.cca_decode_step(cfg, wt, x[:, 0].contiguous(), state, -1)
+    small = P.CCADecodeState(state.k_cache, state.v_cache, state.lat_ring, state.workspace[:16])
+    with pytest.raises(P.CCAError):
+        P.cca_decode_step(cfg, wt, x[:, 0].contiguous(), small, 0)
