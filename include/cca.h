@@ -221,10 +221,11 @@ typedef struct {
   void *k_cache;  /* (B, T, H_k, d_h): rows 0..pos-1 valid on entry; row pos is written */
   void *v_cache;  /* (B, T, H_k, d_h): likewise */
   void *lat_ring; /* (B, P, N_lat): the down-projected rows of the last P tokens, token s in slot s % P, where
-                     P = max(k_seq + k_ch - 2, 1) counting only the convolutions whose flag is on
-                     (cca_decode_workspace_size reports it).  After a prefill: copy the last P rows of
-                     cca_saved.lat.  Slots of tokens before the sequence start are never read.  The step
-                     overwrites slot pos % P with the new token's row. */
+                     P = max(k_seq + k_ch - 2, 1) + 1 counting only the convolutions whose flag is on
+                     (cca_decode_workspace_size reports it): the earlier rows the convolutions and the value
+                     shift reach back to, plus the new token's own row, which the step writes into slot
+                     pos % P.  After a prefill: copy the last P - 1 (or P) rows of cca_saved.lat.  Slots of
+                     tokens before the sequence start are never read. */
 } cca_decode_state;
 
 /* Bytes of device workspace one step needs, and (optional) the ring depth P. */

@@ -4,11 +4,13 @@
 // row t of the whole block applied to the tokens 0..t; that identity is what the tests check.
 //
 // Per step and sequence:  lat = x W_down (small GEMM);  conv / qk-mean / value-shift / norm / temperature / RoPE
-// for the ONE new token from a ring of the last D-1 latent rows (D = k_seq + k_ch - 1 taps; one row at least, for
-// the value shift);  k, v appended to the cache;  attention of the new query against the cache;  out = o W_O.
+// for the ONE new token from a ring of latent rows (the D-1 earlier rows the D = k_seq + k_ch - 1 taps reach, one
+// at least for the value shift, plus the new row, which the projection writes straight into its slot);  k, v appended to the cache;  attention of the new query against the cache;  out = o W_O.
 // The attention is bound by reading the cache (2 * len * H_k * d_h elements per sequence), so the key range is
 // split over workgroups (each serves all R query heads of one KV head: the cache is read once per group, not
 // once per query head) and a second kernel merges the partial softmax states in a fixed order.
+#include <type_traits>
+
 #include "cca_internal.h"
 
 namespace cca {
@@ -63,10 +65,9 @@ __device__ __forceinline__ void load_vec(const bf16_t *p, float *dst) {
   }
 }
 
-// latent row of token `tok` of sequence b: the new row, a ring slot, or nothing (before the sequence start)
+// latent row of token `tok` of sequence b: ring slot tok % P (the new token's row is written there by the projection)
 template <typename T>
-__device__ __forceinline__ const T *lat_row(const DecArgs &a, const T *hist, const T *lat_new, int b, int tok) {
-  if (tok == a.pos) return lat_new + (long long)b * a.n_lat;
+__device__ __forceinline__ const T *lat_row(const DecArgs &a, const T *hist, int b, int tok) {
   return hist + ((long long)b * a.P + tok % a.P) * a.n_lat;
 }
 
@@ -75,7 +76,7 @@ __device__ __forceinline__ const T *lat_row(const DecArgs &a, const T *hist, con
 // Same arithmetic, in the same order, as the shape-generic prefill prologue.
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist, const T *__restrict__ lat_new,
+__global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist,
                                        const T *__restrict__ w0, const T *__restrict__ w1,
                                        const float *__restrict__ temp, float *__restrict__ q_new,
                                        T *__restrict__ k_cache, T *__restrict__ v_cache) {
@@ -85,8 +86,8 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist, co
 
   if (head >= a.Hq + a.Hk) {  // value head: second stream delayed by one token
     const int g = head - a.Hq - a.Hk;
-    const T *cur = lat_row(a, hist, lat_new, b, t) + a.e_q + a.e_kv;
-    const T *prev = t > 0 ? lat_row(a, hist, lat_new, b, t - 1) + a.e_q + a.e_kv : nullptr;
+    const T *cur = lat_row(a, hist, b, t) + a.e_q + a.e_kv;
+    const T *prev = t > 0 ? lat_row(a, hist, b, t - 1) + a.e_q + a.e_kv : nullptr;
     for (int i = tid; i < dh; i += blockDim.x) {
       const int c = g * dh + i;
       float val;
@@ -112,17 +113,17 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist, co
         for (int jj = 0; jj < ks; ++jj) {
           const int ts = tj - (ks - 1) + jj;
           if (ts >= 0)
-            acc = fmaf(load_f(w0 + (long long)(ch0 + i) * ks + jj), load_f(lat_row(a, hist, lat_new, b, ts) + ch0 + i), acc);
+            acc = fmaf(load_f(w0 + (long long)(ch0 + i) * ks + jj), load_f(lat_row(a, hist, b, ts) + ch0 + i), acc);
         }
       } else {
-        acc = load_f(lat_row(a, hist, lat_new, b, tj) + ch0 + i);
+        acc = load_f(lat_row(a, hist, b, tj) + ch0 + i);
       }
     }
     y0[i * kc + j] = acc;  // in the order the channel filter stores its (input channel, tap) pairs
   }
   __syncthreads();
 
-  const T *me = lat_new + (long long)b * a.n_lat;
+  const T *me = lat_row(a, hist, b, a.pos);
   float ssq = 0.f;
   for (int o = tid; o < dh; o += blockDim.x) {
     float y;
@@ -190,15 +191,6 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist, co
       store_f(k_cache + crow * a.e_kv + (head - a.Hq) * dh + o, y);
     }
   }
-}
-
-// the new latent row replaces the oldest ring slot (after every head of the step has read its taps)
-template <typename T>
-__global__ void decode_commit_kernel(DecArgs a, const T *__restrict__ lat_new, T *__restrict__ hist) {
-  const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (id >= (long long)a.B * a.n_lat) return;
-  const int b = (int)(id / a.n_lat), c = (int)(id % a.n_lat);
-  hist[((long long)b * a.P + a.pos % a.P) * a.n_lat + c] = lat_new[id];
 }
 
 // ---------------------------------------------------------------------------
@@ -361,6 +353,206 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_kernel(DecArgs a, 
   }
 }
 
+// ---------------------------------------------------------------------------
+// The same attention for bf16 caches with d_h in {64, 128, 256}: rows of K and V are read the way they lie in
+// memory.  A row is d_h / 8 chunks of 16 bytes; lane = (row of a group of 64 / LPR rows, chunk), so one load
+// instruction fetches whole adjacent rows and every byte of every cache line it touches.  A lane's share of a score
+// is the dot product over its 8 channels (bf16 pair dot instructions against the query, which the prologue has
+// already rounded to bf16, packed in registers); the LPR shares of a row are added with DPP lane exchanges inside a
+// row of 16 lanes, after which every lane of the row holds the score.  Each row group of a wavefront keeps its own
+// online-softmax state (m, l, o over its 8 channels) so the main loop has no other cross-lane step; the groups, then
+// the wavefronts, are merged once at the end.  The next block's K loads are issued as soon as the scores of the
+// current one have left the K registers and the next V loads after the P V step, so a wavefront always has one or
+// two blocks of loads in flight.  NR = query heads per pass, U = load instructions (groups of rows) per block.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  return x + __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
+}
+
+template <int NR, int DH, int U>
+__global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_rows_kernel(DecArgs a, const float *__restrict__ q_new,
+                                                                         const bf16_t *__restrict__ k_cache,
+                                                                         const bf16_t *__restrict__ v_cache,
+                                                                         float *__restrict__ part, int nsplit, int r0) {
+  constexpr int LPR = DH / 8, RPL = 64 / LPR, BLK = U * RPL;  // lanes per row, rows per load, rows per block
+  typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  __shared__ float mrg[DEC_WAVES][NR][2 + DH];
+  const int len = a.pos + 1;
+  const int split = blockIdx.x % nsplit, g = (blockIdx.x / nsplit) % a.Hk, b = blockIdx.x / (nsplit * a.Hk);
+  const int nr = min(NR, a.R - r0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rr = lane / LPR, cc = lane % LPR;
+  const float c = a.scale * 1.44269504088896340736f;
+
+  uint32_t q2[NR][4];  // this lane's 8 channels of each query head, bf16 pairs (exact: q_new holds bf16 values)
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    f4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
+    if (r < nr) {
+      const float *qp = q_new + ((long long)b * a.Hq + g * a.R + r0 + r) * DH + cc * 8;
+      lo = *reinterpret_cast<const f4 *>(qp);
+      hi = *reinterpret_cast<const f4 *>(qp + 4);
+    }
+    q2[r][0] = (__float_as_uint(lo.x) >> 16) | (__float_as_uint(lo.y) & 0xffff0000u);
+    q2[r][1] = (__float_as_uint(lo.z) >> 16) | (__float_as_uint(lo.w) & 0xffff0000u);
+    q2[r][2] = (__float_as_uint(hi.x) >> 16) | (__float_as_uint(hi.y) & 0xffff0000u);
+    q2[r][3] = (__float_as_uint(hi.z) >> 16) | (__float_as_uint(hi.w) & 0xffff0000u);
+  }
+
+  float m[NR], l[NR], o[NR][8];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    m[r] = -INFINITY;
+    l[r] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[r][e] = 0.f;
+  }
+  const int per = (len + nsplit - 1) / nsplit;
+  const int k_begin = split * per, k_end = min(len, k_begin + per);
+  int k0 = k_begin + wave * BLK;
+  if (k0 < k_end) {  // wave-uniform
+    const uint32_t rowb = (uint32_t)a.Hk * DH * 2;  // bytes between consecutive tokens (S * rowb < 2^31: host check)
+    const unsigned char *kb = reinterpret_cast<const unsigned char *>(k_cache + ((long long)b * a.S * a.Hk + g) * DH);
+    const unsigned char *vb = reinterpret_cast<const unsigned char *>(v_cache + ((long long)b * a.S * a.Hk + g) * DH);
+    // byte offsets of this lane's chunk in the U row groups of a block (the same for K and V); rows past the end of
+    // the split repeat its last row (in bounds) and their probabilities are set to zero
+    uint32_t off[U];
+    auto offsets = [&](int kk) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) off[u] = (uint32_t)min(kk + u * RPL + rr, k_end - 1) * rowb + cc * 16;
+    };
+    u4 kr[U], vr[U];
+    offsets(k0);
+#pragma unroll
+    for (int u = 0; u < U; ++u) kr[u] = *reinterpret_cast<const u4 *>(kb + off[u]);
+    __builtin_amdgcn_sched_barrier(0);  // K before V, as in the loop: the first wait is then for the K loads only
+#pragma unroll
+    for (int u = 0; u < U; ++u) vr[u] = *reinterpret_cast<const u4 *>(vb + off[u]);
+    __builtin_amdgcn_sched_barrier(0);
+    for (; k0 < k_end; k0 += DEC_WAVES * BLK) {
+      float s[U][NR];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+          float acc = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const uint32_t kw = kr[u][i], qw = q2[r][i];  // scalars first: a bit cast straight from a vector element is not safe
+            acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2, kw), __builtin_bit_cast(bf2, qw), acc, false);
+          }
+          s[u][r] = acc;
+        }
+      // the next block of this wavefront (clamped to the last row when there is none): K now, V after the P V step
+      offsets(k0 + DEC_WAVES * BLK);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) kr[u] = *reinterpret_cast<const u4 *>(kb + off[u]);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const bool live = k0 + u * RPL + rr < k_end;
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+          float x = s[u][r];
+          x = dpp_add<0xB1>(x);   // quad_perm [1,0,3,2]
+          x = dpp_add<0x4E>(x);   // quad_perm [2,3,0,1]
+          x = dpp_add<0x141>(x);  // row_half_mirror
+          if constexpr (LPR >= 16) x = dpp_add<0x140>(x);  // row_mirror
+          if constexpr (LPR >= 32) x += __shfl_xor(x, 16);
+          s[u][r] = live ? x * c : -INFINITY;
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < NR; ++r) {
+        float mx = s[0][r];
+#pragma unroll
+        for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][r]);
+        const float mn = fmaxf(m[r], mx);
+        const float ms = mn == -INFINITY ? 0.f : mn;  // a row group that has seen no live key yet
+        const float alpha = exp2f(m[r] - ms);
+        float sum = 0.f;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          s[u][r] = exp2f(s[u][r] - ms);
+          sum += s[u][r];
+        }
+        l[r] = l[r] * alpha + sum;
+        m[r] = mn;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[r][e] *= alpha;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float vf[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          vf[2 * i] = __uint_as_float(vr[u][i] << 16);
+          vf[2 * i + 1] = __uint_as_float(vr[u][i] & 0xffff0000u);
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[r][e] = fmaf(s[u][r], vf[e], o[r][e]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < U; ++u) vr[u] = *reinterpret_cast<const u4 *>(vb + off[u]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  // merge the row groups of the wavefront (lane <-> lane ^ step), then the wavefronts through LDS
+#pragma unroll
+  for (int step = LPR; step < 64; step *= 2) {
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const float mo = __shfl_xor(m[r], step), lo = __shfl_xor(l[r], step);
+      const float M = fmaxf(m[r], mo), Ms = M == -INFINITY ? 0.f : M;
+      const float f = exp2f(m[r] - Ms), fo = exp2f(mo - Ms);
+      l[r] = l[r] * f + lo * fo;
+      m[r] = M;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[r][e] = o[r][e] * f + __shfl_xor(o[r][e], step) * fo;
+    }
+  }
+  if (rr == 0) {
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      if (cc == 0) {
+        mrg[wave][r][0] = m[r];
+        mrg[wave][r][1] = l[r];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) mrg[wave][r][2 + cc * 8 + e] = o[r][e];
+    }
+  }
+  __syncthreads();
+  constexpr int stride = 2 + DH;
+  for (int i = tid; i < nr * DH; i += DEC_WAVES * 64) {
+    const int r = i / DH, ch = i % DH;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) M = fmaxf(M, mrg[w][r][0]);
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < DEC_WAVES; ++w) {
+      const float f = mrg[w][r][0] == -INFINITY ? 0.f : exp2f(mrg[w][r][0] - M);
+      L += mrg[w][r][1] * f;
+      acc += mrg[w][r][2 + ch] * f;
+    }
+    float *out = part + (((long long)b * a.Hq + g * a.R + r0 + r) * nsplit + split) * stride;
+    if (ch == 0) {
+      out[0] = M;  // -inf when the split holds no key
+      out[1] = L;
+    }
+    out[2 + ch] = acc;
+  }
+}
+
 // o[b, h, :] = sum_s part_o * 2^(m_s - M) / sum_s l_s * 2^(m_s - M), splits in index order
 template <typename T>
 __global__ __launch_bounds__(128) void decode_combine_kernel(DecArgs a, const float *__restrict__ part, int nsplit,
@@ -390,59 +582,83 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecArgs a, const fl
 // Projections of a decode step: C (M, N) = A (M, K) W (K, N) with M = batch size (a handful of rows), bound by
 // reading W once.  Workgroup = 128 columns x one slice of K; a lane owns 2 adjacent columns (one 4- or 8-byte load
 // per row of W), the 4 wavefronts take quarters of the slice and are added through LDS, rows of A go through LDS
-// 16 at a time ([k][16] floats, so one 16-byte broadcast read feeds 4 rows).  K slices write fp32 partial sums
+// 16 or 32 at a time ([k][rows] floats, so one 16-byte broadcast read feeds 4 rows).  K slices write fp32 partial sums
 // that a second kernel adds in index order (no atomics).
 // ---------------------------------------------------------------------------
-constexpr int SK_COLS = 128, SK_ROWS = 16, SK_MAXCHUNK = 256;
+constexpr int SK_COLS = 128, SK_MAXCHUNK = 128, SK_KB = 16, SK_PAD = 4;
 
-template <typename T>
+// ROWS = rows of A per pass (16 or 32).  A wavefront requests SK_KB rows of W at a time and the next batch before it
+// multiplies the current one, so its loads overlap the arithmetic instead of being waited for one by one.
+template <typename T, int ROWS>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(const T *__restrict__ A, const T *__restrict__ W,
                                                          float *__restrict__ part, int M, int N, int K, int chunk) {
-  __shared__ float xs[SK_MAXCHUNK][SK_ROWS];
-  __shared__ float red[3][64][SK_ROWS * 2];
+  constexpr int XS = ROWS + SK_PAD;  // padded row of the A tile: the transposing store spreads over 8 banks
+  constexpr int XS_FLOATS = SK_MAXCHUNK * XS, RED_FLOATS = 3 * 64 * ROWS * 2;
+  __shared__ float buf[XS_FLOATS > RED_FLOATS ? XS_FLOATS : RED_FLOATS];
+  float *xs = buf;   // [klen][XS] A tile, fp32
+  float *red = buf;  // [3][64][2 * ROWS] sums of wavefronts 1..3 (after the A tile is no longer read)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n0 = blockIdx.x * SK_COLS + lane * 2;
   const int k_begin = blockIdx.y * chunk, k_end = min(K, k_begin + chunk);
   const int klen = k_end - k_begin;
   const int per_wave = (klen + 3) / 4;
   const int kw0 = wave * per_wave, kw1 = min(klen, kw0 + per_wave);
-  for (int m0 = 0; m0 < M; m0 += SK_ROWS) {
-    __syncthreads();  // previous group's xs and red are free
-    for (int i = tid; i < klen * SK_ROWS; i += 256) {
-      const int kk = i / SK_ROWS, m = i % SK_ROWS;
-      xs[kk][m] = m0 + m < M ? load_f(A + (long long)(m0 + m) * K + k_begin + kk) : 0.f;
+  const bool col_ok = n0 < N;
+  // rows of W past the wavefront's range are read from its last row (in bounds) and multiplied by nothing
+  const T *wp = W + (long long)k_begin * N + (col_ok ? n0 : 0);
+  auto load_rows = [&](int kk0, float (&wv)[SK_KB][2]) {
+#pragma unroll
+    for (int j = 0; j < SK_KB; ++j) load_vec<2>(wp + (long long)min(kk0 + j, max(kw1 - 1, 0)) * N, wv[j]);
+  };
+  for (int m0 = 0; m0 < M; m0 += ROWS) {
+    __syncthreads();  // the previous pass no longer reads buf
+    for (int i = tid; i < klen * ROWS; i += 256) {
+      const int m = i / klen, kk = i % klen;  // consecutive threads read consecutive k of one row
+      xs[kk * XS + m] = m0 + m < M ? load_f(A + (long long)(m0 + m) * K + k_begin + kk) : 0.f;
     }
     __syncthreads();
-    float acc[SK_ROWS][2];
+    float acc[ROWS][2];
 #pragma unroll
-    for (int m = 0; m < SK_ROWS; ++m) acc[m][0] = acc[m][1] = 0.f;
-    if (n0 < N) {
-      for (int kk = kw0; kk < kw1; ++kk) {
-        float wv[2];
-        load_vec<2>(W + (long long)(k_begin + kk) * N + n0, wv);
+    for (int m = 0; m < ROWS; ++m) acc[m][0] = acc[m][1] = 0.f;
+    if (kw0 < kw1) {
+      float wa[SK_KB][2], wb[SK_KB][2];
+      load_rows(kw0, wa);
+      for (int kk0 = kw0; kk0 < kw1; kk0 += SK_KB) {
+        load_rows(kk0 + SK_KB, wb);
 #pragma unroll
-        for (int m4 = 0; m4 < SK_ROWS; m4 += 4) {
-          typedef float f4 __attribute__((ext_vector_type(4)));
-          const f4 xv = *reinterpret_cast<const f4 *>(&xs[kk][m4]);
+        for (int j = 0; j < SK_KB; ++j) {
+          if (kk0 + j < kw1) {  // wave-uniform
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc[m4 + e][0] = fmaf(xv[e], wv[0], acc[m4 + e][0]);
-            acc[m4 + e][1] = fmaf(xv[e], wv[1], acc[m4 + e][1]);
+            for (int m4 = 0; m4 < ROWS; m4 += 4) {
+              typedef float f4 __attribute__((ext_vector_type(4)));
+              const f4 xv = *reinterpret_cast<const f4 *>(&xs[(kk0 + j) * XS + m4]);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                acc[m4 + e][0] = fmaf(xv[e], wa[j][0], acc[m4 + e][0]);
+                acc[m4 + e][1] = fmaf(xv[e], wa[j][1], acc[m4 + e][1]);
+              }
+            }
           }
         }
+#pragma unroll
+        for (int j = 0; j < SK_KB; ++j) wa[j][0] = wb[j][0], wa[j][1] = wb[j][1];
       }
     }
+    __syncthreads();  // every wavefront is done with the A tile: its memory now takes the partial sums
     if (wave > 0) {
 #pragma unroll
-      for (int m = 0; m < SK_ROWS; ++m) red[wave - 1][lane][2 * m] = acc[m][0], red[wave - 1][lane][2 * m + 1] = acc[m][1];
+      for (int m = 0; m < ROWS; ++m) {
+        red[((wave - 1) * 64 + lane) * 2 * ROWS + 2 * m] = acc[m][0];
+        red[((wave - 1) * 64 + lane) * 2 * ROWS + 2 * m + 1] = acc[m][1];
+      }
     }
     __syncthreads();
-    if (wave == 0 && n0 < N) {
+    if (wave == 0 && col_ok) {
 #pragma unroll
-      for (int m = 0; m < SK_ROWS; ++m) {
+      for (int m = 0; m < ROWS; ++m) {
         if (m0 + m < M) {
           float a0 = acc[m][0], a1 = acc[m][1];
-          for (int w = 0; w < 3; ++w) a0 += red[w][lane][2 * m], a1 += red[w][lane][2 * m + 1];
+          for (int w = 0; w < 3; ++w) a0 += red[(w * 64 + lane) * 2 * ROWS + 2 * m], a1 += red[(w * 64 + lane) * 2 * ROWS + 2 * m + 1];
           float *dst = part + ((long long)blockIdx.y * M + m0 + m) * N + n0;
           dst[0] = a0;
           dst[1] = a1;
@@ -452,13 +668,96 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(const T *__restrict__ 
   }
 }
 
+// The same product on the matrix cores for bf16 (N and K multiples of 8).  The W tile (a K slice x 128 columns) is
+// staged row-major in LDS and read as MFMA fragments with the transposing LDS read (the contraction index is the ROW
+// of W); the fragments of A (32 rows x 16 k) come straight from memory: lane (row l % 32, half l / 32) holds
+// k = 4*half .. +3 and 8 + 4*half .. +3 of each group of 16, the order the transposing read delivers W in.  Each
+// wavefront owns 32 of the 128 columns over the whole slice, so nothing is added across wavefronts.
+typedef __bf16 sk_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float sk_f32x16 __attribute__((ext_vector_type(16)));
+typedef float sk_f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t sk_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t sk_u32x2 __attribute__((ext_vector_type(2)));
+typedef short sk_v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) sk_v4i16 sk_lds_v4i16;
+constexpr int SM_ROW = SK_COLS * 2 + 16;  // padded LDS row of the W tile, bytes
+
+__global__ __launch_bounds__(256) void gemm_skinny_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
+                                                              float *__restrict__ part, int M, int N, int K, int chunk) {
+  __shared__ __attribute__((aligned(16))) unsigned char wt[SK_MAXCHUNK * SM_ROW];
+  constexpr int NK16 = SK_MAXCHUNK / 16, STAGE = SK_MAXCHUNK * 16 / 256;  // k groups of a slice; 16-byte chunks per thread
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
+  const int n0 = blockIdx.x * SK_COLS;
+  const int k_begin = blockIdx.y * chunk, k_end = min(K, k_begin + chunk);
+  const int nk16 = (k_end - k_begin + 15) / 16;
+  // W tile: all loads first, then the LDS stores; rows past the slice and columns past N are zero
+  sk_u32x4 wv[STAGE];
+#pragma unroll
+  for (int i = 0; i < STAGE; ++i) {
+    const int id = tid + i * 256, row = id >> 4, c = id & 15;
+    sk_u32x4 v = {0, 0, 0, 0};
+    if (row < nk16 * 16 && k_begin + row < k_end && n0 + c * 8 < N)
+      v = *reinterpret_cast<const sk_u32x4 *>(W + (long long)(k_begin + row) * N + n0 + c * 8);
+    wv[i] = v;
+  }
+  // fragments of the first 32 rows of A for the whole slice (k past the slice reads as zero)
+  auto load_a = [&](int m0, sk_u32x4 (&xa)[NK16]) {
+    const bf16_t *ap = A + (long long)min(m0 + l32, M - 1) * K + k_begin + 4 * half;
+#pragma unroll
+    for (int kk = 0; kk < NK16; ++kk) {
+      sk_u32x2 lo = {0, 0}, hi = {0, 0};
+      if (kk < nk16) {
+        if (k_begin + kk * 16 + 4 * half < k_end) lo = *reinterpret_cast<const sk_u32x2 *>(ap + kk * 16);
+        if (k_begin + kk * 16 + 8 + 4 * half < k_end) hi = *reinterpret_cast<const sk_u32x2 *>(ap + kk * 16 + 8);
+      }
+      xa[kk] = sk_u32x4{lo.x, lo.y, hi.x, hi.y};
+    }
+  };
+  sk_u32x4 xa[NK16];
+  load_a(0, xa);
+#pragma unroll
+  for (int i = 0; i < STAGE; ++i) {
+    const int id = tid + i * 256, row = id >> 4, c = id & 15;
+    if (row < nk16 * 16) *reinterpret_cast<sk_u32x4 *>(wt + row * SM_ROW + c * 16) = wv[i];
+  }
+  __syncthreads();
+  const unsigned char *pw = wt + (4 * half + ((lane & 15) >> 2)) * SM_ROW + (wave * 32 + ((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+  for (int m0 = 0; m0 < M; m0 += 32) {
+    if (m0 > 0) load_a(m0, xa);
+    sk_f32x16 acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < NK16; ++kk) {
+      if (kk < nk16) {
+        const unsigned char *p = pw + kk * 16 * SM_ROW;
+        const sk_v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sk_lds_v4i16 *)p);
+        const sk_v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((sk_lds_v4i16 *)(p + 8 * SM_ROW));
+        const sk_bf16x8 fw = __builtin_bit_cast(sk_bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw, __builtin_bit_cast(sk_bf16x8, xa[kk]), acc, 0, 0, 0);
+      }
+    }
+    // acc[r] = C[m0 + l32][n0 + 32*wave + 8*(r/4) + 4*half + r%4]
+    const int m = m0 + l32;
+    if (m < M) {
+      float *dst = part + ((long long)blockIdx.y * M + m) * N + n0 + wave * 32 + half * 4;
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg)
+        if (n0 + wave * 32 + rg * 8 + half * 4 < N)  // N % 8 == 0: the four columns are inside
+          *reinterpret_cast<sk_f32x4 *>(dst + rg * 8) = sk_f32x4{acc[rg * 4], acc[rg * 4 + 1], acc[rg * 4 + 2], acc[rg * 4 + 3]};
+    }
+  }
+}
+
+// C row m starts at C + m * ldc (the rows of a projection may go straight into a strided destination)
 template <typename T>
-__global__ void skinny_reduce_kernel(const float *__restrict__ part, T *__restrict__ C, long long mn, int splits) {
+__global__ void skinny_reduce_kernel(const float *__restrict__ part, T *__restrict__ C, long long mn, int N,
+                                     long long ldc, int splits) {
   const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
   if (id >= mn) return;
   float a = 0.f;
   for (int s = 0; s < splits; ++s) a += part[(long long)s * mn + id];
-  store_f(C + id, a);
+  store_f(C + (id / N) * ldc + id % N, a);
 }
 
 int skinny_splits(int N, int K) {
@@ -471,28 +770,43 @@ int skinny_splits(int N, int K) {
 size_t skinny_scratch_bytes(int M, int N, int K) { return (size_t)skinny_splits(N, K) * M * N * sizeof(float); }
 
 template <typename T>
-hipError_t gemm_skinny(const T *A, const T *W, T *C, float *part, int M, int N, int K, hipStream_t s) {
+hipError_t gemm_skinny(const T *A, const T *W, T *C, long long ldc, float *part, int M, int N, int K, hipStream_t s) {
   const int splits = skinny_splits(N, K);
   int chunk = (K + splits - 1) / splits;
   const dim3 grid((N + SK_COLS - 1) / SK_COLS, (K + chunk - 1) / chunk);
-  gemm_skinny_kernel<T><<<grid, 256, 0, s>>>(A, W, part, M, N, K, chunk);
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    if (N % 8 == 0 && K % 8 == 0) {
+      chunk = (chunk + 15) / 16 * 16;  // whole groups of 16 k (never above SK_MAXCHUNK, itself a multiple of 16)
+      const dim3 grid_m((N + SK_COLS - 1) / SK_COLS, (K + chunk - 1) / chunk);
+      gemm_skinny_mfma_kernel<<<grid_m, 256, 0, s>>>(A, W, part, M, N, K, chunk);
+      hipError_t em = hipGetLastError();
+      if (em != hipSuccess) return em;
+      const long long mn_m = (long long)M * N;
+      skinny_reduce_kernel<T><<<(unsigned)((mn_m + 255) / 256), 256, 0, s>>>(part, C, mn_m, N, ldc, (int)grid_m.y);
+      return hipGetLastError();
+    }
+  }
+  if (M > 16) gemm_skinny_kernel<T, 32><<<grid, 256, 0, s>>>(A, W, part, M, N, K, chunk);
+  else gemm_skinny_kernel<T, 16><<<grid, 256, 0, s>>>(A, W, part, M, N, K, chunk);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long long mn = (long long)M * N;
-  skinny_reduce_kernel<T><<<(unsigned)((mn + 255) / 256), 256, 0, s>>>(part, C, mn, (int)grid.y);
+  skinny_reduce_kernel<T><<<(unsigned)((mn + 255) / 256), 256, 0, s>>>(part, C, mn, N, ldc, (int)grid.y);
   return hipGetLastError();
 }
 
+// slots of the latent ring: the taps - 1 earlier rows the convolutions reach back to (one at least, for the value
+// shift) plus the slot the new row is written to
 int ring_rows(const Dims &d) {
   const int ks = (d.flags & CCA_CONV_SEQ) ? d.k_seq : 1, kc = (d.flags & CCA_CONV_CH) ? d.k_ch : 1;
   const int taps = ks + kc - 1;
-  return taps - 1 > 1 ? taps - 1 : 1;
+  return (taps - 1 > 1 ? taps - 1 : 1) + 1;
 }
 
 size_t align256(size_t n) { return (n + 255) / 256 * 256; }
 
 struct DecLayout {
-  size_t lat_new, q_new, o, part, gemm, total;
+  size_t q_new, o, part, gemm, total;
 };
 DecLayout layout(const Dims &d) {
   DecLayout L;
@@ -502,7 +816,6 @@ DecLayout layout(const Dims &d) {
     off += align256(n);
     return at;
   };
-  L.lat_new = take((size_t)d.B * d.n_lat * d.esize());
   L.q_new = take((size_t)d.B * d.e_q * sizeof(float));
   L.o = take((size_t)d.B * d.e_q * d.esize());
   L.part = take((size_t)d.B * d.Hq * MAX_SPLITS * (2 + d.dh) * sizeof(float));
@@ -519,12 +832,13 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
   const int P = ring_rows(d);
   DecArgs a{d.B, d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, P, pos,
             d.flags, d.rope_base, d.scale};
-  T *lat_new = reinterpret_cast<T *>(ws + L.lat_new);
   float *q_new = reinterpret_cast<float *>(ws + L.q_new);
   T *o = reinterpret_cast<T *>(ws + L.o);
   float *part = reinterpret_cast<float *>(ws + L.part);
   float *gpart = reinterpret_cast<float *>(ws + L.gemm);
-  hipError_t e = gemm_skinny<T>((const T *)x_new, (const T *)w.w_down, lat_new, gpart, d.B, d.n_lat, d.E, s);
+  // the new latent rows go straight into their ring slot
+  hipError_t e = gemm_skinny<T>((const T *)x_new, (const T *)w.w_down, (T *)hist + (long long)(pos % P) * d.n_lat,
+                                (long long)P * d.n_lat, gpart, d.B, d.n_lat, d.E, s);
   if (e != hipSuccess) return e;
   {
     int threads = 64;
@@ -532,10 +846,8 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
     const int kc = (d.flags & CCA_CONV_CH) ? d.k_ch : 1;
     const size_t smem = sizeof(float) * ((size_t)kc * d.dh + threads + d.dh);
     decode_prologue_kernel<T><<<dim3(d.B, d.Hq + 2 * d.Hk), threads, smem, s>>>(
-        a, (const T *)hist, lat_new, (const T *)w.w_conv_seq, (const T *)w.w_conv_ch, w.temp, q_new, (T *)k_cache,
+        a, (const T *)hist, (const T *)w.w_conv_seq, (const T *)w.w_conv_ch, w.temp, q_new, (T *)k_cache,
         (T *)v_cache);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    decode_commit_kernel<T><<<(unsigned)(((long long)d.B * d.n_lat + 255) / 256), 256, 0, s>>>(a, lat_new, (T *)hist);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
@@ -551,6 +863,33 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
                         smem_base + DEC_WAVES * 64 * (rowb + 16) <= 144 * 1024 && false;  // measured slower: one workgroup per CU
     const size_t smem = smem_base + (staged ? DEC_WAVES * 64 * (rowb + 16) : 0);
     const unsigned grid = (unsigned)((long long)d.B * d.Hk * nsplit);
+    if constexpr (std::is_same<T, bf16_t>::value) {
+      // the row kernel addresses a sequence's cache with 32-bit byte offsets
+      if ((d.dh == 64 || d.dh == 128 || d.dh == 256) && (long long)d.T * d.Hk * d.dh * 2 < (1ll << 31)) {
+        for (int r0 = 0; r0 < d.R; r0 += R_MAX) {
+          const int left = d.R - r0;
+#define CCA_DEC_ROWS(NR, DH, U)                                                                                    \
+  decode_attn_rows_kernel<NR, DH, U><<<grid, DEC_WAVES * 64, 0, s>>>(a, q_new, (const bf16_t *)k_cache,             \
+                                                                     (const bf16_t *)v_cache, part, nsplit, r0)
+#define CCA_DEC_ROWS_DH(NR, U)                                                                                     \
+  {                                                                                                                \
+    if (d.dh == 64) CCA_DEC_ROWS(NR, 64, U);                                                                       \
+    else if (d.dh == 128) CCA_DEC_ROWS(NR, 128, U);                                                                \
+    else CCA_DEC_ROWS(NR, 256, U);                                                                                 \
+  }
+          if (left == 1) CCA_DEC_ROWS_DH(1, 8)
+          else if (left == 2) CCA_DEC_ROWS_DH(2, 8)
+          else if (left <= 4) CCA_DEC_ROWS_DH(4, 8)
+          else CCA_DEC_ROWS_DH(8, 4)
+#undef CCA_DEC_ROWS_DH
+#undef CCA_DEC_ROWS
+          if ((e = hipGetLastError()) != hipSuccess) return e;
+        }
+        decode_combine_kernel<T><<<(unsigned)(d.B * d.Hq), 128, 0, s>>>(a, part, nsplit, o);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        return gemm_skinny<T>(o, (const T *)w.w_out, (T *)out, d.E, gpart, d.B, d.E, d.e_q, s);
+      }
+    }
     for (int r0 = 0; r0 < d.R; r0 += R_MAX) {
 #define CCA_DEC_ATTN(CPL, DHC, ST)                                                                              \
   {                                                                                                             \
@@ -575,7 +914,7 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
     decode_combine_kernel<T><<<(unsigned)(d.B * d.Hq), 128, 0, s>>>(a, part, nsplit, o);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  return gemm_skinny<T>(o, (const T *)w.w_out, (T *)out, gpart, d.B, d.E, d.e_q, s);
+  return gemm_skinny<T>(o, (const T *)w.w_out, (T *)out, d.E, gpart, d.B, d.E, d.e_q, s);
 }
 
 }  // namespace

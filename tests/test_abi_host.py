@@ -126,12 +126,12 @@ def test_decode_rejects_bad_arguments_and_reports_ring_depth():
     st = B.cca_decode_state(p, p, p)
     n, ring = C.c_size_t(0), C.c_int32(0)
     assert lib.cca_decode_workspace_size(C.byref(cc), C.byref(n), C.byref(ring)) == B.CCA_OK and n.value > 0
-    assert ring.value == max(cfg.k_seq + cfg.k_ch - 2, 1)  # both convolutions are on in the paper's flags
+    assert ring.value == max(cfg.k_seq + cfg.k_ch - 2, 1) + 1  # both convolutions are on in the paper's flags
     assert lib.cca_decode_workspace_size(C.byref(cc), None, None) == B.CCA_ERR_NULL
     noconv = good()
     noconv.flags = B.CCA_FLAGS_MHA
     c2 = noconv.c()
-    assert lib.cca_decode_workspace_size(C.byref(c2), C.byref(n), C.byref(ring)) == B.CCA_OK and ring.value == 1
+    assert lib.cca_decode_workspace_size(C.byref(c2), C.byref(n), C.byref(ring)) == B.CCA_OK and ring.value == 2
     need = C.c_size_t(0)
     lib.cca_decode_workspace_size(C.byref(cc), C.byref(need), None)
     call = lambda w_, x, st_, pos, out, wsp, nb: lib.cca_decode_step(
