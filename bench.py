@@ -110,7 +110,7 @@ def main() -> int:
     ap.add_argument("--no-backward", action="store_true", help="skip the forward+backward measurement")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-step measurement")
     ap.add_argument("--only", choices=["forward", "attention", "prologue", "down_project", "up_project", "backward",
-                                       "attention_backward", "prologue_backward"],
+                                       "attention_backward", "prologue_backward", "decode"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
     ap.add_argument("--grid", action="store_true",
                     help="latency grid on the axes of the paper's kernel figures (App. D.1: E = 2048, bf16, S = 512..16384, "
@@ -155,6 +155,25 @@ def main() -> int:
                     d_o=torch.randn_like(saved.o), d_q=torch.empty_like(saved.q), d_k=torch.empty_like(saved.k),
                     d_v=torch.empty_like(saved.v), d_lat=torch.empty_like(saved.lat))
 
+    def decode_setup(Bd):
+        """State of Bd sequences with a full cache of random contents (timing only)."""
+        cd = P.config_from_workload(dict(w, B=Bd))
+        g = torch.Generator(device=x.device).manual_seed(1)
+        st = P.CCADecodeState.allocate(cd, x.device)
+        for t_ in (st.k_cache, st.v_cache, st.lat_ring):
+            t_.copy_(torch.randn(t_.shape, device=x.device, generator=g).to(t_.dtype))
+        xd = torch.randn(Bd, cd.d_model, device=x.device, generator=g).to(cd.torch_dtype)
+        od = torch.empty_like(xd)
+        return cd, st, (lambda: P.cca_decode_step(cd, wt, xd, st, cd.T - 1, out=od))
+
+    if args.only == "decode":
+        cd, st, dstep = decode_setup(32)
+        for _ in range(args.steps):
+            dstep()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": "decode", "launches": args.steps, "workload": args.workload, "batch": 32,
+                          "cache_len": cd.T}))
+        return 0
     if args.only:
         P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
         bb = backward_buffers() if "backward" in args.only else None
@@ -314,17 +333,8 @@ def main() -> int:
     dec = None
     if args.workload == "ccgqa_16k" and not args.no_decode:
         Bd = 32
-        cd = P.config_from_workload(dict(w, B=Bd))
-        g = torch.Generator(device=x.device).manual_seed(1)
-        st = P.CCADecodeState.allocate(cd, x.device)
-        for t_ in (st.k_cache, st.v_cache, st.lat_ring):
-            t_.copy_(torch.randn(t_.shape, device=x.device, generator=g).to(t_.dtype))
-        xd = torch.randn(Bd, cd.d_model, device=x.device, generator=g).to(cd.torch_dtype)
-        od = torch.empty_like(xd)
-        pos = cd.T - 1
-        for _ in range(3):
-            P.cca_decode_step(cd, wt, xd, st, pos, out=od)
-        d_ms = timed(lambda: P.cca_decode_step(cd, wt, xd, st, pos, out=od), 20)
+        cd, st, dstep = decode_setup(Bd)
+        d_ms = timed(dstep, 20)
         cache_b = 2.0 * Bd * cd.T * cd.e_kv * 2
         weight_b = (cd.d_model * cd.n_lat + cd.e_q * cd.d_model) * 2.0
         dec = {"batch": Bd, "cache_len": cd.T, "ms_per_step": round(d_ms, 4),

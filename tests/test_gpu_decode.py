@@ -46,6 +46,11 @@ CASES = [
     dict(B=3, T=40, E=384, Hq=3, Hk=3, dh=128, k_seq=4, k_ch=1, dtype="bf16", paper_flags=True),
     dict(B=1, T=33, E=512, Hq=2, Hk=1, dh=256, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=1, T=20, E=2048, Hq=16, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),  # R = 16 > 8
+    # batch above 32 rows (two row blocks in the projections), R = 3, projection widths that are not multiples of
+    # 128 and a contraction length that is not a multiple of 16
+    dict(B=40, T=6, E=264, Hq=3, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=20, T=5, E=256, Hq=4, Hk=2, dh=32, k_seq=2, k_ch=2, dtype="f32", paper_flags=True),   # fp32, 17..32 rows
+    dict(B=33, T=4, E=248, Hq=2, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),  # 33 rows, widths 8 * odd
 ]
 
 
@@ -102,6 +107,37 @@ def test_decode_long_cache_split_over_workgroups():
     rows = np.arange(start, w["T"])
     ref = oracle_forward(w, inp, rows=rows)
     say(check_out(to_np(out), ref["out"], w["dtype"]))
+
+
+def test_decode_bench_configuration_sampled():
+    """The configuration bench.py times (32 sequences, a 16k cache, the headline layer): two distinct sequences
+    alternate over the batch; the oracle computes the last row of each."""
+    from synth_inputs import WORKLOADS
+    w0 = WORKLOADS["ccgqa_16k"]
+    w2 = dict(w0, B=2)
+    T, Bd = w0["T"], 32
+    say("case decode at the benchmark configuration", w2, "batch", Bd)
+    inp = make_inputs(w2, seed=7)
+    cfg2 = P.config_from_workload(dict(w2, T=T - 1))
+    x, wt = P.weights_to_device(P.config_from_workload(w2), inp)
+    saved = P.CCASaved.allocate(cfg2, x.device)
+    P.cca_forward(cfg2, wt, x[:, :T - 1].contiguous(), saved=saved)
+    cfg = P.config_from_workload(dict(w0, B=Bd))
+    state = P.CCADecodeState.allocate(cfg, x.device)
+    two = P.CCADecodeState.allocate(P.config_from_workload(w2), x.device)
+    two.load_prefill(saved, T - 1)
+    for b in range(Bd):
+        state.k_cache[b].copy_(two.k_cache[b % 2])
+        state.v_cache[b].copy_(two.v_cache[b % 2])
+        state.lat_ring[b].copy_(two.lat_ring[b % 2])
+    del two, saved
+    x_new = x[:, T - 1].repeat(Bd // 2, 1).contiguous()  # rows b -> sequence b % 2
+    out = P.cca_decode_step(cfg, wt, x_new, state, T - 1)
+    torch.cuda.synchronize()
+    ref = oracle_forward(w2, inp, rows=np.array([T - 1]))["out"][:, 0]  # (2, E)
+    got = to_np(out)
+    say(check_out(got, np.tile(ref, (Bd // 2, 1)), "bf16"))
+    assert np.array_equal(got[0], got[2]) and np.array_equal(got[1], got[31]), "same sequence, different result"
 
 
 def test_decode_rejects_bad_arguments():
