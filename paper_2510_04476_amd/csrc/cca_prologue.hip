@@ -14,8 +14,8 @@
 // workgroup, the token operands are the latent rows of tokens t-D+1..t.
 //
 // The MFMA is issued with the filter as its first operand, so each lane ends
-// up with 64 of the 128 output channels of ONE token (the other half-wave has
-// the rest): the L2 norm is an in-lane sum plus one half-wave exchange, and
+// up with half of the d_h output channels of ONE token (the other half-wave has
+// the rest; d_h = 128 or 64): the L2 norm is an in-lane sum plus one half-wave exchange, and
 // the rotate-half RoPE partner (o, o + d_h/2) sits in the same lane.  The
 // qk-mean skip branch is added by the matrix core as well (a scaled identity
 // times the pre-conv latent rows), so it needs no loads in another layout.
@@ -36,7 +36,6 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 namespace {
 
-constexpr int DH = 128;
 constexpr int NT = 512;
 constexpr int MAX_TILES_PER_WAVE = 3;  // a workgroup takes 256 * tiles_per_wave tokens, tiles dealt round-robin
 
@@ -75,7 +74,7 @@ __device__ __forceinline__ float hi_f(uint32_t w) { return __uint_as_float(w & 0
 __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D, const bf16_t *__restrict__ w0,
                                                             const bf16_t *__restrict__ w1, bf16_t *__restrict__ wc,
                                                             float2 *__restrict__ ropeA, float2 *__restrict__ ropeB,
-                                                            int n_fold_blocks, int n_thi, int transposed) {
+                                                            int n_fold_blocks, int n_thi, int transposed, int DH) {
   const int NH = a.Hq + a.Hk;
   if ((int)blockIdx.x < n_fold_blocks) {
     const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (h, o, i)
@@ -122,12 +121,15 @@ __global__ __launch_bounds__(256) void prologue_setup_kernel(FusedArgs a, int D,
 // rows t .. t+D-1, zero past the end of its sequence), the qk-mean adjoint through the same identity MFMAs, no
 // norm / RoPE (those are undone by a pointwise kernel before), and the value role running the shift backwards.
 // ---------------------------------------------------------------------------
-template <int D, bool BWD>
+// DH = d_h (64 or 128): KK fragments of 16 input channels, NTL tiles of 32 output channels, CPR 16-byte chunks per
+// tap of a filter row.
+template <int DH, int D, bool BWD>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_fused_kernel(
     FusedArgs a, const bf16_t *__restrict__ lat, const bf16_t *__restrict__ vsrc, const u32x4 *__restrict__ wc,
     const float2 *__restrict__ ropeA, const float2 *__restrict__ ropeB, const float *__restrict__ temp,
     bf16_t *__restrict__ q, bf16_t *__restrict__ k, bf16_t *__restrict__ v, float *__restrict__ rnorm) {
-  constexpr int WROW = D * 16;  // 16-byte chunks per filter row (one output channel)
+  constexpr int KK = DH / 16, NTL = DH / 32, CPR = DH / 8;
+  constexpr int WROW = D * CPR;  // 16-byte chunks per filter row (one output channel)
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   u32x4 *sW = reinterpret_cast<u32x4 *>(smem);
 
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll 4
     for (int id = tid; id < DH * WROW; id += NT) {
       const int o = id / WROW, c = id % WROW;
-      sW[o * WROW + ((c & ~15) | ((c ^ o) & 15))] = src[id];
+      sW[o * WROW + ((c & ~(CPR - 1)) | ((c ^ o) & (CPR - 1)))] = src[id];
     }
   }
   __syncthreads();  // the only workgroup-wide synchronisation
@@ -212,7 +214,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const bool any_pad = __any(BWD ? tpos + D - 1 >= a.T : tpos < D - 1) != 0;
 
     // ---- operands: source rows of tokens t-D+1 .. t (adjoint: t+D-1 .. t) of this head; d = D-1 is the token itself
-    bf16x8 uf[D][8];
+    bf16x8 uf[D][KK];
 #pragma unroll
     for (int d = 0; d < D; ++d) {
       const int back = D - 1 - d;
@@ -220,7 +222,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       src_row = src_row < 0 ? 0 : (src_row >= a.rows ? a.rows - 1 : src_row);
       const bf16_t *p = lat + src_row * a.src_stride + ch0 + half * 8;
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
+      for (int kk = 0; kk < KK; ++kk) {
         u32x4 raw = *reinterpret_cast<const u32x4 *>(p + kk * 16);
         if (any_pad && (BWD ? tpos + back >= a.T : tpos < back)) raw = u32x4{0, 0, 0, 0};
         uf[d][kk] = __builtin_bit_cast(bf16x8, raw);
@@ -228,20 +230,20 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     }
 
     // ---- y1^T = Wc * [u(t-D+1) .. u(t)]^T
-    f32x16 acc[4];
+    f32x16 acc[NTL];
 #pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
+    for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
 #pragma unroll
     for (int d = 0; d < D; ++d)
 #pragma unroll
-      for (int kk = 0; kk < 8; ++kk)
+      for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
+        for (int nt = 0; nt < NTL; ++nt) {
           const int o = nt * 32 + l32;
-          const int c = d * 16 + kk * 2 + half;
-          const bf16x8 wf = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~15) | ((c ^ o) & 15))]);
+          const int c = d * CPR + kk * 2 + half;
+          const bf16x8 wf = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~(CPR - 1)) | ((c ^ o) & (CPR - 1)))]);
           acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[d][kk], acc[nt], 0, 0, 0);
         }
 
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     //      Adjoint: q head + d3_q / 2 + d3_k[g] / (2R);  k head: + (sum_r d3_q[gR + r] + d3_k) / 2.
     if (mean) {
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
           acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_half[j], uf[D - 1][2 * nt + j], acc[nt], 0, 0, 0);
@@ -257,12 +259,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       for (int sidx = 0; sidx < nsrc; ++sidx) {
         const int col = is_q ? a.e_q + g * DH : (g * a.R + sidx) * DH;
         const bf16_t *p = lat + rowc * a.src_stride + col + half * 8;
-        bf16x8 mf[8];
+        bf16x8 mf[KK];
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk)
+        for (int kk = 0; kk < KK; ++kk)
           mf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p + kk * 16));
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt)
+        for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp[j], mf[2 * nt + j], acc[nt], 0, 0, 0);
@@ -274,13 +276,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (!BWD && (a.flags & CCA_QK_NORM)) {
       float ssq = 0.f;
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) ssq = fmaf(acc[nt][r], acc[nt][r], ssq);
       ssq += __shfl_xor(ssq, 32);
       const float mul = sqrtf((float)DH) / sqrtf(ssq) * beta;
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[nt][r] *= mul;
       if (rnorm && half == 0 && row < a.rows) rnorm[row * NH + head] = mul;
@@ -290,7 +292,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (!BWD && (a.flags & CCA_ROPE)) {
       const int thi = tpos >> 7, tlo = tpos & 127;
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt)
+      for (int nt = 0; nt < NTL / 2; ++nt)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
           const int i0 = nt * 32 + rg * 8 + half * 4;  // 4 consecutive pair indices
@@ -303,9 +305,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           for (int e = 0; e < 4; ++e) {
             const float cs = ca[e] * cb[e] - sa[e] * sb[e];
             const float sn = sa[e] * cb[e] + ca[e] * sb[e];
-            const float x1 = acc[nt][rg * 4 + e], x2 = acc[nt + 2][rg * 4 + e];
+            const float x1 = acc[nt][rg * 4 + e], x2 = acc[nt + NTL / 2][rg * 4 + e];
             acc[nt][rg * 4 + e] = x1 * cs - x2 * sn;
-            acc[nt + 2][rg * 4 + e] = x2 * cs + x1 * sn;
+            acc[nt + NTL / 2][rg * 4 + e] = x2 * cs + x1 * sn;
           }
         }
     }
@@ -314,7 +316,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (row < a.rows) {
       bf16_t *orow = dst + row * dst_stride;
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt)
+      for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
           u32x2 w;
@@ -382,17 +384,17 @@ __global__ __launch_bounds__(256) void split_copy_bwd_kernel(const unsigned char
   }
 }
 
-template <int D, bool BWD>
+template <int DH, int D, bool BWD>
 hipError_t launch_main(const FusedArgs &a, const void *lat, const void *vsrc, const void *wc, const float2 *ropeA,
                        const float2 *ropeB, const float *temp, void *q, void *k, void *v, float *rnorm, int grid,
                        hipStream_t s) {
-  constexpr size_t smem = (size_t)DH * D * 16 * 16;
+  constexpr size_t smem = (size_t)DH * D * (DH / 8) * 16;
   {  // per launch: the attribute belongs to the current device, and the library keeps no state
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<D, BWD>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<DH, D, BWD>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
   }
-  prologue_fused_kernel<D, BWD><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc, (const u32x4 *)wc,
+  prologue_fused_kernel<DH, D, BWD><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc, (const u32x4 *)wc,
                                                        ropeA, ropeB, temp, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
   return hipGetLastError();
 }
@@ -433,7 +435,7 @@ struct FusedScratch {
   size_t bytes;
 };
 FusedScratch carve(const Dims &d, void *scratch, int D) {
-  const int NH = d.Hq + d.Hk, n_thi = (d.T + 127) / 128;
+  const int NH = d.Hq + d.Hk, n_thi = (d.T + 127) / 128, DH = d.dh;
   const size_t wc_bytes = ((size_t)NH * DH * D * DH * 2 + 255) / 256 * 256;
   const size_t ra_bytes = ((size_t)n_thi * (DH / 2) * 8 + 255) / 256 * 256;
   const size_t rb_bytes = (size_t)(DH / 2) * 128 * 8;
@@ -444,11 +446,11 @@ FusedScratch carve(const Dims &d, void *scratch, int D) {
 
 hipError_t run_setup(const Dims &d, const FusedArgs &a, const cca_weights &w, const FusedScratch &fs, int D,
                      bool transposed, hipStream_t s) {
-  const int NH = d.Hq + d.Hk, n_thi = (d.T + 127) / 128;
+  const int NH = d.Hq + d.Hk, n_thi = (d.T + 127) / 128, DH = d.dh;
   const int n_fold = (NH * DH * DH + 255) / 256;
   const int n_rope = (n_thi * (DH / 2) + (DH / 2) * 128 + 255) / 256;
   prologue_setup_kernel<<<n_fold + n_rope, 256, 0, s>>>(a, D, (const bf16_t *)w.w_conv_seq, (const bf16_t *)w.w_conv_ch,
-                                                        fs.wc, fs.ropeA, fs.ropeB, n_fold, n_thi, transposed ? 1 : 0);
+                                                        fs.wc, fs.ropeA, fs.ropeB, n_fold, n_thi, transposed ? 1 : 0, DH);
   return hipGetLastError();
 }
 
@@ -488,7 +490,7 @@ hipError_t prologue_split_copy_bwd(const Dims &d, const void *d_q, const void *d
 }
 
 bool prologue_fused_supported(const Dims &d) {
-  return d.bf16 && d.dh == DH && (d.flags & CCA_CONV_CH) && !(d.flags & CCA_ROPE_INTERLEAVED) && taps(d) <= 3 &&
+  return d.bf16 && (d.dh == 128 || d.dh == 64) && (d.flags & CCA_CONV_CH) && !(d.flags & CCA_ROPE_INTERLEAVED) && taps(d) <= 3 &&
          d.v_half % 8 == 0;
 }
 
@@ -507,10 +509,11 @@ hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *
   if (e != hipSuccess) return e;
   const int grid = plan_grid(d, a);
   const bf16_t *vsrc = (const bf16_t *)lat + d.e_q + d.e_kv;
+#define LAUNCH_DH(D_, B_) (d.dh == 64 ? launch_main<64, D_, B_> : launch_main<128, D_, B_>)
   switch (D) {
-    case 1: return launch_main<1, false>(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
-    case 2: return launch_main<2, false>(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
-    default: return launch_main<3, false>(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
+    case 1: return LAUNCH_DH(1, false)(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
+    case 2: return LAUNCH_DH(2, false)(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
+    default: return LAUNCH_DH(3, false)(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
   }
 }
 
@@ -539,9 +542,9 @@ hipError_t prologue_fused_bwd_dlat(const Dims &d, const void *d3, const void *d_
   const int grid = plan_grid(d, a);
   bf16_t *dl = (bf16_t *)d_lat;
   switch (D) {
-    case 1: return launch_main<1, true>(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
-    case 2: return launch_main<2, true>(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
-    default: return launch_main<3, true>(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
+    case 1: return LAUNCH_DH(1, true)(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
+    case 2: return LAUNCH_DH(2, true)(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
+    default: return LAUNCH_DH(3, true)(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
   }
 }
 

@@ -345,7 +345,8 @@ BwdScratch bwd_layout(const Dims &d) {
 
 }  // namespace
 
-bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d); }
+// the adjoint kernels of this file are written for d_h = 128 only (the forward prologue also takes 64)
+bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d) && d.dh == 128; }
 
 size_t prologue_bwd_fused_scratch_bytes(const Dims &d) {
   return prologue_bwd_fused_supported(d) ? bwd_layout(d).total : 0;

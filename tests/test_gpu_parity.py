@@ -82,6 +82,9 @@ SMALL = [
     dict(B=3, T=130, E=384, Hq=3, Hk=3, dh=128, k_seq=4, k_ch=1, dtype="bf16", paper_flags=True),
     dict(B=1, T=1, E=256, Hq=2, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=2, T=2, E=256, Hq=2, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="f32", paper_flags=True),
+    # d_h = 64 on the fused prologue: three taps, R = 4, several 256-token tiles with a ragged tail, T past 128 * 8
+    dict(B=2, T=1100, E=512, Hq=8, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=260, E=512, Hq=3, Hk=3, dh=64, k_seq=1, k_ch=3, dtype="bf16", paper_flags=True),
 ]
 
 
@@ -96,7 +99,7 @@ def test_small_shapes(i, conv_visible):
     say(res)
 
 
-@pytest.mark.parametrize("i", [1, 2, 3, 5, 6])
+@pytest.mark.parametrize("i", [1, 2, 3, 5, 6, 8])
 @pytest.mark.parametrize("causal", [True, False])
 def test_small_shapes_inference_path(i, causal):
     """Without saved tensors the attention kernel takes its inference form (row sums of the unrounded
@@ -131,7 +134,7 @@ FLAG_CASES = {
 
 
 @pytest.mark.parametrize("name", sorted(FLAG_CASES))
-@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128)])
+@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128), ("bf16", 64)])
 def test_each_flag(name, dtype, dh):
     flags, okw = FLAG_CASES[name]
     w = dict(B=2, T=200, E=4 * dh * 2, Hq=4, Hk=2, dh=dh, k_seq=2, k_ch=2, dtype=dtype, paper_flags=True)
