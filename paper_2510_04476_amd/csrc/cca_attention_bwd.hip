@@ -44,9 +44,12 @@ typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
 
 namespace {
 
-constexpr int DH = 128;
-constexpr int KK = DH / 16, DT = DH / 32, KCH = DH / 8;
-constexpr int ROW = DH * 2 + 16;  // padded LDS row of one token: conflict-free 16-byte reads down a column of rows
+// Shapes that follow from the head width d_h (128 or 64): KK fragments of 16 channels, DT tiles of 32 channels,
+// KCH 16-byte chunks per row, ROW = padded LDS row of one token in bytes (conflict-free 16-byte reads down a
+// column of rows).
+#define CCA_BWD_GEOMETRY(DH) \
+  constexpr int KK = (DH) / 16, DT = (DH) / 32, KCH = (DH) / 8, ROW = (DH) * 2 + 16; \
+  (void)KK; (void)DT; (void)KCH; (void)ROW
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2 = 0.69314718055994530942f;  // the scaled q carries scale * log2(e): scale * q = ln 2 * q_scaled
 
@@ -60,6 +63,7 @@ __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 
 // MFMA first-operand fragment of the TRANSPOSE of a row-major LDS tile: lane (c = l32, half) receives
 // tile[r0 + 4*half + {0..3}][c0 + c] and tile[r0 + 8 + 4*half + {0..3}][c0 + c].  `base` already holds the
 // per-lane part  (4*half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2.
+template <int ROW>
 __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int c0) {
   const unsigned char *a = base + r0 * ROW + c0 * 2;
   const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)a);
@@ -68,13 +72,15 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int
 }
 
 // ---------------------------------------------------------------------------
-// Delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d]; one wavefront per 4 (t,h) rows (16 lanes x 16 bytes each)
+// Delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d]; d_h / 8 lanes x 16 bytes per (t,h) row
 // ---------------------------------------------------------------------------
+template <int DH>
 __global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ dO, const bf16_t *__restrict__ O,
                                                    const bf16_t *__restrict__ OLO, float *__restrict__ delta,
                                                    long long n_rows, int T, int Hq) {
-  const long long row = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);  // row = (b*T + t)*Hq + h
-  const int sub = threadIdx.x & 15;
+  constexpr int LPR = DH / 8;  // lanes per row
+  const long long row = (long long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;  // row = (b*T + t)*Hq + h
+  const int sub = threadIdx.x % LPR;
   float acc = 0.f;
   if (row < n_rows) {
     const u32x4 a = *reinterpret_cast<const u32x4 *>(dO + row * DH + sub * 8);
@@ -89,7 +95,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ d
     }
   }
 #pragma unroll
-  for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
   if (sub == 0 && row < n_rows) {
     const long long bt = row / Hq;
     const int h = (int)(row % Hq);
@@ -104,11 +110,12 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ d
 // ---------------------------------------------------------------------------
 constexpr int DQ_BQ = 256, DQ_NT = 512, BKV = 64;
 
-template <bool CAUSAL>
+template <int DH, bool CAUSAL>
 __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
     bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale) {
+  CCA_BWD_GEOMETRY(DH);
   constexpr int TILE = BKV * ROW;
   constexpr int PER_THREAD = BKV * KCH / DQ_NT;  // 16-byte chunks of K (and of V) per thread per tile
   constexpr int ROWS_PER_PASS = DQ_NT / KCH;
@@ -231,7 +238,7 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(kp + tr_off, ks * 32 + jj * 16, dt * 32), dsf[jj],
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(kp + tr_off, ks * 32 + jj * 16, dt * 32), dsf[jj],
                                                               acc[dt], 0, 0, 0);
       }
     }
@@ -278,12 +285,13 @@ constexpr int KV_BK = 256, KV_NT = 512, BQT = 64;  // keys per workgroup, thread
 // staging registers; q arrives pre-scaled from scale_q_kernel), S is turned into bf16 P before dP is formed, and
 // dS is computed from that bf16 P.  (With register staging and fp32 P the pass spilled 98 registers; split into a
 // dV pass and a dK pass it cost a fifth contraction.)
-template <bool CAUSAL, bool PARTIAL>
+template <int DH, bool CAUSAL, bool PARTIAL>
 __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
     bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
     int Hk, int BH, int nkb, float scale) {
+  CCA_BWD_GEOMETRY(DH);
   constexpr int TILE = BQT * ROW;
   constexpr int PER_THREAD = BQT * KCH / KV_NT;
   constexpr int ROWS_PER_PASS = KV_NT / KCH;
@@ -329,9 +337,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const int steps = nqt - qt_first;
 
   // Q (pre-scaled) and dO tiles travel global -> LDS directly: wave instruction i deposits 64 x 16 bytes at LDS
-  // chunks [i*64, i*64+64) of a tile laid out in padded rows of 17 chunks; lanes landing on padding fetch a duplicate.
-  constexpr int CPR = ROW / 16;                 // 17
-  constexpr int T_INSTR = BQT * CPR / 64;       // 17 instructions per tile
+  // chunks [i*64, i*64+64) of a tile laid out in padded rows of CPR chunks; lanes landing on padding fetch a duplicate.
+  constexpr int CPR = ROW / 16;                 // 17 (d_h = 128), 9 (d_h = 64)
+  constexpr int T_INSTR = BQT * CPR / 64;       // wave instructions per tile
   static_assert(BQT * CPR % 64 == 0, "tile must be a whole number of wave instructions");
   constexpr int PER_WAVE = (2 * T_INSTR + KV_NT / 64 - 1) / (KV_NT / 64);
   typedef __attribute__((address_space(3))) void lds_void;
@@ -438,9 +446,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) {
-            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(dp_ + tr_off, qs * 32 + jj * 16, dt * 32),
+            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(dp_ + tr_off, qs * 32 + jj * 16, dt * 32),
                                                                pf[jj], dv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag(qp + tr_off, qs * 32 + jj * 16, dt * 32),
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(qp + tr_off, qs * 32 + jj * 16, dt * 32),
                                                                dsf[jj], dk[dt], 0, 0, 0);
           }
       }
@@ -484,6 +492,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 }
 
 // out[(row, g), :] = bf16(sum_r part[(row, g*R + r), :]) for dK and dV, 4 channels per thread, fixed order
+template <int DH>
 __global__ __launch_bounds__(256) void group_sum_kernel(const float *__restrict__ pk, const float *__restrict__ pv,
                                                        bf16_t *__restrict__ dK, bf16_t *__restrict__ dV,
                                                        long long n_out, int R) {
@@ -508,7 +517,7 @@ __global__ __launch_bounds__(256) void group_sum_kernel(const float *__restrict_
 }  // namespace
 
 bool attention_bwd_supported(const Dims &d) {
-  return d.bf16 && d.dh == DH && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
+  return d.bf16 && (d.dh == 128 || d.dh == 64) && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
 }
 
 // Delta (B,H_q,T) fp32, then (R > 1 only) the per-query-head fp32 contributions to dK and dV, (B,T,H_q,d_h) each,
@@ -519,12 +528,14 @@ size_t attention_bwd_scratch_bytes(const Dims &d) {
   return delta_bytes(d) + (d.R > 1 ? 2 * (size_t)d.rows() * d.e_q * sizeof(float) : 0) + (size_t)d.rows() * d.e_q * 2;
 }
 
-hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
-                              const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
-                              hipStream_t s) {
+template <int DH>
+static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k, const void *v, const void *o,
+                                    const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v,
+                                    float *delta, hipStream_t s) {
   const bool causal = d.flags & CCA_CAUSAL;
   const long long n_rows = d.rows() * d.Hq;
-  delta_kernel<<<(unsigned)((n_rows + 15) / 16), 256, 0, s>>>((const bf16_t *)d_o, (const bf16_t *)o, (const bf16_t *)o_lo, delta,
+  constexpr int DELTA_ROWS = 256 / (DH / 8);  // rows per workgroup of delta_kernel
+  delta_kernel<DH><<<(unsigned)((n_rows + DELTA_ROWS - 1) / DELTA_ROWS), 256, 0, s>>>((const bf16_t *)d_o, (const bf16_t *)o, (const bf16_t *)o_lo, delta,
                                                              n_rows, d.T,
                                                              d.Hq);
   hipError_t e = hipGetLastError();
@@ -549,27 +560,34 @@ hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const
   const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 256 ? 1 : 0;
   const bool partial = d.R > 1;
   if (causal) {
-    attn_bwd_dq_kernel<true><<<(unsigned)((long long)BH * (paired ? (nqb + 1) / 2 : nqb)), DQ_NT, 0, s>>>(ARGS_DQ);
+    attn_bwd_dq_kernel<DH, true><<<(unsigned)((long long)BH * (paired ? (nqb + 1) / 2 : nqb)), DQ_NT, 0, s>>>(ARGS_DQ);
     if (partial) {
-      attn_bwd_dkdv_kernel<true, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<DH, true, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     } else {
-      attn_bwd_dkdv_kernel<true, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<DH, true, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     }
   } else {
-    attn_bwd_dq_kernel<false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
+    attn_bwd_dq_kernel<DH, false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
     if (partial) {
-      attn_bwd_dkdv_kernel<false, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<DH, false, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     } else {
-      attn_bwd_dkdv_kernel<false, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      attn_bwd_dkdv_kernel<DH, false, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
     }
   }
 #undef ARGS_DQ
 #undef ARGS_KV
   if (partial) {
     const long long n_out = d.rows() * d.Hk * (DH / 4);
-    group_sum_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(pk, pv, (bf16_t *)d_k, (bf16_t *)d_v, n_out, d.R);
+    group_sum_kernel<DH><<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(pk, pv, (bf16_t *)d_k, (bf16_t *)d_v, n_out, d.R);
   }
   return hipGetLastError();
+}
+
+hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
+                              const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
+                              hipStream_t s) {
+  return d.dh == 64 ? attention_bwd_run<64>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s)
+                    : attention_bwd_run<128>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s);
 }
 
 }  // namespace cca

@@ -88,6 +88,9 @@ SMALL = [
     # bf16 shapes off the MFMA paths (generic kernels with bf16 storage)
     dict(B=2, T=200, E=512, Hq=4, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=1, T=150, E=1024, Hq=4, Hk=2, dh=128, k_seq=3, k_ch=4, dtype="bf16", paper_flags=True),
+    # d_h = 64 on the matrix-core attention backward: several key blocks, ragged tail, R = 4; R = 1
+    dict(B=2, T=700, E=512, Hq=8, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=300, E=256, Hq=3, Hk=3, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
 ]
 
 
@@ -102,7 +105,7 @@ def test_backward_small_shapes(i):
     say(compare(got, ref, w["dtype"]))
 
 
-@pytest.mark.parametrize("i", [3, 4, 7])
+@pytest.mark.parametrize("i", [3, 4, 7, 9])
 def test_backward_small_shapes_literal_weights(i):
     """0.02-scaled weights: the softmax is nearly flat, the regime in which <d_o, o> taken from the bf16-rounded o
     alone would put a 2 % error on d_q / d_k and, through them, on the convolution filter gradients."""
@@ -138,7 +141,7 @@ FLAG_CASES = {
 
 
 @pytest.mark.parametrize("name", sorted(FLAG_CASES))
-@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128)])
+@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128), ("bf16", 64)])
 def test_backward_each_flag(name, dtype, dh):
     flags, okw, skip = FLAG_CASES[name]
     w = dict(B=2, T=200, E=4 * dh * 2, Hq=4, Hk=2, dh=dh, k_seq=2, k_ch=2, dtype=dtype, paper_flags=True)
