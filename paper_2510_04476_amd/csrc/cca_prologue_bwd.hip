@@ -1,5 +1,5 @@
 // Backward of the fused latent-space prologue for gfx950, bf16 storage,
-// d_h = 128 (adjoint of the convolution, qk-mean and value-shift equations
+// d_h = 128 or 64 (adjoint of the convolution, qk-mean and value-shift equations
 // and of the first two lines of the final equation block of Sec. 2.2; the
 // paper states these steps forward only).
 //
@@ -42,8 +42,7 @@ hipError_t prologue_fused_bwd_dlat(const Dims &d, const void *d3, const void *d_
 
 namespace {
 
-constexpr int DH = 128;
-constexpr int ROW = DH * 2 + 16;  // padded LDS row of one token
+// ROW below = DH * 2 + 16: padded LDS row of one token, bytes
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   bf16x2 v = {(__bf16)lo, (__bf16)hi};
@@ -59,9 +58,10 @@ struct PointArgs {
 };
 
 // ---------------------------------------------------------------------------
-// 1. pointwise: 16 lanes per (token, head); lane j holds channels 4j..4j+3 and 64+4j..64+4j+3, so the
-//    rotate-half partner sits in the same lane and the row dot product is a 16-lane butterfly.
+// 1. pointwise: d_h / 8 lanes per (token, head); lane j holds channels 4j..4j+3 and d_h/2 + 4j .. + 3, so the
+//    rotate-half partner sits in the same lane and the row dot product is a butterfly over those lanes.
 // ---------------------------------------------------------------------------
+template <int DH>
 __global__ __launch_bounds__(256) void pro_bwd_point_kernel(PointArgs a, const bf16_t *__restrict__ q,
                                                            const bf16_t *__restrict__ k,
                                                            const float *__restrict__ rnorm,
@@ -71,8 +71,9 @@ __global__ __launch_bounds__(256) void pro_bwd_point_kernel(PointArgs a, const b
                                                            const float2 *__restrict__ ropeB, bf16_t *__restrict__ d3,
                                                            float *__restrict__ rowdot) {
   const int NH = a.Hq + a.Hk;
-  const long long item = (long long)blockIdx.x * 16 + (threadIdx.x >> 4);  // row * NH + head
-  const int j = threadIdx.x & 15;
+  constexpr int LPI = DH / 8, HALF = DH / 2;  // lanes per item
+  const long long item = (long long)blockIdx.x * (256 / LPI) + threadIdx.x / LPI;  // row * NH + head
+  const int j = threadIdx.x % LPI;
   const bool live = item < a.rows * NH;
   const long long it = live ? item : 0;
   const long long row = it / NH;
@@ -82,15 +83,15 @@ __global__ __launch_bounds__(256) void pro_bwd_point_kernel(PointArgs a, const b
   const int g = head - a.Hq;
   const bf16_t *y5 = is_q ? q + (row * a.Hq + head) * DH : k + (row * a.Hk + g) * DH;
   const bf16_t *dy5 = is_q ? dq + (row * a.Hq + head) * DH : dk + (row * a.Hk + g) * DH;
-  const u32x2 ya = *reinterpret_cast<const u32x2 *>(y5 + 4 * j), yb = *reinterpret_cast<const u32x2 *>(y5 + 64 + 4 * j);
-  const u32x2 da = *reinterpret_cast<const u32x2 *>(dy5 + 4 * j), db = *reinterpret_cast<const u32x2 *>(dy5 + 64 + 4 * j);
+  const u32x2 ya = *reinterpret_cast<const u32x2 *>(y5 + 4 * j), yb = *reinterpret_cast<const u32x2 *>(y5 + HALF + 4 * j);
+  const u32x2 da = *reinterpret_cast<const u32x2 *>(dy5 + 4 * j), db = *reinterpret_cast<const u32x2 *>(dy5 + HALF + 4 * j);
   float y[8] = {bf_lo(ya.x), bf_hi(ya.x), bf_lo(ya.y), bf_hi(ya.y), bf_lo(yb.x), bf_hi(yb.x), bf_lo(yb.y), bf_hi(yb.y)};
   float dy[8] = {bf_lo(da.x), bf_hi(da.x), bf_lo(da.y), bf_hi(da.y), bf_lo(db.x), bf_hi(db.x), bf_lo(db.y), bf_hi(db.y)};
   float dot = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) dot = fmaf(y[e], dy[e], dot);
 #pragma unroll
-  for (int off = 8; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
+  for (int off = LPI / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off);
   float mul = 1.f, c = 0.f;
   if (a.flags & CCA_QK_NORM) {
     mul = rnorm[row * NH + head];
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(256) void pro_bwd_point_kernel(PointArgs a, const b
     hi.x = pack2(r[4] * mul, r[5] * mul);
     hi.y = pack2(r[6] * mul, r[7] * mul);
     *reinterpret_cast<u32x2 *>(dst + 4 * j) = lo;
-    *reinterpret_cast<u32x2 *>(dst + 64 + 4 * j) = hi;
+    *reinterpret_cast<u32x2 *>(dst + HALF + 4 * j) = hi;
   }
 }
 
@@ -148,12 +149,13 @@ __global__ __launch_bounds__(256) void column_sum_f32_kernel(const float *__rest
 
 // ---------------------------------------------------------------------------
 // 3. folded-filter gradient, partial sums per chunk of tokens.
-//    Workgroup = (head, chunk of `chunk` tokens of one sequence), 8 wavefronts; wavefront w owns output-channel
-//    tiles 2*(w&1), 2*(w&1)+1 and input-channel tile w>>1, for all D taps.
+//    Workgroup = (head, chunk of `chunk` tokens of one sequence), d_h / 16 wavefronts; wavefront w owns OX = d_h / 64
+//    output-channel tiles starting at OX*(w&1) and input-channel tile w>>1, for all D taps.
 // ---------------------------------------------------------------------------
 // MFMA operand fragment of the TRANSPOSE of a row-major LDS tile: lane (c = lane & 31, half) receives
 // tile[r0 + 4*half + {0..3}][c0 + c] and tile[r0 + 8 + 4*half + {0..3}][c0 + c].  `base` already holds the
 // per-lane part  (4*half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2.
+template <int ROW>
 __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int c0) {
   const unsigned char *p = base + r0 * ROW + c0 * 2;
   const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)p);
@@ -161,12 +163,13 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-constexpr int DW_NT = 512, DW_BT = 64;  // threads, tokens per LDS tile
+constexpr int DW_BT = 64;  // tokens per LDS tile
 
-template <int D>
-__global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__restrict__ d3, const bf16_t *__restrict__ lat,
+template <int DH, int D>
+__global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__restrict__ d3, const bf16_t *__restrict__ lat,
                                                            float *__restrict__ part, int T, int Hq, int Hk, int e_q,
                                                            int e_kv, int n_lat, int chunk, int chunks_per_seq) {
+  constexpr int DW_NT = DH * 4, ROW = DH * 2 + 16, CPW = DH / 8, OX = DH / 64;  // threads, LDS row, chunks per row
   constexpr int UROWS = DW_BT + D - 1;
   constexpr int DY_TILE = DW_BT * ROW, U_TILE = UROWS * ROW;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (DY_TILE + U_TILE)];
@@ -183,13 +186,13 @@ __global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__rest
   const bf16_t *const d3b = d3 + (long long)b * T * ld3 + ch0;
   const bf16_t *const ub = lat + (long long)b * T * n_lat + ch0;
 
-  constexpr int DY_CHUNKS = DW_BT * 16, U_CHUNKS = UROWS * 16;  // 16-byte chunks per tile
+  constexpr int DY_CHUNKS = DW_BT * CPW, U_CHUNKS = UROWS * CPW;  // 16-byte chunks per tile
   constexpr int DY_PER = DY_CHUNKS / DW_NT, U_PER = (U_CHUNKS + DW_NT - 1) / DW_NT;
   u32x4 rdy[DY_PER], ru[U_PER];
   auto load_tile = [&](int t0) {
 #pragma unroll
     for (int i = 0; i < DY_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
       const int t = t0 + r;
       u32x4 val = {0, 0, 0, 0};
       if (t < t_end) val = *reinterpret_cast<const u32x4 *>(d3b + (long long)t * ld3 + c * 8);
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__rest
     }
 #pragma unroll
     for (int i = 0; i < U_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
       const int t = t0 - (D - 1) + r;  // row r of the tile holds token t0 - (D-1) + r
       u32x4 val = {0, 0, 0, 0};
       if (id < U_CHUNKS && t >= 0 && t < t_end) val = *reinterpret_cast<const u32x4 *>(ub + (long long)t * n_lat + c * 8);
@@ -207,22 +210,22 @@ __global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__rest
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < DY_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
       *reinterpret_cast<u32x4 *>(sDy + buf * DY_TILE + r * ROW + c * 16) = rdy[i];
     }
 #pragma unroll
     for (int i = 0; i < U_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id >> 4, c = id & 15;
+      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
       if (id < U_CHUNKS) *reinterpret_cast<u32x4 *>(sU + buf * U_TILE + r * ROW + c * 16) = ru[i];
     }
   };
 
   const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
-  const int o_tile0 = 2 * (wave & 1), i_tile = wave >> 1;
+  const int o_tile0 = OX * (wave & 1), i_tile = wave >> 1;
 
-  f32x16 acc[2][D];
+  f32x16 acc[OX][D];
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < OX; ++x)
 #pragma unroll
     for (int d = 0; d < D; ++d)
 #pragma unroll
@@ -240,13 +243,13 @@ __global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__rest
     const unsigned char *dyp = sDy + buf * DY_TILE + tr_off, *up = sU + buf * U_TILE + tr_off;
 #pragma unroll
     for (int kk = 0; kk < DW_BT / 16; ++kk) {
-      bf16x8 fo[2], fu[D];
+      bf16x8 fo[OX], fu[D];
 #pragma unroll
-      for (int x = 0; x < 2; ++x) fo[x] = tr_frag(dyp, kk * 16, (o_tile0 + x) * 32);
+      for (int x = 0; x < OX; ++x) fo[x] = tr_frag<ROW>(dyp, kk * 16, (o_tile0 + x) * 32);
 #pragma unroll
-      for (int d = 0; d < D; ++d) fu[d] = tr_frag(up, kk * 16 + d, i_tile * 32);  // token t - (D-1-d)
+      for (int d = 0; d < D; ++d) fu[d] = tr_frag<ROW>(up, kk * 16 + d, i_tile * 32);  // token t - (D-1-d)
 #pragma unroll
-      for (int x = 0; x < 2; ++x)
+      for (int x = 0; x < OX; ++x)
 #pragma unroll
         for (int d = 0; d < D; ++d) acc[x][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[x], fu[d], acc[x][d], 0, 0, 0);
     }
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__rest
   // acc[x][d][r]: o = (o_tile0 + x)*32 + 8*(r/4) + 4*half + r%4,  i = i_tile*32 + l32
   float *out = part + (long long)blockIdx.x * DH * D * DH;  // [o][d][i] of (cid, head); blockIdx.x = cid*NH + head
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < OX; ++x)
 #pragma unroll
     for (int d = 0; d < D; ++d)
 #pragma unroll
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(DW_NT) void pro_bwd_dwc_kernel(const bf16_t *__rest
 __global__ __launch_bounds__(256) void pro_bwd_unfold_w1_kernel(const float *__restrict__ part, int n_chunks, int NH,
                                                                int D, int ks, int kc, int use_w0,
                                                                const bf16_t *__restrict__ w0, float *__restrict__ dwc,
-                                                               bf16_t *__restrict__ dw1) {
+                                                               bf16_t *__restrict__ dw1, int DH) {
   const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (h*DH + o)*DH + i
   if (id >= (long long)NH * DH * DH) return;
   const int i = (int)(id % DH), o = (int)((id / DH) % DH), h = (int)(id / (DH * DH));
@@ -290,14 +293,15 @@ __global__ __launch_bounds__(256) void pro_bwd_unfold_w1_kernel(const float *__r
   }
 }
 
-// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j].  One workgroup per head, 8 groups of 16 output
-// channels x 128 input channels; the 8 partial sums are added through LDS in a fixed order.
-__global__ __launch_bounds__(1024) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
+// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j].  One workgroup per head, 8 groups of d_h / 8 output
+// channels x d_h input channels; the 8 partial sums are added through LDS in a fixed order.
+template <int DH>
+__global__ __launch_bounds__(DH * 8) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
                                                                 const bf16_t *__restrict__ w1, bf16_t *__restrict__ dw0) {
   __shared__ float red[8][4][DH];
-  const int h = blockIdx.x, i = threadIdx.x & (DH - 1), og = threadIdx.x >> 7;
+  const int h = blockIdx.x, i = threadIdx.x % DH, og = threadIdx.x / DH;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int o = og * 16; o < og * 16 + 16; ++o) {
+  for (int o = og * (DH / 8); o < (og + 1) * (DH / 8); ++o) {
     const float *p = dwc + (((long long)h * DH + o) * D) * DH + i;
     const bf16_t *wp = w1 + (((long long)h * DH + o) * DH + i) * kc;
     for (int j = 0; j < kc; ++j) {
@@ -332,7 +336,7 @@ BwdScratch bwd_layout(const Dims &d) {
   BwdScratch L;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += (bytes + 255) / 256 * 256; return o; };
-  const int D = taps(d), NH = d.Hq + d.Hk, chunk = dwc_chunk(d);
+  const int D = taps(d), NH = d.Hq + d.Hk, chunk = dwc_chunk(d), DH = d.dh;
   const size_t n_chunks = (size_t)d.B * ((d.T + chunk - 1) / chunk);
   L.fused = take(prologue_fused_scratch_bytes(d));
   L.d3 = take((size_t)d.rows() * (d.e_q + d.e_kv) * 2);
@@ -345,14 +349,14 @@ BwdScratch bwd_layout(const Dims &d) {
 
 }  // namespace
 
-// the adjoint kernels of this file are written for d_h = 128 only (the forward prologue also takes 64)
-bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d) && d.dh == 128; }
+bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d); }
 
 size_t prologue_bwd_fused_scratch_bytes(const Dims &d) {
   return prologue_bwd_fused_supported(d) ? bwd_layout(d).total : 0;
 }
 
-hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
+template <int DH>
+static hipError_t prologue_bwd_run(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
                                    const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
                                    const cca_grads *gr, void *scratch, hipStream_t s) {
   const BwdScratch L = bwd_layout(d);
@@ -370,7 +374,8 @@ hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const vo
   const bool want_temp = (d.flags & CCA_KEY_TEMP) && gr && gr->temp;
   PointArgs pa{d.T, d.Hq, d.Hk, d.e_q, d.e_kv, d.rows(), d.flags};
   const long long items = d.rows() * NH;
-  pro_bwd_point_kernel<<<(unsigned)((items + 15) / 16), 256, 0, s>>>(pa, (const bf16_t *)q, (const bf16_t *)k, rnorm,
+  constexpr int IPB = 256 / (DH / 8);  // items per workgroup of the pointwise kernel
+  pro_bwd_point_kernel<DH><<<(unsigned)((items + IPB - 1) / IPB), 256, 0, s>>>(pa, (const bf16_t *)q, (const bf16_t *)k, rnorm,
                                                                     w.temp, (const bf16_t *)d_q, (const bf16_t *)d_k,
                                                                     ropeA, ropeB, d3, want_temp ? rowdot : nullptr);
   if (want_temp) column_sum_f32_kernel<<<d.Hk, 256, 0, s>>>(rowdot, d.rows(), d.Hk, gr->temp);
@@ -385,7 +390,7 @@ hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const vo
   if (!want_w1 && !want_w0) return hipSuccess;
   const int chunk = dwc_chunk(d), cps = (d.T + chunk - 1) / chunk, n_chunks = d.B * cps;
 #define DWC(DD)                                                                                                     \
-  pro_bwd_dwc_kernel<DD><<<n_chunks * NH, DW_NT, 0, s>>>(d3, (const bf16_t *)lat, part, d.T, d.Hq, d.Hk, d.e_q, d.e_kv, \
+  pro_bwd_dwc_kernel<DH, DD><<<n_chunks * NH, DH * 4, 0, s>>>(d3, (const bf16_t *)lat, part, d.T, d.Hq, d.Hk, d.e_q, d.e_kv, \
                                                          d.n_lat, chunk, cps)
   switch (D) {
     case 1: DWC(1); break;
@@ -397,11 +402,18 @@ hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const vo
   pro_bwd_unfold_w1_kernel<<<(NH * DH * DH + 255) / 256, 256, 0, s>>>(part, n_chunks, NH, D, ks, d.k_ch,
                                                                      (d.flags & CCA_CONV_SEQ) ? 1 : 0,
                                                                      (const bf16_t *)w.w_conv_seq, dwc,
-                                                                     want_w1 ? (bf16_t *)gr->w_conv_ch : nullptr);
+                                                                     want_w1 ? (bf16_t *)gr->w_conv_ch : nullptr, DH);
   if (want_w0)
-    pro_bwd_unfold_w0_kernel<<<NH, 1024, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
+    pro_bwd_unfold_w0_kernel<DH><<<NH, DH * 8, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
                                                (bf16_t *)gr->w_conv_seq);
   return hipGetLastError();
+}
+
+hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
+                                   const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
+                                   const cca_grads *gr, void *scratch, hipStream_t s) {
+  return d.dh == 64 ? prologue_bwd_run<64>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s)
+                    : prologue_bwd_run<128>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s);
 }
 
 }  // namespace cca
