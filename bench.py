@@ -32,8 +32,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((147.04 + 32.06) * 2 ** 20)}
 
 
-# Layouts of the grid, all at E = 2048 and d_h = 128 through the same entry points.  "gqa8" reads the paper's GQA-8 as
-# 8x fewer KV heads than MHA (16 query heads, 2 KV heads: the KV-cache size of the C2 = 8 layouts).
+# Layouts of the grid, all at E = 2048 through the same entry points, head counts for d_h = 128 (at d_h = 64 there
+# are twice as many heads, so the latent widths stay the same).  "gqa8" reads the paper's GQA-8 as 8x fewer KV heads
+# than MHA (16 query heads, 2 KV heads: the KV-cache size of the C2 = 8 layouts).
 GRID_LAYOUTS = {
     "mha": dict(Hq=16, Hk=16, paper_flags=False),
     "gqa8": dict(Hq=16, Hk=2, paper_flags=False),
@@ -42,7 +43,7 @@ GRID_LAYOUTS = {
 }
 
 
-def run_grid(P, torch) -> int:
+def run_grid(P, torch, dh=128) -> int:
     from paper_2510_04476_amd import binding as b
     dev = "cuda"
     rows = []
@@ -50,7 +51,8 @@ def run_grid(P, torch) -> int:
         for S in (512, 1024, 2048, 4096, 8192, 16384):
             base = {}
             for name, lay in GRID_LAYOUTS.items():
-                w = dict(B=1, T=S, E=2048, dh=128, k_seq=2, k_ch=2, dtype="bf16", **lay)
+                w = dict(B=1, T=S, E=2048, dh=dh, k_seq=2, k_ch=2, dtype="bf16", paper_flags=lay["paper_flags"],
+                         Hq=lay["Hq"] * 128 // dh, Hk=lay["Hk"] * 128 // dh)
                 cfg = P.config_from_workload(w)
                 if not causal:
                     cfg.flags &= ~b.CCA_CAUSAL
@@ -86,7 +88,7 @@ def run_grid(P, torch) -> int:
                 f_ms, fb_ms = timeit(fwd, n), timeit(fwd_bwd, max(3, n // 3))
                 base.setdefault("f", f_ms if name == "mha" else None)
                 base.setdefault("fb", fb_ms if name == "mha" else None)
-                r = {"layout": name, "S": S, "causal": causal, "fwd_ms": round(f_ms, 4), "fwd_bwd_ms": round(fb_ms, 4),
+                r = {"layout": name, "d_h": dh, "S": S, "causal": causal, "fwd_ms": round(f_ms, 4), "fwd_bwd_ms": round(fb_ms, 4),
                      "bwd_ms": round(fb_ms - f_ms, 4), "fwd_speedup_vs_mha": round(base["f"] / f_ms, 3),
                      "bwd_speedup_vs_mha": round((base["fb"] - base["f"]) / (fb_ms - f_ms), 3)}
                 rows.append(r)
@@ -112,9 +114,11 @@ def main() -> int:
     ap.add_argument("--only", choices=["forward", "attention", "prologue", "down_project", "up_project", "backward",
                                        "attention_backward", "prologue_backward", "decode"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
+    ap.add_argument("--grid-dh", type=int, default=128, choices=[64, 128],
+                    help="head width of the --grid run (the matrix-core kernels cover 64 and 128)")
     ap.add_argument("--grid", action="store_true",
                     help="latency grid on the axes of the paper's kernel figures (App. D.1: E = 2048, bf16, S = 512..16384, "
-                         "causal and non-causal, forward and forward+backward) for four layouts at d_h = 128, instead "
+                         "causal and non-causal, forward and forward+backward) for four layouts at d_h = --grid-dh, instead "
                          "of the one-line benchmark; prints one JSON line per point and a table")
     ap.add_argument("--cpu-prefix", type=int, default=16384, help="tokens of the causal prefix the oracle is timed on")
     args = ap.parse_args()
@@ -134,7 +138,7 @@ def main() -> int:
         return 3
     P.load_library()  # raises if the HIP library is not built: there is no fallback
     if args.grid:
-        return run_grid(P, torch)
+        return run_grid(P, torch, args.grid_dh)
     w = WORKLOADS[args.workload]
     cfg = P.config_from_workload(w)
     inp = make_inputs(w, seed=0)
