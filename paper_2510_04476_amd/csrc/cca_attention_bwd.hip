@@ -45,11 +45,45 @@ typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
 namespace {
 
 // Shapes that follow from the head width d_h (128 or 64): KK fragments of 16 channels, DT tiles of 32 channels,
-// KCH 16-byte chunks per row, ROW = padded LDS row of one token in bytes (conflict-free 16-byte reads down a
-// column of rows).
+// KCH 16-byte chunks per row, ROW = LDS row of one token in bytes (64 bytes of padding: see below).
 #define CCA_BWD_GEOMETRY(DH) \
-  constexpr int KK = (DH) / 16, DT = (DH) / 32, KCH = (DH) / 8, ROW = (DH) * 2 + 16; \
+  constexpr int KK = (DH) / 16, DT = (DH) / 32, KCH = (DH) / 8, ROW = (DH) * 2 + 64; \
   (void)KK; (void)DT; (void)KCH; (void)ROW
+
+// LDS tiles of this file are read two ways: 16-byte reads down a column of 16 rows (first MFMA operand of the score
+// products) and transposing reads that touch 4 consecutive rows x 64 consecutive bytes (operands of the products
+// that contract over tokens).  Padding alone cannot serve both: a stride that spreads 16 rows over the banks (+16
+// bytes) makes neighbouring rows overlap within 64 bytes, and the transposing reads then ran 4-way conflicted (half
+// of all LDS cycles of these kernels).  So: the row stride is a multiple of 64 bytes that is odd in units of 64
+// (4 consecutive rows land in 4 different 64-byte bank groups: transposing reads conflict-free), and chunk c of
+// row r is stored at chunk position c ^ ((r >> 2) & 3): among 16 rows, those that share a bank group (r & 3 equal)
+// differ in r >> 2 and so in the low two bits of the position (column reads conflict-free).  The XOR touches only
+// bits 4-5 of the address, so every read is a per-lane base plus a compile-time offset.
+__device__ __forceinline__ int swz(int r) { return (r >> 2) & 3; }
+
+// Per-lane byte offsets of the two read patterns.  Column read of this lane's chunk 2*kk + half of row 32*blk + l32:
+//   tile + blk*32*ROW + col[kk & 1] + 64*(kk >> 1).
+// Transposing read of rows r0 + {4*half + q, 8 + 4*half + q} (q = (lane & 15) >> 2; r0 a multiple of 16), channel
+// tile dt (32 channels = 64 bytes), this lane's 8 bytes:  tile + r0*ROW + tr[x] + 64*dt  for x = lo, hi.
+struct LaneSwz {
+  uint32_t col[2], tr[2];
+};
+template <int DH>
+__device__ __forceinline__ LaneSwz lane_swz(int lane) {
+  constexpr int ROW = DH * 2 + 64;
+  const int l32 = lane & 31, half = lane >> 5;
+  LaneSwz L;
+#pragma unroll
+  for (int x = 0; x < 2; ++x) L.col[x] = (uint32_t)l32 * ROW + (((2 * x + half) ^ swz(l32)) << 4);
+  const int l2 = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1), sub8 = (lane & 1) * 8;
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    const int rr = 8 * x + 4 * half + ((lane & 15) >> 2);
+    L.tr[x] = (uint32_t)rr * ROW + ((l2 ^ swz(rr)) << 4) + sub8;
+  }
+  return L;
+}
+
 constexpr float LOG2E = 1.44269504088896340736f;
 constexpr float LN2 = 0.69314718055994530942f;  // the scaled q carries scale * log2(e): scale * q = ln 2 * q_scaled
 
@@ -60,14 +94,13 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// MFMA first-operand fragment of the TRANSPOSE of a row-major LDS tile: lane (c = l32, half) receives
-// tile[r0 + 4*half + {0..3}][c0 + c] and tile[r0 + 8 + 4*half + {0..3}][c0 + c].  `base` already holds the
-// per-lane part  (4*half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2.
+// MFMA first-operand fragment of the TRANSPOSE of a row-major LDS tile (layout above): lane (c = l32, half) receives
+// tile[r0 + 4*half + {0..3}][32*dt + c] and tile[r0 + 8 + 4*half + {0..3}][32*dt + c].
 template <int ROW>
-__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int c0) {
-  const unsigned char *a = base + r0 * ROW + c0 * 2;
-  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)a);
-  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + 8 * ROW));
+__device__ __forceinline__ bf16x8 tr_frag(const unsigned char *tile, const LaneSwz &L, int r0, int dt) {
+  const unsigned char *a = tile + r0 * ROW + dt * 64;
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + L.tr[0]));
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + L.tr[1]));
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
@@ -133,9 +166,9 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
 
   const int s_r0 = tid / KCH, s_ch = tid % KCH;
-  const uint32_t s_off = (uint32_t)s_r0 * ROW + s_ch * 16;
-  const uint32_t rd_off = (uint32_t)l32 * ROW + half * 16;
-  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+  const uint32_t s_off = (uint32_t)s_r0 * ROW + ((s_ch ^ swz(s_r0)) << 4);  // rows of later passes: + multiples of 16
+  static_assert(ROWS_PER_PASS % 16 == 0, "the swizzle of a row depends on its index modulo 16");
+  const LaneSwz LS = lane_swz<DH>(lane);
 
   u32x4 rk[PER_THREAD], rv[PER_THREAD];
   auto load_tile = [&](int kv0) {
@@ -209,10 +242,9 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-          const bf16x8 kf = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const u32x4 *>(kp + rd_off + ks * 32 * ROW + kk * 32));
-          const bf16x8 vf = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const u32x4 *>(vp + rd_off + ks * 32 * ROW + kk * 32));
+          const uint32_t co = LS.col[kk & 1] + ks * 32 * ROW + 64 * (kk >> 1);
+          const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + co));
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vp + co));
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
         }
@@ -238,7 +270,7 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(kp + tr_off, ks * 32 + jj * 16, dt * 32), dsf[jj],
+            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(kp, LS, ks * 32 + jj * 16, dt), dsf[jj],
                                                               acc[dt], 0, 0, 0);
       }
     }
@@ -308,10 +340,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const float c = scale * LOG2E;
   const int qrow_bytes = Hq * DH * 2;
 
-  const int s_r0 = tid / KCH, s_ch = tid % KCH;
-  const uint32_t s_off = (uint32_t)s_r0 * ROW + s_ch * 16;
-  const uint32_t rd_off = (uint32_t)l32 * ROW + half * 16;
-  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+  const LaneSwz LS = lane_swz<DH>(lane);
 
   // this wavefront's 32 keys: K and V rows as second MFMA operands, resident in registers
   bf16x8 kf[KK], vf[KK];
@@ -337,8 +366,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const int steps = nqt - qt_first;
 
   // Q (pre-scaled) and dO tiles travel global -> LDS directly: wave instruction i deposits 64 x 16 bytes at LDS
-  // chunks [i*64, i*64+64) of a tile laid out in padded rows of CPR chunks; lanes landing on padding fetch a duplicate.
-  constexpr int CPR = ROW / 16;                 // 17 (d_h = 128), 9 (d_h = 64)
+  // chunks [i*64, i*64+64) of the tile, so each lane fetches the chunk that the layout puts at its position (lanes
+  // landing on padding fetch a duplicate).
+  constexpr int CPR = ROW / 16;                 // chunk positions per padded row: 20 (d_h = 128), 12 (d_h = 64)
   constexpr int T_INSTR = BQT * CPR / 64;       // wave instructions per tile
   static_assert(BQT * CPR % 64 == 0, "tile must be a whole number of wave instructions");
   constexpr int PER_WAVE = (2 * T_INSTR + KV_NT / 64 - 1) / (KV_NT / 64);
@@ -356,7 +386,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         const bool isd = i >= T_INSTR;
         const int ii = isd ? i - T_INSTR : i;
         const int L = ii * 64 + lane;
-        const int row = L / CPR, ch = min(L % CPR, KCH - 1);
+        const int row = L / CPR, ch = min(L % CPR, KCH - 1) ^ swz(row);
         const int t = min(t0 + row, T - 1);  // clamped rows get probability 0 below
         const unsigned char *src = (isd ? Dg : Qg) + (long long)t * qrow_bytes + ch * 16;
         unsigned char *dst = (isd ? sD : sQ) + buf * TILE + ii * 1024;
@@ -398,7 +428,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
           for (int kk = 0; kk < KK; ++kk) {
             const bf16x8 qa = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const u32x4 *>(qp + rd_off + qs * 32 * ROW + kk * 32));
+                bf16x8, *reinterpret_cast<const u32x4 *>(qp + LS.col[kk & 1] + qs * 32 * ROW + 64 * (kk >> 1)));
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
           }
           // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4
@@ -426,7 +456,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
           for (int kk = 0; kk < KK; ++kk) {
             const bf16x8 da = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + rd_off + qs * 32 * ROW + kk * 32));
+                bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + LS.col[kk & 1] + qs * 32 * ROW + 64 * (kk >> 1)));
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);
           }
           u32x4 x[2];
@@ -446,9 +476,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) {
-            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(dp_ + tr_off, qs * 32 + jj * 16, dt * 32),
+            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(dp_, LS, qs * 32 + jj * 16, dt),
                                                                pf[jj], dv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(qp + tr_off, qs * 32 + jj * 16, dt * 32),
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(qp, LS, qs * 32 + jj * 16, dt),
                                                                dsf[jj], dk[dt], 0, 0, 0);
           }
       }

@@ -680,7 +680,7 @@ typedef uint32_t sk_u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t sk_u32x2 __attribute__((ext_vector_type(2)));
 typedef short sk_v4i16 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) sk_v4i16 sk_lds_v4i16;
-constexpr int SM_ROW = SK_COLS * 2 + 16;  // padded LDS row of the W tile, bytes
+constexpr int SM_ROW = SK_COLS * 2 + 64;  // LDS row of the W tile, bytes: padded so that the 4 rows a transposing read touches differ in bank group
 
 __global__ __launch_bounds__(256) void gemm_skinny_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
                                                               float *__restrict__ part, int M, int N, int K, int chunk) {

@@ -208,7 +208,8 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t *__res
 typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
 
-constexpr int TN_BN = 256, TN_ROW = 256 * 2 + 16;  // tile width (both operands), padded LDS row in bytes
+constexpr int TN_BN = 256, TN_ROW = 256 * 2 + 64;  // tile width (both operands); LDS row in bytes, padded by 64 so
+                                                   // that the 4 rows a transposing read touches fall in 4 different bank groups
 
 __device__ __forceinline__ bf16x8 tr_frag_tn(const unsigned char *base, int r0, int c0) {
   const unsigned char *p = base + r0 * TN_ROW + c0 * 2;

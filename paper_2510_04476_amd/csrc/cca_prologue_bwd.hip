@@ -169,7 +169,8 @@ template <int DH, int D>
 __global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__restrict__ d3, const bf16_t *__restrict__ lat,
                                                            float *__restrict__ part, int T, int Hq, int Hk, int e_q,
                                                            int e_kv, int n_lat, int chunk, int chunks_per_seq) {
-  constexpr int DW_NT = DH * 4, ROW = DH * 2 + 16, CPW = DH / 8, OX = DH / 64;  // threads, LDS row, chunks per row
+  constexpr int DW_NT = DH * 4, ROW = DH * 2 + 64, CPW = DH / 8, OX = DH / 64;  // threads, LDS row (the 64-byte pad keeps
+                                                                               // the transposing reads conflict-free), chunks per row
   constexpr int UROWS = DW_BT + D - 1;
   constexpr int DY_TILE = DW_BT * ROW, U_TILE = UROWS * ROW;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (DY_TILE + U_TILE)];
