@@ -161,3 +161,25 @@ def test_flop_counter_matches_cost_table():
     mha = P.CCAConfig(B=1, T=16384, d_model=2048, n_q_heads=16, n_kv_heads=16, head_dim=128, flags=0)
     fm = P.forward_flops(mha)
     assert fm["total"] == 8 * Bn * S * E * E + 4 * Bn * E * S * S
+
+
+def test_cost_model_against_the_papers_cost_table():
+    """Parameter count, KV-cache size and forward FLOPs of the four layouts of the latency grid against the paper's
+    cost table evaluated at E = 2048, S = 16384 (tests/golden/cost_table_e2048_s16384.txt; the Conv term is covered
+    by test_flop_counter_matches_cost_table)."""
+    import os
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "cost_table_e2048_s16384.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                name, params, kv, flops = line.split()
+                rows[name] = (int(params), int(kv), int(flops))
+    layouts = {"MHA": (16, 16), "GQA_G8": (16, 2), "CCA_C4": (4, 4), "CCGQA_C1_2_C2_8": (8, 2)}
+    assert set(rows) == set(layouts)
+    for name, (hq, hk) in layouts.items():
+        cfg = P.CCAConfig(B=1, T=16384, d_model=2048, n_q_heads=hq, n_kv_heads=hk, head_dim=128, flags=0)
+        params, kv, flops = rows[name]
+        assert cfg.d_model * cfg.n_lat + cfg.e_q * cfg.d_model == params, name   # w_down and w_out as the ABI takes them
+        assert 2 * cfg.B * cfg.T * cfg.e_kv == kv, name                          # k_cache + v_cache of cca_decode_state
+        f = P.forward_flops(cfg)
+        assert f["conv"] == 0 and f["proj"] + f["attn_dense"] == flops, name
