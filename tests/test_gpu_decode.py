@@ -140,6 +140,46 @@ def test_decode_bench_configuration_sampled():
     assert np.array_equal(got[0], got[2]) and np.array_equal(got[1], got[31]), "same sequence, different result"
 
 
+def test_decode_step_and_prefill_replay_in_a_hip_graph():
+    """The library allocates nothing, never synchronises and enqueues only kernels on the caller's stream, so a call
+    can be captured into a HIP graph: every replay, with eager calls in between, gives the eager result bit for bit."""
+    w = CASES[2]
+    inp = make_inputs(w, seed=72, conv_visible=True)
+    cfg = P.config_from_workload(w)
+    x, wt = P.weights_to_device(cfg, inp)
+    saved = P.CCASaved.allocate(cfg, x.device)
+    P.cca_forward(cfg, wt, x, saved=saved)
+    state = P.CCADecodeState.allocate(cfg, x.device)
+    pos = w["T"] - 1
+    state.load_prefill(saved, pos)
+    x_new = x[:, pos].contiguous()
+    ws = P.new_workspace(cfg, x.device)
+    out_e, out_g = torch.empty_like(x_new), torch.empty_like(x_new)
+    full_e, full_g = torch.empty_like(x), torch.empty_like(x)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):  # warm-up on the capture stream
+        P.cca_decode_step(cfg, wt, x_new, state, pos, out=out_g)
+        P.cca_forward(cfg, wt, x, out=full_g, workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        P.cca_decode_step(cfg, wt, x_new, state, pos, out=out_g)
+        P.cca_forward(cfg, wt, x, out=full_g, workspace=ws)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out_g.zero_()
+        full_g.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        P.cca_decode_step(cfg, wt, x_new, state, pos, out=out_e)
+        P.cca_forward(cfg, wt, x, out=full_e, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e) and torch.equal(full_g, full_e), f"replay {rep} differs from the eager call"
+    ref = oracle_forward(w, inp)
+    say(check_out(to_np(full_g), ref["out"], w["dtype"]))
+    say(check_out(to_np(out_g), ref["out"][:, pos], w["dtype"]))
+
+
 def test_decode_rejects_bad_arguments():
     w = CASES[2]
     cfg = P.config_from_workload(w)
