@@ -174,27 +174,49 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
 }
 
 // Up to two independent transposes in one launch (both projection weights of a forward pass): workgroups
-// [0, n1) serve the first matrix, the rest the second.
+// [0, n1) serve the first matrix, the rest the second.  64 x 64 tiles; with both sizes multiples of 8 a thread moves
+// 16 bytes per memory access (the tile is transposed element by element on its way into LDS).
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t *__restrict__ src1, bf16_t *__restrict__ dst1,
                                                             int rows1, int cols1, int n1,
                                                             const bf16_t *__restrict__ src2, bf16_t *__restrict__ dst2,
                                                             int rows2, int cols2) {
-  __shared__ bf16_t tile[64][66];
+  __shared__ __attribute__((aligned(16))) bf16_t tile[64][72];  // [source column][source row], rows of 144 bytes
   const bool second = (int)blockIdx.x >= n1;
   const bf16_t *src = second ? src2 : src1;
   bf16_t *dst = second ? dst2 : dst1;
   const int rows = second ? rows2 : rows1, cols = second ? cols2 : cols1;
   const int id = second ? blockIdx.x - n1 : blockIdx.x, tiles_c = (cols + 63) / 64;
   const int c0 = (id % tiles_c) * 64, r0 = (id / tiles_c) * 64;
+  if (rows % 8 == 0 && cols % 8 == 0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int ch = threadIdx.x + i * 256, r = ch >> 3, c = (ch & 7) * 8;  // chunk of 8 columns of source row r0 + r
+      u32x4 v = {0, 0, 0, 0};
+      if (r0 + r < rows && c0 + c < cols) v = *reinterpret_cast<const u32x4 *>(src + (long long)(r0 + r) * cols + c0 + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        tile[c + 2 * e][r] = (bf16_t)(v[e] & 0xffffu);
+        tile[c + 2 * e + 1][r] = (bf16_t)(v[e] >> 16);
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int ch = threadIdx.x + i * 256, c = ch >> 3, r = (ch & 7) * 8;  // 8 source rows of source column c0 + c
+      if (c0 + c < cols && r0 + r < rows)
+        *reinterpret_cast<u32x4 *>(dst + (long long)(c0 + c) * rows + r0 + r) = *reinterpret_cast<const u32x4 *>(&tile[c][r]);
+    }
+    return;
+  }
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int i = ty; i < 64; i += 4) {
     const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < rows && c < cols) ? src[(long long)r * cols + c] : (bf16_t)0;
+    tile[tx][i] = (r < rows && c < cols) ? src[(long long)r * cols + c] : (bf16_t)0;
   }
   __syncthreads();
   for (int i = ty; i < 64; i += 4) {
     const int c = c0 + i, r = r0 + tx;
-    if (c < cols && r < rows) dst[(long long)c * rows + r] = tile[tx][i];
+    if (c < cols && r < rows) dst[(long long)c * rows + r] = tile[i][tx];
   }
 }
 
