@@ -329,6 +329,10 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   constexpr int ROWS_PER_PASS = KV_NT / KCH;
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];  // Q0 Q1 dO0 dO1
   __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];                                      // [buf][lse2 | delta][row]
+  // this workgroup's V rows as MFMA operand fragments, [wavefront][kk][lane] x 16 bytes: each wavefront keeps its own
+  // (read back one fragment per dP product; holding them in registers next to the K fragments and the two
+  // accumulators leaves no room for fragments requested ahead of their use)
+  __shared__ __attribute__((aligned(16))) u32x4 sVf[KV_NT / 64][KK][64];
   unsigned char *const sQ = smem, *const sD = smem + 2 * TILE;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -343,7 +347,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const LaneSwz LS = lane_swz<DH>(lane);
 
   // this wavefront's 32 keys: K and V rows as second MFMA operands, resident in registers
-  bf16x8 kf[KK], vf[KK];
+  bf16x8 kf[KK];
   {
     const int s = min(kw0 + l32, T - 1);
     const bf16_t *pk = K + (((long long)b * T + s) * Hk + g) * DH + half * 8;
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pk + kk * 16));
-      vf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pv + kk * 16));
+      sVf[wave][kk][lane] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
     }
   }
   f32x16 dk[DT], dv[DT];  // dK^T, dV^T: lane = key, registers = channels
@@ -404,6 +408,107 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
+  // One block of 32 query rows of the tile in stage `buf` against this wavefront's 32 keys.  LDS fragments are
+  // requested PF MFMAs ahead of their use (the compiler on its own issues read, wait, MFMA one at a time, and the
+  // wavefronts then spend most of their cycles waiting for LDS), the first ones of a chain before the arithmetic
+  // that precedes it.
+  constexpr int PF = 3;
+  auto block = [&](const unsigned char *qp, const unsigned char *dp_, int buf, int t0, int qs, auto masked_t) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_t)::value;
+    auto col = [&](const unsigned char *tile, int kk) {
+      return *reinterpret_cast<const u32x4 *>(tile + LS.col[kk & 1] + qs * 32 * ROW + 64 * (kk >> 1));
+    };
+    bf16x8 pf[2], dsf[2];
+    u32x4 fr[PF], fd[PF], fv[PF];
+#pragma unroll
+    for (int i = 0; i < PF; ++i) fr[i] = col(qp, i);
+    {  // S[t, key] -> P, packed to bf16 at once
+      f32x16 s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 qa = __builtin_bit_cast(bf16x8, fr[kk % PF]);
+        if (kk + PF < KK) fr[kk % PF] = col(qp, kk + PF);
+        else {  // first fragments of the dP chain
+          fd[kk + PF - KK] = col(dp_, kk + PF - KK);
+          fv[kk + PF - KK] = sVf[wave][kk + PF - KK][lane];
+        }
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4.  Masked tiles: the
+      // row index relative to t0 + qs*32 + 4*half must lie in [lo, hi] (lo: causal, hi: end of the sequence; a key
+      // past the end has an empty range).
+      const int key = kw0 + l32, tb = t0 + qs * 32 + 4 * half;
+      const int lo = CAUSAL ? key - tb : -(1 << 20);
+      const unsigned span = key < T ? (unsigned)(T - 1 - tb - lo) : 0u;
+      const bool none = MASKED && (key >= T || T - 1 - tb < lo);
+      u32x4 w[2];
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
+        float p[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          p[e] = __builtin_amdgcn_exp2f(s[rg * 4 + e] - l4[e]);
+          if (MASKED) p[e] = (!none & ((unsigned)(rg * 8 + e - lo) <= span)) ? p[e] : 0.f;
+        }
+        w[rg >> 1][(rg & 1) * 2 + 0] = pack2(p[0], p[1]);
+        w[rg >> 1][(rg & 1) * 2 + 1] = pack2(p[2], p[3]);
+      }
+      pf[0] = __builtin_bit_cast(bf16x8, w[0]);
+      pf[1] = __builtin_bit_cast(bf16x8, w[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int NP = 4 * DT;  // products of the last phase: dV (jj, dt), then dK (jj, dt)
+    auto frag_of = [&](int i) {  // i -> (dO | Q, jj, dt)
+      const int which = i / (2 * DT), jj = (i / DT) & 1, dt = i % DT;
+      return tr_frag<ROW>(which ? qp : dp_, LS, qs * 32 + jj * 16, dt);
+    };
+    bf16x8 tv[PF];  // transposed fragments of the first products of the last phase, requested under the dP chain
+    {  // dP[t, key] -> dS = P (dP - Delta), P taken back from its bf16 form
+      f32x16 dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 da = __builtin_bit_cast(bf16x8, fd[kk % PF]), vb = __builtin_bit_cast(bf16x8, fv[kk % PF]);
+        if (kk + PF < KK) {
+          fd[kk % PF] = col(dp_, kk + PF);
+          fv[kk % PF] = sVf[wave][kk + PF][lane];
+        } else {
+          tv[kk + PF - KK] = frag_of(kk + PF - KK);
+        }
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, dp, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      u32x4 x[2];
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
+        const u32x4 w = __builtin_bit_cast(u32x4, pf[rg >> 1]);
+        const uint32_t p01 = w[(rg & 1) * 2 + 0], p23 = w[(rg & 1) * 2 + 1];
+        x[rg >> 1][(rg & 1) * 2 + 0] = pack2(bf_lo(p01) * (dp[rg * 4 + 0] - d4[0]), bf_hi(p01) * (dp[rg * 4 + 1] - d4[1]));
+        x[rg >> 1][(rg & 1) * 2 + 1] = pack2(bf_lo(p23) * (dp[rg * 4 + 2] - d4[2]), bf_hi(p23) * (dp[rg * 4 + 3] - d4[3]));
+      }
+      dsf[0] = __builtin_bit_cast(bf16x8, x[0]);
+      dsf[1] = __builtin_bit_cast(bf16x8, x[1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // dV^T += dO^T P (all of them first: they do not wait for dS), then dK^T += Q^T dS; product i of the 4*DT
+    // uses fragment i, requested PF products earlier
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const bf16x8 f = tv[i % PF];
+      if (i + PF < NP) tv[i % PF] = frag_of(i + PF);
+      const int which = i / (2 * DT), jj = (i / DT) & 1, dt = i % DT;
+      if (which == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[jj], dv[dt], 0, 0, 0);
+      else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[jj], dk[dt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   const bool wave_live = kw0 < T;
   if (steps > 0) {
     issue_tile(0, 0);
@@ -416,71 +521,14 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     if (step + 1 < steps) issue_tile(step + 1, buf ^ 1);  // that buffer was last read before the previous barrier
     if (wave_live && !(CAUSAL && t0 + BQT - 1 < kw0)) {
       const unsigned char *qp = sQ + buf * TILE, *dp_ = sD + buf * TILE;
+      // wave-uniform: tiles away from the diagonal and from the end of the sequence need no mask at all
       const bool need_mask = (CAUSAL && t0 < kw0 + 31) || (t0 + BQT > T) || (kw0 + 32 > T);
+      if (need_mask) {
 #pragma unroll
-      for (int qs = 0; qs < 2; ++qs) {  // 32 query rows at a time
-        const int key = kw0 + l32;
-        bf16x8 pf[2], dsf[2];
-        {  // S[t, key] -> P, packed to bf16 at once
-          f32x16 s;
+        for (int qs = 0; qs < 2; ++qs) block(qp, dp_, buf, t0, qs, std::true_type{});
+      } else {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-          for (int kk = 0; kk < KK; ++kk) {
-            const bf16x8 qa = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const u32x4 *>(qp + LS.col[kk & 1] + qs * 32 * ROW + 64 * (kk >> 1)));
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
-          }
-          // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4
-          u32x4 w[2];
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg) {
-            const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
-            float p[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const int t = t0 + qs * 32 + rg * 8 + half * 4 + e;
-              p[e] = __builtin_amdgcn_exp2f(s[rg * 4 + e] - l4[e]);
-              if (need_mask && ((CAUSAL && key > t) || t >= T || key >= T)) p[e] = 0.f;
-            }
-            w[rg >> 1][(rg & 1) * 2 + 0] = pack2(p[0], p[1]);
-            w[rg >> 1][(rg & 1) * 2 + 1] = pack2(p[2], p[3]);
-          }
-          pf[0] = __builtin_bit_cast(bf16x8, w[0]);
-          pf[1] = __builtin_bit_cast(bf16x8, w[1]);
-        }
-        {  // dP[t, key] -> dS = P (dP - Delta), P taken back from its bf16 form
-          f32x16 dp;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) dp[r] = 0.f;
-#pragma unroll
-          for (int kk = 0; kk < KK; ++kk) {
-            const bf16x8 da = __builtin_bit_cast(
-                bf16x8, *reinterpret_cast<const u32x4 *>(dp_ + LS.col[kk & 1] + qs * 32 * ROW + 64 * (kk >> 1)));
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vf[kk], dp, 0, 0, 0);
-          }
-          u32x4 x[2];
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg) {
-            const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
-            const u32x4 w = __builtin_bit_cast(u32x4, pf[rg >> 1]);
-            const uint32_t p01 = w[(rg & 1) * 2 + 0], p23 = w[(rg & 1) * 2 + 1];
-            x[rg >> 1][(rg & 1) * 2 + 0] = pack2(bf_lo(p01) * (dp[rg * 4 + 0] - d4[0]), bf_hi(p01) * (dp[rg * 4 + 1] - d4[1]));
-            x[rg >> 1][(rg & 1) * 2 + 1] = pack2(bf_lo(p23) * (dp[rg * 4 + 2] - d4[2]), bf_hi(p23) * (dp[rg * 4 + 3] - d4[3]));
-          }
-          dsf[0] = __builtin_bit_cast(bf16x8, x[0]);
-          dsf[1] = __builtin_bit_cast(bf16x8, x[1]);
-        }
-        // dV^T += dO^T P,  dK^T += Q^T dS
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(dp_, LS, qs * 32 + jj * 16, dt),
-                                                               pf[jj], dv[dt], 0, 0, 0);
-            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(qp, LS, qs * 32 + jj * 16, dt),
-                                                               dsf[jj], dk[dt], 0, 0, 0);
-          }
+        for (int qs = 0; qs < 2; ++qs) block(qp, dp_, buf, t0, qs, std::false_type{});
       }
     }
     if (step + 1 < steps) land_tile(buf ^ 1);
