@@ -222,6 +222,64 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
 
+  // One block of 32 keys of the tile at kp / vp against this wavefront's 32 query rows.  LDS fragments are requested
+  // PF products ahead of their use, the first transposed ones before the arithmetic that precedes their chain (left
+  // to itself the compiler issues read, wait, MFMA one at a time).
+  constexpr int PF = 2, PT = 3;
+  auto block = [&](const unsigned char *kp, const unsigned char *vp, int kv0, int ks, auto masked_t) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_t)::value;
+    auto col = [&](const unsigned char *tile, int kk) {
+      return *reinterpret_cast<const u32x4 *>(tile + LS.col[kk & 1] + ks * 32 * ROW + 64 * (kk >> 1));
+    };
+    auto frag_of = [&](int i) { return tr_frag<ROW>(kp, LS, ks * 32 + (i / DT) * 16, i % DT); };  // i -> (jj, dt)
+    constexpr int NP = 2 * DT;
+    static_assert(PT <= NP && PF <= KK, "prefetch depth");
+    u32x4 fk[PF], fv[PF];
+    bf16x8 tk[PT];
+#pragma unroll
+    for (int i = 0; i < PF; ++i) fk[i] = col(kp, i), fv[i] = col(vp, i);
+    f32x16 s, dp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 kf = __builtin_bit_cast(bf16x8, fk[kk % PF]), vf = __builtin_bit_cast(bf16x8, fv[kk % PF]);
+      if (kk + PF < KK) fk[kk % PF] = col(kp, kk + PF), fv[kk % PF] = col(vp, kk + PF);
+      else if (kk + PF - KK < PT) tk[kk + PF - KK] = frag_of(kk + PF - KK);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = PF; i < PT; ++i) tk[i] = frag_of(i);
+    // lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of query row qw0 + l32
+    float ds[16];
+    const int lim = (CAUSAL ? min(qw0 + l32, T - 1) : T - 1) - kv0 - ks * 32 - 4 * half;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float p = __builtin_amdgcn_exp2f(s[r] - lse2);
+      if (MASKED) p = (8 * (r >> 2) + (r & 3) <= lim) ? p : 0.f;
+      ds[r] = p * (dp[r] - delta);
+    }
+    bf16x8 dsf[2];
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+      u32x4 w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) w[e] = pack2(ds[8 * jj + 2 * e], ds[8 * jj + 2 * e + 1]);
+      dsf[jj] = __builtin_bit_cast(bf16x8, w);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // dQ^T += K^T dS^T
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      const bf16x8 f = tk[i % PT];
+      if (i + PT < NP) tk[i % PT] = frag_of(i + PT);
+      acc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[i / DT], acc[i % DT], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
   const int kv_end = CAUSAL ? min(q0 + DQ_BQ, T) : T;
   const int ntiles = (kv_end + BKV - 1) / BKV;
   load_tile(0);
@@ -234,44 +292,14 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     if (j + 2 < ntiles) load_tile(kv0 + 2 * BKV);
     if (wave_live && !(CAUSAL && kv0 > wave_last)) {
       const unsigned char *kp = sK + buf * TILE, *vp = sV + buf * TILE;
+      // wave-uniform: tiles below the diagonal and inside the sequence need no mask
       const bool need_mask = (CAUSAL && kv0 + BKV - 1 > qw0) || (kv0 + BKV > T);
+      if (need_mask) {
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {  // 32 keys at a time
-        f32x16 s, dp;
+        for (int ks = 0; ks < 2; ++ks) block(kp, vp, kv0, ks, std::true_type{});
+      } else {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-          const uint32_t co = LS.col[kk & 1] + ks * 32 * ROW + 64 * (kk >> 1);
-          const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + co));
-          const bf16x8 vf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(vp + co));
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
-        }
-        // lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of query row qw0 + l32
-        float ds[16];
-        const int lim = (CAUSAL ? min(qw0 + l32, T - 1) : T - 1) - kv0 - ks * 32 - 4 * half;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(s[r] - lse2);
-          if (need_mask && (8 * (r >> 2) + (r & 3) > lim)) p = 0.f;
-          ds[r] = p * (dp[r] - delta);
-        }
-        bf16x8 dsf[2];
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-          u32x4 w;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = pack2(ds[8 * jj + 2 * e], ds[8 * jj + 2 * e + 1]);
-          dsf[jj] = __builtin_bit_cast(bf16x8, w);
-        }
-        // dQ^T += K^T dS^T
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-            acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<ROW>(kp, LS, ks * 32 + jj * 16, dt), dsf[jj],
-                                                              acc[dt], 0, 0, 0);
+        for (int ks = 0; ks < 2; ++ks) block(kp, vp, kv0, ks, std::false_type{});
       }
     }
     __syncthreads();
@@ -381,6 +409,17 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const unsigned char *const Qg = reinterpret_cast<const unsigned char *>(Q + ((long long)b * T * Hq + h) * DH);
   const unsigned char *const Dg = reinterpret_cast<const unsigned char *>(dO + ((long long)b * T * Hq + h) * DH);
   float rstat = 0.f;
+  // per lane and wave instruction: (row of the tile, byte offset of the chunk in its row), packed; the global address
+  // is a wave-uniform base plus a 32-bit offset (T * H_q * d_h * 2 < 2^31 is a precondition of this path)
+  uint32_t dma_rc[PER_WAVE];
+#pragma unroll
+  for (int u = 0; u < PER_WAVE; ++u) {
+    const int i = wave + u * (KV_NT / 64);
+    const int ii = i >= T_INSTR ? i - T_INSTR : i;
+    const int L = ii * 64 + lane;
+    const int row = L / CPR, ch = min(L % CPR, KCH - 1) ^ swz(row);
+    dma_rc[u] = (uint32_t)row | ((uint32_t)ch << 12);  // ch * 16 = dma_rc >> 8 with the row bits masked off
+  }
   auto issue_tile = [&](int step, int buf) {
     const int t0 = (qt_first + step) * BQT;
 #pragma unroll
@@ -389,10 +428,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
       if (i < 2 * T_INSTR) {
         const bool isd = i >= T_INSTR;
         const int ii = isd ? i - T_INSTR : i;
-        const int L = ii * 64 + lane;
-        const int row = L / CPR, ch = min(L % CPR, KCH - 1) ^ swz(row);
-        const int t = min(t0 + row, T - 1);  // clamped rows get probability 0 below
-        const unsigned char *src = (isd ? Dg : Qg) + (long long)t * qrow_bytes + ch * 16;
+        const int t = min(t0 + (int)(dma_rc[u] & 0xfffu), T - 1);  // clamped rows get probability 0 below
+        const uint32_t off = (uint32_t)t * (uint32_t)qrow_bytes + ((dma_rc[u] >> 8) & 0xfff0u);
+        const unsigned char *src = (isd ? Dg : Qg) + off;
         unsigned char *dst = (isd ? sD : sQ) + buf * TILE + ii * 1024;
         __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)dst, 16, 0, 0);
       }
@@ -412,7 +450,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   // requested PF MFMAs ahead of their use (the compiler on its own issues read, wait, MFMA one at a time, and the
   // wavefronts then spend most of their cycles waiting for LDS), the first ones of a chain before the arithmetic
   // that precedes it.
-  constexpr int PF = 3;
+  constexpr int PF = 2;
   auto block = [&](const unsigned char *qp, const unsigned char *dp_, int buf, int t0, int qs, auto masked_t) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_t)::value;
     auto col = [&](const unsigned char *tile, int kk) {
