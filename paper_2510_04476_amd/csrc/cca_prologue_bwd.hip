@@ -137,7 +137,15 @@ __global__ __launch_bounds__(256) void column_sum_f32_kernel(const float *__rest
   __shared__ float red[256];
   const int col = blockIdx.x, tid = threadIdx.x;
   float acc = 0.f;
-  for (long long r = tid; r < rows; r += 256) acc += src[r * ncol + col];
+  long long r = tid;
+  for (; r + 7 * 256 < rows; r += 8 * 256) {  // 8 loads in flight, added in row order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[(r + u * 256) * ncol + col];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  for (; r < rows; r += 256) acc += src[r * ncol + col];
   red[tid] = acc;
   __syncthreads();
   for (int s = 128; s > 0; s >>= 1) {
@@ -277,11 +285,23 @@ __global__ __launch_bounds__(256) void pro_bwd_unfold_w1_kernel(const float *__r
   const long long id = (long long)blockIdx.x * 256 + threadIdx.x;  // (h*DH + o)*DH + i
   if (id >= (long long)NH * DH * DH) return;
   const int i = (int)(id % DH), o = (int)((id / DH) % DH), h = (int)(id / (DH * DH));
-  float sum[4] = {0.f, 0.f, 0.f, 0.f};  // D <= 4
-  for (int c = 0; c < n_chunks; ++c) {
-    const float *p = part + (((long long)c * NH + h) * DH + o) * D * DH + i;
-    for (int d = 0; d < D; ++d) sum[d] += p[d * DH];
+  float sum[4] = {0.f, 0.f, 0.f, 0.f};  // D <= 3 on this path
+  const long long cstride = (long long)NH * DH * D * DH;
+  const float *p0 = part + ((long long)h * DH + o) * D * DH + i;
+  int c = 0;
+  for (; c + 8 <= n_chunks; c += 8) {  // 8 chunks of loads in flight, added in chunk order
+    float v[8][3];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int d = 0; d < 3; ++d) v[u][d] = d < D ? p0[(c + u) * cstride + d * DH] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int d = 0; d < 3; ++d) sum[d] += v[u][d];
   }
+  for (; c < n_chunks; ++c)
+    for (int d = 0; d < D; ++d) sum[d] += p0[c * cstride + d * DH];
   for (int d = 0; d < D; ++d) dwc[(((long long)h * DH + o) * D + d) * DH + i] = sum[d];
   if (!dw1) return;
   for (int j = 0; j < kc; ++j) {
@@ -294,28 +314,42 @@ __global__ __launch_bounds__(256) void pro_bwd_unfold_w1_kernel(const float *__r
   }
 }
 
-// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j].  One workgroup per head, 8 groups of d_h / 8 output
-// channels x d_h input channels; the 8 partial sums are added through LDS in a fixed order.
+// d w0[c(h,i), jj] = sum_o sum_j dwc[h,o,j+jj,i] * w1[h,o,i,j].  Workgroup = (head, 16 input channels): 8 groups of
+// d_h / 8 output channels x 16 input channels; the 8 partial sums are added through LDS in a fixed order.
+constexpr int W0_IW = 16;
 template <int DH>
-__global__ __launch_bounds__(DH * 8) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
-                                                                const bf16_t *__restrict__ w1, bf16_t *__restrict__ dw0) {
-  __shared__ float red[8][4][DH];
-  const int h = blockIdx.x, i = threadIdx.x % DH, og = threadIdx.x / DH;
+__global__ __launch_bounds__(W0_IW * 8) void pro_bwd_unfold_w0_kernel(const float *__restrict__ dwc, int D, int ks, int kc,
+                                                                     const bf16_t *__restrict__ w1, bf16_t *__restrict__ dw0) {
+  __shared__ float red[8][4][W0_IW];
+  const int h = blockIdx.x, il = threadIdx.x % W0_IW, i = blockIdx.y * W0_IW + il, og = threadIdx.x / W0_IW;
+  // D = ks + kc - 1 <= 3 on this path: every load of the d_h / 8 output channels is issued before the first use
+  // (absent taps read as zero), so the thread waits for memory once instead of once per channel
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int o = og * (DH / 8); o < (og + 1) * (DH / 8); ++o) {
+  float pv[DH / 8][3], wv[DH / 8][3];
+#pragma unroll
+  for (int x = 0; x < DH / 8; ++x) {
+    const int o = og * (DH / 8) + x;
     const float *p = dwc + (((long long)h * DH + o) * D) * DH + i;
     const bf16_t *wp = w1 + (((long long)h * DH + o) * DH + i) * kc;
-    for (int j = 0; j < kc; ++j) {
-      const float f1 = bf16_to_f32(wp[j]);
-      for (int jj = 0; jj < ks; ++jj) acc[jj] = fmaf(p[(j + jj) * DH], f1, acc[jj]);
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      pv[x][t] = t < D ? p[t * DH] : 0.f;
+      wv[x][t] = t < kc ? bf16_to_f32(wp[t]) : 0.f;
     }
   }
-  for (int jj = 0; jj < 4; ++jj) red[og][jj][i] = acc[jj];
+#pragma unroll
+  for (int x = 0; x < DH / 8; ++x)
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+      for (int jj = 0; jj < 3; ++jj)
+        if (j + jj < 3) acc[jj] = fmaf(pv[x][j + jj], wv[x][j], acc[jj]);  // j >= kc: wv = 0; j + jj >= D: pv = 0
+  for (int jj = 0; jj < 4; ++jj) red[og][jj][il] = acc[jj];
   __syncthreads();
   if (og == 0)
     for (int jj = 0; jj < ks; ++jj) {
       float sum = 0.f;
-      for (int x = 0; x < 8; ++x) sum += red[x][jj][i];
+      for (int x = 0; x < 8; ++x) sum += red[x][jj][il];
       dw0[(long long)(h * DH + i) * ks + jj] = f32_to_bf16(sum);
     }
 }
@@ -405,7 +439,7 @@ static hipError_t prologue_bwd_run(const Dims &d, const cca_weights &w, const vo
                                                                      (const bf16_t *)w.w_conv_seq, dwc,
                                                                      want_w1 ? (bf16_t *)gr->w_conv_ch : nullptr, DH);
   if (want_w0)
-    pro_bwd_unfold_w0_kernel<DH><<<NH, DH * 8, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
+    pro_bwd_unfold_w0_kernel<DH><<<dim3(NH, DH / W0_IW), W0_IW * 8, 0, s>>>(dwc, D, ks, d.k_ch, (const bf16_t *)w.w_conv_ch,
                                                (bf16_t *)gr->w_conv_seq);
   return hipGetLastError();
 }
