@@ -130,7 +130,17 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist,
     if (a.flags & CCA_CONV_CH) {
       y = 0.f;
       const T *wp = w1 + ((long long)head * dh + o) * dh * kc;  // one contiguous row of d_h * k_ch weights
-      for (int c8 = 0; c8 < dh * kc; c8 += 8) {
+      int c8 = 0;
+      for (; c8 + 32 <= dh * kc; c8 += 32) {  // four 16-byte loads in flight; the sum keeps its order
+        float wv[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) load_vec<8>(wp + c8 + 8 * u, wv[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) y = fmaf(wv[u][e], y0[c8 + 8 * u + e], y);
+      }
+      for (; c8 < dh * kc; c8 += 8) {
         float wv[8];
         load_vec<8>(wp + c8, wv);
 #pragma unroll
@@ -756,7 +766,15 @@ __global__ void skinny_reduce_kernel(const float *__restrict__ part, T *__restri
   const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
   if (id >= mn) return;
   float a = 0.f;
-  for (int s = 0; s < splits; ++s) a += part[(long long)s * mn + id];
+  int s = 0;
+  for (; s + 8 <= splits; s += 8) {  // 8 loads in flight, added in split order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = part[(long long)(s + u) * mn + id];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a += v[u];
+  }
+  for (; s < splits; ++s) a += part[(long long)s * mn + id];
   store_f(C + (id / N) * ldc + id % N, a);
 }
 
