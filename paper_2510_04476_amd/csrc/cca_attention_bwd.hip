@@ -214,7 +214,10 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     }
   }
   const float lse2 = LSE[((long long)b * Hq + h) * T + trow] * LOG2E;  // exp(s*scale - lse) = exp2(s*c - lse2)
-  const float delta = DELTA[((long long)b * Hq + h) * T + trow];
+  float delta = DELTA[((long long)b * Hq + h) * T + trow];
+  // taken through an empty asm once: as a value still "in flight" from memory it made the first use in every tile
+  // iteration wait for all vector memory operations, i.e. for the tile loads issued just before
+  asm volatile("" : "+v"(delta));
 
   f32x16 acc[DT];  // dQ^T: lane = query row, registers = channels
 #pragma unroll
@@ -355,7 +358,10 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   constexpr int TILE = BQT * ROW;
   constexpr int PER_THREAD = BQT * KCH / KV_NT;
   constexpr int ROWS_PER_PASS = KV_NT / KCH;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];  // Q0 Q1 dO0 dO1
+  // Q0 Q1 dO0 dO1, 4 * TILE bytes of dynamic LDS: with a static array the compiler makes every LDS read wait for the
+  // tile loads in flight (vmcnt(0): a load into LDS might alias what is read), which puts the latency of the next
+  // tile's loads in front of each step
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];                                      // [buf][lse2 | delta][row]
   // this workgroup's V rows as MFMA operand fragments, [wavefront][kk][lane] x 16 bytes: each wavefront keeps its own
   // (read back one fragment per dP product; holding them in registers next to the K fragments and the two
@@ -422,6 +428,13 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   }
   auto issue_tile = [&](int step, int buf) {
     const int t0 = (qt_first + step) * BQT;
+    // the row statistics first, untouched until they land: arithmetic on them here would wait for them and, loads
+    // completing in order, for every tile load issued before
+    if (tid < 2 * BQT) {
+      const int t = min(t0 + (tid & (BQT - 1)), T - 1);
+      const long long o = ((long long)b * Hq + h) * T + t;
+      rstat = tid < BQT ? LSE[o] : DELTA[o];
+    }
 #pragma unroll
     for (int u = 0; u < PER_WAVE; ++u) {
       const int i = wave + u * (KV_NT / 64);
@@ -435,14 +448,9 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)dst, 16, 0, 0);
       }
     }
-    if (tid < 2 * BQT) {
-      const int t = min(t0 + (tid & (BQT - 1)), T - 1);
-      const long long o = ((long long)b * Hq + h) * T + t;
-      rstat = tid < BQT ? LSE[o] * LOG2E : DELTA[o];
-    }
   };
   auto land_tile = [&](int buf) {  // before the barrier that publishes the tile
-    if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = rstat;
+    if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = tid < BQT ? rstat * LOG2E : rstat;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
@@ -671,25 +679,35 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
 #define ARGS_KV (const bf16_t *)qs, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_k, \
                 (bf16_t *)d_v, pk, pv, d.T, d.Hq, d.Hk, BH, nkb, d.scale
   const unsigned gkv = (unsigned)((long long)BH * nkb);
+  constexpr size_t kv_smem = 4ull * BQT * (DH * 2 + 64);  // the Q / dO tiles of attn_bwd_dkdv_kernel
   // pairing query blocks only pays while it still leaves a workgroup for each of the 256 CUs; the dK / dV kernel
   // gains nothing from it (measured)
   const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 256 ? 1 : 0;
   const bool partial = d.R > 1;
+  // per launch: the attribute belongs to the current device, and the library keeps no state
+#define LAUNCH_KV(C_, P_)                                                                                     \
+  {                                                                                                           \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkdv_kernel<DH, C_, P_>),                  \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem);                         \
+    if (e != hipSuccess) return e;                                                                            \
+    attn_bwd_dkdv_kernel<DH, C_, P_><<<gkv, KV_NT, kv_smem, s>>>(ARGS_KV);                                     \
+  }
   if (causal) {
     attn_bwd_dq_kernel<DH, true><<<(unsigned)((long long)BH * (paired ? (nqb + 1) / 2 : nqb)), DQ_NT, 0, s>>>(ARGS_DQ);
     if (partial) {
-      attn_bwd_dkdv_kernel<DH, true, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      LAUNCH_KV(true, true);
     } else {
-      attn_bwd_dkdv_kernel<DH, true, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      LAUNCH_KV(true, false);
     }
   } else {
     attn_bwd_dq_kernel<DH, false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
     if (partial) {
-      attn_bwd_dkdv_kernel<DH, false, true><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      LAUNCH_KV(false, true);
     } else {
-      attn_bwd_dkdv_kernel<DH, false, false><<<gkv, KV_NT, 0, s>>>(ARGS_KV);
+      LAUNCH_KV(false, false);
     }
   }
+#undef LAUNCH_KV
 #undef ARGS_DQ
 #undef ARGS_KV
   if (partial) {
