@@ -207,6 +207,237 @@ __global__ __launch_bounds__(256) void transpose_bf16_kernel(const bf16_t *__res
   }
 }
 
+// ---------------------------------------------------------------------------
+// Weight-gradient GEMM (adjoint of the two projections): C (Mo,No) = A (K,Mo)^T * B (K,No), contraction over
+// the B*T token rows.  Both operands are row-major with the contraction index as the ROW, so the tiles are
+// staged row-major in LDS and the MFMA fragments (8 values along K for one column) come from the transposing
+// LDS read.  The output is small (a weight matrix) and K is long, so K is split over `gridDim.y` workgroups
+// that write fp32 partial sums; a second kernel adds them in a fixed order and rounds to bf16.
+// ---------------------------------------------------------------------------
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4i16 lds_v4i16;
+
+constexpr int TN_BN = 256, TN_ROW = 256 * 2 + 64;  // tile width (both operands); LDS row in bytes, padded by 64 so
+                                                   // that the 4 rows a transposing read touches fall in 4 different bank groups
+
+__device__ __forceinline__ bf16x8 tr_frag_tn(const unsigned char *base, int r0, int c0) {
+  const unsigned char *p = base + r0 * TN_ROW + c0 * 2;
+  const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)p);
+  const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(p + 8 * TN_ROW));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+__global__ __launch_bounds__(512) void gemm_bf16_tn_kernel(const bf16_t *__restrict__ A, long long lda,
+                                                          const bf16_t *__restrict__ Bm, long long ldb,
+                                                          float *__restrict__ part, int Mo, int No, long long K,
+                                                          int tiles_n, int tiles_total, int slabs_per_split) {
+  constexpr int NTHREADS = 512, WAVES_N = 4;
+  constexpr int WM = BM / 2, WN = TN_BN / WAVES_N;  // 128 x 64 wave tile
+  constexpr int MI = WM / 32, NI = WN / 32;
+  constexpr int CHUNKS = BK * (BM / 8) / NTHREADS;  // 16-byte chunks per thread per operand per slab (4)
+  constexpr int TILE = BK * TN_ROW;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [2 stages][A tile | B tile]
+
+  const int wg = blockIdx.x;
+  const int per_xcd = (tiles_total + 7) / 8;
+  const int tile = (wg % 8) * per_xcd + wg / 8;
+  if (tile >= tiles_total) return;
+  const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * TN_BN;
+  const int split = blockIdx.y;
+  const long long nk_all = (K + BK - 1) / BK;
+  const long long slab0 = (long long)split * slabs_per_split;
+  const int nk = (int)((slab0 + slabs_per_split <= nk_all ? slabs_per_split : nk_all - slab0));
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  // chunk id -> (row r of the slab, 16-byte column chunk c); columns past the matrix edge are clamped to
+  // column 0 (they only feed outputs that are never stored), rows past K are zero-filled
+  int c_row[CHUNKS], c_col[CHUNKS];
+  const bf16_t *a_src[CHUNKS], *b_src[CHUNKS];
+#pragma unroll
+  for (int i = 0; i < CHUNKS; ++i) {
+    const int id = tid + i * NTHREADS;
+    c_row[i] = id >> 5;
+    c_col[i] = id & 31;
+    const int am = m0 + c_col[i] * 8, bn = n0 + c_col[i] * 8;
+    a_src[i] = A + (am < Mo ? am : 0);
+    b_src[i] = Bm + (bn < No ? bn : 0);
+  }
+  u32x4 ra[CHUNKS], rb[CHUNKS];
+  auto load_slab = [&](long long k0) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      const long long gk = k0 + c_row[i];
+      u32x4 va = {0, 0, 0, 0}, vb = {0, 0, 0, 0};
+      if (gk < K) {
+        va = *reinterpret_cast<const u32x4 *>(a_src[i] + gk * lda);
+        vb = *reinterpret_cast<const u32x4 *>(b_src[i] + gk * ldb);
+      }
+      ra[i] = va;
+      rb[i] = vb;
+    }
+  };
+  auto store_slab = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < CHUNKS; ++i) {
+      *reinterpret_cast<u32x4 *>(smem + buf * 2 * TILE + c_row[i] * TN_ROW + c_col[i] * 16) = ra[i];
+      *reinterpret_cast<u32x4 *>(smem + buf * 2 * TILE + TILE + c_row[i] * TN_ROW + c_col[i] * 16) = rb[i];
+    }
+  };
+
+  f32x16 acc[NI][MI];
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[ni][mi][r] = 0.f;
+
+  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * TN_ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+  const long long kbase = slab0 * BK;
+  if (nk > 0) {
+    load_slab(kbase);
+    store_slab(0);
+    if (nk > 1) load_slab(kbase + BK);
+  }
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) store_slab(buf ^ 1);
+    if (kt + 2 < nk) load_slab(kbase + (long long)(kt + 2) * BK);
+    const unsigned char *pa = smem + buf * 2 * TILE + tr_off, *pb = pa + TILE;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[MI], fb[NI];
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) fa[mi] = tr_frag_tn(pa, kk * 16, wm * WM + mi * 32);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) fb[ni] = tr_frag_tn(pb, kk * 16, wn * WN + ni * 32);
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[ni][mi], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  // acc[ni][mi][r] = C[m][n], m = m0 + wm*WM + mi*32 + l32, n = n0 + wn*WN + ni*32 + 8*(r/4) + 4*half + r%4
+  float *out = part + (long long)split * Mo * No;
+#pragma unroll
+  for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+      const int m = m0 + wm * WM + mi * 32 + l32;
+      if (m >= Mo) continue;
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int n = n0 + wn * WN + ni * 32 + rg * 8 + half * 4;
+        if (n < No) {  // No % 8 == 0 and n % 4 == 0: the four columns are inside
+          f32x4 v4 = {acc[ni][mi][rg * 4 + 0], acc[ni][mi][rg * 4 + 1], acc[ni][mi][rg * 4 + 2], acc[ni][mi][rg * 4 + 3]};
+          *reinterpret_cast<f32x4 *>(out + (long long)m * No + n) = v4;
+        }
+      }
+    }
+}
+
+// C[i] = bf16(sum_s part[s][i]), 4 elements per thread, fixed summation order
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int splits, long long n,
+                                                           bf16_t *__restrict__ C) {
+  const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  f32x4 acc = *reinterpret_cast<const f32x4 *>(part + i);
+  for (int s = 1; s < splits; ++s) {
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(part + (long long)s * n + i);
+    acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+  }
+  u32x2 w;
+  w.x = pack_bf16x2(acc.x, acc.y);
+  w.y = pack_bf16x2(acc.z, acc.w);
+  *reinterpret_cast<u32x2 *>(C + i) = w;
+}
+
+// Number of K splits: minimise (rounds on 256 CUs) x (slabs per split) x (time of one 256x256x64 slab at ~70 % of
+// the MFMA rate, 1.2 us) + the traffic of the fp32 partial sums (written once, read once, ~3 TB/s).
+int tn_splits(int Mo, int No, long long K) {
+  const long long tiles = (long long)((Mo + BM - 1) / BM) * ((No + TN_BN - 1) / TN_BN);
+  const long long nk = (K + BK - 1) / BK;
+  int best = 1;
+  double best_t = -1.0;
+  for (int sp = 1; sp <= 32; ++sp) {
+    const long long per = (nk + sp - 1) / sp;
+    if (sp > 1 && per < 4) break;
+    if ((per * (sp - 1)) >= nk) continue;  // an empty last split
+    const double t = (double)((tiles * sp + 255) / 256) * (double)per * 1.2e-6 + (double)sp * Mo * No * 8.0 / 3e12;
+    if (best_t < 0 || t < best_t) best_t = t, best = sp;
+  }
+  return best;
+}
+
+template <int BN, int WAVES_M, int WAVES_N>
+hipError_t launch_gemm(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s) {
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  const int per_xcd = (total + 7) / 8;
+  constexpr size_t main_bytes = 2ull * (BM + BN) * BK * 2;
+  constexpr size_t epi_bytes = (size_t)BM * (BN * 2 + 16);
+  constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
+  {  // per launch: the attribute belongs to the current device, and the library keeps no state
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N><<<per_xcd * 8, WAVES_M * WAVES_N * 64, smem, s>>>((const bf16_t *)A, (const bf16_t *)Bt, (bf16_t *)C, M, N,
+                                                             K, tiles_n, total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool gemm_mfma_supported(long long M, int N, int K) { return M >= 1 && K % BK == 0 && K >= BK && N % 8 == 0 && N >= 8; }
+
+hipError_t gemm_mfma_bf16(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s) {
+  // Tile width by the number of rounds the grid needs on 256 CUs:
+  // N = 1536, M = 16384 gives 384 tiles of 256 (2 rounds, half empty) or 512 tiles of 192 (2 full rounds).
+  auto cost = [&](int bn) {
+    const long long tiles = ((M + BM - 1) / BM) * ((N + bn - 1) / bn);
+    return ((tiles + 255) / 256) * bn;
+  };
+  // 8 wavefronts (2 per SIMD) measured 15-20 % faster than 4 wavefronts with 128x128 wave tiles: a second
+  // wavefront hides LDS latency better than the compiler's in-wave schedule does
+  if (cost(192) < cost(256)) return launch_gemm<192, 4, 2>(A, Bt, C, M, N, K, s);
+  return launch_gemm<256, 2, 4>(A, Bt, C, M, N, K, s);
+}
+
+bool gemm_tn_mfma_supported(int Mo, int No, long long K) { return Mo % 8 == 0 && No % 8 == 0 && Mo >= 8 && No >= 8 && K >= 1; }
+
+size_t gemm_tn_scratch_bytes(int Mo, int No, long long K) {
+  return (size_t)tn_splits(Mo, No, K) * Mo * No * sizeof(float);
+}
+
+hipError_t gemm_tn_mfma_bf16(const void *A, long long lda, const void *Bm, long long ldb, void *C, int Mo, int No,
+                             long long K, float *part, hipStream_t s) {
+  const int tiles_m = (Mo + BM - 1) / BM, tiles_n = (No + TN_BN - 1) / TN_BN;
+  const int total = tiles_m * tiles_n, per_xcd = (total + 7) / 8;
+  const int splits = tn_splits(Mo, No, K);
+  const long long nk = (K + BK - 1) / BK;
+  const int per = (int)((nk + splits - 1) / splits);
+  constexpr size_t smem = 2ull * 2 * BK * TN_ROW;
+  {  // per launch: the attribute belongs to the current device, and the library keeps no state
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_tn_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+  }
+  gemm_bf16_tn_kernel<<<dim3(per_xcd * 8, splits), 512, smem, s>>>((const bf16_t *)A, lda, (const bf16_t *)Bm, ldb, part,
+                                                                  Mo, No, K, tiles_n, total, per);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const long long n = (long long)Mo * No;
+  splitk_reduce_kernel<<<(unsigned)((n / 4 + 255) / 256), 256, 0, s>>>(part, splits, n, (bf16_t *)C);
+  return hipGetLastError();
+}
+
 hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStream_t s) {
   return transpose2_bf16(src, dst, rows, cols, nullptr, nullptr, 0, 0, s);
 }
