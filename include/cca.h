@@ -41,6 +41,8 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+/* The library is built with hidden visibility; only what is declared here is exported. */
+#pragma GCC visibility push(default)
 
 typedef enum {
   CCA_OK = 0,
@@ -77,12 +79,19 @@ enum {
 
 typedef struct {
   int32_t B, T, d_model;
-  int32_t n_q_heads, n_kv_heads, head_dim; /* H_q, H_k, d_h; H_q % H_k == 0.  C1 = E/(H_q d_h), C2 = E/(H_k d_h) */
+  int32_t compress_q, compress_kv;         /* C1, C2 of Sec. 2.2 (query / key-value compression, C2 >= C1; equal for
+                                              plain CCA).  Each is either 0 (derived from the head layout, not
+                                              checked) or must satisfy d_model == C * heads * head_dim exactly
+                                              (compress_q with n_q_heads, compress_kv with n_kv_heads), else
+                                              CCA_ERR_SHAPE.  Plain MHA: 1 and 1. */
+  int32_t n_q_heads, n_kv_heads, head_dim; /* H_q, H_k, d_h; H_q % H_k == 0 */
   int32_t k_seq, k_ch;                     /* conv widths, 1..4; ignored when the conv's flag is off */
   int32_t dtype;                           /* cca_dtype */
   uint32_t flags;
   float rope_base;                         /* e.g. 10000; must be > 0 when CCA_ROPE */
   float softmax_scale;                     /* 0 => 1/sqrt(d_h) */
+  float norm_eps;                          /* CCA_QK_NORM divides by sqrt(sum u^2 + norm_eps).  0 => the paper's form
+                                              (App. A listing: plain L2 norm, no epsilon).  Must be >= 0. */
 } cca_config;
 
 /* Weights (device pointers, read-only).  Pointers whose flag is off may be NULL. */
@@ -92,6 +101,13 @@ typedef struct {
   const void *w_conv_ch;  /* (H_q + H_k, d_h_out, d_h_in, k_ch): q heads first, then KV heads; tap k_ch-1 multiplies token t */
   const float *temp;      /* (H_k) fp32 log-temperature, beta_g = exp(temp[g]) */
   const void *w_out;      /* (e_q, E) */
+  const void *prepared;   /* optional, may be NULL: a buffer that cca_prepare filled from THESE weights under a
+                             config equal to the call's in every field but B (cca_prepared_size bytes, caller-
+                             owned).  It holds what depends on the weights and the config only - both projection
+                             weights in the layout the matrix-core GEMM reads, the two convolutions folded into
+                             one filter per head, the RoPE angle tables - so that cca_forward does not derive
+                             them again on every call.  Results are bit-identical with and without it.  Read by
+                             cca_forward only; the library cannot check that it matches the weights. */
 } cca_weights;
 
 /* Intermediates (device pointers, caller-owned).  Any member may be NULL; a
@@ -122,12 +138,26 @@ typedef struct {
   void *w_out;      /* (e_q, E) */
 } cca_grads;
 
-/* Bytes of device workspace cca_forward needs for `cfg` (independent of which
- * cca_saved members are given).  Returns CCA_OK or a validation error. */
-cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes);
+/* Bytes of device workspace cca_forward (*fwd_bytes) and cca_backward
+ * (*bwd_bytes) need for `cfg`, independent of which cca_saved members are
+ * given.  Either out-pointer may be NULL (not wanted), not both.  Returns
+ * CCA_OK or a validation error. */
+cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes, size_t *bwd_bytes);
 
-/* Bytes of device workspace cca_backward needs for `cfg`. */
+/* The second figure alone (same as cca_workspace_size(cfg, NULL, bwd_bytes)). */
 cca_status cca_backward_workspace_size(const cca_config *cfg, size_t *bwd_bytes);
+
+/* Bytes of the buffer cca_prepare fills for `cfg` (0 when this config has
+ * nothing to prepare: fp32 storage, or shapes off the matrix-core kernels). */
+cca_status cca_prepared_size(const cca_config *cfg, size_t *bytes);
+
+/* One-time set-up per set of weights (Sec. 2.2: the projection weights, the
+ * two convolution filters and the RoPE angles do not change between calls):
+ * fills `prepared` (device memory, 16-byte aligned, at least
+ * cca_prepared_size bytes, caller-owned) on the caller's stream.  Pass the
+ * buffer as cca_weights.prepared to cca_forward.  Allocates nothing. */
+cca_status cca_prepare(const cca_config *cfg, const cca_weights *w, void *prepared, size_t prepared_bytes,
+                       void *hip_stream);
 
 /* Whole block.  x: (B,T,E) in, out: (B,T,E) overwritten.  `saved` may be NULL.
  * `workspace` is scratch of at least cca_workspace_size() bytes whose
@@ -173,7 +203,7 @@ cca_status cca_prologue(const cca_config *cfg, const cca_weights *w, const void 
  * normalised by the sum of those rounded probabilities, so o is exactly the
  * convex combination that was formed; when neither is requested it is
  * normalised by the fp32 sum (a common factor 1 + delta per row, |delta| <=
- * 2^-9, below the rounding of o itself) and the kernel is a few percent faster.
+ * 2^-8, at most the rounding of o itself) and the kernel is a few percent faster.
  * If cfg->flags has CCA_QK_NORM the caller PROMISES that q and k are what
  * cca_prologue writes under that flag: |q[t,h]| = sqrt(d_h) and |k[t,g]| =
  * sqrt(d_h) * exp(temp[g]) (temp: H_k fp32 log-temperatures on the device,
@@ -242,12 +272,23 @@ cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const vo
                            const cca_decode_state *state, int32_t pos, void *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
 
+/* Measurement aid (not a step of the method): enqueues a kernel of `blocks`
+ * workgroups x 4 wavefronts that issue iters x 4 independent 32x32x16 bf16
+ * matrix-core instructions each and nothing else, and stores the number of
+ * floating-point operations that is (2*32*32*16 per instruction) in *flops
+ * (host memory).  Timing the launch gives the matrix-core rate the chip
+ * sustains - the measured ceiling quoted beside the nominal peak.  `out`:
+ * device scratch of at least blocks * 256 * 4 bytes, overwritten. */
+cca_status cca_probe_mfma_rate(void *out, size_t out_bytes, int32_t blocks, int32_t iters, double *flops,
+                               void *hip_stream);
+
 /* Human-readable text for a status; never NULL; static storage. */
 const char *cca_strerror(cca_status s);
 
 /* Library version: major*10000 + minor*100 + patch. */
 int cca_version(void);
 
+#pragma GCC visibility pop
 #ifdef __cplusplus
 }
 #endif

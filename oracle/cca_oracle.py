@@ -132,12 +132,15 @@ def value_shift(vc, vp, n_kv_heads, head_dim, shift=True):
 
 
 # -- step 6 -----------------------------------------------------------------
-def qk_norm_temp(q3, k3, temp=None):
+def qk_norm_temp(q3, k3, temp=None, eps=0.0):
     """q <- q sqrt(d_h) / ||q||_2, k <- k sqrt(d_h) / ||k||_2 * exp(temp_g)
-    (first two lines of the final equation block of Sec. 2.2)."""
+    (first two lines of the final equation block of Sec. 2.2).  The paper's
+    norm has no epsilon (eps = 0, the default); a caller-chosen eps > 0 is
+    added to the sum of squares under the root, an option of the library's
+    interface, not of the paper."""
     d = q3.shape[-1]
-    q4 = q3 * np.sqrt(d) / np.sqrt((q3 * q3).sum(-1, keepdims=True))
-    k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True))
+    q4 = q3 * np.sqrt(d) / np.sqrt((q3 * q3).sum(-1, keepdims=True) + eps)
+    k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True) + eps)
     if temp is not None:
         k4 = k4 * np.exp(_f64(temp))[None, None, :, None]
     return q4, k4
@@ -219,7 +222,7 @@ def cca_forward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, *,
                 causal=True, use_conv_seq=True, use_conv_ch=True,
                 use_qk_mean=True, use_v_shift=True, use_qk_norm=True,
                 use_key_temp=True, use_rope=True, rope_interleaved=False,
-                rope_base=10000.0, softmax_scale=None, rows=None):
+                rope_base=10000.0, softmax_scale=None, rows=None, norm_eps=0.0):
     """Whole block, steps 1-9.  Returns a dict with ``out`` (B,n_rows,E) and
     every intermediate (q0, k0 pre-conv latents; q, k, v as they enter
     attention; o; lse)."""
@@ -242,7 +245,7 @@ def cca_forward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, *,
     q3, k3 = q, k                                      # as they enter the norm step
     v = value_shift(vc, vp, Hk, dh, shift=use_v_shift)
     if use_qk_norm:
-        q, k = qk_norm_temp(q, k, temp if use_key_temp else None)
+        q, k = qk_norm_temp(q, k, temp if use_key_temp else None, norm_eps)
     if use_rope:
         q = rope(q, rope_base, rope_interleaved)
         k = rope(k, rope_base, rope_interleaved)
@@ -319,13 +322,13 @@ def value_shift_bwd(dv, shift=True):
     return dvc, dvp
 
 
-def qk_norm_temp_bwd(dq4, dk4, q3, k3, temp=None):
+def qk_norm_temp_bwd(dq4, dk4, q3, k3, temp=None, eps=0.0):
     """y = x sqrt(d) / |x| (* exp(temp_g) for keys)  ->  dx, dtemp and sum_t |<dk4_t, k4_t>| (the magnitude
     the signed sum dtemp cancels down from: the natural error scale for a reduced-precision dtemp)."""
     d = q3.shape[-1]
 
     def one(dy, x, mul):
-        n = np.sqrt((x * x).sum(-1, keepdims=True))
+        n = np.sqrt((x * x).sum(-1, keepdims=True) + eps)   # y = mul sqrt(d) x / n; dn/dx = x / n
         xh = x / n
         return mul * np.sqrt(d) / n * (dy - xh * (xh * dy).sum(-1, keepdims=True))
 
@@ -334,7 +337,7 @@ def qk_norm_temp_bwd(dq4, dk4, q3, k3, temp=None):
         return dq3, one(dk4, k3, 1.0), None, None
     beta = np.exp(_f64(temp))[None, None, :, None]
     dk3 = one(dk4, k3, beta)
-    k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True)) * beta
+    k4 = k3 * np.sqrt(d) / np.sqrt((k3 * k3).sum(-1, keepdims=True) + eps) * beta
     per_token = (dk4 * k4).sum(axis=3)                 # (B,T,Hk): d temp_g is the sum of these signed terms
     return dq3, dk3, per_token.sum(axis=(0, 1)), np.abs(per_token).sum(axis=(0, 1))
 
@@ -399,7 +402,7 @@ def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
                  causal=True, use_conv_seq=True, use_conv_ch=True,
                  use_qk_mean=True, use_v_shift=True, use_qk_norm=True,
                  use_key_temp=True, use_rope=True, rope_interleaved=False,
-                 rope_base=10000.0, softmax_scale=None, rows=None):
+                 rope_base=10000.0, softmax_scale=None, rows=None, norm_eps=0.0):
     """Gradients of sum(out * d_out) with respect to x and every weight.
     Recomputes the forward intermediates it needs.  Returns a dict:
     d_x, d_w_down, d_w_conv_seq, d_w_conv_ch, d_temp, d_w_out plus the
@@ -427,7 +430,7 @@ def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
         q2, k2 = conv_ch(q1, w1[:Hq]), conv_ch(k1, w1[Hq:])
     q3, k3 = qk_mean(q2, k2, q0, k0) if use_qk_mean else (q2, k2)
     v = value_shift(vc, vp, Hk, dh, shift=use_v_shift)
-    q4, k4 = qk_norm_temp(q3, k3, temp if use_key_temp else None) if use_qk_norm else (q3, k3)
+    q4, k4 = qk_norm_temp(q3, k3, temp if use_key_temp else None, norm_eps) if use_qk_norm else (q3, k3)
     q5, k5 = (rope(q4, rope_base, rope_interleaved), rope(k4, rope_base, rope_interleaved)) if use_rope else (q4, k4)
     scale = 1.0 / np.sqrt(dh) if not softmax_scale else float(softmax_scale)
     ridx = np.arange(T) if rows is None else np.asarray(rows, dtype=np.int64)
@@ -442,7 +445,7 @@ def cca_backward(x, w_down, w_conv_seq, w_conv_ch, temp, w_out, d_out, *,
         if use_rope else (d_q5, d_k5)
     d_temp, d_temp_abs = np.zeros(Hk), np.zeros(Hk)
     if use_qk_norm:
-        d_q3, d_k3, dt, dt_abs = qk_norm_temp_bwd(d_q4, d_k4, q3, k3, temp if use_key_temp else None)
+        d_q3, d_k3, dt, dt_abs = qk_norm_temp_bwd(d_q4, d_k4, q3, k3, temp if use_key_temp else None, norm_eps)
         if dt is not None:
             d_temp, d_temp_abs = dt, dt_abs
     else:

@@ -27,21 +27,23 @@ CCA_FLAGS_PAPER = (CCA_CAUSAL | CCA_CONV_SEQ | CCA_CONV_CH | CCA_QK_MEAN | CCA_V
                    | CCA_KEY_TEMP | CCA_ROPE)
 CCA_FLAGS_MHA = CCA_CAUSAL
 
-EXPORTS = ("cca_workspace_size", "cca_backward_workspace_size", "cca_forward", "cca_backward", "cca_down_project",
+EXPORTS = ("cca_workspace_size", "cca_backward_workspace_size", "cca_prepared_size", "cca_prepare", "cca_forward",
+           "cca_backward", "cca_down_project",
            "cca_prologue", "cca_attention", "cca_attention_backward", "cca_prologue_backward", "cca_up_project",
-           "cca_decode_workspace_size", "cca_decode_step", "cca_strerror", "cca_version")
+           "cca_decode_workspace_size", "cca_decode_step", "cca_probe_mfma_rate", "cca_strerror", "cca_version")
 
 
 class cca_config(C.Structure):
     _fields_ = [("B", C.c_int32), ("T", C.c_int32), ("d_model", C.c_int32),
+                ("compress_q", C.c_int32), ("compress_kv", C.c_int32),
                 ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
                 ("k_seq", C.c_int32), ("k_ch", C.c_int32), ("dtype", C.c_int32), ("flags", C.c_uint32),
-                ("rope_base", C.c_float), ("softmax_scale", C.c_float)]
+                ("rope_base", C.c_float), ("softmax_scale", C.c_float), ("norm_eps", C.c_float)]
 
 
 class cca_weights(C.Structure):
     _fields_ = [("w_down", C.c_void_p), ("w_conv_seq", C.c_void_p), ("w_conv_ch", C.c_void_p),
-                ("temp", C.c_void_p), ("w_out", C.c_void_p)]
+                ("temp", C.c_void_p), ("w_out", C.c_void_p), ("prepared", C.c_void_p)]
 
 
 class cca_decode_state(C.Structure):
@@ -77,7 +79,12 @@ def load_library() -> C.CDLL:
     lib = C.CDLL(LIB_PATH)
     vp, sz = C.c_void_p, C.c_size_t
     cfgp = C.POINTER(cca_config)
-    lib.cca_workspace_size.argtypes = [cfgp, C.POINTER(sz)]
+    lib.cca_workspace_size.argtypes = [cfgp, C.POINTER(sz), C.POINTER(sz)]
+    lib.cca_prepared_size.argtypes = [cfgp, C.POINTER(sz)]
+    lib.cca_prepare.argtypes = [cfgp, C.POINTER(cca_weights), vp, sz, vp]
+    lib.cca_decode_workspace_size.argtypes = [cfgp, C.POINTER(sz), C.POINTER(C.c_int32)]
+    lib.cca_decode_step.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_decode_state), C.c_int32, vp, vp,
+                                    sz, vp]
     lib.cca_forward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, C.POINTER(cca_saved), vp, sz, vp]
     lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
@@ -89,6 +96,7 @@ def load_library() -> C.CDLL:
                                  C.POINTER(cca_grads), vp, sz, vp]
     lib.cca_prologue_backward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, vp, vp, vp,
                                           C.POINTER(cca_grads), vp, sz, vp]
+    lib.cca_probe_mfma_rate.argtypes = [vp, sz, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
     lib.cca_strerror.argtypes = [C.c_int]
@@ -111,10 +119,14 @@ class CCAConfig:
     flags: int = CCA_FLAGS_PAPER
     rope_base: float = 10000.0
     softmax_scale: float = 0.0
+    compress_q: int = 0    # 0: derived from the head layout
+    compress_kv: int = 0
+    norm_eps: float = 0.0
 
     def c(self) -> cca_config:
-        return cca_config(self.B, self.T, self.d_model, self.n_q_heads, self.n_kv_heads, self.head_dim,
-                          self.k_seq, self.k_ch, self.dtype, self.flags, self.rope_base, self.softmax_scale)
+        return cca_config(self.B, self.T, self.d_model, self.compress_q, self.compress_kv, self.n_q_heads,
+                          self.n_kv_heads, self.head_dim, self.k_seq, self.k_ch, self.dtype, self.flags,
+                          self.rope_base, self.softmax_scale, self.norm_eps)
 
     @property
     def torch_dtype(self):
@@ -140,10 +152,11 @@ class CCAWeights:
     w_conv_seq: torch.Tensor | None = None
     w_conv_ch: torch.Tensor | None = None
     temp: torch.Tensor | None = None
+    prepared: torch.Tensor | None = None  # buffer filled by cca_prepare (optional)
 
     def c(self) -> cca_weights:
         return cca_weights(_ptr(self.w_down), _ptr(self.w_conv_seq), _ptr(self.w_conv_ch), _ptr(self.temp),
-                           _ptr(self.w_out))
+                           _ptr(self.w_out), _ptr(self.prepared))
 
 
 @dataclass
@@ -224,8 +237,26 @@ def cca_version() -> int:
 def cca_workspace_size(cfg: CCAConfig) -> int:
     n = C.c_size_t(0)
     cc = cfg.c()
-    _check(load_library().cca_workspace_size(C.byref(cc), C.byref(n)), "cca_workspace_size")
+    _check(load_library().cca_workspace_size(C.byref(cc), C.byref(n), None), "cca_workspace_size")
     return n.value
+
+
+def cca_prepared_size(cfg: CCAConfig) -> int:
+    n = C.c_size_t(0)
+    cc = cfg.c()
+    _check(load_library().cca_prepared_size(C.byref(cc), C.byref(n)), "cca_prepared_size")
+    return n.value
+
+
+def cca_prepare(cfg: CCAConfig, w: CCAWeights) -> CCAWeights:
+    """Runs the library's one-time set-up for these weights and returns a copy of `w` whose `prepared` buffer
+    cca_forward reads instead of deriving the same data on every call."""
+    lib = load_library()
+    buf = torch.empty(max(cca_prepared_size(cfg), 256), dtype=torch.uint8, device=w.w_down.device)
+    cc, cw = cfg.c(), w.c()
+    _check(lib.cca_prepare(C.byref(cc), C.byref(cw), _ptr(buf), buf.numel(), _stream()), "cca_prepare")
+    return CCAWeights(w_down=w.w_down, w_out=w.w_out, w_conv_seq=w.w_conv_seq, w_conv_ch=w.w_conv_ch, temp=w.temp,
+                      prepared=buf)
 
 
 def new_workspace(cfg: CCAConfig, device) -> torch.Tensor:
@@ -407,3 +438,20 @@ def cca_decode_step(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecodeState,
     _check(lib.cca_decode_step(C.byref(cc), C.byref(cw), _ptr(x_new), C.byref(cs), C.c_int32(pos), _ptr(out),
                                _ptr(state.workspace), C.c_size_t(state.workspace.numel()), _stream()), "cca_decode_step")
     return out
+
+
+def cca_probe_mfma_rate(blocks: int = 2048, iters: int = 4096, repeats: int = 5) -> float:
+    """Measured bf16 matrix-core rate in TFLOP/s (best of `repeats` launches of the library's MFMA-only kernel)."""
+    lib = load_library()
+    out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    fl = C.c_double(0.0)
+    best = 0.0
+    for _ in range(repeats + 1):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        _check(lib.cca_probe_mfma_rate(_ptr(out), out.numel() * 4, blocks, iters, C.byref(fl), _stream()),
+               "cca_probe_mfma_rate")
+        b.record()
+        torch.cuda.synchronize()
+        best = max(best, fl.value / (a.elapsed_time(b) * 1e-3) / 1e12)
+    return best

@@ -1,6 +1,12 @@
-"""Builds libcca.so (HIP, gfx950 only) in-tree next to this file."""
+"""Builds libcca.so (HIP, gfx950 only) in-tree next to this file.
+
+Each translation unit is compiled to an object under _build/ (in parallel, only
+when its source or a header is newer than the object unless `force` is set),
+then linked.  Internal C++ symbols stay hidden: the dynamic symbol table holds
+the C ABI of include/cca.h only."""
 from __future__ import annotations
 
+import concurrent.futures as cf
 import glob
 import os
 import subprocess
@@ -9,9 +15,10 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libcca.so")
+OBJ_DIR = os.path.join(HERE, "_build")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # packed-fp32 VALU forms are kept off on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
@@ -22,11 +29,34 @@ def sources() -> list[str]:
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build_library(verbose: bool = True, extra: list[str] | None = None) -> str:
+def headers() -> list[str]:
+    return sorted(glob.glob(os.path.join(HERE, "csrc", "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h")))
+
+
+def _compile(hipcc: str, src: str, obj: str, extra: list[str], verbose: bool) -> None:
+    cmd = [hipcc, *HIPCC_FLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
+           "-c", src, "-o", obj]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+
+
+def build_library(verbose: bool = True, extra: list[str] | None = None, force: bool = True, jobs: int = 8) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, *(extra or []),
-           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-           *sources(), "-o", LIB]
+    extra = list(extra or [])
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    newest_header = max(os.path.getmtime(h) for h in headers())
+    todo, objs = [], []
+    for src in sources():
+        obj = os.path.join(OBJ_DIR, os.path.basename(src)[:-4] + ".o")
+        objs.append(obj)
+        stale = force or not os.path.exists(obj) or os.path.getmtime(obj) < max(os.path.getmtime(src), newest_header)
+        if stale:
+            todo.append((src, obj))
+    with cf.ThreadPoolExecutor(max_workers=max(1, min(jobs, len(todo) or 1))) as pool:
+        for f in [pool.submit(_compile, hipcc, s, o, extra, verbose) for s, o in todo]:
+            f.result()
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", *objs, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
@@ -34,4 +64,6 @@ def build_library(verbose: bool = True, extra: list[str] | None = None) -> str:
 
 
 if __name__ == "__main__":
-    build_library(extra=sys.argv[1:])
+    args = sys.argv[1:]
+    incremental = "--incremental" in args
+    build_library(extra=[a for a in args if a != "--incremental"], force=not incremental)

@@ -32,12 +32,17 @@ static cca_status make_dims(const cca_config *cfg, Dims *d) {
   if ((cfg->flags & CCA_ROPE) && (cfg->head_dim % 2 != 0)) return CCA_ERR_LAYOUT;
   if ((cfg->flags & CCA_ROPE) && !(cfg->rope_base > 0.f)) return CCA_ERR_SHAPE;
   if (cfg->softmax_scale < 0.f || isnan(cfg->softmax_scale)) return CCA_ERR_SHAPE;
+  if (!(cfg->norm_eps >= 0.f) || isinf(cfg->norm_eps)) return CCA_ERR_SHAPE;
   const long long e_kv = (long long)cfg->n_kv_heads * cfg->head_dim;
   const long long e_q = (long long)cfg->n_q_heads * cfg->head_dim;
   if (e_q > 65536 || e_kv > 65536 || cfg->d_model > 65536) return CCA_ERR_SHAPE;
   if ((cfg->flags & CCA_V_SHIFT) && (e_kv % 2 != 0)) return CCA_ERR_LAYOUT;
   // the latent must not be wider than the residual stream (compression factors >= 1)
   if (e_q > cfg->d_model || e_kv > e_q) return CCA_ERR_SHAPE;
+  // stated compression factors (Sec. 2.2: latent widths E/C1 and E/C2) must agree with the head layout
+  if (cfg->compress_q < 0 || cfg->compress_kv < 0) return CCA_ERR_SHAPE;
+  if (cfg->compress_q > 0 && (long long)cfg->compress_q * e_q != cfg->d_model) return CCA_ERR_SHAPE;
+  if (cfg->compress_kv > 0 && (long long)cfg->compress_kv * e_kv != cfg->d_model) return CCA_ERR_SHAPE;
   d->B = cfg->B; d->T = cfg->T; d->E = cfg->d_model;
   d->Hq = cfg->n_q_heads; d->Hk = cfg->n_kv_heads; d->dh = cfg->head_dim;
   d->R = d->Hq / d->Hk;
@@ -48,12 +53,16 @@ static cca_status make_dims(const cca_config *cfg, Dims *d) {
   d->bf16 = cfg->dtype == CCA_BF16;
   d->flags = cfg->flags;
   d->rope_base = cfg->rope_base;
+  d->norm_eps = cfg->norm_eps;
   d->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
   return CCA_OK;
 }
 
+// The first three parts depend on the weights and the config only (not on x, not on B): they are what
+// cca_prepare writes into a caller-owned buffer, in this layout.
 struct FwdLayout {
   size_t wt_down, wt_out, pro, lat, q, k, v, o, total;  // byte offsets
+  size_t prepared_bytes() const { return lat; }
 };
 
 static FwdLayout fwd_layout(const Dims &d) {
@@ -62,6 +71,8 @@ static FwdLayout fwd_layout(const Dims &d) {
   const size_t rows = (size_t)d.rows();
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes, 256); return o; };
+  // (the transposed weights are only made when the matrix-core GEMM runs, which does not depend on B: see
+  // both_projections_mfma)
   L.wt_down = take(d.bf16 ? (size_t)d.E * d.n_lat * 2 : 0);
   L.wt_out = take(d.bf16 ? (size_t)d.E * d.e_q * 2 : 0);
   L.pro = take(prologue_fused_scratch_bytes(d));
@@ -91,14 +102,16 @@ static cca_status project(const Dims &d, const void *A, const void *W, void *C, 
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
+// `ready`: scratch already holds the folded filters and RoPE tables (cca_prepare made them)
 static cca_status run_prologue(const Dims &d, const cca_weights *w, const void *lat, void *q, void *k, void *v,
-                               float *rnorm, void *scratch, size_t scratch_bytes, hipStream_t s) {
+                               float *rnorm, void *scratch, size_t scratch_bytes, hipStream_t s, bool ready = false) {
   hipError_t e;
   if (prologue_is_split_copy(d)) {
     e = prologue_split_copy(d, lat, q, k, v, rnorm, s);
   } else if (prologue_fused_supported(d)) {
     if (!scratch || scratch_bytes < prologue_fused_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
-    e = prologue_fused_bf16(d, *w, lat, q, k, v, rnorm, scratch, s);
+    e = ready ? prologue_fused_run(d, *w, lat, q, k, v, rnorm, scratch, s)
+              : prologue_fused_bf16(d, *w, lat, q, k, v, rnorm, scratch, s);
   } else {
     e = prologue_generic(d, *w, lat, q, k, v, rnorm, s);
   }
@@ -183,6 +196,13 @@ static cca_status run_prologue_bwd(const Dims &d, const cca_weights *w, const vo
   return e == hipSuccess ? CCA_OK : CCA_ERR_LAUNCH;
 }
 
+// Both projections of cca_forward on the matrix-core GEMM (then their weights are wanted K-contiguous).  The GEMM's
+// conditions on the row count are met or missed by every B alike only through M = B*T >= 1, so a buffer prepared
+// under one B serves any other.
+static bool both_projections_mfma(const Dims &d) {
+  return d.bf16 && gemm_mfma_supported(d.rows(), d.n_lat, d.E) && gemm_mfma_supported(d.rows(), d.E, d.e_q);
+}
+
 static cca_status check_grads(const cca_grads *g) {
   if (!g) return CCA_OK;
   if (!aligned16(g->w_down) || !aligned16(g->w_conv_seq) || !aligned16(g->w_conv_ch) || !aligned16(g->w_out) ||
@@ -207,12 +227,45 @@ using namespace cca;
 
 extern "C" {
 
-cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes) {
-  if (!fwd_bytes) return CCA_ERR_NULL;
+cca_status cca_workspace_size(const cca_config *cfg, size_t *fwd_bytes, size_t *bwd_bytes) {
+  if (!fwd_bytes && !bwd_bytes) return CCA_ERR_NULL;
   Dims d;
   cca_status st = make_dims(cfg, &d);
   if (st != CCA_OK) return st;
-  *fwd_bytes = fwd_layout(d).total;
+  if (fwd_bytes) *fwd_bytes = fwd_layout(d).total;
+  if (bwd_bytes) *bwd_bytes = bwd_layout(d).total;
+  return CCA_OK;
+}
+
+cca_status cca_prepared_size(const cca_config *cfg, size_t *bytes) {
+  if (!bytes) return CCA_ERR_NULL;
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  *bytes = fwd_layout(d).prepared_bytes();
+  return CCA_OK;
+}
+
+cca_status cca_prepare(const cca_config *cfg, const cca_weights *w, void *prepared, size_t prepared_bytes,
+                       void *hip_stream) {
+  Dims d;
+  cca_status st = make_dims(cfg, &d);
+  if (st != CCA_OK) return st;
+  if (!w || !w->w_down || !w->w_out) return CCA_ERR_NULL;
+  st = check_prologue_weights(d, w);
+  if (st != CCA_OK) return st;
+  const FwdLayout L = fwd_layout(d);
+  if (L.prepared_bytes() == 0) return CCA_OK;  // nothing to prepare for this config
+  if (!prepared || prepared_bytes < L.prepared_bytes()) return CCA_ERR_WORKSPACE;
+  if (!aligned16(prepared) || !aligned16(w->w_down) || !aligned16(w->w_out)) return CCA_ERR_ALIGN;
+  char *pb = static_cast<char *>(prepared);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (both_projections_mfma(d) &&
+      transpose2_bf16(w->w_down, pb + L.wt_down, d.E, d.n_lat, w->w_out, pb + L.wt_out, d.e_q, d.E, s) != hipSuccess)
+    return CCA_ERR_LAUNCH;
+  if (!prologue_is_split_copy(d) && prologue_fused_supported(d) &&
+      prologue_fused_prepare(d, *w, pb + L.pro, s) != hipSuccess)
+    return CCA_ERR_LAUNCH;
   return CCA_OK;
 }
 
@@ -364,7 +417,8 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
   if (!w || !x || !out || !w->w_down || !w->w_out) return CCA_ERR_NULL;
   st = check_prologue_weights(d, w);
   if (st != CCA_OK) return st;
-  if (!aligned16(x) || !aligned16(out) || !aligned16(w->w_down) || !aligned16(w->w_out)) return CCA_ERR_ALIGN;
+  if (!aligned16(x) || !aligned16(out) || !aligned16(w->w_down) || !aligned16(w->w_out) || !aligned16(w->prepared))
+    return CCA_ERR_ALIGN;
   const FwdLayout L = fwd_layout(d);
   if (!workspace || workspace_bytes < L.total) return CCA_ERR_WORKSPACE;
   if (!aligned16(workspace)) return CCA_ERR_ALIGN;
@@ -387,17 +441,21 @@ cca_status cca_forward(const cca_config *cfg, const cca_weights *w, const void *
     if (reinterpret_cast<uintptr_t>(rnorm) & 3u) return CCA_ERR_ALIGN;
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  // both weight transposes in one launch when both projections run on the MFMA GEMM
-  const bool both = d.bf16 && gemm_mfma_supported(d.rows(), d.n_lat, d.E) && gemm_mfma_supported(d.rows(), d.E, d.e_q);
-  if (both && transpose2_bf16(w->w_down, ws + L.wt_down, d.E, d.n_lat, w->w_out, ws + L.wt_out, d.e_q, d.E, s) != hipSuccess)
+  // What depends on the weights only: taken from the caller's prepared buffer, else derived into the workspace
+  // (both weight transposes in one launch when both projections run on the MFMA GEMM).
+  const bool prepared = w->prepared != nullptr;
+  char *pre = prepared ? static_cast<char *>(const_cast<void *>(w->prepared)) : ws;
+  const bool both = both_projections_mfma(d);
+  if (both && !prepared &&
+      transpose2_bf16(w->w_down, pre + L.wt_down, d.E, d.n_lat, w->w_out, pre + L.wt_out, d.e_q, d.E, s) != hipSuccess)
     return CCA_ERR_LAUNCH;
-  st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, ws + L.wt_down, (size_t)d.E * d.n_lat * 2, s, both);
+  st = project(d, x, w->w_down, lat, d.rows(), d.n_lat, d.E, pre + L.wt_down, (size_t)d.E * d.n_lat * 2, s, both);
   if (st != CCA_OK) return st;
-  st = run_prologue(d, w, lat, q, k, v, rnorm, ws + L.pro, L.lat - L.pro, s);
+  st = run_prologue(d, w, lat, q, k, v, rnorm, pre + L.pro, L.lat - L.pro, s, prepared);
   if (st != CCA_OK) return st;
   st = run_attention(d, q, k, v, o, o_lo, lse, w->temp, s);
   if (st != CCA_OK) return st;
-  return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, ws + L.wt_out, (size_t)d.E * d.e_q * 2, s, both);
+  return project(d, o, w->w_out, out, d.rows(), d.E, d.e_q, pre + L.wt_out, (size_t)d.E * d.e_q * 2, s, both);
 }
 
 cca_status cca_decode_workspace_size(const cca_config *cfg, size_t *bytes, int32_t *ring_rows) {
@@ -430,6 +488,17 @@ cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const vo
                      (hipStream_t)hip_stream) == hipSuccess
              ? CCA_OK
              : CCA_ERR_LAUNCH;
+}
+
+cca_status cca_probe_mfma_rate(void *out, size_t out_bytes, int32_t blocks, int32_t iters, double *flops,
+                               void *hip_stream) {
+  if (!out || !flops) return CCA_ERR_NULL;
+  if (blocks <= 0 || iters <= 0 || blocks > (1 << 20) || iters > (1 << 24)) return CCA_ERR_SHAPE;
+  if (out_bytes < (size_t)blocks * 256 * sizeof(float)) return CCA_ERR_WORKSPACE;
+  if (!aligned16(out)) return CCA_ERR_ALIGN;
+  *flops = (double)blocks * 4.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+  return mfma_probe(static_cast<float *>(out), blocks, iters, (hipStream_t)hip_stream) == hipSuccess ? CCA_OK
+                                                                                                    : CCA_ERR_LAUNCH;
 }
 
 const char *cca_strerror(cca_status s) {

@@ -29,7 +29,7 @@
 //   - the row sum uses plain v_add_f32 (two chains).  For inference it adds
 //     the fp32 probabilities while the PV product multiplies their bf16
 //     roundings, so a row's output carries a common factor 1 + delta, |delta|
-//     <= 2^-9 (it averages out over the keys; a row dominated by one key sees
+//     <= 2^-8 (it averages out over the keys; a row dominated by one key sees
 //     all of it).  When the caller saves lse / o_lo for a backward pass the
 //     sum adds the rounded values instead (two more vector instructions per
 //     pair of scores, measured 4 % of the kernel): the backward pass forms
@@ -357,6 +357,10 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
+  // Wavefronts w and w + 4 share a SIMD.  Under the causal mask a row block needs more key tiles the further
+  // down it lies, so the 32-row blocks are dealt such that every SIMD gets a light and a heavy one (0 and 7,
+  // 1 and 6, ...): the SIMDs then carry equal work through the diagonal tiles of a query block.
+  const int wave_r = wave < 4 ? wave : 11 - wave;
   const int idx = blockIdx.x;
   const int bh = idx % BH;
   const int b = bh / Hq, h = bh % Hq, g = h / (Hq / Hk);
@@ -365,7 +369,6 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
   const unsigned char *const Kg = reinterpret_cast<const unsigned char *>(K + ((long long)b * T * Hk + g) * DH);
   const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
   const int k_r0 = tid / KCH, k_ch = tid % KCH;
-  const uint32_t k_goff = (uint32_t)k_r0 * row_bytes + k_ch * 16;
   const uint32_t k_soff = (uint32_t)k_r0 * KROW + k_ch * 16;
   const uint32_t v_soff = (uint32_t)k_r0 * VROW + k_ch * 16;
   const uint32_t kr_off = (uint32_t)l32 * KROW + half * 16;
@@ -373,13 +376,20 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
 
   u32x4 rk[K_PER_THREAD];
   u32x4 rv[K_PER_THREAD];
-  auto load_rows = [&](const unsigned char *base, int kt, u32x4 *dst) {  // branch-free: rows clamped to T - 1
-    const int kv0 = kt * BKV;
+  // K / V tiles are fetched with buffer loads.  Each tile gets its own descriptor (scalar arithmetic only): it
+  // starts at the tile's first row and ends with row T-1 of this (batch item, KV head), so a thread's chunk
+  // offsets are loop constants and rows past the end of the sequence (ragged last tile) fail the hardware's
+  // range check and read as zeros: no address arithmetic on the vector ALU inside the loop.
+  const int kv_span = (T - 1) * row_bytes + DH * 2;
+  int k_goff[K_PER_THREAD];
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int s = min(kv0 + k_r0 + i * K_ROWS_PER_PASS, T - 1);
-      dst[i] = *reinterpret_cast<const u32x4 *>(base + (long long)s * row_bytes + k_ch * 16);
-    }
+  for (int i = 0; i < K_PER_THREAD; ++i) k_goff[i] = (k_r0 + i * K_ROWS_PER_PASS) * row_bytes + k_ch * 16;
+  auto load_rows = [&](const unsigned char *base, int kt, u32x4 *dst) {  // kt * BKV < T
+    const int first = kt * BKV * row_bytes;
+    const __amdgpu_buffer_rsrc_t res =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(base) + first, 0, kv_span - first, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(res, k_goff[i], 0, 0);
   };
   auto store_k = [&](int buf) {
     unsigned char *kd = sKb + buf * KBUF + k_soff;
@@ -399,7 +409,7 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
     const int slot = idx / BH;
     const int qb = (paired && pass == 1) ? slot : nqb - 1 - slot;
     if (pass == 1 && slot >= nqb - 1 - slot) break;
-    const int q0 = qb * BQ, qw0 = q0 + wave * 32;
+    const int q0 = qb * BQ, qw0 = q0 + wave_r * 32;
     const bool wave_live = qw0 < T;
     const int wave_last = min(qw0 + 31, T - 1);
 

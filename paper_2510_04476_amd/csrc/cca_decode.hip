@@ -24,7 +24,7 @@ constexpr int MAX_SPLITS = 32;
 struct DecArgs {
   int B, S, Hq, Hk, dh, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch, P, pos;
   uint32_t flags;
-  float rope_base, scale;
+  float rope_base, scale, norm_eps;
 };
 
 // N consecutive elements as one vector load (N * sizeof(T) bytes, aligned by construction: head offsets and
@@ -172,7 +172,7 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist,
   }
   float mul = 1.f;
   if (a.flags & CCA_QK_NORM) {
-    mul = sqrtf((float)dh) / sqrtf(red[0]);
+    mul = sqrtf((float)dh) / sqrtf(red[0] + a.norm_eps);
     if (!is_q && (a.flags & CCA_KEY_TEMP)) mul *= expf(temp[head - a.Hq]);
   }
   for (int o = tid; o < dh; o += blockDim.x) {
@@ -212,12 +212,7 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist,
 // ---------------------------------------------------------------------------
 // CPL = channels per lane in the P V phase (d_h <= 64 * CPL); DHC = d_h when it is one of the common widths (the
 // loops over channels then unroll and their loads are all in flight together), 0 for any other multiple of 8.
-// STAGED (needs DHC): the 64 key rows of a block are first copied HBM -> LDS with whole rows per load instruction
-// and then read one row per lane from LDS (rows padded by 16 bytes: conflict-free).  Reading a row per lane straight
-// from memory touches 64 cache lines per instruction, 16 bytes of each, and with 16 wavefronts per CU the lines
-// fall out of the 32 KB vector cache before their other chunks are wanted: the cache was re-fetched from L2
-// several times over (measured 1.8 TB/s against 4 TB/s staged).
-template <typename T, int CPL, int DHC, bool STAGED>
+template <typename T, int CPL, int DHC>
 __global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_kernel(DecArgs a, const float *__restrict__ q_new,
                                                                     const T *__restrict__ k_cache,
                                                                     const T *__restrict__ v_cache,
@@ -230,8 +225,6 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_kernel(DecArgs a, 
   float *qs = sm;                             // [R_MAX][dh], scaled to log2 units
   float *ps = qs + R_MAX * dh + wave * 64 * R_MAX;  // [64][R_MAX] probabilities of this wavefront's current keys
   float *mrg = sm + R_MAX * dh + DEC_WAVES * 64 * R_MAX;  // merge area: [DEC_WAVES][R_MAX][2 + dh]
-  constexpr int ROWB = DHC * (int)sizeof(T), KROW = ROWB + 16;  // staged key rows (bytes)
-  unsigned char *sK = reinterpret_cast<unsigned char *>(mrg + DEC_WAVES * R_MAX * (2 + dh)) + wave * 64 * KROW;
   const float c = a.scale * 1.44269504088896340736f;
   for (int i = tid; i < R_MAX * dh; i += blockDim.x) {
     const int r = i / dh, ch = i % dh;
@@ -259,21 +252,8 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_kernel(DecArgs a, 
     float s[R_MAX];
 #pragma unroll
     for (int r = 0; r < R_MAX; ++r) s[r] = 0.f;
-    if constexpr (STAGED) {
-      typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-      constexpr int CH16 = ROWB >= 16 ? ROWB / 16 : 1, RPI = CH16 <= 64 ? 64 / CH16 : 1;  // 16-byte chunks per row, rows per load
-      const int rr = lane / CH16, cc = lane % CH16;
-      u4 tmp[64 / RPI];
-#pragma unroll
-      for (int i = 0; i < 64 / RPI; ++i) {
-        const int row = min(i * RPI + rr, k_end - 1 - k0);  // rows past the end repeat the last live one (unused)
-        tmp[i] = *reinterpret_cast<const u4 *>(reinterpret_cast<const unsigned char *>(kb + (long long)(k0 + row) * row_elems) + cc * 16);
-      }
-#pragma unroll
-      for (int i = 0; i < 64 / RPI; ++i) *reinterpret_cast<u4 *>(sK + (i * RPI + rr) * KROW + cc * 16) = tmp[i];
-    }
     if (live) {
-      const T *kp = STAGED ? reinterpret_cast<const T *>(sK + lane * KROW) : kb + (long long)key * row_elems;
+      const T *kp = kb + (long long)key * row_elems;
 #pragma unroll
       for (int ch = 0; ch < dh; ch += 8) {
         float kv[8];
@@ -849,7 +829,7 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
   const DecLayout L = layout(d);
   const int P = ring_rows(d);
   DecArgs a{d.B, d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, P, pos,
-            d.flags, d.rope_base, d.scale};
+            d.flags, d.rope_base, d.scale, d.norm_eps};
   float *q_new = reinterpret_cast<float *>(ws + L.q_new);
   T *o = reinterpret_cast<T *>(ws + L.o);
   float *part = reinterpret_cast<float *>(ws + L.part);
@@ -874,12 +854,7 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
     int nsplit = (1024 + d.B * d.Hk - 1) / (d.B * d.Hk);
     nsplit = nsplit < (len + 255) / 256 ? nsplit : (len + 255) / 256;
     nsplit = nsplit < 1 ? 1 : (nsplit > MAX_SPLITS ? MAX_SPLITS : nsplit);
-    const size_t smem_base = sizeof(float) * ((size_t)R_MAX * d.dh + DEC_WAVES * 64 * R_MAX + DEC_WAVES * R_MAX * (2 + d.dh));
-    const size_t rowb = (size_t)d.dh * sizeof(T);
-    // the staging area must fit next to the rest in the 160 KB of LDS (bf16 d_h <= 128, fp32 d_h <= 64)
-    const bool staged = (d.dh == 64 || d.dh == 128 || d.dh == 256) && rowb <= 512 &&
-                        smem_base + DEC_WAVES * 64 * (rowb + 16) <= 144 * 1024 && false;  // measured slower: one workgroup per CU
-    const size_t smem = smem_base + (staged ? DEC_WAVES * 64 * (rowb + 16) : 0);
+    const size_t smem = sizeof(float) * ((size_t)R_MAX * d.dh + DEC_WAVES * 64 * R_MAX + DEC_WAVES * R_MAX * (2 + d.dh));
     const unsigned grid = (unsigned)((long long)d.B * d.Hk * nsplit);
     if constexpr (std::is_same<T, bf16_t>::value) {
       // the row kernel addresses a sequence's cache with 32-bit byte offsets
@@ -909,23 +884,20 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
       }
     }
     for (int r0 = 0; r0 < d.R; r0 += R_MAX) {
-#define CCA_DEC_ATTN(CPL, DHC, ST)                                                                              \
+#define CCA_DEC_ATTN(CPL, DHC)                                                                                  \
   {                                                                                                             \
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(decode_attn_kernel<T, CPL, DHC, ST>),                  \
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(decode_attn_kernel<T, CPL, DHC>),                      \
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                              \
     if (e != hipSuccess) return e;                                                                              \
-    decode_attn_kernel<T, CPL, DHC, ST><<<grid, DEC_WAVES * 64, smem, s>>>(a, q_new, (const T *)k_cache,          \
+    decode_attn_kernel<T, CPL, DHC><<<grid, DEC_WAVES * 64, smem, s>>>(a, q_new, (const T *)k_cache,              \
                                                                            (const T *)v_cache, part, nsplit, r0); \
   }
-      if (staged && d.dh == 64) CCA_DEC_ATTN(1, 64, true)
-      else if (staged && d.dh == 128) CCA_DEC_ATTN(2, 128, true)
-      else if (staged) CCA_DEC_ATTN(4, 256, true)
-      else if (d.dh == 64) CCA_DEC_ATTN(1, 64, false)
-      else if (d.dh == 128) CCA_DEC_ATTN(2, 128, false)
-      else if (d.dh == 256) CCA_DEC_ATTN(4, 256, false)
-      else if (d.dh <= 64) CCA_DEC_ATTN(1, 0, false)
-      else if (d.dh <= 128) CCA_DEC_ATTN(2, 0, false)
-      else CCA_DEC_ATTN(4, 0, false)
+      if (d.dh == 64) CCA_DEC_ATTN(1, 64)
+      else if (d.dh == 128) CCA_DEC_ATTN(2, 128)
+      else if (d.dh == 256) CCA_DEC_ATTN(4, 256)
+      else if (d.dh <= 64) CCA_DEC_ATTN(1, 0)
+      else if (d.dh <= 128) CCA_DEC_ATTN(2, 0)
+      else CCA_DEC_ATTN(4, 0)
 #undef CCA_DEC_ATTN
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }

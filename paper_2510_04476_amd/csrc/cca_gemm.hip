@@ -395,6 +395,31 @@ hipError_t launch_gemm(const void *A, const void *Bt, void *C, long long M, int 
 
 }  // namespace
 
+// Measurement aid: nothing but matrix-core instructions (four independent accumulator chains per wavefront, no
+// memory traffic inside the loop), to read off the MFMA rate the chip sustains, i.e. the clock it holds under
+// matrix-core load.  One float per thread is written so that the work cannot be removed.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out, int iters) {
+  bf16x8 a, b;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    a[i] = (__bf16)((float)(threadIdx.x & 7) * 0.125f);
+    b[i] = (__bf16)((float)i * 0.25f);
+  }
+  f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int it = 0; it < iters; ++it) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+  }
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
+}
+
+hipError_t mfma_probe(float *out, int blocks, int iters, hipStream_t s) {
+  mfma_probe_kernel<<<blocks, 256, 0, s>>>(out, iters);
+  return hipGetLastError();
+}
+
 bool gemm_mfma_supported(long long M, int N, int K) { return M >= 1 && K % BK == 0 && K >= BK && N % 8 == 0 && N >= 8; }
 
 hipError_t gemm_mfma_bf16(const void *A, const void *Bt, void *C, long long M, int N, int K, hipStream_t s) {

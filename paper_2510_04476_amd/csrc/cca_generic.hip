@@ -74,7 +74,7 @@ hipError_t gemm_generic(bool bf16, const void *A, const void *Bm, void *C, long 
 struct PrologueArgs {
   int T, Hq, Hk, dh, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch;
   uint32_t flags;
-  float rope_base;
+  float rope_base, norm_eps;
 };
 
 template <typename T>
@@ -168,7 +168,7 @@ __global__ void prologue_generic_kernel(PrologueArgs a, const T *__restrict__ la
   }
   float mul = 1.f;
   if (a.flags & CCA_QK_NORM) {
-    mul = sqrtf((float)dh) / sqrtf(red[0]);
+    mul = sqrtf((float)dh) / sqrtf(red[0] + a.norm_eps);
     if (!is_q && (a.flags & CCA_KEY_TEMP)) mul *= expf(temp[head - a.Hq]);
   }
   if (rnorm && tid == 0) rnorm[row * (a.Hq + a.Hk) + head] = mul;
@@ -197,7 +197,8 @@ __global__ void prologue_generic_kernel(PrologueArgs a, const T *__restrict__ la
 
 hipError_t prologue_generic(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
                             float *rnorm, hipStream_t s) {
-  PrologueArgs a{d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.flags, d.rope_base};
+  PrologueArgs a{d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.flags, d.rope_base,
+                 d.norm_eps};
   int threads = 64;
   while (threads < d.dh && threads < 256) threads *= 2;
   const int kc = (d.flags & CCA_CONV_CH) ? d.k_ch : 1;

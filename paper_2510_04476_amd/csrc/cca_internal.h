@@ -17,6 +17,7 @@ struct Dims {
   bool bf16;
   uint32_t flags;
   float rope_base, scale;
+  float norm_eps;  // added to the sum of squares under the L2 norm (0: the paper's form)
   long long rows() const { return (long long)B * T; }
   size_t esize() const { return bf16 ? 2 : 4; }
 };
@@ -55,6 +56,9 @@ hipError_t transpose_bf16(const void *src, void *dst, int rows, int cols, hipStr
 // two independent transposes in one launch (src2 may be NULL)
 hipError_t transpose2_bf16(const void *src1, void *dst1, int rows1, int cols1, const void *src2, void *dst2, int rows2,
                            int cols2, hipStream_t s);
+
+// measurement aid: blocks x 4 wavefronts x iters x 4 MFMAs (32x32x16 bf16), one float per thread written to out
+hipError_t mfma_probe(float *out, int blocks, int iters, hipStream_t s);
 
 bool attention_mfma_supported(const Dims &d);
 // temp (H_k log-temperatures, device) is read only when d.flags has QK_NORM and KEY_TEMP: it bounds the scores
@@ -105,6 +109,11 @@ bool prologue_fused_supported(const Dims &d);
 size_t prologue_fused_scratch_bytes(const Dims &d);  // folded filters + RoPE tables; 0 if unsupported
 hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
                                float *rnorm, void *scratch, hipStream_t s);
+// The two halves of prologue_fused_bf16: `scratch` (folded filters, RoPE tables) depends on the weights and the
+// config only, so a caller may fill it once (prepare) and run the main kernel many times.
+hipError_t prologue_fused_prepare(const Dims &d, const cca_weights &w, void *scratch, hipStream_t s);
+hipError_t prologue_fused_run(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
+                              float *rnorm, const void *scratch, hipStream_t s);
 
 // ---- decode step (one new token per sequence against the latent KV cache) ----
 int decode_ring_rows(const Dims &d);            // latent rows of history the transforms need: max(taps - 1, 1)

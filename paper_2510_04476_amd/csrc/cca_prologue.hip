@@ -45,7 +45,7 @@ struct FusedArgs {
   uint32_t flags;
   int n_conv_blocks;
   int tiles_per_wave;
-  float rope_base;
+  float rope_base, norm_eps;
   // Row strides (elements).  Forward: the source is the latent (n_lat), q / k / v are dense.  Backward: the source
   // is the gradient entering the convolutions (e_q + e_kv wide), q / k destinations are column ranges of d_lat,
   // the value role reads d_v (e_kv) and writes the value columns of d_lat.
@@ -185,21 +185,30 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   // operand fragment kk = 2*nt + j of the source row; lane (l32, half) is non-zero in fragment l32 >> 4 when
   // (l32 >> 3) & 1 == half, element l32 & 7.
   const bool mean = a.flags & CCA_QK_MEAN;
-  bf16x8 id_half[2], id_grp[2];  // 1/2 * I (own stream), weight of the other stream * I
+  // The weight of the other stream, 1/2 or 1/(2R), is an exact mean in the qk-mean equation.  As a single bf16
+  // it is exact only for R a power of two, so it is fed as the sum of two bf16 numbers, w = hi + lo (the MFMA forms
+  // bf16 products exactly and adds in fp32, so hi*u + lo*u carries w to 2^-17 relative); the second pass is skipped
+  // when lo is zero.
+  bf16x8 id_half[2], id_grp[2], id_grp_lo[2];  // 1/2 * I (own stream), weight of the other stream * I (hi, lo)
+  const float w_other = is_q ? a.mean_q_other : a.mean_k_other;
+  const bf16_t w_other_hi = f32_to_bf16(w_other);
+  const bf16_t w_other_lo = f32_to_bf16(w_other - bf16_to_f32(w_other_hi));
+  const bool grp_lo = (w_other_lo & 0x7fffu) != 0;  // uniform over the workgroup
   {
-    const uint32_t hb = (uint32_t)f32_to_bf16(0.5f),
-                   gb = (uint32_t)f32_to_bf16(is_q ? a.mean_q_other : a.mean_k_other);
+    const uint32_t hb = (uint32_t)f32_to_bf16(0.5f), gb = (uint32_t)w_other_hi, lb = (uint32_t)w_other_lo;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const bool on = ((l32 >> 4) == j) && (((l32 >> 3) & 1) == half);
-      u32x4 wh = {0, 0, 0, 0}, wg = {0, 0, 0, 0};
+      u32x4 wh = {0, 0, 0, 0}, wg = {0, 0, 0, 0}, wl = {0, 0, 0, 0};
       const int e = l32 & 7;
       if (on) {
         wh[e >> 1] = hb << ((e & 1) * 16);
         wg[e >> 1] = gb << ((e & 1) * 16);
+        wl[e >> 1] = lb << ((e & 1) * 16);
       }
       id_half[j] = __builtin_bit_cast(bf16x8, wh);
       id_grp[j] = __builtin_bit_cast(bf16x8, wg);
+      id_grp_lo[j] = __builtin_bit_cast(bf16x8, wl);
     }
   }
 
@@ -268,6 +277,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
           for (int j = 0; j < 2; ++j)
             acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp[j], mf[2 * nt + j], acc[nt], 0, 0, 0);
+        if (grp_lo) {
+#pragma unroll
+          for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp_lo[j], mf[2 * nt + j], acc[nt], 0, 0, 0);
+        }
       }
     }
 
@@ -280,7 +296,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
         for (int r = 0; r < 16; ++r) ssq = fmaf(acc[nt][r], acc[nt][r], ssq);
       ssq += __shfl_xor(ssq, 32);
-      const float mul = sqrtf((float)DH) / sqrtf(ssq) * beta;
+      const float mul = sqrtf((float)DH) / sqrtf(ssq + a.norm_eps) * beta;
 #pragma unroll
       for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
@@ -499,14 +515,21 @@ size_t prologue_fused_scratch_bytes(const Dims &d) {
   return carve(d, nullptr, taps(d)).bytes;
 }
 
-hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
-                               float *rnorm, void *scratch, hipStream_t s) {
+static FusedArgs forward_args(const Dims &d) {
+  return FusedArgs{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1,
+                   d.rope_base, d.norm_eps, d.n_lat, d.e_q, d.e_kv, d.n_lat, d.e_kv, 0.5f, 0.5f / (float)d.R};
+}
+
+hipError_t prologue_fused_prepare(const Dims &d, const cca_weights &w, void *scratch, hipStream_t s) {
   const int D = taps(d);
-  FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1,
-              d.rope_base, d.n_lat, d.e_q, d.e_kv, d.n_lat, d.e_kv, 0.5f, 0.5f / (float)d.R};
-  const FusedScratch fs = carve(d, scratch, D);
-  hipError_t e = run_setup(d, a, w, fs, D, false, s);
-  if (e != hipSuccess) return e;
+  return run_setup(d, forward_args(d), w, carve(d, scratch, D), D, false, s);
+}
+
+hipError_t prologue_fused_run(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
+                              float *rnorm, const void *scratch, hipStream_t s) {
+  const int D = taps(d);
+  FusedArgs a = forward_args(d);
+  const FusedScratch fs = carve(d, const_cast<void *>(scratch), D);
   const int grid = plan_grid(d, a);
   const bf16_t *vsrc = (const bf16_t *)lat + d.e_q + d.e_kv;
 #define LAUNCH_DH(D_, B_) (d.dh == 64 ? launch_main<64, D_, B_> : launch_main<128, D_, B_>)
@@ -517,13 +540,20 @@ hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *
   }
 }
 
+hipError_t prologue_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
+                               float *rnorm, void *scratch, hipStream_t s) {
+  hipError_t e = prologue_fused_prepare(d, w, scratch, s);
+  if (e != hipSuccess) return e;
+  return prologue_fused_run(d, w, lat, q, k, v, rnorm, scratch, s);
+}
+
 // ---- adjoint: d3 (B*T, e_q+e_kv), d_v -> d_lat.  `scratch` as for the forward; the RoPE tables it leaves
 // behind are the ones the pointwise backward kernel reads, so this runs its set-up first (see fused_bwd_setup).
 hipError_t prologue_fused_bwd_setup(const Dims &d, const cca_weights &w, void *scratch, const float2 **ropeA,
                                     const float2 **ropeB, hipStream_t s) {
   const int D = taps(d);
   FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(), d.flags, 0, 1,
-              d.rope_base, 0, 0, 0, 0, 0, 0.f, 0.f};
+              d.rope_base, 0.f, 0, 0, 0, 0, 0, 0.f, 0.f};
   const FusedScratch fs = carve(d, scratch, D);
   *ropeA = fs.ropeA;
   *ropeB = fs.ropeB;
@@ -536,7 +566,7 @@ hipError_t prologue_fused_bwd_dlat(const Dims &d, const void *d3, const void *d_
   const int ld = d.e_q + d.e_kv;
   // only the qk-mean and value-shift flags matter to the adjoint kernel
   FusedArgs a{d.T, d.Hq, d.Hk, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, d.rows(),
-              d.flags & (CCA_QK_MEAN | CCA_V_SHIFT), 0, 1, d.rope_base, ld, d.n_lat, d.n_lat, d.e_kv, d.n_lat,
+              d.flags & (CCA_QK_MEAN | CCA_V_SHIFT), 0, 1, d.rope_base, 0.f, ld, d.n_lat, d.n_lat, d.e_kv, d.n_lat,
               0.5f / (float)d.R, 0.5f};
   const FusedScratch fs = carve(d, scratch, D);
   const int grid = plan_grid(d, a);

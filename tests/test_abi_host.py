@@ -32,15 +32,71 @@ def good():
 def ws(cfg):
     n = C.c_size_t(0)
     cc = cfg.c()
-    return P.load_library().cca_workspace_size(C.byref(cc), C.byref(n)), n.value
+    return P.load_library().cca_workspace_size(C.byref(cc), C.byref(n), None), n.value
 
 
 def test_workspace_size_ok_and_null():
+    lib = P.load_library()
     st, n = ws(good())
     assert st == B.CCA_OK and n > 0
     cc = good().c()
-    assert P.load_library().cca_workspace_size(C.byref(cc), None) == B.CCA_ERR_NULL
-    assert P.load_library().cca_workspace_size(None, C.byref(C.c_size_t())) == B.CCA_ERR_NULL
+    assert lib.cca_workspace_size(C.byref(cc), None, None) == B.CCA_ERR_NULL
+    assert lib.cca_workspace_size(None, C.byref(C.c_size_t()), None) == B.CCA_ERR_NULL
+    # both figures from one call; the backward one agrees with its own entry point
+    f, b_, b2 = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    assert lib.cca_workspace_size(C.byref(cc), C.byref(f), C.byref(b_)) == B.CCA_OK
+    assert lib.cca_backward_workspace_size(C.byref(cc), C.byref(b2)) == B.CCA_OK
+    assert f.value == n and b_.value == b2.value > 0
+    only_b = C.c_size_t(0)
+    assert lib.cca_workspace_size(C.byref(cc), None, C.byref(only_b)) == B.CCA_OK and only_b.value == b2.value
+
+
+def test_compression_factors_are_checked_against_the_head_layout():
+    """Sec. 2.2: latent widths E/C1 (queries) and E/C2 (keys, values).  0 = derive; otherwise exact."""
+    cfg = P.CCAConfig(B=1, T=64, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128)   # C1 = 2, C2 = 8
+    assert ws(cfg)[0] == B.CCA_OK
+    for cq, ckv, status in [(2, 8, B.CCA_OK), (2, 0, B.CCA_OK), (0, 8, B.CCA_OK), (4, 8, B.CCA_ERR_SHAPE),
+                            (2, 4, B.CCA_ERR_SHAPE), (-1, 0, B.CCA_ERR_SHAPE), (0, -2, B.CCA_ERR_SHAPE),
+                            (1, 1, B.CCA_ERR_SHAPE)]:
+        cfg.compress_q, cfg.compress_kv = cq, ckv
+        assert ws(cfg)[0] == status, (cq, ckv)
+    mha = P.CCAConfig(B=1, T=64, d_model=2048, n_q_heads=16, n_kv_heads=16, head_dim=128, flags=B.CCA_FLAGS_MHA,
+                      compress_q=1, compress_kv=1)
+    assert ws(mha)[0] == B.CCA_OK
+    # a latent that is not an integer fraction of d_model is accepted only with the factor left at 0
+    odd = P.CCAConfig(B=1, T=64, d_model=512, n_q_heads=3, n_kv_heads=3, head_dim=128)
+    assert ws(odd)[0] == B.CCA_OK
+    odd.compress_q = 1
+    assert ws(odd)[0] == B.CCA_ERR_SHAPE
+
+
+def test_prepare_validation_and_size():
+    lib = P.load_library()
+    big = P.CCAConfig(B=1, T=4096, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128)
+    cc = big.c()
+    n = C.c_size_t(0)
+    assert lib.cca_prepared_size(C.byref(cc), C.byref(n)) == B.CCA_OK
+    # transposed weights (E x N_lat and e_q x E, bf16) + folded 3-tap filters of 10 heads + RoPE tables
+    assert n.value >= 2048 * 1536 * 2 + 1024 * 2048 * 2 + 10 * 128 * 3 * 128 * 2
+    assert lib.cca_prepared_size(C.byref(cc), None) == B.CCA_ERR_NULL
+    other_b = P.CCAConfig(B=7, T=4096, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128).c()
+    m = C.c_size_t(0)
+    assert lib.cca_prepared_size(C.byref(other_b), C.byref(m)) == B.CCA_OK and m.value == n.value  # independent of B
+    p = C.c_void_p(0x10000)
+    w = B.cca_weights(p, p, p, p, p, None)
+    assert lib.cca_prepare(C.byref(cc), C.byref(w), p, n.value - 1, None) == B.CCA_ERR_WORKSPACE
+    assert lib.cca_prepare(C.byref(cc), C.byref(w), None, n.value, None) == B.CCA_ERR_WORKSPACE
+    assert lib.cca_prepare(C.byref(cc), C.byref(w), C.c_void_p(0x10008), n.value, None) == B.CCA_ERR_ALIGN
+    assert lib.cca_prepare(C.byref(cc), None, p, n.value, None) == B.CCA_ERR_NULL
+    assert lib.cca_prepare(C.byref(cc), C.byref(B.cca_weights(None, p, p, p, p, None)), p, n.value, None) == B.CCA_ERR_NULL
+    # fp32 storage has nothing to prepare: size 0 and the call is a no-op that needs no buffer
+    f32 = good().c()
+    assert lib.cca_prepared_size(C.byref(f32), C.byref(m)) == B.CCA_OK and m.value == 0
+    assert lib.cca_prepare(C.byref(f32), C.byref(w), None, 0, None) == B.CCA_OK
+    # a misaligned prepared buffer is refused by cca_forward before anything is enqueued
+    wbad = B.cca_weights(p, p, p, p, p, C.c_void_p(0x10004))
+    need = ws(big)[1]
+    assert lib.cca_forward(C.byref(cc), C.byref(wbad), p, p, None, p, need, None) == B.CCA_ERR_ALIGN
 
 
 @pytest.mark.parametrize("field,value,status", [
@@ -56,6 +112,11 @@ def test_workspace_size_ok_and_null():
     ("flags", B.CCA_CAUSAL | B.CCA_KEY_TEMP, B.CCA_ERR_UNSUPPORTED),
     ("rope_base", 0.0, B.CCA_ERR_SHAPE),
     ("softmax_scale", -1.0, B.CCA_ERR_SHAPE),
+    ("norm_eps", -1e-6, B.CCA_ERR_SHAPE),
+    ("norm_eps", float("nan"), B.CCA_ERR_SHAPE),
+    ("norm_eps", float("inf"), B.CCA_ERR_SHAPE),
+    ("compress_q", 3, B.CCA_ERR_SHAPE),           # 256 != 3 * 2 * 32
+    ("compress_kv", 8, B.CCA_ERR_SHAPE),
 ])
 def test_config_validation(field, value, status):
     cfg = good()
@@ -69,12 +130,12 @@ def test_forward_rejects_null_misaligned_and_small_workspace():
     cc = cfg.c()
     # fake but never dereferenced device addresses: validation fails first
     p = C.c_void_p(0x10000)
-    w = B.cca_weights(p, p, p, p, p)
+    w = B.cca_weights(p, p, p, p, p, None)
     need = ws(cfg)[1]
     call = lambda w_, x, out, wsp, n: lib.cca_forward(C.byref(cc), C.byref(w_), x, out, None, wsp, n, None)
     assert call(w, None, p, p, need) == B.CCA_ERR_NULL
-    assert call(B.cca_weights(None, p, p, p, p), p, p, p, need) == B.CCA_ERR_NULL
-    assert call(B.cca_weights(p, None, p, p, p), p, p, p, need) == B.CCA_ERR_NULL   # conv flag on, weight missing
+    assert call(B.cca_weights(None, p, p, p, p, None), p, p, p, need) == B.CCA_ERR_NULL
+    assert call(B.cca_weights(p, None, p, p, p, None), p, p, p, need) == B.CCA_ERR_NULL   # conv flag on, weight missing
     assert call(w, C.c_void_p(0x10008), p, p, need) == B.CCA_ERR_ALIGN
     assert call(w, p, p, p, need - 1) == B.CCA_ERR_WORKSPACE
     assert call(w, p, p, None, need) == B.CCA_ERR_WORKSPACE
@@ -89,7 +150,7 @@ def test_backward_rejects_null_misaligned_and_small_workspace():
     cfg = good()
     cc = cfg.c()
     p = C.c_void_p(0x10000)  # fake device addresses: validation fails before anything is dereferenced or enqueued
-    w = B.cca_weights(p, p, p, p, p)
+    w = B.cca_weights(p, p, p, p, p, None)
     sv = B.cca_saved(p, p, p, p, p, p, p, None)
     gr = B.cca_grads(p, p, p, p, p)
     n = C.c_size_t(0)
@@ -122,7 +183,7 @@ def test_decode_rejects_bad_arguments_and_reports_ring_depth():
     cfg = good()
     cc = cfg.c()
     p = C.c_void_p(0x10000)  # fake device addresses: validation fails before anything is dereferenced or enqueued
-    w = B.cca_weights(p, p, p, p, p)
+    w = B.cca_weights(p, p, p, p, p, None)
     st = B.cca_decode_state(p, p, p)
     n, ring = C.c_size_t(0), C.c_int32(0)
     assert lib.cca_decode_workspace_size(C.byref(cc), C.byref(n), C.byref(ring)) == B.CCA_OK and n.value > 0
@@ -140,7 +201,7 @@ def test_decode_rejects_bad_arguments_and_reports_ring_depth():
     assert call(w, None, st, 0, p, p, need.value) == B.CCA_ERR_NULL
     assert call(w, p, None, 0, p, p, need.value) == B.CCA_ERR_NULL
     assert call(w, p, B.cca_decode_state(p, None, p), 0, p, p, need.value) == B.CCA_ERR_NULL
-    assert call(B.cca_weights(None, p, p, p, p), p, st, 0, p, p, need.value) == B.CCA_ERR_NULL
+    assert call(B.cca_weights(None, p, p, p, p, None), p, st, 0, p, p, need.value) == B.CCA_ERR_NULL
     assert call(w, p, st, -1, p, p, need.value) == B.CCA_ERR_SHAPE
     assert call(w, p, st, cfg.T, p, p, need.value) == B.CCA_ERR_SHAPE
     assert call(w, C.c_void_p(0x10004), st, 0, p, p, need.value) == B.CCA_ERR_ALIGN

@@ -5,7 +5,13 @@ Tolerances.  fp32 storage: 1e-5 relative (rel-L2, and max-abs against the larges
 storage: the benchmark spec's 1e-2 rel-L2; every gradient passes through up to six tensors stored in bf16 (d_o, d_q /
 d_k / d_v, the gradient entering the convolutions, d_lat, the result; P and dS inside attention), each adding
 about 1e-3 rms relative error, so ~3e-3 is expected.  max-abs is bounded relative to the largest reference
-magnitude (gradients are not O(1) quantities): 2e-2 * max|ref|."""
+magnitude (gradients are not O(1) quantities): 2e-2 * max|ref|.
+
+The two convolution-filter gradients get 1.5e-2: they sum the gradient entering the convolutions over all tokens,
+and the error of that gradient is not random from token to token (rounding a query or key moves the probability
+mass of its whole row), so it does not average out.  Storing lat, q, k, v in bf16 and doing everything else
+exactly already puts 5e-3 .. 8e-3 on them at d_h = 64 (test_filter_gradient_error_against_the_storage_floor
+computes that floor with the oracle and bounds the kernel's error by 1.6 times it)."""
 import sys
 
 import numpy as np
@@ -63,6 +69,7 @@ def compare(got, ref, dtype, skip=()):
             # against the sum of the magnitudes of its terms, not against the cancelled result
             err = np.abs(to_np(got[key]) - ref[key])
             res[key] = (rel, float((err / np.maximum(ref["d_temp_abs"], 1e-300)).max()))
+            res["d_temp_rel_to_value"] = float((err / np.maximum(np.abs(ref[key]), 1e-300)).max())
             floor = 1e-6 if dtype == "bf16" else 1e-9  # T = 1: every term is zero by construction (see below)
             assert (err <= rtol * ref["d_temp_abs"] + floor).all(), f"d_temp: err={err}, scale={ref['d_temp_abs']}"
             continue
@@ -73,7 +80,11 @@ def compare(got, ref, dtype, skip=()):
             assert mx <= (1e-6 if dtype == "bf16" else 1e-9), f"{key}: reference is zero, max_abs={mx:.3e}"
             continue
         res[key] = (rel, mx / scale)
-        assert rel <= rtol and mx <= arel * scale, f"{key}: rel_l2={rel:.3e} (<= {rtol}), max_abs={mx:.3e} (<= {arel * scale:.3e})"
+        if dtype == "bf16" and key in ("d_w_conv_seq", "d_w_conv_ch"):
+            rtol_k = 1.5e-2  # see the module docstring
+        else:
+            rtol_k = rtol
+        assert rel <= rtol_k and mx <= arel * scale, f"{key}: rel_l2={rel:.3e} (<= {rtol}), max_abs={mx:.3e} (<= {arel * scale:.3e})"
     return res
 
 
@@ -91,6 +102,11 @@ SMALL = [
     # d_h = 64 on the matrix-core attention backward: several key blocks, ragged tail, R = 4; R = 1
     dict(B=2, T=700, E=512, Hq=8, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=1, T=300, E=256, Hq=3, Hk=3, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    # group sizes that are not a power of two: R = 3 (d_h 128), R = 6 (d_h 64), R = 3 (d_h 64), R = 6 (d_h 128)
+    dict(B=2, T=400, E=1536, Hq=6, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=520, E=768, Hq=6, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=2, T=270, E=768, Hq=6, Hk=2, dh=64, k_seq=2, k_ch=1, dtype="bf16", paper_flags=True),
+    dict(B=1, T=300, E=768, Hq=6, Hk=1, dh=128, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
 ]
 
 
@@ -105,7 +121,7 @@ def test_backward_small_shapes(i):
     say(compare(got, ref, w["dtype"]))
 
 
-@pytest.mark.parametrize("i", [3, 4, 7, 9])
+@pytest.mark.parametrize("i", [3, 4, 7, 9, 11, 12])
 def test_backward_small_shapes_literal_weights(i):
     """0.02-scaled weights: the softmax is nearly flat, the regime in which <d_o, o> taken from the bf16-rounded o
     alone would put a 2 % error on d_q / d_k and, through them, on the convolution filter gradients."""
@@ -115,6 +131,56 @@ def test_backward_small_shapes_literal_weights(i):
     d_out = make_upstream_grad(w, seed=1)
     got, _ = gpu_backward(w, inp, d_out)
     say(compare(got, oracle_backward(w, inp, d_out), w["dtype"]))
+
+
+@pytest.mark.parametrize("dh,Hq,Hk,T", [(128, 4, 2, 384), (64, 6, 2, 300)])
+def test_d_temp_relative_error(dh, Hq, Hk, T):
+    """d_temp against its own value.  With a random upstream gradient the per-token terms <d_k, k> cancel 50:1
+    and only a bound relative to the sum of their magnitudes is meaningful (compare()).  Here the upstream
+    gradient is 4 * out (the loss 2 |out|^2), for which the terms mostly share a sign, so the relative error of
+    the value itself is asserted; the test first checks on the oracle that the input has that property."""
+    w = dict(B=2, T=T, E=Hq * dh * 2, Hq=Hq, Hk=Hk, dh=dh, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
+    say("case d_temp relative", w)
+    inp = make_inputs(w, seed=77, conv_visible=True)  # temp ~ N(0, 0.5)
+    fwd = O.cca_forward(inp["x"], inp["w_down"], inp["w_conv_seq"], inp["w_conv_ch"], inp["temp"], inp["w_out"],
+                        n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh)
+    d_out = round_to_bf16((4.0 * fwd["out"]).astype(np.float32))
+    ref = oracle_backward(w, inp, d_out)
+    ratio = np.abs(ref["d_temp"]) / ref["d_temp_abs"]
+    assert (ratio >= 0.5).all(), f"input property lost: the terms of d_temp cancel ({ratio})"
+    got, _ = gpu_backward(w, inp, d_out)
+    rel = np.abs(to_np(got["d_temp"]) - ref["d_temp"]) / np.abs(ref["d_temp"])
+    say("d_temp", to_np(got["d_temp"]), "reference", ref["d_temp"], "relative error", rel, "uncancelled share", ratio)
+    assert (rel <= 1e-2).all(), rel
+    say(compare(got, ref, "bf16"))
+
+
+def test_filter_gradient_error_against_the_storage_floor():
+    """The convolution-filter gradients of the least accurate small case (d_h = 64, R = 3) against the error that
+    bf16 STORAGE of lat, q, k, v alone causes: the oracle's adjoint is run once more with those four tensors
+    rounded to bf16 (once each) and everything else in fp64.  The HIP path also rounds P, dS, d_o, d_q, d_k, d_v,
+    the gradient entering the convolutions and d_lat, and rounds q * scale * log2(e) a second time; all of that
+    together may add at most 60 % to the floor."""
+    w = SMALL[13]
+    say("case filter gradients vs storage floor", w)
+    inp = make_inputs(w, seed=53, conv_visible=True)
+    d_out = make_upstream_grad(w, seed=1)
+    ref = oracle_backward(w, inp, d_out)
+    r64 = lambda a: round_to_bf16(np.asarray(a, np.float32)).astype(np.float64)
+    att, attb, dp = O.attention, O.attention_bwd, O.down_project
+    try:  # planted on the CPU side only: the oracle with bf16 storage of lat, q, k, v
+        O.attention = lambda q, k, v, s, **kw: att(r64(q), r64(k), r64(v), s, **kw)
+        O.attention_bwd = lambda do, q, k, v, s, **kw: attb(do, r64(q), r64(k), r64(v), s, **kw)
+        O.down_project = lambda *a, **kw: tuple(r64(t) for t in dp(*a, **kw))
+        floor = oracle_backward(w, inp, d_out)
+    finally:
+        O.attention, O.attention_bwd, O.down_project = att, attb, dp
+    got, _ = gpu_backward(w, inp, d_out)
+    for key in ("d_w_conv_seq", "d_w_conv_ch", "d_x", "d_w_down"):
+        fl = errors(floor[key], ref[key])[0]
+        rel = errors(to_np(got[key]), ref[key])[0]
+        say(key, "storage floor", fl, "HIP path", rel, "ratio", rel / fl)
+        assert rel <= 1.6 * fl, (key, rel, fl)
 
 
 def test_backward_tiny_fp32_literal():

@@ -19,10 +19,10 @@ def say(*a):
     sys.stdout.flush()
 
 
-def decode_all(w, inp, start=0, flags=None):
+def decode_all(w, inp, start=0, flags=None, **cfg_kw):
     """Prefill tokens [0, start) with cca_forward, then decode tokens start..T-1 one by one.  Returns out
     (B, T - start, E) and the final state."""
-    kw = {} if flags is None else dict(flags=flags)
+    kw = dict(cfg_kw) if flags is None else dict(cfg_kw, flags=flags)
     cfg = P.config_from_workload(w, **kw)
     x, wt = P.weights_to_device(cfg, inp)
     state = P.CCADecodeState.allocate(cfg, x.device)
@@ -95,6 +95,17 @@ def test_decode_flags(name):
     out, _ = decode_all(w, inp, flags=flags)
     ref = oracle_forward(w, inp, **okw)
     say(check_out(to_np(out), ref["out"], w["dtype"]))
+
+
+def test_decode_norm_epsilon():
+    """cfg.norm_eps reaches the decode prologue (prefill of 9 tokens by the fused kernel, then token by token)."""
+    w = dict(B=2, T=30, E=512, Hq=4, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
+    inp = make_inputs(w, seed=92, conv_visible=True)
+    eps = float(np.median((oracle_forward(w, inp)["q3"] ** 2).sum(-1)) / 3)
+    say("case decode norm_eps", w, eps)
+    out, _ = decode_all(w, inp, start=9, norm_eps=eps)
+    ref = oracle_forward(w, inp, norm_eps=eps)
+    say(check_out(to_np(out), ref["out"][:, 9:], w["dtype"]))
 
 
 def test_decode_long_cache_split_over_workgroups():

@@ -85,6 +85,11 @@ SMALL = [
     # d_h = 64 on the fused prologue: three taps, R = 4, several 256-token tiles with a ragged tail, T past 128 * 8
     dict(B=2, T=1100, E=512, Hq=8, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=1, T=260, E=512, Hq=3, Hk=3, dh=64, k_seq=1, k_ch=3, dtype="bf16", paper_flags=True),
+    # group sizes that are not a power of two (R = 3, R = 6) on the fused prologue and the matrix-core attention
+    dict(B=2, T=400, E=1536, Hq=6, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=300, E=768, Hq=6, Hk=1, dh=128, k_seq=2, k_ch=1, dtype="bf16", paper_flags=True),
+    dict(B=2, T=520, E=768, Hq=6, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=270, E=768, Hq=12, Hk=2, dh=64, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
 ]
 
 
@@ -99,7 +104,7 @@ def test_small_shapes(i, conv_visible):
     say(res)
 
 
-@pytest.mark.parametrize("i", [1, 2, 3, 5, 6, 8])
+@pytest.mark.parametrize("i", [1, 2, 3, 5, 6, 8, 10, 13])
 @pytest.mark.parametrize("causal", [True, False])
 def test_small_shapes_inference_path(i, causal):
     """Without saved tensors the attention kernel takes its inference form (row sums of the unrounded
@@ -160,7 +165,8 @@ def test_mha_gqa_flags(Hq, Hk):
 # ---- stage level: attention on oracle-made latents --------------------------
 @pytest.mark.parametrize("mode", ["normed", "normed_hot", "free"])
 @pytest.mark.parametrize("T,Hq,Hk,dh,causal", [(1000, 8, 2, 128, True), (640, 4, 4, 128, False),
-                                                (257, 2, 1, 64, True), (513, 4, 2, 128, True)])
+                                                (257, 2, 1, 64, True), (513, 4, 2, 128, True),
+                                                (700, 6, 2, 128, True), (330, 6, 1, 64, True), (450, 12, 2, 64, False)])
 def test_attention_stage(T, Hq, Hk, dh, causal, mode):
     """normed: q, k on the spheres the prologue produces (bounded-score path of the kernel);
     normed_hot: same with a temperature large enough that the kernel must fall back to the running max;
@@ -193,11 +199,61 @@ def test_attention_stage(T, Hq, Hk, dh, causal, mode):
     o_ref, lse_ref = O.attention(q, k, v, 1.0 / np.sqrt(dh), causal=causal)
     say("o", check_tap(to_np(o).reshape(o_ref.shape), o_ref, "bf16", "o"))
     rel, mx = errors(to_np(lse), lse_ref)
-    # The kernel rounds q * scale * log2(e) to bf16 once more, a relative perturbation of up to 2^-9 per
-    # factor; lse follows its dominating logits, so allow 2^-10 of the largest possible |logit| (>= 8e-3).
-    smax = float(np.linalg.norm(q, axis=-1).max() * np.linalg.norm(k, axis=-1).max() / np.sqrt(dh))
-    lim = 2.0 ** -10 * max(8.0, smax)
+    lim, worst = lse_bounds(q, k, dh)
+    say("lse", dict(max_abs=mx, asserted=lim, worst_case=worst, measured_over_asserted=mx / lim))
     assert mx <= lim, ("lse", rel, mx, lim)
+
+
+def lse_bounds(q, k, dh):
+    """Error model of lse (natural-log units).  The kernel multiplies each q component by c = scale * log2(e)
+    and rounds it to bf16 again: q'_i = q_i c (1 + d_i), |d_i| <= 2^-8 (bf16 keeps 8 significant bits: half a
+    unit in the last place is 2^-8 of a number just above a power of two), so a logit s = scale * <q, k> is off
+    by sum_i scale q_i k_i d_i, at most 2^-8 * scale * sum_i |q_i k_i| <= 2^-8 s_max with s_max = scale |q| |k|
+    (every d_i at its limit with the sign of q_i k_i: test_lse_error_worst_case constructs that input), and lse
+    is a soft maximum of the logits (its gradient is a probability vector), so its error is bounded by the same
+    number.  On top: the row sum adds probabilities rounded to bf16 (relative 2^-8 each at worst, so 2^-8 on lse)
+    and fp32 arithmetic.  Worst case: 2^-8 (s_max + 1) + 1e-3.  For inputs whose d_i are not aligned the d_i
+    average out over the d_h terms (rms 2^-8 / sqrt(12) each); the bound ASSERTED for such inputs is a quarter of
+    the worst case of the logit term with a floor for the other two terms, 2^-10 max(8, s_max): tighter than
+    anything the error model can guarantee."""
+    smax = float(np.linalg.norm(q, axis=-1).max() * np.linalg.norm(k, axis=-1).max() / np.sqrt(dh))
+    return 2.0 ** -10 * max(8.0, smax), 2.0 ** -8 * (smax + 1.0) + 1e-3
+
+
+def test_lse_error_worst_case():
+    """Pins the lse error model from above: an input built so that the kernel's second bf16 rounding of
+    q * scale * log2(e) errs the same way in every component (each q_i is the bf16 number in [0.5, 1) whose
+    product with c is rounded up the most) and one key per row is aligned with the query.  The measured lse
+    error must stay inside the worst-case bound and reach a good part of it (so the bound is not slack that
+    could hide a defect), while the bound asserted for ordinary inputs, a quarter of it, is exceeded here."""
+    dh, T, Hq, Hk, Bn = 128, 300, 2, 1, 1
+    c = np.float32(1.0 / np.sqrt(dh)) * np.float32(1.44269504088896340736)
+    grid = (np.arange(128, 256, dtype=np.float32) / np.float32(256.0))  # bf16 numbers in [0.5, 1)
+    prod = (grid * c).astype(np.float32)
+    d = (round_to_bf16(prod).astype(np.float64) - prod.astype(np.float64)) / prod.astype(np.float64)
+    v0 = float(grid[int(np.argmax(d))])
+    say("worst-case q component", v0, "relative rounding error of q*c", float(d.max()), "limit", 2.0 ** -8)
+    rng = np.random.default_rng(5)
+    sign = np.where(rng.random((Bn, T, Hq, dh)) < 0.5, -1.0, 1.0)
+    q = (v0 * sign).astype(np.float32)                      # |q| = v0 sqrt(d_h) <= sqrt(d_h): inside the promise
+    k = rng.standard_normal((Bn, T, Hk, dh))
+    k *= np.sqrt(dh) / np.linalg.norm(k, axis=-1, keepdims=True)
+    k[:, ::2] = sign[:, ::2, :1]                            # even keys: aligned with head 0's query of the same token
+    v = rng.standard_normal((Bn, T, Hk, dh))
+    q, k, v = (round_to_bf16(np.asarray(a, np.float32)) for a in (q, k, v))
+    cfg = P.CCAConfig(B=Bn, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh, flags=B.CCA_FLAGS_PAPER)
+    dev = lambda a: torch.from_numpy(a).to("cuda", torch.bfloat16)
+    o, lse = P.cca_attention(cfg, dev(q), dev(k), dev(v), want_lse=True, temp=torch.zeros(Hk, device="cuda"))
+    torch.cuda.synchronize()
+    o_ref, lse_ref = O.attention(q, k, v, 1.0 / np.sqrt(dh), causal=True)
+    err = np.abs(to_np(lse) - lse_ref)[:, 0, ::2]           # rows whose own (aligned) key dominates
+    lim, worst = lse_bounds(q, k, dh)
+    say("lse worst case", dict(max_abs=float(err.max()), asserted_for_ordinary_inputs=lim, worst_case=worst))
+    assert err.max() <= worst
+    s_aligned = v0 * np.sqrt(dh)                            # the dominating logit, scale * <q, k> = v0 sqrt(d_h)
+    assert err.max() >= 0.6 * 2.0 ** -8 * s_aligned, "the constructed input no longer exercises the rounding of q"
+    assert err.max() > lim, "the bound asserted for ordinary inputs is not expected to hold for this input"
+    say("o", check_tap(to_np(o).reshape(o_ref.shape), o_ref, "bf16", "o"))
 
 
 # ---- config 2: CCA prefill bf16, T = 4096, literal and conv-visible ----------
@@ -265,7 +321,8 @@ def test_forward_is_deterministic_and_causal_on_gpu():
 
 
 # ---- backward of the attention stage against the oracle's adjoint ------------------------------
-@pytest.mark.parametrize("T,Hq,Hk,causal", [(700, 8, 2, True), (333, 4, 4, True), (520, 4, 1, False), (64, 2, 2, True)])
+@pytest.mark.parametrize("T,Hq,Hk,causal", [(700, 8, 2, True), (333, 4, 4, True), (520, 4, 1, False), (64, 2, 2, True),
+                                            (450, 6, 2, True), (300, 6, 1, False)])
 def test_attention_backward_stage(T, Hq, Hk, causal):
     say("case attention backward", T, Hq, Hk, causal)
     dh, Bn = 128, 2
@@ -309,3 +366,43 @@ def test_head_to_head_b4_sampled_rows(name):
                      lse=pick(saved.lse), rnorm=pick(saved.rnorm), o_lo=pick(saved.o_lo))
     res = compare_all(w2, inp, ref, pick(out), sub, rows=rows)
     say(res)
+
+
+# ---- options of the interface: epsilon under the norm, prepared weights --------------------------------------
+@pytest.mark.parametrize("i", [0, 2, 8])
+def test_norm_epsilon(i):
+    """cfg.norm_eps > 0 on the generic (fp32), the fused d_h = 128 and the fused d_h = 64 prologue; large enough
+    (a third of a typical sum of squares) that ignoring it would fail the q / k taps."""
+    w = SMALL[i]
+    inp = make_inputs(w, seed=70 + i, conv_visible=True)
+    pre = oracle_forward(w, inp)
+    eps = float(np.median((pre["q3"] ** 2).sum(-1)) / 3)
+    say("case norm_eps", i, w, "eps", eps)
+    cfg, out, saved = run_gpu(w, inp, norm_eps=eps)
+    ref = oracle_forward(w, inp, norm_eps=eps)
+    assert errors(pre["q"], ref["q"])[0] > 0.05  # the option matters for this input
+    res = compare_all(w, inp, ref, out, saved)
+    say(res)
+
+
+@pytest.mark.parametrize("i", [2, 3, 8, 10])
+def test_prepared_weights_give_identical_results(i):
+    """cca_prepare + cca_forward(weights.prepared) against cca_forward deriving the same data per call: bit for
+    bit, for a batch size other than the one the buffer was prepared under, with and without saved tensors."""
+    w = SMALL[i]
+    say("case prepared", i, w)
+    inp = make_inputs(w, seed=80 + i, conv_visible=True)
+    cfg = P.config_from_workload(w)
+    x, wt = P.weights_to_device(cfg, inp)
+    wt_p = P.cca_prepare(P.config_from_workload(dict(w, B=w["B"] + 3)), wt)
+    torch.cuda.synchronize()
+    out_a = P.cca_forward(cfg, wt, x)
+    out_b = P.cca_forward(cfg, wt_p, x)
+    s_a, s_b = P.CCASaved.allocate(cfg, x.device), P.CCASaved.allocate(cfg, x.device)
+    out_c = P.cca_forward(cfg, wt, x, saved=s_a)
+    out_d = P.cca_forward(cfg, wt_p, x, saved=s_b)
+    torch.cuda.synchronize()
+    assert torch.equal(out_a, out_b) and torch.equal(out_c, out_d)
+    for name in ("lat", "q", "k", "v", "o", "lse", "rnorm"):
+        assert torch.equal(getattr(s_a, name), getattr(s_b, name)), name
+    say(check_out(to_np(out_b), oracle_forward(w, inp)["out"], w["dtype"]))

@@ -36,6 +36,7 @@ FLAGSETS = [
     dict(use_qk_norm=False, use_key_temp=False),
     dict(use_key_temp=False, rope_interleaved=True),
     dict(causal=False),
+    dict(norm_eps=0.7),
 ]
 
 

@@ -295,3 +295,25 @@ def test_planted_mistakes_are_caught(monkeypatch):
     monkeypatch.setattr(O, "value_shift", bad_shift)
     with pytest.raises(AssertionError):
         test_first_token_closed_form()
+
+
+def test_norm_epsilon_option_closed_form():
+    """The library's optional epsilon under the L2 norm (not in the paper: eps = 0 is the paper's norm and must
+    leave every result bit for bit as it was): |q4| = sqrt(d) |q3| / sqrt(|q3|^2 + eps), direction unchanged."""
+    rng = np.random.default_rng(11)
+    q3 = rng.standard_normal((2, 5, 4, 8))
+    k3 = rng.standard_normal((2, 5, 2, 8))
+    temp = np.array([0.3, -0.2])
+    q_a, k_a = O.qk_norm_temp(q3, k3, temp)
+    q_b, k_b = O.qk_norm_temp(q3, k3, temp, eps=0.0)
+    assert np.array_equal(q_a, q_b) and np.array_equal(k_a, k_b)
+    eps = 2.5
+    q_e, k_e = O.qk_norm_temp(q3, k3, temp, eps=eps)
+    n2q, n2k = (q3 * q3).sum(-1), (k3 * k3).sum(-1)
+    np.testing.assert_allclose(np.linalg.norm(q_e, axis=-1), np.sqrt(8 * n2q / (n2q + eps)), rtol=1e-14)
+    np.testing.assert_allclose(np.linalg.norm(k_e, axis=-1), np.sqrt(8 * n2k / (n2k + eps)) * np.exp(temp), rtol=1e-14)
+    np.testing.assert_allclose(q_e / np.linalg.norm(q_e, axis=-1, keepdims=True),
+                               q3 / np.linalg.norm(q3, axis=-1, keepdims=True), rtol=1e-13)
+    # an all-zero head vector stays finite (zero) once eps > 0
+    z, _ = O.qk_norm_temp(np.zeros((1, 1, 1, 8)), np.ones((1, 1, 1, 8)), None, eps=1e-6)
+    assert np.array_equal(z, np.zeros((1, 1, 1, 8)))
