@@ -17,7 +17,8 @@
  *   - Every data pointer is a DEVICE pointer (HIP), row-major, contiguous,
  *     16-byte aligned, owned by the caller.  The config / weight / saved
  *     structs themselves live in HOST memory.
- *   - The library never allocates, frees or synchronises.  All work is
+ *   - The library never allocates, frees or synchronises (the one buffer it
+ *     owns is the fixed array behind cca_decode_step_static).  All work is
  *     enqueued on the caller's stream (`hip_stream` is a hipStream_t, NULL =
  *     the default stream) and the call returns at once.
  *   - Arguments are validated on the host before the first HIP call; a failed
@@ -26,7 +27,8 @@
  *     out.  Accumulation is always fp32.  bf16 tensors are rounded to nearest
  *     even once per stored tensor.
  *   - No global mutable state: calls on different streams may run
- *     concurrently as long as their buffers (workspace included) are disjoint.
+ *     concurrently as long as their buffers (workspace included) are disjoint
+ *     (cca_decode_step_static is the exception: see there).
  *
  * Symbols: B batch, T sequence length, E = d_model, H_q / H_k latent query /
  * KV heads, d_h latent head width, e_q = H_q*d_h (= E/C1), e_kv = H_k*d_h
@@ -271,6 +273,24 @@ cca_status cca_decode_workspace_size(const cca_config *cfg, size_t *bytes, int32
 cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const void *x_new,
                            const cca_decode_state *state, int32_t pos, void *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
+
+/* cca_decode_step for callers that cannot hand over a workspace and must not
+ * allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results and errors as
+ * cca_decode_step, but the step's scratch (new query, attention partial sums
+ * per cache split, split-K sums of the two projections) lives in a
+ * CCA_DECODE_STATIC_BYTES array that is part of the loaded library (one copy
+ * per GPU, held until the process ends).  Calls no allocating routine.
+ * Returns CCA_ERR_WORKSPACE when cca_decode_workspace_size(cfg) exceeds
+ * CCA_DECODE_STATIC_BYTES (nothing is enqueued then) and CCA_ERR_LAUNCH when
+ * the array's address cannot be obtained on the current device.  Every call
+ * on a GPU uses that GPU's one array: two calls whose kernels may overlap in
+ * time on the same GPU (different streams, or concurrent host threads) race;
+ * calls on one stream are ordered and safe.  Nothing in the array has to
+ * start at zero: each step writes every partial sum before reading it. */
+#define CCA_DECODE_STATIC_BYTES (16u << 20)
+cca_status cca_decode_step_static(const cca_config *cfg, const cca_weights *w, const void *x_new,
+                                  const cca_decode_state *state, int32_t pos, void *out, void *hip_stream);
 
 /* Measurement aid (not a step of the method): enqueues a kernel of `blocks`
  * workgroups x 4 wavefronts that issue iters x 4 independent 32x32x16 bf16

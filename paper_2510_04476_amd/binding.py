@@ -30,7 +30,7 @@ CCA_FLAGS_MHA = CCA_CAUSAL
 EXPORTS = ("cca_workspace_size", "cca_backward_workspace_size", "cca_prepared_size", "cca_prepare", "cca_forward",
            "cca_backward", "cca_down_project",
            "cca_prologue", "cca_attention", "cca_attention_backward", "cca_prologue_backward", "cca_up_project",
-           "cca_decode_workspace_size", "cca_decode_step", "cca_probe_mfma_rate", "cca_strerror", "cca_version")
+           "cca_decode_workspace_size", "cca_decode_step", "cca_decode_step_static", "cca_probe_mfma_rate", "cca_strerror", "cca_version")
 
 
 class cca_config(C.Structure):
@@ -96,6 +96,8 @@ def load_library() -> C.CDLL:
                                  C.POINTER(cca_grads), vp, sz, vp]
     lib.cca_prologue_backward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, vp, vp, vp, vp, vp, vp,
                                           C.POINTER(cca_grads), vp, sz, vp]
+    lib.cca_decode_step_static.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_decode_state), C.c_int32, vp,
+                                           vp]
     lib.cca_probe_mfma_rate.argtypes = [vp, sz, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
@@ -437,6 +439,19 @@ def cca_decode_step(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecodeState,
     cc, cw, cs = cfg.c(), w.c(), state.c()
     _check(lib.cca_decode_step(C.byref(cc), C.byref(cw), _ptr(x_new), C.byref(cs), C.c_int32(pos), _ptr(out),
                                _ptr(state.workspace), C.c_size_t(state.workspace.numel()), _stream()), "cca_decode_step")
+    return out
+
+
+CCA_DECODE_STATIC_BYTES = 16 << 20
+
+
+def cca_decode_step_static(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecodeState, pos: int, out):
+    """cca_decode_step on the library's built-in scratch: no workspace argument, nothing allocated (the caller
+    passes `out`)."""
+    lib = load_library()
+    cc, cw, cs = cfg.c(), w.c(), state.c()
+    _check(lib.cca_decode_step_static(C.byref(cc), C.byref(cw), _ptr(x_new), C.byref(cs), C.c_int32(pos), _ptr(out),
+                                      _stream()), "cca_decode_step_static")
     return out
 
 

@@ -2,9 +2,36 @@
 // carving and the chaining of the four stages on the caller's stream.
 #include <math.h>
 
+#include <mutex>
+
 #include "cca_internal.h"
 
+// Scratch of cca_decode_step_static: part of the loaded code object, one copy per GPU, never allocated or freed.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels get the device address it returns.
+static __device__ __align__(256) unsigned char cca_decode_static_scratch[CCA_DECODE_STATIC_BYTES];
+
 namespace cca {
+
+// Device address of the static scratch on the current device, looked up once per device.
+static hipError_t decode_static_scratch(void **ptr) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void *addr[MAX_DEVICES] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(cca_decode_static_scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
+}
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -469,22 +496,45 @@ cca_status cca_decode_workspace_size(const cca_config *cfg, size_t *bytes, int32
   return CCA_OK;
 }
 
+// Argument checks shared by the two decode entry points (no HIP call).
+static cca_status decode_validate(const cca_config *cfg, Dims *d, const cca_weights *w, const void *x_new,
+                                  const cca_decode_state *state, int32_t pos, const void *out) {
+  cca_status st = make_dims(cfg, d);
+  if (st != CCA_OK) return st;
+  if (d->dh % 8 != 0) return CCA_ERR_UNSUPPORTED;
+  if (!w || !x_new || !state || !out || !state->k_cache || !state->v_cache || !state->lat_ring) return CCA_ERR_NULL;
+  if (!w->w_down || !w->w_out) return CCA_ERR_NULL;
+  if (pos < 0 || pos >= d->T) return CCA_ERR_SHAPE;
+  st = check_prologue_weights(*d, w);
+  if (st != CCA_OK) return st;
+  if (!aligned16(x_new) || !aligned16(out) || !aligned16(state->k_cache) || !aligned16(state->v_cache) ||
+      !aligned16(state->lat_ring) || !aligned16(w->w_down) || !aligned16(w->w_out))
+    return CCA_ERR_ALIGN;
+  return CCA_OK;
+}
+
 cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const void *x_new, const cca_decode_state *state,
                            int32_t pos, void *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
   Dims d;
-  cca_status st = make_dims(cfg, &d);
+  cca_status st = decode_validate(cfg, &d, w, x_new, state, pos, out);
   if (st != CCA_OK) return st;
-  if (d.dh % 8 != 0) return CCA_ERR_UNSUPPORTED;
-  if (!w || !x_new || !state || !out || !state->k_cache || !state->v_cache || !state->lat_ring) return CCA_ERR_NULL;
-  if (!w->w_down || !w->w_out) return CCA_ERR_NULL;
-  if (pos < 0 || pos >= d.T) return CCA_ERR_SHAPE;
-  st = check_prologue_weights(d, w);
-  if (st != CCA_OK) return st;
-  if (!aligned16(x_new) || !aligned16(out) || !aligned16(state->k_cache) || !aligned16(state->v_cache) ||
-      !aligned16(state->lat_ring) || !aligned16(w->w_down) || !aligned16(w->w_out) || !aligned16(workspace))
-    return CCA_ERR_ALIGN;
+  if (!aligned16(workspace)) return CCA_ERR_ALIGN;
   if (!workspace || workspace_bytes < decode_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
   return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, out, workspace,
+                     (hipStream_t)hip_stream) == hipSuccess
+             ? CCA_OK
+             : CCA_ERR_LAUNCH;
+}
+
+cca_status cca_decode_step_static(const cca_config *cfg, const cca_weights *w, const void *x_new,
+                                  const cca_decode_state *state, int32_t pos, void *out, void *hip_stream) {
+  Dims d;
+  cca_status st = decode_validate(cfg, &d, w, x_new, state, pos, out);
+  if (st != CCA_OK) return st;
+  if (decode_scratch_bytes(d) > (size_t)CCA_DECODE_STATIC_BYTES) return CCA_ERR_WORKSPACE;  // does not fit the array
+  void *scratch = nullptr;  // first HIP call: everything above is host arithmetic
+  if (decode_static_scratch(&scratch) != hipSuccess) return CCA_ERR_LAUNCH;
+  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, out, scratch,
                      (hipStream_t)hip_stream) == hipSuccess
              ? CCA_OK
              : CCA_ERR_LAUNCH;
