@@ -222,6 +222,30 @@ def main() -> int:
                           "calibration_copy_bytes_each_way": 256 << 20}))
         return 0
 
+    def timed(fn, n):
+        """Average duration of n back-to-back launches of fn: one HIP event before the first and one after the
+        last, both on the stream the launches go to (torch's current stream, the one the binding passes)."""
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    # ---- measured ceilings beside the nominal peaks: matrix-core rate of an MFMA-only kernel (the clock the chip
+    #      holds under that load sets it), and the device-to-device copy rate of a 1 GiB buffer (read + write).
+    #      Taken first: they also bring the chip out of its idle clocks before anything is timed. ------------------
+    mfma_meas = P.cca_probe_mfma_rate()
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=x.device).fill_(1)
+    dst = torch.empty_like(src)
+    copy_ms = timed(lambda: dst.copy_(src), 5)
+    hbm_meas = 2.0 * src.numel() / copy_ms / 1e6
+    del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -245,18 +269,6 @@ def main() -> int:
 
     # ---- per-stage kernels on their own, HIP events on the launch stream --------------------
     P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
-
-    def timed(fn, n):
-        for _ in range(3):
-            fn()
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-        torch.cuda.synchronize()
-        for a, b in evs:
-            a.record()
-            fn()
-            b.record()
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in evs) / n
 
     n_ev = max(10, min(args.steps, 50))
     attn_ms = timed(lambda: P.cca_attention(cfg, saved.q, saved.k, saved.v, o=saved.o, lse=None, temp=wt.temp), n_ev)
@@ -405,14 +417,6 @@ def main() -> int:
                "parity_rel_l2": rel, "parity_max_abs": mx, "parity_of": "output of the timed inference call",
                "parity_saving_form_rel_l2": rel_s, "parity_saving_form_max_abs": mx_s}
 
-    # ---- measured ceilings beside the nominal peaks: matrix-core rate of an MFMA-only kernel (the clock the chip
-    #      holds under that load sets it), and the device-to-device copy rate of a 1 GiB buffer (read + write) ------
-    mfma_meas = P.cca_probe_mfma_rate()
-    src = torch.empty(1 << 30, dtype=torch.uint8, device=x.device).fill_(1)
-    dst = torch.empty_like(src)
-    copy_ms = timed(lambda: dst.copy_(src), 5)
-    hbm_meas = 2.0 * src.numel() / copy_ms / 1e6
-    del src, dst
     ceilings = {"mfma_bf16_tflops_measured": round(mfma_meas, 1), "mfma_bf16_tflops_nominal": PEAK_BF16_TFLOPS,
                 "hbm_copy_gbps_measured": round(hbm_meas, 1), "hbm_gbps_nominal": 8000.0,
                 "attention_frac_of_measured_mfma": round(attn_tflops / mfma_meas, 4)}

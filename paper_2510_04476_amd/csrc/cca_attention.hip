@@ -74,7 +74,9 @@ __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 
 // BOUNDED: the caller guarantees |score| <= bound (log2 units) for every query / key pair, as the QK L2-norm
 // of Sec. 2.2 does (|q| = sqrt(d_h), |k| = sqrt(d_h) * beta).  Then `bound` itself serves as the reference max
 // of every row: no row max, no rescaling, and exp2 arguments lie in [-2*bound, 0].
-template <int DH, bool CAUSAL, bool BOUNDED, bool RSUM>
+// NTH threads = NTH / 64 wavefronts x 32 rows = BQ_ query rows per workgroup: 512 threads (256 rows, two wavefronts
+// per SIMD) for d_h <= 128, 256 threads (128 rows, one wavefront per SIMD and twice the registers) for d_h = 256.
+template <int DH, bool CAUSAL, bool BOUNDED, bool RSUM, int NTH = NT>
 __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                               const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
                                               bf16_t *__restrict__ OLO, float *__restrict__ LSE, int T, int Hq, int Hk,
@@ -88,8 +90,9 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
   constexpr int VROW = DH * 2 + 64;    // padded value row: the 4 rows x 32 bytes a transposing read touches per
                                        // 16 lanes fall into disjoint banks
   constexpr int VBUF = BKV * VROW;     // bytes per V buffer
-  constexpr int K_PER_THREAD = BKV * KCH / NT;
-  constexpr int K_ROWS_PER_PASS = NT / KCH;
+  constexpr int K_PER_THREAD = BKV * KCH / NTH;
+  constexpr int K_ROWS_PER_PASS = NTH / KCH;
+  constexpr int BQ_ = NTH / 64 * 32;
   unsigned char *const sKb = smem;
   unsigned char *const sVb = smem + 2 * KBUF;
 
@@ -153,7 +156,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
     const int slot = idx / BH;
     const int qb = (paired && pass == 1) ? slot : nqb - 1 - slot;
     if (pass == 1 && slot >= nqb - 1 - slot) break;  // odd count: the middle block was done in pass 0
-    const int q0 = qb * BQ, qw0 = q0 + wave * 32;
+    const int q0 = qb * BQ_, qw0 = q0 + wave * 32;
     const bool wave_live = qw0 < T;
     const int wave_last = min(qw0 + 31, T - 1);
 
@@ -183,7 +186,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
     for (int r = 0; r < 16; ++r) negm[r] = BOUNDED ? -bound : 0.f;
     float l_run = 0.f, l_run2 = 0.f;  // running sums of probabilities (two chains); each half-wave keeps its own part
 
-    const int kv_end = CAUSAL ? min(q0 + BQ, T) : T;  // keys [0, kv_end) matter to this workgroup
+    const int kv_end = CAUSAL ? min(q0 + BQ_, T) : T;  // keys [0, kv_end) matter to this workgroup
     const int ntiles = (kv_end + BKV - 1) / BKV;
 
     auto tile = [&](int j, auto buf_c) {
@@ -617,6 +620,364 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
   }
 }
 
+// Score MFMAs of the one-wavefront-per-SIMD kernel below, written as inline assembly so that their accumulators live in ordinary
+// vector registers: in a kernel that may use more than 256 registers the compiler keeps every MFMA accumulator
+// it selects itself in the accumulation registers, which the vector ALU cannot read, and the exponentials would
+// need one copy per score.  The compiler does not track matrix-core hazards through inline assembly: a chain's
+// result must not be read by a vector-ALU instruction until 11 issue slots after its last MFMA (an 8-pass MFMA
+// writes its result late); the steady-state schedule keeps more than that between a chain and its
+// exponentials, and score_mfma_settle() pads the places where it does not.
+__device__ __forceinline__ f32x16 score_mfma0(bf16x8 kf, bf16x8 qf) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(kf), "v"(qf));
+  return d;
+}
+__device__ __forceinline__ f32x16 score_mfma(bf16x8 kf, bf16x8 qf, f32x16 acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(kf), "v"(qf));
+  return acc;
+}
+// 18 idle issue slots; the accumulators pass through as operands, so no read of them can be scheduled before it
+__device__ __forceinline__ void score_mfma_settle(f32x16 &a, f32x16 &b) {
+  asm volatile("s_nop 15\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+
+// The same software pipeline for ONE wavefront per SIMD (4 wavefronts per workgroup, 512 registers each): the
+// form for d_h = 256, whose 128 output accumulators, 64 query-fragment registers and two sets of scores do not fit
+// the 256 registers two wavefronts per SIMD leave.  RB = row tiles (32 query rows each) per wavefront: 1 at
+// d_h = 256 (128 rows per workgroup).  RB = 2 (64 rows per wavefront, every K / V fragment feeding two MFMAs, half
+// the LDS bytes per MFMA) also works for d_h <= 128 and was measured there: no faster than two wavefronts per
+// SIMD with 32 rows each (a single wavefront issues at most one instruction every ~7 cycles), so d_h <= 128 stays
+// on attn_fwd_pipelined.  The output accumulators live in the accumulation registers (the compiler puts every
+// MFMA accumulator it selects itself there once a kernel may use more than 256 registers); the scores are left
+// un-shifted (|s| <= bound <= 60 in log2 units keeps 2^s, the row sums and the PV products inside the fp32 range),
+// so the chains start from zero.
+template <int DH, bool CAUSAL, bool RSUM, int RB>
+__device__ __forceinline__ void attn_fwd_pipelined_wide(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                     const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
+                                                     bf16_t *__restrict__ OLO, float *__restrict__ LSE, int T, int Hq,
+                                                     int Hk, int BH, int nqb, int paired, float scale,
+                                                     unsigned char *smem) {
+  constexpr int NTH = 256, WROWS = 32 * RB, BQ_ = NTH / 64 * WROWS;
+  constexpr int KK = DH / 16, DT = DH / 32, KCH = DH / 8;
+  constexpr int KROW = DH * 2 + 16, KBUF = BKV * KROW, VROW = DH * 2 + 64, VBUF = BKV * VROW;
+  constexpr int K_PER_THREAD = BKV * KCH / NTH, K_ROWS_PER_PASS = NTH / KCH;
+  constexpr int NB = KK;  // fragments per (half-tile score | half-tile PV) block; 2 * DT == KK
+  static_assert(2 * DT == KK, "block sizes");
+  unsigned char *const sKb = smem;
+  unsigned char *const sVb = smem + 2 * KBUF;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+  const int idx = blockIdx.x;
+  const int bh = idx % BH;
+  const int b = bh / Hq, h = bh % Hq, g = h / (Hq / Hk);
+  const float c = scale * 1.44269504088896340736f;
+  const int row_bytes = Hk * DH * 2;
+  const unsigned char *const Kg = reinterpret_cast<const unsigned char *>(K + ((long long)b * T * Hk + g) * DH);
+  const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
+  const int k_r0 = tid / KCH, k_ch = tid % KCH;
+  const uint32_t k_soff = (uint32_t)k_r0 * KROW + k_ch * 16;
+  const uint32_t v_soff = (uint32_t)k_r0 * VROW + k_ch * 16;
+  const uint32_t kr_off = (uint32_t)l32 * KROW + half * 16;
+  const uint32_t vr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * VROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+
+  // K / V tiles are fetched with buffer loads.  Each tile gets its own descriptor (scalar arithmetic only): it
+  // starts at the tile's first row and ends with row T-1 of this (batch item, KV head), so a thread's chunk
+  // offsets are loop constants and rows past the end of the sequence (ragged last tile) fail the hardware's
+  // range check and read as zeros: no address arithmetic on the vector ALU inside the loop.
+  const int kv_span = (T - 1) * row_bytes + DH * 2;
+  int k_goff[K_PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < K_PER_THREAD; ++i) k_goff[i] = (k_r0 + i * K_ROWS_PER_PASS) * row_bytes + k_ch * 16;
+  u32x4 rk[K_PER_THREAD];
+  u32x4 rv[K_PER_THREAD];
+  auto load_rows = [&](const unsigned char *base, int kt, u32x4 *dst) {  // kt * BKV < T
+    const int first = kt * BKV * row_bytes;
+    const __amdgpu_buffer_rsrc_t res =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(base) + first, 0, kv_span - first, 0x00020000);
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) dst[i] = __builtin_amdgcn_raw_buffer_load_b128(res, k_goff[i], 0, 0);
+  };
+  auto store_k = [&](int buf) {
+    unsigned char *kd = sKb + buf * KBUF + k_soff;
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(kd + i * K_ROWS_PER_PASS * KROW) = rk[i];
+  };
+  auto store_v = [&](int buf) {
+    unsigned char *vd = sVb + buf * VBUF + v_soff;
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i) *reinterpret_cast<u32x4 *>(vd + i * K_ROWS_PER_PASS * VROW) = rv[i];
+  };
+  auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
+
+  const int npass = paired ? 2 : 1;
+  for (int pass = 0; pass < npass; ++pass) {
+    const int slot = idx / BH;
+    const int qb = (paired && pass == 1) ? slot : nqb - 1 - slot;
+    if (pass == 1 && slot >= nqb - 1 - slot) break;
+    const int q0 = qb * BQ_, qw0 = q0 + wave * WROWS;
+    const bool wave_live = qw0 < T;
+    const int wave_last = min(qw0 + WROWS - 1, T - 1);
+
+    bf16x8 qf[RB][KK];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) {
+      const int row = min(qw0 + rb * 32 + l32, T - 1);
+      const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+        w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+        w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+        w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+        w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+        qf[rb][kk] = __builtin_bit_cast(bf16x8, w);
+      }
+    }
+    f32x16 oacc[RB][DT];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[rb][dt][r] = 0.f;
+    float l_run[RB], l_run2[RB];
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) l_run[rb] = l_run2[rb] = 0.f;
+
+    const int kv_end = CAUSAL ? min(q0 + BQ_, T) : T;
+    const int ntiles = (kv_end + BKV - 1) / BKV;
+    const int my_tiles = !wave_live ? 0 : CAUSAL ? min(ntiles, wave_last / BKV + 1) : ntiles;
+    int t_lim[RB];  // last visible key of the lane's row in each row tile (minus the lane's key offset)
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb) t_lim[rb] = (CAUSAL ? min(qw0 + rb * 32 + l32, T - 1) : T - 1) - 4 * half;
+
+    f32x16 sacc[2][RB];      // scores: [0] of tile j+1, [1] of tile j while iteration j runs
+    uint32_t pw[2][RB][8];   // probabilities (bf16 pairs), the second MFMA operand of PV
+
+    float e0, e1;
+    auto unit_exp = [&](int hs, int rb, int u, int kt, bool mask) {
+      float s0 = sacc[hs][rb][2 * u], s1 = sacc[hs][rb][2 * u + 1];
+      if (mask) {
+        const int key = kt * BKV + hs * 32 + 8 * ((2 * u) >> 2) + ((2 * u) & 3);
+        if (key > t_lim[rb]) s0 = -INFINITY;
+        if (key + 1 > t_lim[rb]) s1 = -INFINITY;
+      }
+      e0 = __builtin_amdgcn_exp2f(s0);
+      e1 = __builtin_amdgcn_exp2f(s1);
+    };
+    auto unit_pack = [&](int hs, int rb, int u) {
+      const uint32_t pk = pack2(e0, e1);
+      pw[hs][rb][u] = pk;
+      l_run[rb] += RSUM ? bf_lo(pk) : e0;
+      l_run2[rb] += RSUM ? bf_hi(pk) : e1;
+    };
+    auto pfrag = [&](int hs, int rb, int jj) {
+      const u32x4 w = {pw[hs][rb][4 * jj], pw[hs][rb][4 * jj + 1], pw[hs][rb][4 * jj + 2], pw[hs][rb][4 * jj + 3]};
+      return __builtin_bit_cast(bf16x8, w);
+    };
+
+    auto iter = [&](int j, auto kind_c, auto mask_c) {
+      constexpr int KIND = decltype(kind_c)::value;
+      constexpr bool MASK = decltype(mask_c)::value;
+      const unsigned char *kp = sKb + ((j + 1) & 1) * KBUF + kr_off;  // K(j+1)
+      const unsigned char *vp = sVb + (j & 1) * VBUF + vr_off;        // V(j)
+      auto kfrag = [&](int ks, int kk) {
+        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + ks * 32 * KROW + kk * 32));
+      };
+      auto vfrag = [&](int ks, int p) {  // p = jj * DT + dt
+        const int jj = p / DT, dt = p % DT;
+        const unsigned char *a = vp + (ks * 32 + jj * 16) * VROW + dt * 64;
+        const v4i16 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)a);
+        const v4i16 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16 *)(a + 8 * VROW));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      };
+      auto mem_store = [&]() {  // K(j+2), V(j+1): their buffers were last read in iteration j-1
+        store_k(j & 1);
+        store_v((j + 1) & 1);
+      };
+      auto mem_load = [&]() {  // past the last tile the loads repeat it and the stores land in idle buffers
+        load_rows(Kg, min(j + 3, ntiles - 1), rk);
+        load_rows(Vg, min(j + 2, ntiles - 1), rv);
+      };
+      if (KIND == IT_FULL) {
+        // packet i: fetch fragment i + PF64; the RB MFMAs fed by fragment i, each followed by vector-ALU work.
+        // Fragment order: even i -> K fragment of half (i >= 2 NB) of tile j+1, k-step (i mod 2NB) / 2 (scores);
+        // odd i -> V fragment of that half of tile j (PV).
+        constexpr int NP = 4 * NB;
+        constexpr int PF64 = 4;
+        // softmax work: 8 * RB units per half-phase spread over its 2 * NB * RB MFMA slots: a unit every SPU slots
+        // (exp2 in its first slot, pack in its middle slot), or several units per slot when there are fewer slots
+        constexpr int SLOTS = 2 * NB * RB;
+        constexpr int UNITS = 8 * RB;
+        bf16x8 fr[NP];
+        auto fetch = [&](int i) {
+          const int hs = i / (2 * NB), q = (i % (2 * NB)) / 2;
+          fr[i] = (i & 1) ? vfrag(hs, q) : kfrag(hs, q);
+        };
+#pragma unroll
+        for (int i = 0; i < PF64; ++i) fetch(i);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NP; ++i) {
+          if (i + PF64 < NP) fetch(i + PF64);
+          const int hs = i / (2 * NB), q = (i % (2 * NB)) / 2;
+          const int hs_u = i < 2 * NB ? 1 : 0, kt_u = i < 2 * NB ? j : j + 1;
+          // margin before the first read of the chains that just ended (operands tie the reads behind it)
+          if (i == 2 * NB) {
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb) asm volatile("s_nop 7" : "+v"(sacc[0][rb]));
+          }
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb) {
+            if (i & 1) {
+              const int jj = q / DT, dt = q % DT;
+              oacc[rb][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[i], pfrag(hs, rb, jj), oacc[rb][dt], 0, 0, 0);
+            } else {
+              sacc[hs][rb] = q == 0 ? score_mfma0(fr[i], qf[rb][q]) : score_mfma(fr[i], qf[rb][q], sacc[hs][rb]);
+            }
+            const int slot = (i % (2 * NB)) * RB + rb;  // 0 .. SLOTS-1 within the half-phase
+            if (SLOTS >= 2 * UNITS) {
+              constexpr int SPU = SLOTS / UNITS;
+              const int x = slot / SPU;
+              if (slot % SPU == 0) unit_exp(hs_u, x / 8, x % 8, kt_u, MASK);
+              if (slot % SPU == SPU / 2) unit_pack(hs_u, x / 8, x % 8);
+            } else {
+              constexpr int UPS = UNITS / SLOTS;
+#pragma unroll
+              for (int n = 0; n < UPS; ++n) {
+                const int x = slot * UPS + n;
+                unit_exp(hs_u, x / 8, x % 8, kt_u, MASK);
+                unit_pack(hs_u, x / 8, x % 8);
+              }
+            }
+            if (i == 1 && rb == RB - 1) {
+              mem_store();
+              mem_load();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      } else if (KIND == IT_PRO) {  // j = -1: scores of tile 0 (both halves), probabilities of its half 0
+        mem_store();
+        mem_load();
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+          for (int hs = 0; hs < 2; ++hs) {
+            const bf16x8 kf = kfrag(hs, kk);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+              sacc[hs][rb] = kk == 0 ? score_mfma0(kf, qf[rb][kk]) : score_mfma(kf, qf[rb][kk], sacc[hs][rb]);
+          }
+        for (int rb = 0; rb < RB; ++rb) score_mfma_settle(sacc[0][rb], sacc[1][rb]);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            unit_exp(0, rb, u, 0, MASK);
+            unit_pack(0, rb, u);
+          }
+      } else if (KIND == IT_FINAL) {  // j = my_tiles - 1: no further scores
+        mem_store();
+        mem_load();
+        for (int rb = 0; rb < RB; ++rb) score_mfma_settle(sacc[0][rb], sacc[1][rb]);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            unit_exp(1, rb, u, j, MASK);
+            unit_pack(1, rb, u);
+          }
+#pragma unroll
+        for (int hs = 0; hs < 2; ++hs)
+#pragma unroll
+          for (int p = 0; p < 2 * DT; ++p) {
+            const bf16x8 vf = vfrag(hs, p);
+#pragma unroll
+            for (int rb = 0; rb < RB; ++rb)
+              oacc[rb][p % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pfrag(hs, rb, p / DT), oacc[rb][p % DT], 0, 0, 0);
+          }
+      } else {
+        mem_store();
+        mem_load();
+      }
+      lds_barrier();
+    };
+    using PRO_ = std::integral_constant<int, IT_PRO>;
+    using FULL_ = std::integral_constant<int, IT_FULL>;
+    using FINAL_ = std::integral_constant<int, IT_FINAL>;
+    using IDLE_ = std::integral_constant<int, IT_IDLE>;
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+
+    load_rows(Kg, 0, rk);
+    store_k(0);
+    load_rows(Kg, min(1, ntiles - 1), rk);
+    load_rows(Vg, 0, rv);
+    lds_barrier();
+    int j = -1;
+    if (my_tiles > 0) {
+      if (my_tiles == 1) iter(-1, PRO_{}, T_{});
+      else iter(-1, PRO_{}, F_{});
+      for (j = 0; j < my_tiles - 2; ++j) iter(j, FULL_{}, F_{});
+      if (my_tiles >= 2) iter(my_tiles - 2, FULL_{}, T_{});
+      iter(my_tiles - 1, FINAL_{}, T_{});
+      j = my_tiles;
+    }
+    for (; j < ntiles; ++j) iter(j, IDLE_{}, F_{});
+
+    // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
+    if (wave_live) {
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        const int t = qw0 + rb * 32 + l32;
+        const float lr = l_run[rb] + l_run2[rb];
+        const float l = lr + __shfl_xor(lr, 32);
+        if (t < T) {
+          const float inv = 1.f / l;
+          bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+              u32x2 w;
+              w.x = pack2(oacc[rb][dt][rg * 4 + 0] * inv, oacc[rb][dt][rg * 4 + 1] * inv);
+              w.y = pack2(oacc[rb][dt][rg * 4 + 2] * inv, oacc[rb][dt][rg * 4 + 3] * inv);
+              *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
+              if (OLO) {
+                u32x2 x;
+                x.x = pack2(oacc[rb][dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[rb][dt][rg * 4 + 1] * inv - bf_hi(w.x));
+                x.y = pack2(oacc[rb][dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[rb][dt][rg * 4 + 3] * inv - bf_hi(w.y));
+                *reinterpret_cast<u32x2 *>(OLO + (orow - O) + dt * 32 + rg * 8 + half * 4) = x;
+              }
+            }
+          if (LSE && half == 0) LSE[((long long)b * Hq + h) * T + t] = log2f(l) * 0.69314718055994530942f;
+        }
+      }
+    }
+  }
+}
+
+// d_h = 256: 256 threads, one wavefront per SIMD, 128 query rows per workgroup.
+template <int DH, bool CAUSAL, bool RSUM>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_fwd_wide_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V, bf16_t *__restrict__ O,
+    bf16_t *__restrict__ OLO, float *__restrict__ LSE, const float *__restrict__ temp, int qk_normed, int T, int Hq,
+    int Hk, int BH, int nqb, int paired, float scale) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[2 * BKV * (DH * 2 + 16) + 2 * BKV * (DH * 2 + 64)];
+  float bound = INFINITY;
+  if (qk_normed) {  // |q.k| <= d_h * beta; 2 % head-room for the bf16 rounding of the stored q and k
+    const int g = ((int)blockIdx.x % BH % Hq) / (Hq / Hk);
+    const float beta = temp ? expf(temp[g]) : 1.f;
+    bound = 1.02f * (float)DH * beta * scale * 1.44269504088896340736f;
+  }
+  if (bound <= 60.f)
+    attn_fwd_pipelined_wide<DH, CAUSAL, RSUM, 1>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, smem);
+  else
+    attn_fwd_body<DH, CAUSAL, false, RSUM, 256>(Q, K, V, O, OLO, LSE, T, Hq, Hk, BH, nqb, paired, scale, 0.f, smem);
+}
+
 // RSUM: the row sum adds the bf16-rounded probabilities, so that o is the exact convex combination the PV
 // product formed; chosen when the caller saves lse / o_lo for a backward pass (see the file header).
 template <int DH, bool CAUSAL, bool RSUM>
@@ -642,7 +1003,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 template <int DH>
 hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo, float *lse,
                   const float *temp, hipStream_t s) {
-  const int nqb = (d.T + BQ - 1) / BQ;
+  constexpr bool WIDE = DH > 128;             // one wavefront per SIMD, 128-row query blocks
+  constexpr int BQL = WIDE ? 128 : BQ;
+  const int nqb = (d.T + BQL - 1) / BQL;
   const int BH = d.B * d.Hq;
   const bool causal = d.flags & CCA_CAUSAL;
   // Causal work per query block grows with its index.  With one 8-wavefront workgroup per CU, giving every
@@ -653,16 +1016,22 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
   const int qk_normed = (d.flags & CCA_QK_NORM) ? 1 : 0;
   if (!(d.flags & CCA_KEY_TEMP)) temp = nullptr;
   const bool rsum = lse != nullptr || o_lo != nullptr;
-#define CCA_ATTN_LAUNCH(C, R)                                                                                       \
-  attn_fwd_kernel<DH, C, R><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, \
-                                                            (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T,   \
-                                                            d.Hq, d.Hk, BH, nqb, paired, d.scale)
+#define CCA_ATTN_LAUNCH(C, R)                                                                                          \
+  if constexpr (WIDE)                                                                                                  \
+    attn_fwd_wide_kernel<DH, C, R><<<(unsigned)blocks, 256, 0, s>>>((const bf16_t *)q, (const bf16_t *)k,               \
+                                                                    (const bf16_t *)v, (bf16_t *)o, (bf16_t *)o_lo, lse, \
+                                                                    temp, qk_normed, d.T, d.Hq, d.Hk, BH, nqb, paired,  \
+                                                                    d.scale);                                          \
+  else                                                                                                                 \
+    attn_fwd_kernel<DH, C, R><<<(unsigned)blocks, NT, 0, s>>>((const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,  \
+                                                              (bf16_t *)o, (bf16_t *)o_lo, lse, temp, qk_normed, d.T,   \
+                                                              d.Hq, d.Hk, BH, nqb, paired, d.scale)
   if (causal) {
-    if (rsum) CCA_ATTN_LAUNCH(true, true);
-    else CCA_ATTN_LAUNCH(true, false);
+    if (rsum) { CCA_ATTN_LAUNCH(true, true); }
+    else { CCA_ATTN_LAUNCH(true, false); }
   } else {
-    if (rsum) CCA_ATTN_LAUNCH(false, true);
-    else CCA_ATTN_LAUNCH(false, false);
+    if (rsum) { CCA_ATTN_LAUNCH(false, true); }
+    else { CCA_ATTN_LAUNCH(false, false); }
   }
 #undef CCA_ATTN_LAUNCH
   return hipGetLastError();
@@ -671,13 +1040,15 @@ hipError_t launch(const Dims &d, const void *q, const void *k, const void *v, vo
 }  // namespace
 
 bool attention_mfma_supported(const Dims &d) {
-  return d.bf16 && (d.dh == 128 || d.dh == 64) && (long long)d.B * d.Hq * ((d.T + BQ - 1) / BQ) < (1ll << 31) &&
+  return d.bf16 && (d.dh == 256 || d.dh == 128 || d.dh == 64) && (long long)d.B * d.Hq * ((d.T + 127) / 128) < (1ll << 31) &&
          (long long)d.T * d.Hk * d.dh * 2 < (1ll << 31);
 }
 
 hipError_t attention_mfma_bf16(const Dims &d, const void *q, const void *k, const void *v, void *o, void *o_lo,
                                float *lse, const float *temp, hipStream_t s) {
-  return d.dh == 128 ? launch<128>(d, q, k, v, o, o_lo, lse, temp, s) : launch<64>(d, q, k, v, o, o_lo, lse, temp, s);
+  return d.dh == 256   ? launch<256>(d, q, k, v, o, o_lo, lse, temp, s)
+         : d.dh == 128 ? launch<128>(d, q, k, v, o, o_lo, lse, temp, s)
+                       : launch<64>(d, q, k, v, o, o_lo, lse, temp, s);
 }
 
 }  // namespace cca

@@ -684,11 +684,10 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
   // gains nothing from it (measured)
   const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 256 ? 1 : 0;
   const bool partial = d.R > 1;
-  // per launch: the attribute belongs to the current device, and the library keeps no state
+  // (the dynamic-LDS limit is raised once per kernel and device: raise_lds_limit)
 #define LAUNCH_KV(C_, P_)                                                                                     \
   {                                                                                                           \
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_bwd_dkdv_kernel<DH, C_, P_>),                  \
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kv_smem);                         \
+    e = raise_lds_limit<attn_bwd_dkdv_kernel<DH, C_, P_>>(kv_smem);                                           \
     if (e != hipSuccess) return e;                                                                            \
     attn_bwd_dkdv_kernel<DH, C_, P_><<<gkv, KV_NT, kv_smem, s>>>(ARGS_KV);                                     \
   }

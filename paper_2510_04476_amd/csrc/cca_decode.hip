@@ -886,8 +886,7 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
     for (int r0 = 0; r0 < d.R; r0 += R_MAX) {
 #define CCA_DEC_ATTN(CPL, DHC)                                                                                  \
   {                                                                                                             \
-    e = hipFuncSetAttribute(reinterpret_cast<const void *>(decode_attn_kernel<T, CPL, DHC>),                      \
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);                              \
+    e = raise_lds_limit<decode_attn_kernel<T, CPL, DHC>>(smem);                                                 \
     if (e != hipSuccess) return e;                                                                              \
     decode_attn_kernel<T, CPL, DHC><<<grid, DEC_WAVES * 64, smem, s>>>(a, q_new, (const T *)k_cache,              \
                                                                            (const T *)v_cache, part, nsplit, r0); \

@@ -31,8 +31,11 @@ constexpr int BM = 256, BK = 64;
 // LDS position of the 16-byte chunk c (0..7) of row r in a [rows][64] bf16 tile
 __device__ __forceinline__ int swz(int r, int c) { return r * 8 + (c ^ ((r & 7) ^ ((r >> 3) & 1))); }
 
+// two floats -> one word of two bf16 (round to nearest even) with the hardware conversion instruction
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
 }
 
 template <int BN, int WAVES_M, int WAVES_N>
@@ -380,14 +383,10 @@ hipError_t launch_gemm(const void *A, const void *Bt, void *C, long long M, int 
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
   const int total = tiles_m * tiles_n;
   const int per_xcd = (total + 7) / 8;
-  constexpr size_t main_bytes = 2ull * (BM + BN) * BK * 2;
   constexpr size_t epi_bytes = (size_t)BM * (BN * 2 + 16);
+  constexpr size_t main_bytes = 2ull * (BM + BN) * BK * 2;
   constexpr size_t smem = main_bytes > epi_bytes ? main_bytes : epi_bytes;
-  {  // per launch: the attribute belongs to the current device, and the library keeps no state
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-  }
+  if (hipError_t e = raise_lds_limit<gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N>>(smem); e != hipSuccess) return e;
   gemm_bf16_nt_kernel<BN, WAVES_M, WAVES_N><<<per_xcd * 8, WAVES_M * WAVES_N * 64, smem, s>>>((const bf16_t *)A, (const bf16_t *)Bt, (bf16_t *)C, M, N,
                                                              K, tiles_n, total);
   return hipGetLastError();
@@ -449,11 +448,7 @@ hipError_t gemm_tn_mfma_bf16(const void *A, long long lda, const void *Bm, long 
   const long long nk = (K + BK - 1) / BK;
   const int per = (int)((nk + splits - 1) / splits);
   constexpr size_t smem = 2ull * 2 * BK * TN_ROW;
-  {  // per launch: the attribute belongs to the current device, and the library keeps no state
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_bf16_tn_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-  }
+  if (hipError_t e = raise_lds_limit<gemm_bf16_tn_kernel>(smem); e != hipSuccess) return e;
   gemm_bf16_tn_kernel<<<dim3(per_xcd * 8, splits), 512, smem, s>>>((const bf16_t *)A, lda, (const bf16_t *)Bm, ldb, part,
                                                                   Mo, No, K, tiles_n, total, per);
   hipError_t e = hipGetLastError();

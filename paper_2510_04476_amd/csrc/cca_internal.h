@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "cca.h"
 
 namespace cca {
@@ -36,6 +38,22 @@ __device__ __forceinline__ float load_f(const float *p) { return *p; }
 __device__ __forceinline__ float load_f(const bf16_t *p) { return bf16_to_f32(*p); }
 __device__ __forceinline__ void store_f(float *p, float v) { *p = v; }
 __device__ __forceinline__ void store_f(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// Raises a kernel's dynamic-LDS limit (needed above 64 KB).  The attribute belongs to the device's copy of the
+// kernel and never changes afterwards, so it is set on the first launch per (kernel, device) and remembered in one
+// atomic bit mask per kernel: the only state the launchers keep, idempotent and safe from any thread.
+template <auto Kernel>
+inline hipError_t raise_lds_limit(size_t bytes) {
+  static std::atomic<unsigned long long> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess && dev < 64) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 // ---- generic kernels (any supported shape, fp32 or bf16 storage) ----------
 // C (M,N) = A (M,K) * Bm (K,N), all row-major.

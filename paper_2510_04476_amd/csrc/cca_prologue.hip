@@ -405,11 +405,7 @@ hipError_t launch_main(const FusedArgs &a, const void *lat, const void *vsrc, co
                        const float2 *ropeB, const float *temp, void *q, void *k, void *v, float *rnorm, int grid,
                        hipStream_t s) {
   constexpr size_t smem = (size_t)DH * D * (DH / 8) * 16;
-  {  // per launch: the attribute belongs to the current device, and the library keeps no state
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(prologue_fused_kernel<DH, D, BWD>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-  }
+  if (hipError_t e = raise_lds_limit<prologue_fused_kernel<DH, D, BWD>>(smem); e != hipSuccess) return e;
   prologue_fused_kernel<DH, D, BWD><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc, (const u32x4 *)wc,
                                                        ropeA, ropeB, temp, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
   return hipGetLastError();

@@ -90,6 +90,9 @@ SMALL = [
     dict(B=1, T=300, E=768, Hq=6, Hk=1, dh=128, k_seq=2, k_ch=1, dtype="bf16", paper_flags=True),
     dict(B=2, T=520, E=768, Hq=6, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=1, T=270, E=768, Hq=12, Hk=2, dh=64, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
+    # d_h = 256 on the matrix-core attention kernel (one wavefront per SIMD, 128-row query blocks): several query
+    # blocks with a ragged tail, R = 2; the prologue of this width runs on the shape-generic kernel
+    dict(B=2, T=700, E=2048, Hq=4, Hk=2, dh=256, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
 ]
 
 
@@ -104,7 +107,7 @@ def test_small_shapes(i, conv_visible):
     say(res)
 
 
-@pytest.mark.parametrize("i", [1, 2, 3, 5, 6, 8, 10, 13])
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 5, 6, 8, 10, 13, 14])
 @pytest.mark.parametrize("causal", [True, False])
 def test_small_shapes_inference_path(i, causal):
     """Without saved tensors the attention kernel takes its inference form (row sums of the unrounded
@@ -166,7 +169,8 @@ def test_mha_gqa_flags(Hq, Hk):
 @pytest.mark.parametrize("mode", ["normed", "normed_hot", "free"])
 @pytest.mark.parametrize("T,Hq,Hk,dh,causal", [(1000, 8, 2, 128, True), (640, 4, 4, 128, False),
                                                 (257, 2, 1, 64, True), (513, 4, 2, 128, True),
-                                                (700, 6, 2, 128, True), (330, 6, 1, 64, True), (450, 12, 2, 64, False)])
+                                                (700, 6, 2, 128, True), (330, 6, 1, 64, True), (450, 12, 2, 64, False),
+                                                (900, 4, 2, 256, True), (390, 3, 1, 256, False), (129, 2, 2, 256, True)])
 def test_attention_stage(T, Hq, Hk, dh, causal, mode):
     """normed: q, k on the spheres the prologue produces (bounded-score path of the kernel);
     normed_hot: same with a temperature large enough that the kernel must fall back to the running max;
@@ -303,6 +307,33 @@ def test_paired_query_blocks_odd_count_ragged():
     out_inf = P.cca_forward(cfg, wt, x)
     torch.cuda.synchronize()
     say("inference form", check_out(to_np(out_inf)[:, rows], ref["out"], w["dtype"]))
+
+
+def test_paired_query_blocks_head_width_256():
+    """d_h = 256: B*H_q = 32 and 17 query blocks of 128 rows (paired heavy / light, the middle one alone, ragged
+    last block), attention stage on unit-sphere q, k against the oracle on sampled rows."""
+    T, Hq, Hk, dh, Bn = 2100, 8, 2, 256, 4
+    say("case paired blocks d_h 256", T, Hq, Hk)
+    rng = np.random.default_rng(9)
+    q = rng.standard_normal((Bn, T, Hq, dh))
+    k = rng.standard_normal((Bn, T, Hk, dh))
+    temp = np.array([0.2, -0.1], np.float32)
+    q *= np.sqrt(dh) / np.linalg.norm(q, axis=-1, keepdims=True)
+    k *= np.sqrt(dh) / np.linalg.norm(k, axis=-1, keepdims=True) * np.exp(temp)[None, None, :, None]
+    v = rng.standard_normal((Bn, T, Hk, dh))
+    q, k, v = (round_to_bf16(a.astype(np.float32)) for a in (q, k, v))
+    cfg = P.CCAConfig(B=Bn, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh, flags=B.CCA_FLAGS_PAPER)
+    dev = lambda a: torch.from_numpy(a).to("cuda", torch.bfloat16)
+    o, lse = P.cca_attention(cfg, dev(q), dev(k), dev(v), want_lse=True, temp=torch.from_numpy(temp).cuda())
+    o_inf = P.cca_attention(cfg, dev(q), dev(k), dev(v), temp=torch.from_numpy(temp).cuda())
+    torch.cuda.synchronize()
+    rows = sample_rows(T, 96)
+    o_ref, lse_ref = O.attention(q, k, v, 1.0 / np.sqrt(dh), causal=True, rows=rows)
+    shape = (Bn, len(rows), Hq, dh)
+    say("o", check_tap(to_np(o)[:, rows].reshape(shape), o_ref, "bf16", "o"))
+    say("o, inference form", check_tap(to_np(o_inf)[:, rows].reshape(shape), o_ref, "bf16", "o"))
+    lim, _ = lse_bounds(q, k, dh)
+    assert float(np.abs(to_np(lse)[:, :, rows] - lse_ref).max()) <= lim
 
 
 def test_forward_is_deterministic_and_causal_on_gpu():
