@@ -29,7 +29,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # 147.04 MiB after scaling by 2.000, WRITE_SIZE 32.06 MiB after scaling by 1.000, the factors a 256 MiB
 # device-to-device copy gives for the same counters); summary in profiles/ccgqa_16k_hbm_traffic_pmc.txt.
 # Algorithmic bytes of the kernel: 80 MiB (Q 32 + K,V 16 read, O 32 written).
-ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((147.04 + 32.06) * 2 ** 20)}
+ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((146.42 + 32.05) * 2 ** 20)}
 
 
 # Layouts of the grid, all at E = 2048 through the same entry points, head counts for d_h = 128 (at d_h = 64 there
@@ -47,6 +47,9 @@ def run_grid(P, torch, dh=128) -> int:
     from paper_2510_04476_amd import binding as b
     dev = "cuda"
     rows = []
+    # d_h = 256 has matrix-core kernels for the forward pass only (its backward runs on the shape-generic kernels,
+    # seconds at S = 16384): that grid is forward-only
+    with_bwd = dh <= 128
     for causal in (True, False):
         for S in (512, 1024, 2048, 4096, 8192, 16384):
             base = {}
@@ -63,12 +66,13 @@ def run_grid(P, torch, dh=128) -> int:
                                   w_conv_seq=rn(cfg.e_q + cfg.e_kv, cfg.k_seq, sc=0.02),
                                   w_conv_ch=rn(cfg.n_q_heads + cfg.n_kv_heads, cfg.head_dim, cfg.head_dim, cfg.k_ch, sc=0.02),
                                   temp=torch.randn(cfg.n_kv_heads, device=dev, generator=g) * 0.02)
+                wt_p = P.cca_prepare(cfg, wt)  # forward timing: weights prepared once, as a deployment would
                 d_out = rn(cfg.B, cfg.T, cfg.d_model)
                 out, d_x = torch.empty_like(x), torch.empty_like(x)
                 saved = P.CCASaved.allocate(cfg, dev)
                 grads = P.CCAGrads.allocate_like(wt)
                 ws, wsb = P.new_workspace(cfg, dev), P.new_backward_workspace(cfg, dev)
-                fwd = lambda: P.cca_forward(cfg, wt, x, out=out, saved=None, workspace=ws)
+                fwd = lambda: P.cca_forward(cfg, wt_p, x, out=out, saved=None, workspace=ws)
 
                 def fwd_bwd():
                     P.cca_forward(cfg, wt, x, out=out, saved=saved, workspace=ws)
@@ -85,19 +89,23 @@ def run_grid(P, torch, dh=128) -> int:
                     return (time.perf_counter() - t0) * 1e3 / n
 
                 n = 30 if S <= 4096 else 10
-                f_ms, fb_ms = timeit(fwd, n), timeit(fwd_bwd, max(3, n // 3))
+                f_ms = timeit(fwd, n)
+                fb_ms = timeit(fwd_bwd, max(3, n // 3)) if with_bwd else float("nan")
                 base.setdefault("f", f_ms if name == "mha" else None)
                 base.setdefault("fb", fb_ms if name == "mha" else None)
-                r = {"layout": name, "d_h": dh, "S": S, "causal": causal, "fwd_ms": round(f_ms, 4), "fwd_bwd_ms": round(fb_ms, 4),
-                     "bwd_ms": round(fb_ms - f_ms, 4), "fwd_speedup_vs_mha": round(base["f"] / f_ms, 3),
-                     "bwd_speedup_vs_mha": round((base["fb"] - base["f"]) / (fb_ms - f_ms), 3)}
+                r = {"layout": name, "d_h": dh, "S": S, "causal": causal, "fwd_ms": round(f_ms, 4),
+                     "fwd_bwd_ms": round(fb_ms, 4) if with_bwd else None,
+                     "bwd_ms": round(fb_ms - f_ms, 4) if with_bwd else None,
+                     "fwd_speedup_vs_mha": round(base["f"] / f_ms, 3),
+                     "bwd_speedup_vs_mha": round((base["fb"] - base["f"]) / (fb_ms - f_ms), 3) if with_bwd else None}
                 rows.append(r)
                 print(json.dumps(r), flush=True)
                 del x, wt, d_out, out, d_x, saved, grads, ws, wsb
     print(f"{'layout':8s} {'S':>6s} {'causal':>6s} {'fwd ms':>9s} {'bwd ms':>9s} {'fwd x MHA':>10s} {'bwd x MHA':>10s}")
     for r in rows:
-        print(f"{r['layout']:8s} {r['S']:6d} {str(r['causal']):>6s} {r['fwd_ms']:9.4f} {r['bwd_ms']:9.4f} "
-              f"{r['fwd_speedup_vs_mha']:10.3f} {r['bwd_speedup_vs_mha']:10.3f}")
+        nb = lambda v, f: format(v, f) if v is not None else format("-", ">" + f.split(".")[0])
+        print(f"{r['layout']:8s} {r['S']:6d} {str(r['causal']):>6s} {r['fwd_ms']:9.4f} {nb(r['bwd_ms'], '9.4f')} "
+              f"{r['fwd_speedup_vs_mha']:10.3f} {nb(r['bwd_speedup_vs_mha'], '10.3f')}")
     return 0
 
 
@@ -114,8 +122,8 @@ def main() -> int:
     ap.add_argument("--only", choices=["forward", "attention", "prologue", "down_project", "up_project", "backward",
                                        "attention_backward", "prologue_backward", "decode"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
-    ap.add_argument("--grid-dh", type=int, default=128, choices=[64, 128],
-                    help="head width of the --grid run (the matrix-core kernels cover 64 and 128)")
+    ap.add_argument("--grid-dh", type=int, default=128, choices=[64, 128, 256],
+                    help="head width of the --grid run (256: forward only)")
     ap.add_argument("--grid", action="store_true",
                     help="latency grid on the axes of the paper's kernel figures (App. D.1: E = 2048, bf16, S = 512..16384, "
                          "causal and non-causal, forward and forward+backward) for four layouts at d_h = --grid-dh, instead "

@@ -71,6 +71,32 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
+// Score MFMAs of the one-wavefront-per-SIMD kernels (d_h = 256), written as inline assembly so that their accumulators live in ordinary
+// vector registers: in a kernel that may use more than 256 registers the compiler keeps every MFMA accumulator
+// it selects itself in the accumulation registers, which the vector ALU cannot read, and the exponentials would
+// need one copy per score.  The compiler does not track matrix-core hazards through inline assembly: a chain's
+// result must not be read by a vector-ALU instruction until 11 issue slots after its last MFMA (an 8-pass MFMA
+// writes its result late); the steady-state schedule keeps more than that between a chain and its
+// exponentials, and score_mfma_settle() pads the places where it does not.
+__device__ __forceinline__ f32x16 score_mfma0(bf16x8 kf, bf16x8 qf) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(kf), "v"(qf));
+  return d;
+}
+__device__ __forceinline__ f32x16 score_mfma_from(bf16x8 kf, bf16x8 qf, const f32x16 &start) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(d) : "v"(kf), "v"(qf), "v"(start));
+  return d;
+}
+__device__ __forceinline__ f32x16 score_mfma(bf16x8 kf, bf16x8 qf, f32x16 acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(kf), "v"(qf));
+  return acc;
+}
+// 18 idle issue slots; the accumulators pass through as operands, so no read of them can be scheduled before it
+__device__ __forceinline__ void score_mfma_settle(f32x16 &a, f32x16 &b) {
+  asm volatile("s_nop 15\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+
 // BOUNDED: the caller guarantees |score| <= bound (log2 units) for every query / key pair, as the QK L2-norm
 // of Sec. 2.2 does (|q| = sqrt(d_h), |k| = sqrt(d_h) * beta).  Then `bound` itself serves as the reference max
 // of every row: no row max, no rescaling, and exp2 arguments lie in [-2*bound, 0].
@@ -200,11 +226,14 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
       if (wave_live && !(CAUSAL && kv0 > wave_last)) {
         const unsigned char *kp = sKb + BUF * KBUF + kr_off;
         // ---- S^T - m = K Q^T - m for 64 keys x 32 query rows (log2 units)
+        // (one wavefront per SIMD: inline-assembly MFMAs keep the scores in ordinary vector registers, see above)
+        constexpr bool INLINE_S = NTH == 256;
         f32x16 sacc[2];
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
           const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + ks * 32 * KROW));
-          sacc[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], negm, 0, 0, 0);
+          sacc[ks] = INLINE_S ? score_mfma_from(kf, qf[0], negm)
+                              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[0], negm, 0, 0, 0);
         }
 #pragma unroll
         for (int kk = 1; kk < KK; ++kk)
@@ -212,8 +241,10 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
           for (int ks = 0; ks < 2; ++ks) {
             const bf16x8 kf =
                 __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kp + ks * 32 * KROW + kk * 32));
-            sacc[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[ks], 0, 0, 0);
+            sacc[ks] = INLINE_S ? score_mfma(kf, qf[kk], sacc[ks])
+                                : __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[ks], 0, 0, 0);
           }
+        if (INLINE_S) score_mfma_settle(sacc[0], sacc[1]);
 
         // ---- lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of row qw0 + l32
         if ((CAUSAL && kv0 + BKV - 1 > qw0) || (kv0 + BKV > T)) {
@@ -618,27 +649,6 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
       }
     }
   }
-}
-
-// Score MFMAs of the one-wavefront-per-SIMD kernel below, written as inline assembly so that their accumulators live in ordinary
-// vector registers: in a kernel that may use more than 256 registers the compiler keeps every MFMA accumulator
-// it selects itself in the accumulation registers, which the vector ALU cannot read, and the exponentials would
-// need one copy per score.  The compiler does not track matrix-core hazards through inline assembly: a chain's
-// result must not be read by a vector-ALU instruction until 11 issue slots after its last MFMA (an 8-pass MFMA
-// writes its result late); the steady-state schedule keeps more than that between a chain and its
-// exponentials, and score_mfma_settle() pads the places where it does not.
-__device__ __forceinline__ f32x16 score_mfma0(bf16x8 kf, bf16x8 qf) {
-  f32x16 d;
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(kf), "v"(qf));
-  return d;
-}
-__device__ __forceinline__ f32x16 score_mfma(bf16x8 kf, bf16x8 qf, f32x16 acc) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(kf), "v"(qf));
-  return acc;
-}
-// 18 idle issue slots; the accumulators pass through as operands, so no read of them can be scheduled before it
-__device__ __forceinline__ void score_mfma_settle(f32x16 &a, f32x16 &b) {
-  asm volatile("s_nop 15\n\ts_nop 1" : "+v"(a), "+v"(b));
 }
 
 // The same software pipeline for ONE wavefront per SIMD (4 wavefronts per workgroup, 512 registers each): the

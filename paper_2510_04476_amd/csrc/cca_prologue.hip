@@ -345,6 +345,232 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 }
 
 // ---------------------------------------------------------------------------
+// The same prologue for d_h = 256, where one head's folded filter (D x 256 x 256 bf16 = 128 KB per tap) cannot
+// stay in LDS: the filter is STREAMED through a double-buffered LDS slab of 256 outputs x 64 input channels
+// (one slab per tap and quarter of the head width), all 8 wavefronts of a workgroup walking the slabs in step.
+// Workgroup = one head x 256 tokens, wavefront = 32 tokens x all 256 outputs (8 accumulator tiles).  The token
+// operands of a slab (4 fragments) come straight from the latent rows as in the kernel above; the qk-mean, norm,
+// temperature, RoPE and the value role are the same code.  Forward only.
+// ---------------------------------------------------------------------------
+template <int DH, int D>
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_stream_kernel(
+    FusedArgs a, const bf16_t *__restrict__ lat, const bf16_t *__restrict__ vsrc, const u32x4 *__restrict__ wc,
+    const float2 *__restrict__ ropeA, const float2 *__restrict__ ropeB, const float *__restrict__ temp,
+    bf16_t *__restrict__ q, bf16_t *__restrict__ k, bf16_t *__restrict__ v, float *__restrict__ rnorm) {
+  constexpr int NTL = DH / 32, CPR = DH / 8;
+  constexpr int WROW = D * CPR;              // 16-byte chunks per filter row (one output channel) in memory
+  constexpr int KC = 64, KCK = KC / 16;      // input channels per slab, MFMA k-steps per slab
+  constexpr int NCH = DH / KC, NSLAB = D * NCH;
+  constexpr int SROW = KC * 2 + 16;          // padded slab row in LDS: conflict-free 16-byte reads down a column of rows
+  constexpr int SLAB = DH * SROW;
+  constexpr int W_PER_THREAD = DH * (KC / 8) / NT;  // 16-byte chunks of a slab per thread
+  __shared__ __attribute__((aligned(16))) unsigned char sW[2 * SLAB];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, half = lane >> 5;
+
+  if ((int)blockIdx.x >= a.n_conv_blocks) {
+    // ---- value-shift role (as in prologue_fused_kernel)
+    const int cpr = a.e_kv / 8;
+    const long long total = a.rows * cpr;
+    const long long first = ((long long)blockIdx.x - a.n_conv_blocks) * (NT * 4);
+    for (int it = 0; it < 4; ++it) {
+      const long long id = first + it * NT + tid;
+      if (id >= total) break;
+      const long long row = id / cpr;
+      const int ch = (int)(id % cpr) * 8;
+      const int t = (int)(row % a.T);
+      u32x4 val = {0, 0, 0, 0};
+      const bool shifted = (a.flags & CCA_V_SHIFT) && ch >= a.v_half;
+      if (!shifted || t > 0) val = *reinterpret_cast<const u32x4 *>(vsrc + (row - (shifted ? 1 : 0)) * a.vsrc_stride + ch);
+      *reinterpret_cast<u32x4 *>(v + row * a.vdst_stride + ch) = val;
+    }
+    return;
+  }
+
+  const int NH = a.Hq + a.Hk;
+  const bool is_q = (int)blockIdx.x >= a.n_k_blocks;
+  const int bid = is_q ? (int)blockIdx.x - a.n_k_blocks : (int)blockIdx.x;
+  const int head = is_q ? bid % a.Hq : a.Hq + bid % a.Hk;
+  const long long row_begin = (long long)(bid / (is_q ? a.Hq : a.Hk)) * 256;
+  const int g = is_q ? head / a.R : head - a.Hq;
+  const int ch0 = is_q ? head * DH : a.e_q + g * DH;
+  const float beta = (!is_q && (a.flags & CCA_KEY_TEMP)) ? expf(temp[g]) : 1.f;
+  bf16_t *dst = is_q ? q + head * DH : k + g * DH;
+  const int dst_stride = is_q ? a.q_stride : a.k_stride;
+
+  // qk-mean weights as identity fragments (see prologue_fused_kernel); the other stream's are made after the
+  // convolution, when fewer registers are live
+  const bool mean = a.flags & CCA_QK_MEAN;
+  auto identity_frag = [&](bf16_t wbits, int j) {
+    const bool on = ((l32 >> 4) == j) && (((l32 >> 3) & 1) == half);
+    u32x4 w = {0, 0, 0, 0};
+    const int e = l32 & 7;
+    if (on) w[e >> 1] = (uint32_t)wbits << ((e & 1) * 16);
+    return __builtin_bit_cast(bf16x8, w);
+  };
+  bf16x8 id_half[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) id_half[j] = identity_frag(f32_to_bf16(0.5f), j);
+
+  // this wavefront's 32 tokens (a wavefront past the end keeps walking the slabs: it stages filter chunks too)
+  const long long trow0 = row_begin + wave * 32;
+  const long long row = trow0 + l32;
+  const long long rowc = row < a.rows ? row : a.rows - 1;
+  const int tpos = (int)(rowc % a.T);
+
+  // slab s = (tap d = s / NCH, channel quarter c = s % NCH): rows o = 0..DH-1, bytes [c*128, c*128+128) of tap d
+  const u32x4 *wsrc = wc + (long long)head * DH * WROW;
+  u32x4 wreg[W_PER_THREAD];
+  auto load_slab = [&](int s_) {
+    const int d = s_ / NCH, c = s_ % NCH;
+#pragma unroll
+    for (int i = 0; i < W_PER_THREAD; ++i) {
+      const int id = tid + i * NT, o = id / (KC / 8), cc = id % (KC / 8);
+      wreg[i] = wsrc[o * WROW + d * CPR + c * (KC / 8) + cc];
+    }
+  };
+  auto store_slab = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < W_PER_THREAD; ++i) {
+      const int id = tid + i * NT, o = id / (KC / 8), cc = id % (KC / 8);
+      *reinterpret_cast<u32x4 *>(sW + buf * SLAB + o * SROW + cc * 16) = wreg[i];
+    }
+  };
+
+  f32x16 acc[NTL];
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+
+  load_slab(0);
+  store_slab(0);
+#pragma unroll  // tap and channel quarter must be compile-time: they pick accumulator tiles
+  for (int s_ = 0; s_ < NSLAB; ++s_) {
+    const int d = s_ / NCH, c = s_ % NCH;
+    if (s_ + 1 < NSLAB) load_slab(s_ + 1);
+    // token operands of this slab: row t - (D-1-d), channels c*64 .. c*64+63; rows before the sequence start are zero
+    const int back = D - 1 - d;
+    bf16x8 uf[KCK];
+    {
+      long long src_row = rowc - back;
+      src_row = src_row < 0 ? 0 : src_row;
+      const bf16_t *p = lat + src_row * a.src_stride + ch0 + c * KC + half * 8;
+#pragma unroll
+      for (int kk = 0; kk < KCK; ++kk) {
+        u32x4 raw = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+        if (tpos < back) raw = u32x4{0, 0, 0, 0};
+        uf[kk] = __builtin_bit_cast(bf16x8, raw);
+      }
+    }
+    __syncthreads();  // slab s_ is in LDS (stored one step ago); the other buffer is no longer read
+    if (s_ + 1 < NSLAB) store_slab((s_ + 1) & 1);
+    const unsigned char *sw = sW + (s_ & 1) * SLAB + l32 * SROW + half * 16;
+#pragma unroll
+    for (int kk = 0; kk < KCK; ++kk)
+#pragma unroll
+      for (int nt = 0; nt < NTL; ++nt) {
+        const bf16x8 wf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(sw + nt * 32 * SROW + kk * 32));
+        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[kk], acc[nt], 0, 0, 0);
+      }
+    if (mean && d == D - 1) {  // own stream of the qk-mean: + 1/2 of the token's own latent row
+#pragma unroll
+      for (int kk = 0; kk < KCK; ++kk) {
+        // channels c*64 + kk*16 .. +15 lie in output tile 2c + kk/2, half kk % 2 of it
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt)
+          if (nt == 2 * c + kk / 2) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_half[kk & 1], uf[kk], acc[nt], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- other stream of the qk-mean, a quarter of the head width at a time
+  if (mean) {
+    const float w_other = is_q ? a.mean_q_other : a.mean_k_other;
+    const bf16_t w_other_hi = f32_to_bf16(w_other);
+    const bf16_t w_other_lo = f32_to_bf16(w_other - bf16_to_f32(w_other_hi));
+    const bool grp_lo = (w_other_lo & 0x7fffu) != 0;  // uniform over the workgroup
+    bf16x8 id_grp[2], id_grp_lo[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      id_grp[j] = identity_frag(w_other_hi, j);
+      id_grp_lo[j] = identity_frag(w_other_lo, j);
+    }
+    const int nsrc = is_q ? 1 : a.R;
+    for (int sidx = 0; sidx < nsrc; ++sidx) {
+      const int col = is_q ? a.e_q + g * DH : (g * a.R + sidx) * DH;
+      const bf16_t *p = lat + rowc * a.src_stride + col + half * 8;
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        bf16x8 mf[KCK];
+#pragma unroll
+        for (int kk = 0; kk < KCK; ++kk)
+          mf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p + c * KC + kk * 16));
+#pragma unroll
+        for (int kk = 0; kk < KCK; ++kk) {
+          acc[2 * c + kk / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp[kk & 1], mf[kk], acc[2 * c + kk / 2], 0, 0, 0);
+          if (grp_lo)
+            acc[2 * c + kk / 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp_lo[kk & 1], mf[kk], acc[2 * c + kk / 2], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // ---- per token: norm, temperature, RoPE, store (lane (l32, half): channels 32*nt + 8*rg + 4*half + e)
+  if (a.flags & CCA_QK_NORM) {
+    float ssq = 0.f;
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) ssq = fmaf(acc[nt][r], acc[nt][r], ssq);
+    ssq += __shfl_xor(ssq, 32);
+    const float mul = sqrtf((float)DH) / sqrtf(ssq + a.norm_eps) * beta;
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[nt][r] *= mul;
+    if (rnorm && half == 0 && row < a.rows) rnorm[row * NH + head] = mul;
+  } else if (rnorm && half == 0 && row < a.rows) {
+    rnorm[row * NH + head] = 1.f;
+  }
+  if (a.flags & CCA_ROPE) {
+    const int thi = tpos >> 7, tlo = tpos & 127;
+#pragma unroll
+    for (int nt = 0; nt < NTL / 2; ++nt)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int i0 = nt * 32 + rg * 8 + half * 4;
+        const f32x4 *pa = reinterpret_cast<const f32x4 *>(ropeA + thi * (DH / 2) + i0);
+        const f32x4 *pb = reinterpret_cast<const f32x4 *>(ropeB + ((i0 >> 2) * 128 + tlo) * 4);
+        const f32x4 a01 = pa[0], a23 = pa[1], b01 = pb[0], b23 = pb[1];
+        const float ca[4] = {a01.x, a01.z, a23.x, a23.z}, sa[4] = {a01.y, a01.w, a23.y, a23.w};
+        const float cb[4] = {b01.x, b01.z, b23.x, b23.z}, sb[4] = {b01.y, b01.w, b23.y, b23.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float cs = ca[e] * cb[e] - sa[e] * sb[e];
+          const float sn = sa[e] * cb[e] + ca[e] * sb[e];
+          const float x1 = acc[nt][rg * 4 + e], x2 = acc[nt + NTL / 2][rg * 4 + e];
+          acc[nt][rg * 4 + e] = x1 * cs - x2 * sn;
+          acc[nt + NTL / 2][rg * 4 + e] = x2 * cs + x1 * sn;
+        }
+      }
+  }
+  if (row < a.rows) {
+    bf16_t *orow = dst + row * dst_stride;
+#pragma unroll
+    for (int nt = 0; nt < NTL; ++nt)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        u32x2 w;
+        w.x = pack2(acc[nt][rg * 4 + 0], acc[nt][rg * 4 + 1]);
+        w.y = pack2(acc[nt][rg * 4 + 2], acc[nt][rg * 4 + 3]);
+        *reinterpret_cast<u32x2 *>(orow + nt * 32 + rg * 8 + half * 4) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // No transform selected (plain MHA / GQA, Sec. 2.1): q, k, v are column slices
 // of the latent rows; only the optional value-shift moves data in time.
 // 16 bytes per thread, storage-type agnostic (`es` = bytes per element).
@@ -502,7 +728,7 @@ hipError_t prologue_split_copy_bwd(const Dims &d, const void *d_q, const void *d
 }
 
 bool prologue_fused_supported(const Dims &d) {
-  return d.bf16 && (d.dh == 128 || d.dh == 64) && (d.flags & CCA_CONV_CH) && !(d.flags & CCA_ROPE_INTERLEAVED) && taps(d) <= 3 &&
+  return d.bf16 && (d.dh == 256 || d.dh == 128 || d.dh == 64) && (d.flags & CCA_CONV_CH) && !(d.flags & CCA_ROPE_INTERLEAVED) && taps(d) <= 3 &&
          d.v_half % 8 == 0;
 }
 
@@ -521,11 +747,34 @@ hipError_t prologue_fused_prepare(const Dims &d, const cca_weights &w, void *scr
   return run_setup(d, forward_args(d), w, carve(d, scratch, D), D, false, s);
 }
 
+template <int D>
+static hipError_t launch_stream(const Dims &d, FusedArgs a, const cca_weights &w, const void *lat, const FusedScratch &fs,
+                                void *q, void *k, void *v, float *rnorm, hipStream_t s) {
+  // one 256-token block per workgroup for every head, key heads first (the kernel's block map)
+  const long long blocks = (d.rows() + 255) / 256;
+  a.tiles_per_wave = a.tiles_per_wave_k = 1;
+  a.n_k_blocks = (int)(d.Hk * blocks);
+  a.n_conv_blocks = (int)((d.Hq + d.Hk) * blocks);
+  const long long v_chunks = d.rows() * (d.e_kv / 8);
+  const int grid = a.n_conv_blocks + (int)((v_chunks + NT * 4 - 1) / (NT * 4));
+  prologue_stream_kernel<256, D><<<grid, NT, 0, s>>>(a, (const bf16_t *)lat, (const bf16_t *)lat + d.e_q + d.e_kv,
+                                                   (const u32x4 *)fs.wc, fs.ropeA, fs.ropeB, w.temp, (bf16_t *)q,
+                                                   (bf16_t *)k, (bf16_t *)v, rnorm);
+  return hipGetLastError();
+}
+
 hipError_t prologue_fused_run(const Dims &d, const cca_weights &w, const void *lat, void *q, void *k, void *v,
                               float *rnorm, const void *scratch, hipStream_t s) {
   const int D = taps(d);
   FusedArgs a = forward_args(d);
   const FusedScratch fs = carve(d, const_cast<void *>(scratch), D);
+  if (d.dh == 256) {
+    switch (D) {
+      case 1: return launch_stream<1>(d, a, w, lat, fs, q, k, v, rnorm, s);
+      case 2: return launch_stream<2>(d, a, w, lat, fs, q, k, v, rnorm, s);
+      default: return launch_stream<3>(d, a, w, lat, fs, q, k, v, rnorm, s);
+    }
+  }
   const int grid = plan_grid(d, a);
   const bf16_t *vsrc = (const bf16_t *)lat + d.e_q + d.e_kv;
 #define LAUNCH_DH(D_, B_) (d.dh == 64 ? launch_main<64, D_, B_> : launch_main<128, D_, B_>)

@@ -384,7 +384,7 @@ BwdScratch bwd_layout(const Dims &d) {
 
 }  // namespace
 
-bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d); }
+bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d) && d.dh <= 128; }  // the adjoint kernels keep a head's filter in LDS
 
 size_t prologue_bwd_fused_scratch_bytes(const Dims &d) {
   return prologue_bwd_fused_supported(d) ? bwd_layout(d).total : 0;

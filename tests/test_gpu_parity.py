@@ -91,8 +91,10 @@ SMALL = [
     dict(B=2, T=520, E=768, Hq=6, Hk=2, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=1, T=270, E=768, Hq=12, Hk=2, dh=64, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
     # d_h = 256 on the matrix-core attention kernel (one wavefront per SIMD, 128-row query blocks): several query
-    # blocks with a ragged tail, R = 2; the prologue of this width runs on the shape-generic kernel
+    # blocks with a ragged tail, R = 2; the prologue of this width streams its folded filter through LDS
     dict(B=2, T=700, E=2048, Hq=4, Hk=2, dh=256, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    # d_h = 256 with two taps, R = 3, a token count that leaves the last 256-token block of the streamed prologue ragged
+    dict(B=1, T=530, E=1536, Hq=3, Hk=1, dh=256, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
 ]
 
 
