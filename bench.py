@@ -248,6 +248,7 @@ def main() -> int:
     #      holds under that load sets it), and the device-to-device copy rate of a 1 GiB buffer (read + write).
     #      Taken first: they also bring the chip out of its idle clocks before anything is timed. ------------------
     mfma_meas = P.cca_probe_mfma_rate()
+    mfma_meas_random = P.cca_probe_mfma_rate(random_operands=True)
     src = torch.empty(1 << 30, dtype=torch.uint8, device=x.device).fill_(1)
     dst = torch.empty_like(src)
     copy_ms = timed(lambda: dst.copy_(src), 5)
@@ -425,9 +426,12 @@ def main() -> int:
                "parity_rel_l2": rel, "parity_max_abs": mx, "parity_of": "output of the timed inference call",
                "parity_saving_form_rel_l2": rel_s, "parity_saving_form_max_abs": mx_s}
 
-    ceilings = {"mfma_bf16_tflops_measured": round(mfma_meas, 1), "mfma_bf16_tflops_nominal": PEAK_BF16_TFLOPS,
+    ceilings = {"mfma_bf16_tflops_measured": round(mfma_meas, 1),
+                "mfma_bf16_tflops_measured_random_operands": round(mfma_meas_random, 1),
+                "mfma_bf16_tflops_nominal": PEAK_BF16_TFLOPS,
                 "hbm_copy_gbps_measured": round(hbm_meas, 1), "hbm_gbps_nominal": 8000.0,
-                "attention_frac_of_measured_mfma": round(attn_tflops / mfma_meas, 4)}
+                "attention_frac_of_measured_mfma": round(attn_tflops / mfma_meas, 4),
+                "attention_frac_of_measured_mfma_random_operands": round(attn_tflops / mfma_meas_random, 4)}
 
     res = {
         "metric": "CCGQA prefill TFLOP/s (causal attention counted at half the dense T^2 term) at T=16k, 1 MI355X",

@@ -98,7 +98,7 @@ def load_library() -> C.CDLL:
                                           C.POINTER(cca_grads), vp, sz, vp]
     lib.cca_decode_step_static.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_decode_state), C.c_int32, vp,
                                            vp]
-    lib.cca_probe_mfma_rate.argtypes = [vp, sz, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
+    lib.cca_probe_mfma_rate.argtypes = [vp, sz, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_double), vp]
     for name in EXPORTS:
         getattr(lib, name).restype = C.c_int
     lib.cca_strerror.argtypes = [C.c_int]
@@ -455,18 +455,23 @@ def cca_decode_step_static(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecod
     return out
 
 
-def cca_probe_mfma_rate(blocks: int = 2048, iters: int = 4096, repeats: int = 5) -> float:
-    """Measured bf16 matrix-core rate in TFLOP/s (best of `repeats` launches of the library's MFMA-only kernel)."""
+def cca_probe_mfma_rate(blocks: int = 2048, iters: int = 4096, repeats: int = 10, random_operands: bool = False) -> float:
+    """Measured bf16 matrix-core rate in TFLOP/s: `repeats` back-to-back launches of the library's MFMA-only kernel
+    under one event pair, after one untimed launch - the rate the chip sustains, not a first-launch burst.  On
+    fixed operands or, with `random_operands`, on operands that change with every instruction."""
     lib = load_library()
     out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
     fl = C.c_double(0.0)
-    best = 0.0
-    for _ in range(repeats + 1):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        _check(lib.cca_probe_mfma_rate(_ptr(out), out.numel() * 4, blocks, iters, C.byref(fl), _stream()),
-               "cca_probe_mfma_rate")
-        b.record()
-        torch.cuda.synchronize()
-        best = max(best, fl.value / (a.elapsed_time(b) * 1e-3) / 1e12)
-    return best
+
+    def launch():
+        _check(lib.cca_probe_mfma_rate(_ptr(out), out.numel() * 4, blocks, iters, int(random_operands), C.byref(fl),
+                                       _stream()), "cca_probe_mfma_rate")
+
+    launch()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(repeats):
+        launch()
+    b.record()
+    torch.cuda.synchronize()
+    return repeats * fl.value / (a.elapsed_time(b) * 1e-3) / 1e12

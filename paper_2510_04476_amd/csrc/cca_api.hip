@@ -540,15 +540,17 @@ cca_status cca_decode_step_static(const cca_config *cfg, const cca_weights *w, c
              : CCA_ERR_LAUNCH;
 }
 
-cca_status cca_probe_mfma_rate(void *out, size_t out_bytes, int32_t blocks, int32_t iters, double *flops,
-                               void *hip_stream) {
+cca_status cca_probe_mfma_rate(void *out, size_t out_bytes, int32_t blocks, int32_t iters, int32_t operands,
+                               double *flops, void *hip_stream) {
   if (!out || !flops) return CCA_ERR_NULL;
-  if (blocks <= 0 || iters <= 0 || blocks > (1 << 20) || iters > (1 << 24)) return CCA_ERR_SHAPE;
+  if (blocks <= 0 || iters <= 0 || blocks > (1 << 20) || iters > (1 << 24) || (iters & 1)) return CCA_ERR_SHAPE;
+  if (operands != 0 && operands != 1) return CCA_ERR_UNSUPPORTED;
   if (out_bytes < (size_t)blocks * 256 * sizeof(float)) return CCA_ERR_WORKSPACE;
   if (!aligned16(out)) return CCA_ERR_ALIGN;
   *flops = (double)blocks * 4.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
-  return mfma_probe(static_cast<float *>(out), blocks, iters, (hipStream_t)hip_stream) == hipSuccess ? CCA_OK
-                                                                                                    : CCA_ERR_LAUNCH;
+  return mfma_probe(static_cast<float *>(out), blocks, iters, operands == 1, (hipStream_t)hip_stream) == hipSuccess
+             ? CCA_OK
+             : CCA_ERR_LAUNCH;
 }
 
 const char *cca_strerror(cca_status s) {

@@ -414,8 +414,38 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
 }
 
-hipError_t mfma_probe(float *out, int blocks, int iters, hipStream_t s) {
-  mfma_probe_kernel<<<blocks, 256, 0, s>>>(out, iters);
+// The same loop on operands that change from one instruction to the next: 8 register sets of pseudo-random
+// values in (-2, 2) with random mantissas, as activations and weights have.  The matrix cores draw more power
+// on such operands than on the fixed ones above, and the clock the chip holds follows the power.
+__global__ __launch_bounds__(256) void mfma_probe_random_kernel(float *__restrict__ out, int iters) {
+  bf16x8 a[8], b[8];
+  unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
+#pragma unroll
+  for (int s = 0; s < 8; ++s)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      h = h * 1664525u + 1013904223u;
+      a[s][i] = (__bf16)((float)(int)(h >> 8) * (1.0f / 4194304.0f) - 2.0f);
+      h = h * 1664525u + 1013904223u;
+      b[s][i] = (__bf16)((float)(int)(h >> 8) * (1.0f / 4194304.0f) - 2.0f);
+    }
+  f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+  for (int it = 0; it < iters; it += 2) {
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1], b[1], c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2], b[2], c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3], b[3], c3, 0, 0, 0);
+    c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[4], b[4], c0, 0, 0, 0);
+    c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[5], b[5], c1, 0, 0, 0);
+    c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[6], b[6], c2, 0, 0, 0);
+    c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[7], b[7], c3, 0, 0, 0);
+  }
+  out[(size_t)blockIdx.x * 256 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
+}
+
+hipError_t mfma_probe(float *out, int blocks, int iters, bool random_operands, hipStream_t s) {
+  if (random_operands) mfma_probe_random_kernel<<<blocks, 256, 0, s>>>(out, iters);
+  else mfma_probe_kernel<<<blocks, 256, 0, s>>>(out, iters);
   return hipGetLastError();
 }
 

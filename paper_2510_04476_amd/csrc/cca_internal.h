@@ -76,7 +76,7 @@ hipError_t transpose2_bf16(const void *src1, void *dst1, int rows1, int cols1, c
                            int cols2, hipStream_t s);
 
 // measurement aid: blocks x 4 wavefronts x iters x 4 MFMAs (32x32x16 bf16), one float per thread written to out
-hipError_t mfma_probe(float *out, int blocks, int iters, hipStream_t s);
+hipError_t mfma_probe(float *out, int blocks, int iters, bool random_operands, hipStream_t s);
 
 bool attention_mfma_supported(const Dims &d);
 // temp (H_k log-temperatures, device) is read only when d.flags has QK_NORM and KEY_TEMP: it bounds the scores

@@ -209,6 +209,20 @@ def test_decode_rejects_bad_arguments_and_reports_ring_depth():
     assert call(w, p, st, 0, p, None, need.value) == B.CCA_ERR_WORKSPACE
 
 
+def test_mfma_probe_rejects_bad_arguments_before_any_launch():
+    lib = P.load_library()
+    fl = C.c_double(0.0)
+    fake = C.c_void_p(0x10000)  # never dereferenced: every case below is refused on the host
+    call = lambda out, nbytes, blocks, iters, operands, f: lib.cca_probe_mfma_rate(out, nbytes, blocks, iters, operands, f, None)
+    assert call(None, 1 << 20, 4, 8, 0, C.byref(fl)) == B.CCA_ERR_NULL
+    assert call(fake, 1 << 20, 4, 8, 0, None) == B.CCA_ERR_NULL
+    assert call(fake, 1 << 20, 0, 8, 0, C.byref(fl)) == B.CCA_ERR_SHAPE
+    assert call(fake, 1 << 20, 4, 7, 1, C.byref(fl)) == B.CCA_ERR_SHAPE        # odd iteration count
+    assert call(fake, 1 << 20, 4, 8, 2, C.byref(fl)) == B.CCA_ERR_UNSUPPORTED  # operand kinds are 0 and 1
+    assert call(fake, 4 * 256 * 4 - 1, 4, 8, 0, C.byref(fl)) == B.CCA_ERR_WORKSPACE
+    assert call(C.c_void_p(0x10004), 1 << 20, 4, 8, 0, C.byref(fl)) == B.CCA_ERR_ALIGN
+
+
 def test_flop_counter_matches_cost_table():
     """Forward FLOPs of the cost table: (1/C1 + 1/C2) 4BSE^2 + 4BES^2/C1 + Conv
     (dense attention term; the grouped-conv term counted per actual MAC)."""
