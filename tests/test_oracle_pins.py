@@ -6,6 +6,7 @@ import math
 
 import numpy as np
 import pytest
+import scipy.linalg
 import torch
 import torch.nn.functional as F
 
@@ -203,35 +204,114 @@ def test_first_token_closed_form():
     np.testing.assert_allclose(r["out"][:, 0], ref, atol=1e-13)
 
 
-# --- P7: prologue against library routines (grouped conv1d, normalize) ------
-def test_prologue_against_library_convolutions():
-    w = dict(B=2, T=17, E=40, Hq=4, Hk=2, dh=6, k_seq=3, k_ch=2, dtype="f32")
+
+# --- P7: the two convolutions written as matrices (Sec. 2.2 convolution equation): a causal convolution along time
+#     is a lower-triangular Toeplitz operator, the grouped one a block-Toeplitz operator with a dense d x d block
+#     per tap; qk-mean and value-shift written index by index (qk-mean and value-shift equations) -----------------
+def seq_operator(w0c, T):
+    """(T, T) matrix of one channel's causal filter: entry (t, s) is the tap that reaches t - s steps back."""
+    ks = len(w0c)
+    col = np.zeros(T)
+    col[:min(ks, T)] = w0c[::-1][:T]          # 0 steps back = last tap
+    return scipy.linalg.toeplitz(col, np.zeros(T))
+
+
+def ch_operator(w1h, T):
+    """(T*d_out, T*d_in) matrix of one head's filter (d_out, d_in, k_ch): block (t, t - s) is the tap for s steps back."""
+    kc = w1h.shape[2]
+    return sum(np.kron(np.eye(T, k=-s), w1h[:, :, kc - 1 - s]) for s in range(min(kc, T)))
+
+
+def test_conv_seq_is_a_lower_triangular_toeplitz_product():
+    rng = np.random.default_rng(21)
+    B, T, C, ks = 2, 9, 5, 3
+    u, w0 = rng.standard_normal((B, T, C)), rng.standard_normal((C, ks))
+    y = O.conv_seq(u, w0)
+    for c in range(C):
+        L = seq_operator(w0[c], T)
+        assert np.array_equal(np.triu(L, 1), np.zeros((T, T)))          # causal
+        np.testing.assert_allclose(y[:, :, c], u[:, :, c] @ L.T, rtol=1e-12, atol=1e-14)
+
+
+def test_conv_ch_is_a_block_toeplitz_product():
+    rng = np.random.default_rng(22)
+    B, T, H, d, kc = 2, 7, 3, 4, 2
+    u, w1 = rng.standard_normal((B, T, H, d)), rng.standard_normal((H, d, d, kc))
+    y = O.conv_ch(u, w1)
+    for h in range(H):
+        M = ch_operator(w1[h], T)
+        for b in range(B):
+            np.testing.assert_allclose(y[b, :, h].ravel(), M @ u[b, :, h].ravel(), rtol=1e-12, atol=1e-14)
+
+
+@pytest.mark.parametrize("which", ["seq", "ch"])
+def test_each_convolution_against_the_library_grouped_conv1d(which):
+    """One step at a time against the library routine: a left-padded grouped cross-correlation."""
+    rng = np.random.default_rng(24)
+    B, T, H, d, k = 2, 13, 3, 4, 3
+    u = rng.standard_normal((B, T, H, d))
+    ut = F.pad(torch.from_numpy(u.reshape(B, T, H * d)).transpose(1, 2), (k - 1, 0))
+    if which == "seq":
+        w0 = rng.standard_normal((H * d, k))
+        got = O.conv_seq(u.reshape(B, T, H * d), w0)
+        want = F.conv1d(ut, torch.from_numpy(w0)[:, None, :], groups=H * d)
+    else:
+        w1 = rng.standard_normal((H, d, d, k))
+        got = O.conv_ch(u, w1).reshape(B, T, H * d)
+        want = F.conv1d(ut, torch.from_numpy(w1.reshape(H * d, d, k)), groups=H)
+    np.testing.assert_allclose(got, want.transpose(1, 2).numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_qk_mean_and_value_shift_index_by_index():
+    rng = np.random.default_rng(23)
+    B, T, Hq, Hk, d = 2, 5, 6, 2, 4
+    R = Hq // Hk
+    q0, k0 = rng.standard_normal((B, T, Hq, d)), rng.standard_normal((B, T, Hk, d))
+    q2, k2 = rng.standard_normal((B, T, Hq, d)), rng.standard_normal((B, T, Hk, d))
+    q3, k3 = O.qk_mean(q2, k2, q0, k0)
+    for h in range(Hq):
+        np.testing.assert_allclose(q3[:, :, h], q2[:, :, h] + (q0[:, :, h] + k0[:, :, h // R]) / 2, rtol=1e-14)
+    for g in range(Hk):
+        mean_of_group = sum((q0[:, :, h] + k0[:, :, g]) / 2 for h in range(g * R, (g + 1) * R)) / R
+        np.testing.assert_allclose(k3[:, :, g], k2[:, :, g] + mean_of_group, rtol=1e-14)
+    e_kv = Hk * d
+    vc, vp = rng.standard_normal((B, T, e_kv // 2)), rng.standard_normal((B, T, e_kv // 2))
+    v = O.value_shift(vc, vp, Hk, d).reshape(B, T, e_kv)
+    for t in range(T):
+        assert np.array_equal(v[:, t, :e_kv // 2], vc[:, t])
+        assert np.array_equal(v[:, t, e_kv // 2:], vp[:, t - 1] if t else np.zeros_like(vp[:, 0]))
+
+
+def test_prologue_composition_with_matrix_operators():
+    """What enters the norm is conv2(conv1(latent)) plus the means of the latents BEFORE the convolutions, and the
+    value stream bypasses both (Sec. 2.2): rebuilt from the matrix operators above, no step function involved."""
+    w = dict(B=2, T=11, E=40, Hq=4, Hk=2, dh=6, k_seq=3, k_ch=2, dtype="f32")
     inp = make_inputs(w, seed=8, w_scale=0.3, conv_visible=True)
     r = run(w, inp, use_rope=False)
-    Hq, Hk, dh, ks, kc = w["Hq"], w["Hk"], w["dh"], w["k_seq"], w["k_ch"]
-    e_q, e_kv = Hq * dh, Hk * dh
-    x = torch.from_numpy(inp["x"]).double()
-    wd = torch.from_numpy(inp["w_down"]).double()
-    lat = x @ wd
-    qk = lat[..., :e_q + e_kv].transpose(1, 2)                       # (B, C, T)
-    qk = F.pad(qk, (ks - 1 + kc - 1, 0))                             # left pad once
-    y = F.conv1d(qk, torch.from_numpy(inp["w_conv_seq"]).double()[:, None, :], groups=e_q + e_kv)
-    w1 = torch.from_numpy(inp["w_conv_ch"]).double().reshape((Hq + Hk) * dh, dh, kc)
-    y = F.conv1d(y, w1, groups=Hq + Hk).transpose(1, 2)              # (B, T, C)
-    q_pre = lat[..., :e_q].view(2, 17, Hq, dh)
-    k_pre = lat[..., e_q:e_q + e_kv].view(2, 17, Hk, dh)
-    m_q = (q_pre + k_pre.repeat_interleave(Hq // Hk, dim=2)) / 2
-    m_k = m_q.view(2, 17, Hk, Hq // Hk, dh).mean(3)
-    q = y[..., :e_q].reshape(2, 17, Hq, dh) + m_q
-    k = y[..., e_q:].reshape(2, 17, Hk, dh) + m_k
-    q = F.normalize(q, dim=-1, eps=0) * math.sqrt(dh)
-    k = F.normalize(k, dim=-1, eps=0) * math.sqrt(dh) * torch.exp(torch.from_numpy(inp["temp"]).double())[None, None, :, None]
-    xs = torch.cat([torch.zeros_like(x[:, :1]), x[:, :-1]], dim=1)
-    half = e_kv // 2
-    v = torch.cat([x @ wd[:, e_q + e_kv:e_q + e_kv + half], xs @ wd[:, e_q + e_kv + half:]], -1).view(2, 17, Hk, dh)
-    np.testing.assert_allclose(r["q"], q.numpy(), rtol=1e-11, atol=1e-13)
-    np.testing.assert_allclose(r["k"], k.numpy(), rtol=1e-11, atol=1e-13)
-    np.testing.assert_allclose(r["v"], v.numpy(), rtol=1e-11, atol=1e-13)
+    Hq, Hk, dh, T = w["Hq"], w["Hk"], w["dh"], w["T"]
+    R, e_q, e_kv = Hq // Hk, Hq * dh, Hk * dh
+    lat = inp["x"].astype(np.float64) @ inp["w_down"].astype(np.float64)
+    w0, w1 = inp["w_conv_seq"].astype(np.float64), inp["w_conv_ch"].astype(np.float64)
+    for b in range(w["B"]):
+        pre = [lat[b, :, h * dh:(h + 1) * dh] for h in range(Hq + Hk)]               # (T, dh) per latent head
+        conv = []
+        for h in range(Hq + Hk):
+            after_seq = np.stack([seq_operator(w0[h * dh + i], T) @ pre[h][:, i] for i in range(dh)], axis=1)
+            conv.append((ch_operator(w1[h], T) @ after_seq.ravel()).reshape(T, dh))
+        for h in range(Hq):
+            want = conv[h] + (pre[h] + pre[Hq + h // R]) / 2
+            np.testing.assert_allclose(r["q3"][b, :, h], want, rtol=1e-11, atol=1e-13)
+            np.testing.assert_allclose(r["q"][b, :, h], want * math.sqrt(dh) / np.linalg.norm(want, axis=1, keepdims=True),
+                                       rtol=1e-11, atol=1e-13)
+        for g in range(Hk):
+            want = conv[Hq + g] + pre[Hq + g] / 2 + sum(pre[g * R:(g + 1) * R]) / (2 * R)
+            np.testing.assert_allclose(r["k3"][b, :, g], want, rtol=1e-11, atol=1e-13)
+            np.testing.assert_allclose(r["k"][b, :, g], want * math.sqrt(dh) * math.exp(inp["temp"][g])
+                                       / np.linalg.norm(want, axis=1, keepdims=True), rtol=1e-11, atol=1e-13)
+        v = r["v"][b].reshape(T, e_kv)
+        np.testing.assert_allclose(v[:, :e_kv // 2], lat[b, :, e_q + e_kv:e_q + e_kv + e_kv // 2], rtol=1e-12)
+        np.testing.assert_allclose(v[1:, e_kv // 2:], lat[b, :-1, e_q + e_kv + e_kv // 2:], rtol=1e-12)
+        assert np.array_equal(v[0, e_kv // 2:], np.zeros(e_kv // 2))
 
 
 # --- P8: RoPE = multiplication of (u_i + i u_{i+d/2}) by exp(i t theta_i);
@@ -286,7 +366,7 @@ def test_planted_mistakes_are_caught(monkeypatch):
     monkeypatch.setitem(O.__dict__, "_conv_ch_orig", O.conv_ch)
     monkeypatch.setattr(O, "conv_ch", bad_conv_ch)
     with pytest.raises(AssertionError):
-        test_prologue_against_library_convolutions()
+        test_prologue_composition_with_matrix_operators()
     monkeypatch.setattr(O, "conv_ch", O.__dict__["_conv_ch_orig"])
 
     def bad_shift(vc, vp, Hk, dh, shift=True):   # shifts the wrong half
