@@ -79,9 +79,11 @@ def run_grid(P, torch, dh=128) -> int:
                     P.cca_backward(cfg, wt, x, saved, d_out, d_x=d_x, grads=grads, workspace=wsb)
 
                 def timeit(fn, n):
-                    for _ in range(2):
+                    t0 = time.perf_counter()       # enter the timed loop from ~60 ms of sustained work, never from
+                    while time.perf_counter() - t0 < 0.06:  # idle clocks (see prewarm() in main)
                         fn()
-                    torch.cuda.synchronize()
+                        fn()
+                        torch.cuda.synchronize()
                     t0 = time.perf_counter()
                     for _ in range(n):
                         fn()
@@ -230,11 +232,22 @@ def main() -> int:
                           "calibration_copy_bytes_each_way": 256 << 20}))
         return 0
 
+    def prewarm(fn, seconds):
+        """Untimed calls of fn for `seconds` of wall-clock.  After an idle gap as short as 0.1 s the chip needs some
+        50 ms of work to return to the clocks it sustains (measured: the same 20 steps take 0.735 ms each from cold and
+        0.668 ms once warm), so every timed region is entered from sustained work, never from idle."""
+        t0, n = time.perf_counter(), 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            n += 5
+        return n
+
     def timed(fn, n):
         """Average duration of n back-to-back launches of fn: one HIP event before the first and one after the
         last, both on the stream the launches go to (torch's current stream, the one the binding passes)."""
-        for _ in range(3):
-            fn()
+        prewarm(fn, 0.05)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         a.record()
@@ -246,7 +259,7 @@ def main() -> int:
 
     # ---- measured ceilings beside the nominal peaks: matrix-core rate of an MFMA-only kernel (the clock the chip
     #      holds under that load sets it), and the device-to-device copy rate of a 1 GiB buffer (read + write).
-    #      Taken first: they also bring the chip out of its idle clocks before anything is timed. ------------------
+    #      Taken first, outside every timed region. ------------------------------------------------------------
     mfma_meas = P.cca_probe_mfma_rate()
     mfma_meas_random = P.cca_probe_mfma_rate(random_operands=True)
     src = torch.empty(1 << 30, dtype=torch.uint8, device=x.device).fill_(1)
@@ -255,6 +268,7 @@ def main() -> int:
     hbm_meas = 2.0 * src.numel() / copy_ms / 1e6
     del src, dst
 
+    n_prewarm = prewarm(step, 0.25)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -267,9 +281,7 @@ def main() -> int:
     # the attention kernel, prepared weights), copied out before anything else writes `out`
     out_timed = out.clone()
     n_u = max(5, args.steps // 2)
-    for _ in range(3):
-        step_unprepared()
-    torch.cuda.synchronize()
+    prewarm(step_unprepared, 0.05)
     t0 = time.perf_counter()
     for _ in range(n_u):
         step_unprepared()
@@ -296,9 +308,7 @@ def main() -> int:
             P.cca_backward(cfg, wt, x, saved, bb["d_out"], d_x=bb["d_x"], grads=bb["grads"], workspace=bb["ws"])
 
         n_b = max(5, args.steps // 2)
-        for _ in range(3):
-            train_step()
-        torch.cuda.synchronize()
+        prewarm(train_step, 0.1)
         t0 = time.perf_counter()
         for _ in range(n_b):
             train_step()
@@ -333,9 +343,7 @@ def main() -> int:
         wtm = P.cca_prepare(cm, wtm)  # prepared like the CCGQA weights it is compared with
         wsm = P.new_workspace(cm, xm.device)
         outm = torch.empty_like(xm)
-        for _ in range(3):
-            P.cca_forward(cm, wtm, xm, out=outm, workspace=wsm)
-        torch.cuda.synchronize()
+        prewarm(lambda: P.cca_forward(cm, wtm, xm, out=outm, workspace=wsm), 0.1)
         t0 = time.perf_counter()
         n_m = max(5, args.steps // 2)
         for _ in range(n_m):
@@ -363,9 +371,7 @@ def main() -> int:
             wtb = P.cca_prepare(cb, wtb)
             wsb = P.new_workspace(cb, x.device)
             ob = torch.empty_like(xb)
-            for _ in range(2):
-                P.cca_forward(cb, wtb, xb, out=ob, workspace=wsb)
-            torch.cuda.synchronize()
+            prewarm(lambda: P.cca_forward(cb, wtb, xb, out=ob, workspace=wsb), 0.1)
             t0 = time.perf_counter()
             for _ in range(5):
                 P.cca_forward(cb, wtb, xb, out=ob, workspace=wsb)
@@ -437,7 +443,7 @@ def main() -> int:
         "metric": "CCGQA prefill TFLOP/s (causal attention counted at half the dense T^2 term) at T=16k, 1 MI355X",
         "value": round(fl["total"] / ms / 1e9, 2),
         "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "prewarm_steps": n_prewarm,
         "ms_per_step": round(ms, 4),
         "ms_per_step_unprepared": round(ms_unprepared, 4),
         "pct_bf16_mfma_peak": round(fl["total"] / ms / 1e9 / PEAK_BF16_TFLOPS * 100, 2),

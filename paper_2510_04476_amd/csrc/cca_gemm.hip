@@ -6,9 +6,9 @@
 // 16-byte LDS read.  Workgroup tile 256 x BN x 64 with 8 wavefronts; LDS is
 // double-buffered and XOR-swizzled per 16-byte chunk; K-slab k+1 travels HBM ->
 // LDS directly (global_load_lds, no staging registers, no ds_write) while slab k
-// is multiplied, its loads spread over the slab's four 16-wide MFMA steps so
-// that the LDS writes trickle in between the fragment reads instead of
-// arriving in one burst (the LDS write port, ~75 B/clk against ~230 B/clk for
+// is multiplied, its loads spread over the first two of the slab's four 16-wide
+// MFMA steps so that the LDS writes trickle in between the fragment reads
+// instead of arriving in one burst (the LDS write port, ~75 B/clk against ~230 B/clk for
 // reads, is what this kernel feels first: without the stores it runs a third
 // faster).  The MFMA is issued with the weight rows as its first operand,
 // which leaves every lane with 4 consecutive output columns of one row, so
@@ -27,6 +27,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 namespace {
 
 constexpr int BM = 256, BK = 64;
+constexpr int SPREAD = 2;  // k-steps of a slab over which the next slab's loads are issued (4 k-steps per slab)
 
 // LDS position of the 16-byte chunk c (0..7) of row r in a [rows][64] bf16 tile
 __device__ __forceinline__ int swz(int r, int c) { return r * 8 + (c ^ ((r & 7) ^ ((r >> 3) & 1))); }
@@ -116,10 +117,12 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
     const int buf = kt & 1;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      // the loads of slab kt+1 trickle in between this slab's fragment reads instead of arriving in one burst
-      if (kt + 1 < nk) {
+      // the loads of slab kt+1 are issued over the first SPREAD k-steps: not in one burst (the LDS write port), not
+      // over all four either (the last quarter then has a fraction of a slab to land before the wait below).
+      // Warm same-box A/B of the whole forward pass: spread over 4 / 3 / 2 / 1 steps 0.6935 / 0.687 / 0.6865 / 0.690 ms
+      if (kt + 1 < nk && kk < SPREAD) {
 #pragma unroll
-        for (int u = kk * PER_WAVE / 4; u < (kk + 1) * PER_WAVE / 4; ++u) {
+        for (int u = kk * PER_WAVE / SPREAD; u < (kk + 1) * PER_WAVE / SPREAD; ++u) {
           const int i = wave + u * (NTHREADS / 64);
           __builtin_amdgcn_global_load_lds((glb_void *)(g_src[u] + (kt + 1) * BK), (lds_void *)(sbase + (buf ^ 1) * STAGE + i * 64), 16, 0, 0);
         }
