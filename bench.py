@@ -297,6 +297,11 @@ def main() -> int:
     pro_ms = timed(lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws), n_ev)
     up_ms = timed(lambda: P.cca_up_project(cfg, saved.o, wt.w_out, out=out, workspace=ws), n_ev)
     attn_tflops = fl["attn"] / attn_ms / 1e9
+    # the same kernel, same launch, on all-zero q, k, v: identical instruction stream, no operand toggling.  What it
+    # gains over the run above is what the chip's power management takes on real data (diagnostic, not the roofline).
+    zq, zk, zo = torch.zeros_like(saved.q), torch.zeros_like(saved.k), torch.empty_like(saved.o)
+    attn_zero_ms = timed(lambda: P.cca_attention(cfg, zq, zk, zk, o=zo, lse=None, temp=wt.temp), n_ev)
+    del zq, zk, zo
 
     # ---- forward + backward (training step of the block): cca_forward saving intermediates, then cca_backward ----
     bwd = None
@@ -437,7 +442,8 @@ def main() -> int:
                 "mfma_bf16_tflops_nominal": PEAK_BF16_TFLOPS,
                 "hbm_copy_gbps_measured": round(hbm_meas, 1), "hbm_gbps_nominal": 8000.0,
                 "attention_frac_of_measured_mfma": round(attn_tflops / mfma_meas, 4),
-                "attention_frac_of_measured_mfma_random_operands": round(attn_tflops / mfma_meas_random, 4)}
+                "attention_frac_of_measured_mfma_random_operands": round(attn_tflops / mfma_meas_random, 4),
+                "attention_tflops_same_kernel_zero_inputs": round(fl["attn"] / attn_zero_ms / 1e9, 1)}
 
     res = {
         "metric": "CCGQA prefill TFLOP/s (causal attention counted at half the dense T^2 term) at T=16k, 1 MI355X",
