@@ -97,6 +97,54 @@ __device__ __forceinline__ void score_mfma_settle(f32x16 &a, f32x16 &b) {
   asm volatile("s_nop 15\n\ts_nop 1" : "+v"(a), "+v"(b));
 }
 
+// ---- pieces shared by the three forms of the kernel below -----------------------------------------------------
+// Query fragments of row `row` of head h: 8 channels per k-step for lane (l32, half), multiplied by c = scale *
+// log2(e) and rounded back to bf16 (the scores then come out of the MFMA in log2 units).
+template <int DH>
+__device__ __forceinline__ void load_q_frags(const bf16_t *__restrict__ Q, long long row_index, int Hq, int h, int half,
+                                             float c, bf16x8 *qf) {
+  const bf16_t *p = Q + (row_index * Hq + h) * DH + half * 8;
+#pragma unroll
+  for (int kk = 0; kk < DH / 16; ++kk) {
+    u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+    w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
+    w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
+    w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
+    w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
+    qf[kk] = __builtin_bit_cast(bf16x8, w);
+  }
+}
+
+// Epilogue of one 32-row tile: lane (l32, half) holds o[t][32 dt + 8 rg + 4 half + e] / l in oacc[dt][4 rg + e].
+// Normalises by the row sum, rounds once to bf16, stores 8 bytes per (dt, rg); o_lo (optional) gets what the
+// rounding dropped (the backward pass forms <dO, O> from o + o_lo); lse = ln of the row sum in the caller's
+// units: (log2 l + shift) ln 2, with shift the reference max the scores were taken against.
+template <int DH>
+__device__ __forceinline__ void store_rows(const f32x16 *oacc, float l_part, float shift, bf16_t *__restrict__ O,
+                                           bf16_t *__restrict__ OLO, float *__restrict__ LSE, int b, int h, int t, int T,
+                                           int Hq, int half) {
+  const float l = l_part + __shfl_xor(l_part, 32);  // each half-wave has summed half of the keys
+  if (t >= T) return;
+  const float inv = 1.f / l;
+  const long long off = (((long long)b * T + t) * Hq + h) * DH;
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      u32x2 w;
+      w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
+      w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
+      *reinterpret_cast<u32x2 *>(O + off + dt * 32 + rg * 8 + half * 4) = w;
+      if (OLO) {
+        u32x2 x;
+        x.x = pack2(oacc[dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[dt][rg * 4 + 1] * inv - bf_hi(w.x));
+        x.y = pack2(oacc[dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[dt][rg * 4 + 3] * inv - bf_hi(w.y));
+        *reinterpret_cast<u32x2 *>(OLO + off + dt * 32 + rg * 8 + half * 4) = x;
+      }
+    }
+  if (LSE && half == 0) LSE[((long long)b * Hq + h) * T + t] = (log2f(l) + shift) * 0.69314718055994530942f;
+}
+
 // BOUNDED: the caller guarantees |score| <= bound (log2 units) for every query / key pair, as the QK L2-norm
 // of Sec. 2.2 does (|q| = sqrt(d_h), |k| = sqrt(d_h) * beta).  Then `bound` itself serves as the reference max
 // of every row: no row max, no rescaling, and exp2 arguments lie in [-2*bound, 0].
@@ -188,19 +236,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
 
     // ---- query fragment of row qw0 + l32, scaled to log2 units and rounded back to bf16
     bf16x8 qf[KK];
-    {
-      const int row = min(qw0 + l32, T - 1);
-      const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
-        w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
-        w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
-        w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
-        w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
-        qf[kk] = __builtin_bit_cast(bf16x8, w);
-      }
-    }
+    load_q_frags<DH>(Q, (long long)b * T + min(qw0 + l32, T - 1), Hq, h, half, c, qf);
 
     f32x16 oacc[DT];
 #pragma unroll
@@ -333,32 +369,7 @@ __device__ __forceinline__ void attn_fwd_body(const bf16_t *__restrict__ Q, cons
     }
 
     // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
-    if (wave_live) {
-      const int t = qw0 + l32;
-      l_run += l_run2;
-      const float l = l_run + __shfl_xor(l_run, 32);
-      if (t < T) {
-        const float inv = 1.f / l;
-        bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg) {
-            u32x2 w;
-            w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
-            w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
-            *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
-            if (OLO) {  // what the rounding dropped: the backward pass forms <dO, O> from o + o_lo
-              u32x2 x;
-              x.x = pack2(oacc[dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[dt][rg * 4 + 1] * inv - bf_hi(w.x));
-              x.y = pack2(oacc[dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[dt][rg * 4 + 3] * inv - bf_hi(w.y));
-              *reinterpret_cast<u32x2 *>(OLO + (orow - O) + dt * 32 + rg * 8 + half * 4) = x;
-            }
-          }
-        if (LSE && half == 0)
-          LSE[((long long)b * Hq + h) * T + t] = (log2f(l) - negm[0]) * 0.69314718055994530942f;
-      }
-    }
+    if (wave_live) store_rows<DH>(oacc, l_run + l_run2, -negm[0], O, OLO, LSE, b, h, qw0 + l32, T, Hq, half);
   }
 }
 
@@ -448,19 +459,7 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
     const int wave_last = min(qw0 + 31, T - 1);
 
     bf16x8 qf[KK];
-    {
-      const int row = min(qw0 + l32, T - 1);
-      const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
-        w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
-        w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
-        w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
-        w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
-        qf[kk] = __builtin_bit_cast(bf16x8, w);
-      }
-    }
+    load_q_frags<DH>(Q, (long long)b * T + min(qw0 + l32, T - 1), Hq, h, half, c, qf);
     f32x16 oacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -623,31 +622,7 @@ __device__ __forceinline__ void attn_fwd_pipelined(const bf16_t *__restrict__ Q,
     for (; j < ntiles; ++j) iter(j, IDLE_{}, F_{});
 
     // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
-    if (wave_live) {
-      const int t = qw0 + l32;
-      l_run += l_run2;
-      const float l = l_run + __shfl_xor(l_run, 32);
-      if (t < T) {
-        const float inv = 1.f / l;
-        bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg) {
-            u32x2 w;
-            w.x = pack2(oacc[dt][rg * 4 + 0] * inv, oacc[dt][rg * 4 + 1] * inv);
-            w.y = pack2(oacc[dt][rg * 4 + 2] * inv, oacc[dt][rg * 4 + 3] * inv);
-            *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
-            if (OLO) {
-              u32x2 x;
-              x.x = pack2(oacc[dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[dt][rg * 4 + 1] * inv - bf_hi(w.x));
-              x.y = pack2(oacc[dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[dt][rg * 4 + 3] * inv - bf_hi(w.y));
-              *reinterpret_cast<u32x2 *>(OLO + (orow - O) + dt * 32 + rg * 8 + half * 4) = x;
-            }
-          }
-        if (LSE && half == 0) LSE[((long long)b * Hq + h) * T + t] = (log2f(l) + bound) * 0.69314718055994530942f;
-      }
-    }
+    if (wave_live) store_rows<DH>(oacc, l_run + l_run2, bound, O, OLO, LSE, b, h, qw0 + l32, T, Hq, half);
   }
 }
 
@@ -731,19 +706,8 @@ __device__ __forceinline__ void attn_fwd_pipelined_wide(const bf16_t *__restrict
 
     bf16x8 qf[RB][KK];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const int row = min(qw0 + rb * 32 + l32, T - 1);
-      const bf16_t *p = Q + (((long long)b * T + row) * Hq + h) * DH + half * 8;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        u32x4 w = *reinterpret_cast<const u32x4 *>(p + kk * 16);
-        w.x = pack2(bf_lo(w.x) * c, bf_hi(w.x) * c);
-        w.y = pack2(bf_lo(w.y) * c, bf_hi(w.y) * c);
-        w.z = pack2(bf_lo(w.z) * c, bf_hi(w.z) * c);
-        w.w = pack2(bf_lo(w.w) * c, bf_hi(w.w) * c);
-        qf[rb][kk] = __builtin_bit_cast(bf16x8, w);
-      }
-    }
+    for (int rb = 0; rb < RB; ++rb)
+      load_q_frags<DH>(Q, (long long)b * T + min(qw0 + rb * 32 + l32, T - 1), Hq, h, half, c, qf[rb]);
     f32x16 oacc[RB][DT];
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
@@ -937,34 +901,11 @@ __device__ __forceinline__ void attn_fwd_pipelined_wide(const bf16_t *__restrict
     }
     for (; j < ntiles; ++j) iter(j, IDLE_{}, F_{});
 
-    // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits
+    // ---- epilogue: normalise, round once to bf16, store; log-sum-exp of the scaled logits (scores un-shifted)
     if (wave_live) {
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        const int t = qw0 + rb * 32 + l32;
-        const float lr = l_run[rb] + l_run2[rb];
-        const float l = lr + __shfl_xor(lr, 32);
-        if (t < T) {
-          const float inv = 1.f / l;
-          bf16_t *orow = O + (((long long)b * T + t) * Hq + h) * DH;
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-              u32x2 w;
-              w.x = pack2(oacc[rb][dt][rg * 4 + 0] * inv, oacc[rb][dt][rg * 4 + 1] * inv);
-              w.y = pack2(oacc[rb][dt][rg * 4 + 2] * inv, oacc[rb][dt][rg * 4 + 3] * inv);
-              *reinterpret_cast<u32x2 *>(orow + dt * 32 + rg * 8 + half * 4) = w;
-              if (OLO) {
-                u32x2 x;
-                x.x = pack2(oacc[rb][dt][rg * 4 + 0] * inv - bf_lo(w.x), oacc[rb][dt][rg * 4 + 1] * inv - bf_hi(w.x));
-                x.y = pack2(oacc[rb][dt][rg * 4 + 2] * inv - bf_lo(w.y), oacc[rb][dt][rg * 4 + 3] * inv - bf_hi(w.y));
-                *reinterpret_cast<u32x2 *>(OLO + (orow - O) + dt * 32 + rg * 8 + half * 4) = x;
-              }
-            }
-          if (LSE && half == 0) LSE[((long long)b * Hq + h) * T + t] = log2f(l) * 0.69314718055994530942f;
-        }
-      }
+      for (int rb = 0; rb < RB; ++rb)
+        store_rows<DH>(oacc[rb], l_run[rb] + l_run2[rb], 0.f, O, OLO, LSE, b, h, qw0 + rb * 32 + l32, T, Hq, half);
     }
   }
 }
