@@ -274,6 +274,17 @@ cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const vo
                            const cca_decode_state *state, int32_t pos, void *out, void *workspace,
                            size_t workspace_bytes, void *hip_stream);
 
+/* The same step for a batch whose sequences are at DIFFERENT positions (a serving batch of mixed lengths):
+ * `pos` is a DEVICE array of B int32 (4-byte aligned), sequence b's new token is at position pos[b] and attends
+ * to its cache rows 0..pos[b]; `max_pos` (host) is an upper bound of every entry, 0 <= max_pos < T
+ * (CCA_ERR_SHAPE otherwise) - it sizes the split of the key range, and every entry is clamped into
+ * [0, max_pos] on the device, so that no value in the array can carry an access outside the cache.  Row b of the
+ * result equals row pos[b] of cca_forward over that sequence's tokens 0..pos[b] (Sec. 2.2; causality).  The
+ * array is read by the kernels of this call only; everything else as for cca_decode_step. */
+cca_status cca_decode_step_ragged(const cca_config *cfg, const cca_weights *w, const void *x_new,
+                                  const cca_decode_state *state, const int32_t *pos, int32_t max_pos, void *out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* cca_decode_step for callers that cannot hand over a workspace and must not
  * allocate: code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc.  Same arguments, results and errors as

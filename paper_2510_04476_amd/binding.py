@@ -30,7 +30,7 @@ CCA_FLAGS_MHA = CCA_CAUSAL
 EXPORTS = ("cca_workspace_size", "cca_backward_workspace_size", "cca_prepared_size", "cca_prepare", "cca_forward",
            "cca_backward", "cca_down_project",
            "cca_prologue", "cca_attention", "cca_attention_backward", "cca_prologue_backward", "cca_up_project",
-           "cca_decode_workspace_size", "cca_decode_step", "cca_decode_step_static", "cca_probe_mfma_rate", "cca_strerror", "cca_version")
+           "cca_decode_workspace_size", "cca_decode_step", "cca_decode_step_ragged", "cca_decode_step_static", "cca_probe_mfma_rate", "cca_strerror", "cca_version")
 
 
 class cca_config(C.Structure):
@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
     lib.cca_decode_workspace_size.argtypes = [cfgp, C.POINTER(sz), C.POINTER(C.c_int32)]
     lib.cca_decode_step.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_decode_state), C.c_int32, vp, vp,
                                     sz, vp]
+    lib.cca_decode_step_ragged.argtypes = [cfgp, C.POINTER(cca_weights), vp, C.POINTER(cca_decode_state), vp, C.c_int32,
+                                           vp, vp, sz, vp]
     lib.cca_forward.argtypes = [cfgp, C.POINTER(cca_weights), vp, vp, C.POINTER(cca_saved), vp, sz, vp]
     lib.cca_down_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
     lib.cca_up_project.argtypes = [cfgp, vp, vp, vp, vp, sz, vp]
@@ -439,6 +441,21 @@ def cca_decode_step(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecodeState,
     cc, cw, cs = cfg.c(), w.c(), state.c()
     _check(lib.cca_decode_step(C.byref(cc), C.byref(cw), _ptr(x_new), C.byref(cs), C.c_int32(pos), _ptr(out),
                                _ptr(state.workspace), C.c_size_t(state.workspace.numel()), _stream()), "cca_decode_step")
+    return out
+
+
+def cca_decode_step_ragged(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecodeState, pos: torch.Tensor,
+                           max_pos: int, out=None):
+    """out (B, E): sequence b's new token is at position pos[b] (int32 device tensor of B entries, each within
+    [0, max_pos]); updates `state` row pos[b] of each sequence."""
+    lib = load_library()
+    assert pos.dtype == torch.int32 and pos.is_cuda and pos.is_contiguous() and pos.numel() == cfg.B
+    if out is None:
+        out = torch.empty(cfg.B, cfg.d_model, dtype=cfg.torch_dtype, device=x_new.device)
+    cc, cw, cs = cfg.c(), w.c(), state.c()
+    _check(lib.cca_decode_step_ragged(C.byref(cc), C.byref(cw), _ptr(x_new), C.byref(cs), _ptr(pos), C.c_int32(max_pos),
+                                      _ptr(out), _ptr(state.workspace), C.c_size_t(state.workspace.numel()), _stream()),
+           "cca_decode_step_ragged")
     return out
 
 

@@ -520,7 +520,7 @@ cca_status cca_decode_step(const cca_config *cfg, const cca_weights *w, const vo
   if (st != CCA_OK) return st;
   if (!aligned16(workspace)) return CCA_ERR_ALIGN;
   if (!workspace || workspace_bytes < decode_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
-  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, out, workspace,
+  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, nullptr, out, workspace,
                      (hipStream_t)hip_stream) == hipSuccess
              ? CCA_OK
              : CCA_ERR_LAUNCH;
@@ -534,8 +534,24 @@ cca_status cca_decode_step_static(const cca_config *cfg, const cca_weights *w, c
   if (decode_scratch_bytes(d) > (size_t)CCA_DECODE_STATIC_BYTES) return CCA_ERR_WORKSPACE;  // does not fit the array
   void *scratch = nullptr;  // first HIP call: everything above is host arithmetic
   if (decode_static_scratch(&scratch) != hipSuccess) return CCA_ERR_LAUNCH;
-  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, out, scratch,
+  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, pos, nullptr, out, scratch,
                      (hipStream_t)hip_stream) == hipSuccess
+             ? CCA_OK
+             : CCA_ERR_LAUNCH;
+}
+
+cca_status cca_decode_step_ragged(const cca_config *cfg, const cca_weights *w, const void *x_new,
+                                  const cca_decode_state *state, const int32_t *pos, int32_t max_pos, void *out,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream) {
+  Dims d;
+  cca_status st = decode_validate(cfg, &d, w, x_new, state, max_pos, out);
+  if (st != CCA_OK) return st;
+  if (!pos) return CCA_ERR_NULL;
+  if (reinterpret_cast<uintptr_t>(pos) % 4 != 0 || !aligned16(workspace)) return CCA_ERR_ALIGN;
+  if (!workspace || workspace_bytes < decode_scratch_bytes(d)) return CCA_ERR_WORKSPACE;
+  static_assert(sizeof(int) == sizeof(int32_t), "positions are passed to the kernels as int");
+  return decode_step(d, *w, x_new, state->k_cache, state->v_cache, state->lat_ring, max_pos,
+                     reinterpret_cast<const int *>(pos), out, workspace, (hipStream_t)hip_stream) == hipSuccess
              ? CCA_OK
              : CCA_ERR_LAUNCH;
 }

@@ -25,7 +25,17 @@ struct DecArgs {
   int B, S, Hq, Hk, dh, R, e_q, e_kv, n_lat, v_half, k_seq, k_ch, P, pos;
   uint32_t flags;
   float rope_base, scale, norm_eps;
+  const int *pos_seq;  // per-sequence positions (device, B entries) or null: every sequence at `pos`
 };
+
+// Position of sequence b's new token.  With per-sequence positions `pos` is the largest one the host vouched for
+// (it is below the cache capacity); a value outside [0, pos] is clamped into that range, so whatever the array
+// holds no cache or ring access can leave its allocation.
+__device__ __forceinline__ int seq_pos(const DecArgs &a, int b) {
+  if (!a.pos_seq) return a.pos;
+  const int p = a.pos_seq[b];
+  return p < 0 ? 0 : (p > a.pos ? a.pos : p);
+}
 
 // N consecutive elements as one vector load (N * sizeof(T) bytes, aligned by construction: head offsets and
 // channel offsets are multiples of N elements)
@@ -81,7 +91,7 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist,
                                        const float *__restrict__ temp, float *__restrict__ q_new,
                                        T *__restrict__ k_cache, T *__restrict__ v_cache) {
   extern __shared__ float sm[];  // y0[dh][k_ch] | red[blockDim] | yrot[dh]
-  const int b = blockIdx.x, head = blockIdx.y, dh = a.dh, tid = threadIdx.x, t = a.pos;
+  const int b = blockIdx.x, head = blockIdx.y, dh = a.dh, tid = threadIdx.x, t = seq_pos(a, b);
   const long long crow = (long long)b * a.S + t;  // cache row of the new token
 
   if (head >= a.Hq + a.Hk) {  // value head: second stream delayed by one token
@@ -123,7 +133,7 @@ __global__ void decode_prologue_kernel(DecArgs a, const T *__restrict__ hist,
   }
   __syncthreads();
 
-  const T *me = lat_row(a, hist, b, a.pos);
+  const T *me = lat_row(a, hist, b, t);
   float ssq = 0.f;
   for (int o = tid; o < dh; o += blockDim.x) {
     float y;
@@ -218,8 +228,9 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_kernel(DecArgs a, 
                                                                     const T *__restrict__ v_cache,
                                                                     float *__restrict__ part, int nsplit, int r0) {
   extern __shared__ float sm[];
-  const int dh = DHC ? DHC : a.dh, len = a.pos + 1;
+  const int dh = DHC ? DHC : a.dh;
   const int split = blockIdx.x % nsplit, g = (blockIdx.x / nsplit) % a.Hk, b = blockIdx.x / (nsplit * a.Hk);
+  const int len = seq_pos(a, b) + 1;  // a short sequence leaves its last splits empty: they write (-inf, 0, 0)
   const int nr = min(R_MAX, a.R - r0);  // query heads of this pass: g*R + r0 .. + nr
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float *qs = sm;                             // [R_MAX][dh], scaled to log2 units
@@ -370,8 +381,8 @@ __global__ __launch_bounds__(DEC_WAVES * 64) void decode_attn_rows_kernel(DecArg
   typedef float f4 __attribute__((ext_vector_type(4)));
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
   __shared__ float mrg[DEC_WAVES][NR][2 + DH];
-  const int len = a.pos + 1;
   const int split = blockIdx.x % nsplit, g = (blockIdx.x / nsplit) % a.Hk, b = blockIdx.x / (nsplit * a.Hk);
+  const int len = seq_pos(a, b) + 1;  // a short sequence leaves its last splits empty: they write (-inf, 0, 0)
   const int nr = min(NR, a.R - r0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rr = lane / LPR, cc = lane % LPR;
@@ -739,10 +750,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_mfma_kernel(const bf16_t *__r
   }
 }
 
-// C row m starts at C + m * ldc (the rows of a projection may go straight into a strided destination)
+// C row m starts at C + m * ldc (the rows of a projection may go straight into a strided destination).  With
+// `row_pos` row m goes to ring slot clamp(row_pos[m], 0, pos_max) % ring of its sequence: C + m * ldc + slot * N.
 template <typename T>
 __global__ void skinny_reduce_kernel(const float *__restrict__ part, T *__restrict__ C, long long mn, int N,
-                                     long long ldc, int splits) {
+                                     long long ldc, int splits, const int *__restrict__ row_pos, int pos_max,
+                                     int ring) {
   const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
   if (id >= mn) return;
   float a = 0.f;
@@ -755,7 +768,13 @@ __global__ void skinny_reduce_kernel(const float *__restrict__ part, T *__restri
     for (int u = 0; u < 8; ++u) a += v[u];
   }
   for (; s < splits; ++s) a += part[(long long)s * mn + id];
-  store_f(C + (id / N) * ldc + id % N, a);
+  const long long m = id / N;
+  long long slot_off = 0;
+  if (row_pos) {
+    const int p = row_pos[m];
+    slot_off = (long long)((p < 0 ? 0 : (p > pos_max ? pos_max : p)) % ring) * N;
+  }
+  store_f(C + m * ldc + slot_off + id % N, a);
 }
 
 int skinny_splits(int N, int K) {
@@ -768,7 +787,8 @@ int skinny_splits(int N, int K) {
 size_t skinny_scratch_bytes(int M, int N, int K) { return (size_t)skinny_splits(N, K) * M * N * sizeof(float); }
 
 template <typename T>
-hipError_t gemm_skinny(const T *A, const T *W, T *C, long long ldc, float *part, int M, int N, int K, hipStream_t s) {
+hipError_t gemm_skinny(const T *A, const T *W, T *C, long long ldc, float *part, int M, int N, int K, hipStream_t s,
+                       const int *row_pos = nullptr, int pos_max = 0, int ring = 1) {
   const int splits = skinny_splits(N, K);
   int chunk = (K + splits - 1) / splits;
   const dim3 grid((N + SK_COLS - 1) / SK_COLS, (K + chunk - 1) / chunk);
@@ -780,7 +800,8 @@ hipError_t gemm_skinny(const T *A, const T *W, T *C, long long ldc, float *part,
       hipError_t em = hipGetLastError();
       if (em != hipSuccess) return em;
       const long long mn_m = (long long)M * N;
-      skinny_reduce_kernel<T><<<(unsigned)((mn_m + 255) / 256), 256, 0, s>>>(part, C, mn_m, N, ldc, (int)grid_m.y);
+      skinny_reduce_kernel<T><<<(unsigned)((mn_m + 255) / 256), 256, 0, s>>>(part, C, mn_m, N, ldc, (int)grid_m.y, row_pos,
+                                                                             pos_max, ring);
       return hipGetLastError();
     }
   }
@@ -789,7 +810,8 @@ hipError_t gemm_skinny(const T *A, const T *W, T *C, long long ldc, float *part,
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const long long mn = (long long)M * N;
-  skinny_reduce_kernel<T><<<(unsigned)((mn + 255) / 256), 256, 0, s>>>(part, C, mn, N, ldc, (int)grid.y);
+  skinny_reduce_kernel<T><<<(unsigned)((mn + 255) / 256), 256, 0, s>>>(part, C, mn, N, ldc, (int)grid.y, row_pos, pos_max,
+                                                                         ring);
   return hipGetLastError();
 }
 
@@ -825,18 +847,22 @@ DecLayout layout(const Dims &d) {
 
 template <typename T>
 hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *k_cache, void *v_cache, void *hist,
-                  int pos, void *out, unsigned char *ws, hipStream_t s) {
+                  int pos, const int *pos_seq, void *out, unsigned char *ws, hipStream_t s) {
+  // pos: the position of every sequence, or with pos_seq (device, one entry per sequence) the largest of them
   const DecLayout L = layout(d);
   const int P = ring_rows(d);
   DecArgs a{d.B, d.T, d.Hq, d.Hk, d.dh, d.R, d.e_q, d.e_kv, d.n_lat, d.v_half, d.k_seq, d.k_ch, P, pos,
-            d.flags, d.rope_base, d.scale, d.norm_eps};
+            d.flags, d.rope_base, d.scale, d.norm_eps, pos_seq};
   float *q_new = reinterpret_cast<float *>(ws + L.q_new);
   T *o = reinterpret_cast<T *>(ws + L.o);
   float *part = reinterpret_cast<float *>(ws + L.part);
   float *gpart = reinterpret_cast<float *>(ws + L.gemm);
   // the new latent rows go straight into their ring slot
-  hipError_t e = gemm_skinny<T>((const T *)x_new, (const T *)w.w_down, (T *)hist + (long long)(pos % P) * d.n_lat,
-                                (long long)P * d.n_lat, gpart, d.B, d.n_lat, d.E, s);
+  hipError_t e = pos_seq ? gemm_skinny<T>((const T *)x_new, (const T *)w.w_down, (T *)hist, (long long)P * d.n_lat, gpart,
+                                          d.B, d.n_lat, d.E, s, pos_seq, pos, P)
+                         : gemm_skinny<T>((const T *)x_new, (const T *)w.w_down,
+                                          (T *)hist + (long long)(pos % P) * d.n_lat, (long long)P * d.n_lat, gpart, d.B,
+                                          d.n_lat, d.E, s);
   if (e != hipSuccess) return e;
   {
     int threads = 64;
@@ -849,7 +875,7 @@ hipError_t step_t(const Dims &d, const cca_weights &w, const void *x_new, void *
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
-    const int len = pos + 1;
+    const int len = pos + 1;  // the longest sequence sizes the splits
     // enough workgroups to fill the chip, at least 256 keys each, at most MAX_SPLITS
     int nsplit = (1024 + d.B * d.Hk - 1) / (d.B * d.Hk);
     nsplit = nsplit < (len + 255) / 256 ? nsplit : (len + 255) / 256;
@@ -912,10 +938,10 @@ int decode_ring_rows(const Dims &d) { return ring_rows(d); }
 size_t decode_scratch_bytes(const Dims &d) { return layout(d).total; }
 
 hipError_t decode_step(const Dims &d, const cca_weights &w, const void *x_new, void *k_cache, void *v_cache, void *hist,
-                       int pos, void *out, void *workspace, hipStream_t s) {
+                       int pos, const int *pos_seq, void *out, void *workspace, hipStream_t s) {
   unsigned char *ws = static_cast<unsigned char *>(workspace);
-  return d.bf16 ? step_t<bf16_t>(d, w, x_new, k_cache, v_cache, hist, pos, out, ws, s)
-                : step_t<float>(d, w, x_new, k_cache, v_cache, hist, pos, out, ws, s);
+  return d.bf16 ? step_t<bf16_t>(d, w, x_new, k_cache, v_cache, hist, pos, pos_seq, out, ws, s)
+                : step_t<float>(d, w, x_new, k_cache, v_cache, hist, pos, pos_seq, out, ws, s);
 }
 
 }  // namespace cca

@@ -136,7 +136,9 @@ hipError_t prologue_fused_run(const Dims &d, const cca_weights &w, const void *l
 // ---- decode step (one new token per sequence against the latent KV cache) ----
 int decode_ring_rows(const Dims &d);            // latent rows of history the transforms need: max(taps - 1, 1)
 size_t decode_scratch_bytes(const Dims &d);
+// pos: the position of every sequence; with pos_seq (device, one int per sequence) the largest position, and each
+// sequence takes its own (clamped to [0, pos] in the kernels)
 hipError_t decode_step(const Dims &d, const cca_weights &w, const void *x_new, void *k_cache, void *v_cache, void *hist,
-                       int pos, void *out, void *workspace, hipStream_t s);
+                       int pos, const int *pos_seq, void *out, void *workspace, hipStream_t s);
 
 }  // namespace cca

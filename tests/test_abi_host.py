@@ -207,6 +207,14 @@ def test_decode_rejects_bad_arguments_and_reports_ring_depth():
     assert call(w, C.c_void_p(0x10004), st, 0, p, p, need.value) == B.CCA_ERR_ALIGN
     assert call(w, p, st, 0, p, p, need.value - 1) == B.CCA_ERR_WORKSPACE
     assert call(w, p, st, 0, p, None, need.value) == B.CCA_ERR_WORKSPACE
+    # the ragged form: same checks, the host-side bound takes the place of the position
+    rag = lambda pos_arr, mx, wsp, nb: lib.cca_decode_step_ragged(C.byref(cc), C.byref(w), p, C.byref(st), pos_arr,
+                                                                  C.c_int32(mx), p, wsp, C.c_size_t(nb), None)
+    assert rag(None, 0, p, need.value) == B.CCA_ERR_NULL
+    assert rag(p, -1, p, need.value) == B.CCA_ERR_SHAPE
+    assert rag(p, cfg.T, p, need.value) == B.CCA_ERR_SHAPE
+    assert rag(C.c_void_p(0x10002), 0, p, need.value) == B.CCA_ERR_ALIGN
+    assert rag(p, 0, p, need.value - 1) == B.CCA_ERR_WORKSPACE
 
 
 def test_mfma_probe_rejects_bad_arguments_before_any_launch():

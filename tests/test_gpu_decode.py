@@ -151,6 +151,76 @@ def test_decode_bench_configuration_sampled():
     assert np.array_equal(got[0], got[2]) and np.array_equal(got[1], got[31]), "same sequence, different result"
 
 
+@pytest.mark.parametrize("i", [0, 2, 3, 6])
+def test_decode_ragged_batch_matches_forward_oracle(i):
+    """Sequences of one batch at different positions (cca_decode_step_ragged).  Sequence b starts delay[b] calls
+    late - until then it decodes its token 0 at position 0 again, which rewrites the same cache row and ring slot -
+    and after its last token it repeats that one, so from the second call on every call carries a different
+    position, ring slot and cache length per sequence.  Every row of every sequence is compared with the oracle."""
+    w = CASES[i]
+    say("case ragged decode", i, w)
+    inp = make_inputs(w, seed=110 + i, conv_visible=True)
+    cfg = P.config_from_workload(w)
+    x, wt = P.weights_to_device(cfg, inp)
+    state = P.CCADecodeState.allocate(cfg, x.device)
+    Bn, T = w["B"], w["T"]
+    delay = np.array([(5 * b + 3 * (b % 2)) % 9 for b in range(Bn)])
+    got = torch.empty(Bn, T, w["E"], dtype=x.dtype, device=x.device)
+    seen = np.zeros((Bn, T), bool)
+    rows = torch.arange(Bn, device=x.device)
+    for s in range(T + int(delay.max())):
+        pos = np.clip(s - delay, 0, T - 1)
+        pos_d = torch.tensor(pos, dtype=torch.int32, device=x.device)
+        out = P.cca_decode_step_ragged(cfg, wt, x[rows, pos_d.long()].contiguous(), state, pos_d, int(pos.max()))
+        got[rows, pos_d.long()] = out
+        seen[np.arange(Bn), pos] = True
+    torch.cuda.synchronize()
+    assert seen.all()
+    ref = oracle_forward(w, inp)
+    say(check_out(to_np(got), ref["out"], w["dtype"]))
+    say(check_tap(to_np(state.k_cache), ref["k"], w["dtype"], "k_cache"))
+    say(check_tap(to_np(state.v_cache), ref["v"], w["dtype"], "v_cache"))
+
+
+def test_decode_ragged_long_and_short_sequence_share_a_call():
+    """One sequence near the end of a 3000-token cache (several splits of the key range) and one 40 tokens long
+    (all but the first split empty) in the same call; positions beyond the host's bound are clamped to it."""
+    w = dict(B=2, T=3000, E=1024, Hq=8, Hk=2, dh=128, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True)
+    say("case ragged decode, long and short", w)
+    inp = make_inputs(w, seed=97)
+    cfg = P.config_from_workload(w)
+    x, wt = P.weights_to_device(cfg, inp)
+    saved = P.CCASaved.allocate(cfg, x.device)
+    P.cca_forward(cfg, wt, x, saved=saved)
+    state = P.CCADecodeState.allocate(cfg, x.device)
+    state.k_cache.copy_(saved.k)   # rows at and beyond a sequence's position are rewritten or never read
+    state.v_cache.copy_(saved.v)
+    ring = state.lat_ring.shape[1]
+    start = np.array([2990, 40])
+    for b in range(2):
+        for t in range(start[b] - ring, start[b]):
+            state.lat_ring[b, t % ring].copy_(saved.lat[b, t])
+    outs, n_steps = [], 4
+    for s in range(n_steps):
+        pos = start + s
+        pos_d = torch.tensor(pos, dtype=torch.int32, device=x.device)
+        x_new = torch.stack([x[b, pos[b]] for b in range(2)]).contiguous()
+        outs.append(P.cca_decode_step_ragged(cfg, wt, x_new, state, pos_d, int(pos.max())))
+    # an entry above max_pos is clamped to max_pos: the same call as the last one, the short sequence's entry too large
+    pos = start + n_steps - 1
+    bad = torch.tensor([pos[0], 10 ** 6], dtype=torch.int32, device=x.device)
+    x_new = torch.stack([x[0, pos[0]], x[1, pos[0]]]).contiguous()
+    clamped = P.cca_decode_step_ragged(cfg, wt, x_new, state, bad, int(pos[0]))
+    torch.cuda.synchronize()
+    want = np.concatenate([start[0] + np.arange(n_steps), start[1] + np.arange(n_steps)])
+    ref = oracle_forward(w, inp, rows=want)["out"]   # (2, 2 * n_steps, E)
+    got = to_np(torch.stack(outs, dim=1))            # (2, n_steps, E)
+    say(check_out(got[0], ref[0, :n_steps], "bf16"))
+    say(check_out(got[1], ref[1, n_steps:], "bf16"))
+    say(check_out(to_np(clamped)[0], ref[0, n_steps - 1], "bf16"))
+    assert torch.isfinite(clamped.float()).all()
+
+
 def test_decode_step_and_prefill_replay_in_a_hip_graph():
     """The library allocates nothing, never synchronises and enqueues only kernels on the caller's stream, so a call
     can be captured into a HIP graph: every replay, with eager calls in between, gives the eager result bit for bit."""
@@ -204,3 +274,8 @@ def test_decode_rejects_bad_arguments():
     small = P.CCADecodeState(state.k_cache, state.v_cache, state.lat_ring, state.workspace[:16])
     with pytest.raises(P.CCAError):
         P.cca_decode_step(cfg, wt, x[:, 0].contiguous(), small, 0)
+    pos_d = torch.zeros(w["B"], dtype=torch.int32, device=x.device)
+    with pytest.raises(P.CCAError):
+        P.cca_decode_step_ragged(cfg, wt, x[:, 0].contiguous(), state, pos_d, w["T"])  # bound outside the cache
+    with pytest.raises(P.CCAError):
+        P.cca_decode_step_ragged(cfg, wt, x[:, 0].contiguous(), small, pos_d, 0)
