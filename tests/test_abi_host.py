@@ -51,6 +51,22 @@ def test_workspace_size_ok_and_null():
     assert lib.cca_workspace_size(C.byref(cc), None, C.byref(only_b)) == B.CCA_OK and only_b.value == b2.value
 
 
+def test_workspace_sizes_of_a_very_large_shape_do_not_wrap():
+    """B * T = 2^23 rows: every per-row buffer is beyond 2^32 bytes, so a 32-bit product anywhere in the size
+    arithmetic would show as far too few bytes per token row.  (The small shape carries a larger share of
+    buffers that do not grow with the tokens, so its bytes per row bound the large shape's from above.)"""
+    small = P.CCAConfig(B=1, T=16384, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128)
+    big = P.CCAConfig(B=64, T=131072, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128)
+    rows_small, rows_big = 16384, 64 * 131072
+    for size in (P.cca_workspace_size, P.cca_backward_workspace_size):
+        per_row_small, per_row_big = size(small) / rows_small, size(big) / rows_big
+        assert size(big) > 1 << 33
+        assert 0.7 * per_row_small <= per_row_big <= per_row_small, (per_row_small, per_row_big)
+    assert per_row_big >= 2 * (1536 + 1024 + 2 * 256) * 2  # at least lat, q, k, v and their gradients in bf16
+    fixed = P.cca_prepared_size(small)
+    assert fixed <= P.cca_prepared_size(big) < 2 * fixed  # RoPE table rows grow with T, nothing else
+
+
 def test_compression_factors_are_checked_against_the_head_layout():
     """Sec. 2.2: latent widths E/C1 (queries) and E/C2 (keys, values).  0 = derive; otherwise exact."""
     cfg = P.CCAConfig(B=1, T=64, d_model=2048, n_q_heads=8, n_kv_heads=2, head_dim=128)   # C1 = 2, C2 = 8
