@@ -297,7 +297,7 @@ def main() -> int:
     pro_ms = timed(lambda: P.cca_prologue(cfg, wt, saved.lat, saved.q, saved.k, saved.v, workspace=ws), n_ev)
     up_ms = timed(lambda: P.cca_up_project(cfg, saved.o, wt.w_out, out=out, workspace=ws), n_ev)
     attn_tflops = fl["attn"] / attn_ms / 1e9
-    # the same kernel, same launch, on all-zero q, k, v: identical instruction stream, no operand toggling.  What it
+    # the same kernel, same launch, on all-zero q, k, v: identical instruction stream, constant operands.  What it
     # gains over the run above is what the chip's power management takes on real data (diagnostic, not the roofline).
     zq, zk, zo = torch.zeros_like(saved.q), torch.zeros_like(saved.k), torch.empty_like(saved.o)
     attn_zero_ms = timed(lambda: P.cca_attention(cfg, zq, zk, zk, o=zo, lse=None, temp=wt.temp), n_ev)

@@ -309,10 +309,11 @@ cca_status cca_decode_step_static(const cca_config *cfg, const cca_weights *w, c
  * floating-point operations that is (2*32*32*16 per instruction) in *flops
  * (host memory).  Timing the launch gives the matrix-core rate the chip
  * sustains - the measured ceiling quoted beside the nominal peak.
- * `operands` = 0: every instruction multiplies the same small fixed values;
- * 1: the operands rotate over 8 register sets of pseudo-random values in
- * (-2, 2), as activations have - the chip draws more power on those and
- * holds a lower clock, so this is the ceiling a kernel on real data meets.
+ * `operands` = 0: every instruction multiplies the same few small constants;
+ * 1: the operands are pseudo-random values in (-2, 2), as activations are
+ * (8 register sets in rotation) - the chip draws more power multiplying
+ * those and holds a lower clock, so this is the ceiling a kernel on real
+ * data meets.
  * `iters` must be even.  `out`: device scratch of at least
  * blocks * 256 * 4 bytes, overwritten.  CCA_ERR_UNSUPPORTED for another `operands`. */
 cca_status cca_probe_mfma_rate(void *out, size_t out_bytes, int32_t blocks, int32_t iters, int32_t operands,

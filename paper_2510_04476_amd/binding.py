@@ -475,7 +475,8 @@ def cca_decode_step_static(cfg: CCAConfig, w: CCAWeights, x_new, state: CCADecod
 def cca_probe_mfma_rate(blocks: int = 2048, iters: int = 4096, repeats: int = 10, random_operands: bool = False) -> float:
     """Measured bf16 matrix-core rate in TFLOP/s: `repeats` back-to-back launches of the library's MFMA-only kernel
     under one event pair, after one untimed launch - the rate the chip sustains, not a first-launch burst.  On
-    fixed operands or, with `random_operands`, on operands that change with every instruction."""
+    a few small constants or, with `random_operands`, on pseudo-random values as activations are (the chip holds a
+    lower clock on those)."""
     lib = load_library()
     out = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
     fl = C.c_double(0.0)

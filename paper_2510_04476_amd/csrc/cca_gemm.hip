@@ -417,9 +417,10 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float *__restrict__ out
   out[(size_t)blockIdx.x * 256 + threadIdx.x] = c0[0] + c1[1] + c2[2] + c3[3];
 }
 
-// The same loop on operands that change from one instruction to the next: 8 register sets of pseudo-random
-// values in (-2, 2) with random mantissas, as activations and weights have.  The matrix cores draw more power
-// on such operands than on the fixed ones above, and the clock the chip holds follows the power.
+// The same loop on varied operands: 8 register sets of pseudo-random values in (-2, 2) with random mantissas, as
+// activations and weights have.  The matrix cores draw more power multiplying such values than the few small
+// constants above (it is the values, not their changing: one random set used for every instruction costs the
+// same), and the clock the chip holds follows the power.
 __global__ __launch_bounds__(256) void mfma_probe_random_kernel(float *__restrict__ out, int iters) {
   bf16x8 a[8], b[8];
   unsigned h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u + 12345u;
