@@ -133,7 +133,7 @@ def main() -> int:
     ap.add_argument("--cpu-prefix", type=int, default=16384, help="tokens of the causal prefix the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (a second GPU would take a KV group or a batch item; not built)",
               file=sys.stderr)
         return 2
 
