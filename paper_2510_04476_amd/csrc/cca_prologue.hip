@@ -327,10 +327,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           }
         }
     }
-    // ---- round once to bf16 and store: 4 consecutive channels (8 bytes) per lane and store, the two
-    //      half-waves side by side; the 16 stores of a wavefront fill whole 256-byte rows in L2
-    if (row < a.rows) {
-      bf16_t *orow = dst + row * dst_stride;
+    // ---- round once to bf16 and store.  In the accumulator layout a lane holds 4 consecutive channels (8 bytes) of
+    //      one token per (nt, rg): stored from there, a wavefront's store instruction would touch 32 rows with 16
+    //      bytes each, and the vector memory pipeline works per cache line touched (timing the kernel with 1 such
+    //      store per lane instead of 16: 56 -> 45 us).  So the tile is transposed through this wavefront's private
+    //      staging rows in LDS (16-byte chunk c of row r at position c ^ (r mod CPR): conflict-free both ways) and
+    //      leaves as whole rows, 16 bytes per lane, 64 / CPR rows per instruction.
+    {
+      unsigned char *stg = smem + (size_t)DH * WROW * 16 + wave * (32 * DH * 2);
 #pragma unroll
       for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
@@ -338,8 +342,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           u32x2 w;
           w.x = pack2(acc[nt][rg * 4 + 0], acc[nt][rg * 4 + 1]);
           w.y = pack2(acc[nt][rg * 4 + 2], acc[nt][rg * 4 + 3]);
-          *reinterpret_cast<u32x2 *>(orow + nt * 32 + rg * 8 + half * 4) = w;
+          const int pos = (nt * 4 + rg) ^ (l32 & (CPR - 1));
+          *reinterpret_cast<u32x2 *>(stg + l32 * (DH * 2) + pos * 16 + half * 8) = w;
         }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS handles a wavefront's accesses in order
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      constexpr int RPI = 64 / CPR;  // rows per store instruction
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int rr = it * RPI + lane / CPR, p = lane % CPR, c = p ^ (rr & (CPR - 1));
+        const u32x4 val = *reinterpret_cast<const u32x4 *>(stg + rr * (DH * 2) + p * 16);
+        if (trow0 + rr < a.rows) *reinterpret_cast<u32x4 *>(dst + (trow0 + rr) * dst_stride + c * 8) = val;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // the next tile's writes come after these reads
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
@@ -630,7 +647,9 @@ template <int DH, int D, bool BWD>
 hipError_t launch_main(const FusedArgs &a, const void *lat, const void *vsrc, const void *wc, const float2 *ropeA,
                        const float2 *ropeB, const float *temp, void *q, void *k, void *v, float *rnorm, int grid,
                        hipStream_t s) {
-  constexpr size_t smem = (size_t)DH * D * (DH / 8) * 16;
+  // the head's filter, then 32 staging rows of d_h channels per wavefront (160 KB at d_h = 128 with 3 taps)
+  constexpr size_t smem = (size_t)DH * D * (DH / 8) * 16 + (size_t)(NT / 64) * 32 * DH * 2;
+  static_assert(smem <= 160 * 1024, "filter and staging rows must fit the LDS");
   if (hipError_t e = raise_lds_limit<prologue_fused_kernel<DH, D, BWD>>(smem); e != hipSuccess) return e;
   prologue_fused_kernel<DH, D, BWD><<<grid, NT, smem, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc, (const u32x4 *)wc,
                                                        ropeA, ropeB, temp, (bf16_t *)q, (bf16_t *)k, (bf16_t *)v, rnorm);
