@@ -222,21 +222,65 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     // has such taps: everywhere else the loads are unconditional and all in flight together.
     const bool any_pad = __any(BWD ? tpos + D - 1 >= a.T : tpos < D - 1) != 0;
 
-    // ---- operands: source rows of tokens t-D+1 .. t (adjoint: t+D-1 .. t) of this head; d = D-1 is the token itself
-    bf16x8 uf[D][KK];
+    // ---- operands: source rows of tokens t-D+1 .. t (adjoint: t .. t+D-1) of this head.  The taps of a tile are
+    //      the same 32 rows shifted by a token, so the rows are fetched ONCE, whole (16 bytes per lane, 64 / CPR rows
+    //      per load instruction: every cache line touched is used in full), parked in this wavefront's staging rows
+    //      in LDS (chunk c of row r at position c ^ (r mod CPR)) and read from there as MFMA fragments, tap by tap.
+    //      Fetched as fragments straight from memory, each tap cost 8 load instructions that touch 32 rows with 32
+    //      bytes each; the vector memory pipeline works per cache line touched (timing without the D-1 earlier taps'
+    //      loads: 56 -> 46 us).  The D-1 rows before the tile (adjoint: after it) go to the lanes that need them:
+    //      lane l32 < D-1 holds row l32 - (D-1) (adjoint: lane l32 >= 33-D holds row l32 + D-1) in hA.
+    constexpr int RPI = 64 / CPR, NLD = 32 / RPI, ROWB = DH * 2;
+    unsigned char *const stg = smem + (size_t)DH * WROW * 16 + wave * (32 * ROWB);
+    {
+      u32x4 rreg[NLD];
 #pragma unroll
-    for (int d = 0; d < D; ++d) {
-      const int back = D - 1 - d;
-      long long src_row = BWD ? rowc + back : rowc - back;  // clamped in bounds; zeroed below
-      src_row = src_row < 0 ? 0 : (src_row >= a.rows ? a.rows - 1 : src_row);
-      const bf16_t *p = lat + src_row * a.src_stride + ch0 + half * 8;
+      for (int it = 0; it < NLD; ++it) {
+        const int rr = it * RPI + lane / CPR, p = lane % CPR, c = p ^ (rr & (CPR - 1));
+        long long grow = trow0 + rr;
+        grow = grow < a.rows ? grow : a.rows - 1;
+        rreg[it] = *reinterpret_cast<const u32x4 *>(lat + grow * a.src_stride + ch0 + c * 8);
+      }
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        u32x4 raw = *reinterpret_cast<const u32x4 *>(p + kk * 16);
-        if (any_pad && (BWD ? tpos + back >= a.T : tpos < back)) raw = u32x4{0, 0, 0, 0};
-        uf[d][kk] = __builtin_bit_cast(bf16x8, raw);
+      for (int it = 0; it < NLD; ++it) {
+        const int rr = it * RPI + lane / CPR, p = lane % CPR;
+        *reinterpret_cast<u32x4 *>(stg + rr * ROWB + p * 16) = rreg[it];
       }
     }
+    u32x4 hA[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) hA[kk] = u32x4{0, 0, 0, 0};
+    if (D > 1 && (BWD ? l32 >= 33 - D : l32 < D - 1)) {
+      long long hrow = BWD ? trow0 + l32 + (D - 1) : trow0 + l32 - (D - 1);  // clamped in bounds; zeroed below
+      hrow = hrow < 0 ? 0 : (hrow >= a.rows ? a.rows - 1 : hrow);
+      const bf16_t *p = lat + hrow * a.src_stride + ch0 + half * 8;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) hA[kk] = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS handles a wavefront's accesses in order
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // fragment kk of tap `back` for this lane's token: row l32 -+ back of the tile, or the halo row
+    auto row_frag = [&](auto back_c, int kk, int l32v) {
+      constexpr int back = decltype(back_c)::value;
+      const int r = BWD ? l32v + back : l32v - back;
+      const bool inside = BWD ? r < 32 : r >= 0;
+      const int rc = inside ? r : l32v;  // the lanes that take the halo read their own row and drop it
+      u32x4 raw = *reinterpret_cast<const u32x4 *>(stg + rc * ROWB + (((2 * kk + half) ^ (rc & (CPR - 1))) * 16));
+      if constexpr (back > 0) {
+        // the lane that needs row -back (adjoint: 31 + back ...) finds it in hA of the lane (D-1) - back further on
+        // (adjoint: back); both lie in the same row of 16 lanes
+        constexpr int sh = (D - 1) - back;
+        u32x4 h = hA[kk];
+        if constexpr (sh > 0) {
+          constexpr int ctrl = (BWD ? 0x110 : 0x100) + sh;  // row_shr : row_shl
+#pragma unroll
+          for (int e = 0; e < 4; ++e) h[e] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hA[kk][e], ctrl, 0xf, 0xf, true);
+        }
+        if (!inside) raw = h;
+      }
+      return __builtin_bit_cast(bf16x8, raw);
+    };
 
     // ---- y1^T = Wc * [u(t-D+1) .. u(t)]^T
     f32x16 acc[NTL];
@@ -244,17 +288,39 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[nt][r] = 0.f;
+    bf16x8 uf[KK];  // the fragments of the tap being multiplied; after the loop: the token's own row (back = 0)
+    auto conv_tap = [&](auto d_c) {
+      constexpr int d = decltype(d_c)::value;
+      constexpr int back = D - 1 - d;
+      // the LDS addresses of a tap (one per k-step: the swizzle is an XOR, not an offset) are formed here, per tap
+      // and tile, from a copy of the lane index the compiler cannot see through: hoisted out of the tile loop as
+      // loop invariants they cost 8 registers per tap for the whole kernel
+      int l32v = l32;
+      asm volatile("" : "+v"(l32v));
 #pragma unroll
-    for (int d = 0; d < D; ++d)
+      for (int kk = 0; kk < KK; ++kk) uf[kk] = row_frag(std::integral_constant<int, back>{}, kk, l32v);
+      if (back > 0 && any_pad) {  // wave-uniform and rare: a tap that reaches outside the token's sequence is zero
+        const bool outside = BWD ? tpos + back >= a.T : tpos < back;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
+        for (int kk = 0; kk < KK; ++kk)
+          if (outside) uf[kk] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
         for (int nt = 0; nt < NTL; ++nt) {
-          const int o = nt * 32 + l32;
+          const int o = nt * 32 + l32v;
           const int c = d * CPR + kk * 2 + half;
           const bf16x8 wf = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~(CPR - 1)) | ((c ^ o) & (CPR - 1)))]);
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[d][kk], acc[nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[kk], acc[nt], 0, 0, 0);
         }
+        if (kk % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // one tap's fragments at a time: the next tap's reads stay behind this one's products
+    };
+    conv_tap(std::integral_constant<int, 0>{});
+    if constexpr (D > 1) conv_tap(std::integral_constant<int, 1>{});
+    if constexpr (D > 2) conv_tap(std::integral_constant<int, 2>{});
 
     // ---- qk-mean.  q head: + (q0 + k0[g]) / 2.  k head: + (mean_r q0[gR + r] + k0) / 2.
     //      Adjoint: q head + d3_q / 2 + d3_k[g] / (2R);  k head: + (sum_r d3_q[gR + r] + d3_k) / 2.
@@ -263,7 +329,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_half[j], uf[D - 1][2 * nt + j], acc[nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_half[j], uf[2 * nt + j], acc[nt], 0, 0, 0);
       const int nsrc = is_q ? 1 : a.R;
       for (int sidx = 0; sidx < nsrc; ++sidx) {
         const int col = is_q ? a.e_q + g * DH : (g * a.R + sidx) * DH;
@@ -287,6 +353,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       }
     }
 
+    __builtin_amdgcn_sched_barrier(0);
     // ---- per token: norm, temperature, RoPE.  Lane (l32, half) holds channels
     //      o = 32*nt + 8*rg + 4*half + e of token l32 in acc[nt][4*rg + e].
     if (!BWD && (a.flags & CCA_QK_NORM)) {
@@ -305,6 +372,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     } else if (!BWD && rnorm && half == 0 && row < a.rows) {
       rnorm[row * NH + head] = 1.f;
     }
+    __builtin_amdgcn_sched_barrier(0);
     if (!BWD && (a.flags & CCA_ROPE)) {
       const int thi = tpos >> 7, tlo = tpos & 127;
 #pragma unroll
@@ -334,7 +402,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     //      staging rows in LDS (16-byte chunk c of row r at position c ^ (r mod CPR): conflict-free both ways) and
     //      leaves as whole rows, 16 bytes per lane, 64 / CPR rows per instruction.
     {
-      unsigned char *stg = smem + (size_t)DH * WROW * 16 + wave * (32 * DH * 2);
+      int l32w = l32;  // as for the tap reads: the 16 swizzled positions are formed here, not kept across tiles
+      asm volatile("" : "+v"(l32w));
 #pragma unroll
       for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
@@ -342,13 +411,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
           u32x2 w;
           w.x = pack2(acc[nt][rg * 4 + 0], acc[nt][rg * 4 + 1]);
           w.y = pack2(acc[nt][rg * 4 + 2], acc[nt][rg * 4 + 3]);
-          const int pos = (nt * 4 + rg) ^ (l32 & (CPR - 1));
-          *reinterpret_cast<u32x2 *>(stg + l32 * (DH * 2) + pos * 16 + half * 8) = w;
+          const int pos = (nt * 4 + rg) ^ (l32w & (CPR - 1));
+          *reinterpret_cast<u32x2 *>(stg + l32w * (DH * 2) + pos * 16 + half * 8) = w;
         }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS handles a wavefront's accesses in order
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      constexpr int RPI = 64 / CPR;  // rows per store instruction
 #pragma unroll
       for (int it = 0; it < 32 / RPI; ++it) {
         const int rr = it * RPI + lane / CPR, p = lane % CPR, c = p ^ (rr & (CPR - 1));
