@@ -189,28 +189,25 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   // it is exact only for R a power of two, so it is fed as the sum of two bf16 numbers, w = hi + lo (the MFMA forms
   // bf16 products exactly and adds in fp32, so hi*u + lo*u carries w to 2^-17 relative); the second pass is skipped
   // when lo is zero.
-  bf16x8 id_half[2], id_grp[2], id_grp_lo[2];  // 1/2 * I (own stream), weight of the other stream * I (hi, lo)
+  // c * I as fragments: lane (l32, half) holds c in ONE half-word of fragment j = l32 >> 4 (when (l32 >> 3) & 1 == half:
+  // element l32 & 7) and zeros elsewhere, so one mask per fragment is kept and c is and-ed in where it is used.
   const float w_other = is_q ? a.mean_q_other : a.mean_k_other;
   const bf16_t w_other_hi = f32_to_bf16(w_other);
   const bf16_t w_other_lo = f32_to_bf16(w_other - bf16_to_f32(w_other_hi));
   const bool grp_lo = (w_other_lo & 0x7fffu) != 0;  // uniform over the workgroup
-  {
-    const uint32_t hb = (uint32_t)f32_to_bf16(0.5f), gb = (uint32_t)w_other_hi, lb = (uint32_t)w_other_lo;
+  u32x4 id_sel[2];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const bool on = ((l32 >> 4) == j) && (((l32 >> 3) & 1) == half);
-      u32x4 wh = {0, 0, 0, 0}, wg = {0, 0, 0, 0}, wl = {0, 0, 0, 0};
-      const int e = l32 & 7;
-      if (on) {
-        wh[e >> 1] = hb << ((e & 1) * 16);
-        wg[e >> 1] = gb << ((e & 1) * 16);
-        wl[e >> 1] = lb << ((e & 1) * 16);
-      }
-      id_half[j] = __builtin_bit_cast(bf16x8, wh);
-      id_grp[j] = __builtin_bit_cast(bf16x8, wg);
-      id_grp_lo[j] = __builtin_bit_cast(bf16x8, wl);
-    }
+  for (int j = 0; j < 2; ++j) {
+    const bool on = ((l32 >> 4) == j) && (((l32 >> 3) & 1) == half);
+    const int e = l32 & 7;
+    id_sel[j] = u32x4{0, 0, 0, 0};
+    if (on) id_sel[j][e >> 1] = 0xffffu << ((e & 1) * 16);
   }
+  auto identity_frag = [&](bf16_t c, int j) {
+    const uint32_t cc = (uint32_t)c | ((uint32_t)c << 16);
+    const u32x4 w = {id_sel[j].x & cc, id_sel[j].y & cc, id_sel[j].z & cc, id_sel[j].w & cc};
+    return __builtin_bit_cast(bf16x8, w);
+  };
 
   for (int tt = 0; tt < tiles_per_wave; ++tt) {
     const long long trow0 = row_begin + (tt * 8 + wave) * 32;
@@ -232,30 +229,37 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     //      lane l32 < D-1 holds row l32 - (D-1) (adjoint: lane l32 >= 33-D holds row l32 + D-1) in hA.
     constexpr int RPI = 64 / CPR, NLD = 32 / RPI, ROWB = DH * 2;
     unsigned char *const stg = smem + (size_t)DH * WROW * 16 + wave * (32 * ROWB);
-    {
+    // Addresses of the whole-row transfers: a wave-uniform pointer to the tile's first row plus a 32-bit offset per
+    // lane (row it * RPI + lane / CPR of the tile, clamped to the last row of the tensor on a ragged last tile).
+    const int rows_left = (int)(a.rows - trow0 < 32 ? a.rows - trow0 : 32);  // >= 1
+    auto stage_rows = [&](const bf16_t *tile_src, int stride) {  // rows of `tile_src` -> staging rows (swizzled)
       u32x4 rreg[NLD];
 #pragma unroll
       for (int it = 0; it < NLD; ++it) {
         const int rr = it * RPI + lane / CPR, p = lane % CPR, c = p ^ (rr & (CPR - 1));
-        long long grow = trow0 + rr;
-        grow = grow < a.rows ? grow : a.rows - 1;
-        rreg[it] = *reinterpret_cast<const u32x4 *>(lat + grow * a.src_stride + ch0 + c * 8);
+        const int rs = rr < rows_left ? rr : rows_left - 1;
+        rreg[it] = *reinterpret_cast<const u32x4 *>(tile_src + rs * stride + c * 8);
       }
 #pragma unroll
       for (int it = 0; it < NLD; ++it) {
         const int rr = it * RPI + lane / CPR, p = lane % CPR;
         *reinterpret_cast<u32x4 *>(stg + rr * ROWB + p * 16) = rreg[it];
       }
-    }
+    };
+    stage_rows(lat + trow0 * a.src_stride + ch0, a.src_stride);
     u32x4 hA[KK];
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) hA[kk] = u32x4{0, 0, 0, 0};
     if (D > 1 && (BWD ? l32 >= 33 - D : l32 < D - 1)) {
-      long long hrow = BWD ? trow0 + l32 + (D - 1) : trow0 + l32 - (D - 1);  // clamped in bounds; zeroed below
-      hrow = hrow < 0 ? 0 : (hrow >= a.rows ? a.rows - 1 : hrow);
-      const bf16_t *p = lat + hrow * a.src_stride + ch0 + half * 8;
+      // row of the tensor relative to the tile's first, clamped in bounds (a clamped row is zeroed below: it lies
+      // outside the token's sequence)
+      const long long lo = -trow0, hi = a.rows - 1 - trow0;
+      int hrel = BWD ? l32 + (D - 1) : l32 - (D - 1);
+      hrel = hrel < lo ? (int)lo : (hrel > hi ? (int)hi : hrel);
+      const bf16_t *tile_src = lat + trow0 * a.src_stride + ch0;  // wave-uniform
+      const int off = hrel * a.src_stride + half * 8;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) hA[kk] = *reinterpret_cast<const u32x4 *>(p + kk * 16);
+      for (int kk = 0; kk < KK; ++kk) hA[kk] = *reinterpret_cast<const u32x4 *>(tile_src + off + kk * 16);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS handles a wavefront's accesses in order
     __builtin_amdgcn_wave_barrier();
@@ -329,26 +333,34 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_half[j], uf[2 * nt + j], acc[nt], 0, 0, 0);
+          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(identity_frag(f32_to_bf16(0.5f), j), uf[2 * nt + j], acc[nt], 0, 0, 0);
       const int nsrc = is_q ? 1 : a.R;
       for (int sidx = 0; sidx < nsrc; ++sidx) {
+        // the other stream's rows of this tile travel like the tile's own: whole rows -> staging rows -> fragments
         const int col = is_q ? a.e_q + g * DH : (g * a.R + sidx) * DH;
-        const bf16_t *p = lat + rowc * a.src_stride + col + half * 8;
+        __builtin_amdgcn_sched_barrier(0);  // not hoisted above the products before: their registers are needed there
+        stage_rows(lat + trow0 * a.src_stride + col, a.src_stride);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        int l32v = l32;
+        asm volatile("" : "+v"(l32v));
         bf16x8 mf[KK];
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk)
-          mf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(p + kk * 16));
+          mf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(
+                                                  stg + l32v * ROWB + (((2 * kk + half) ^ (l32v & (CPR - 1))) * 16)));
 #pragma unroll
         for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
           for (int j = 0; j < 2; ++j)
-            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp[j], mf[2 * nt + j], acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(identity_frag(w_other_hi, j), mf[2 * nt + j], acc[nt], 0, 0, 0);
         if (grp_lo) {
 #pragma unroll
           for (int nt = 0; nt < NTL; ++nt)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-              acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(id_grp_lo[j], mf[2 * nt + j], acc[nt], 0, 0, 0);
+              acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(identity_frag(w_other_lo, j), mf[2 * nt + j], acc[nt], 0, 0, 0);
         }
       }
     }
@@ -417,11 +429,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS handles a wavefront's accesses in order
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      bf16_t *const tile_dst = dst + trow0 * dst_stride;
 #pragma unroll
       for (int it = 0; it < 32 / RPI; ++it) {
         const int rr = it * RPI + lane / CPR, p = lane % CPR, c = p ^ (rr & (CPR - 1));
         const u32x4 val = *reinterpret_cast<const u32x4 *>(stg + rr * (DH * 2) + p * 16);
-        if (trow0 + rr < a.rows) *reinterpret_cast<u32x4 *>(dst + (trow0 + rr) * dst_stride + c * 8) = val;
+        if (rr < rows_left) *reinterpret_cast<u32x4 *>(tile_dst + rr * dst_stride + c * 8) = val;
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // the next tile's writes come after these reads
       __builtin_amdgcn_wave_barrier();
