@@ -247,19 +247,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       }
     };
     stage_rows(lat + trow0 * a.src_stride + ch0, a.src_stride);
-    u32x4 hA[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) hA[kk] = u32x4{0, 0, 0, 0};
-    if (D > 1 && (BWD ? l32 >= 33 - D : l32 < D - 1)) {
-      // row of the tensor relative to the tile's first, clamped in bounds (a clamped row is zeroed below: it lies
-      // outside the token's sequence)
-      const long long lo = -trow0, hi = a.rows - 1 - trow0;
-      int hrel = BWD ? l32 + (D - 1) : l32 - (D - 1);
+    // The D-1 rows before the tile (adjoint: after it), which the first (last) D-1 tokens' taps reach: fetched whole as
+    // well, one 16-byte chunk per lane - halo row j, chunk c in lane j * CPR + c - and handed to the lane that needs a
+    // fragment of them by a lane gather (4 registers instead of a set of fragments in every lane).
+    u32x4 halo = {0, 0, 0, 0};
+    if (D > 1 && lane < (D - 1) * CPR) {
+      const long long lo = -trow0, hi = a.rows - 1 - trow0;  // clamped in bounds; a clamped row is zeroed below:
+      int hrel = BWD ? 32 + lane / CPR : lane / CPR - (D - 1);  // it lies outside the token's sequence
       hrel = hrel < lo ? (int)lo : (hrel > hi ? (int)hi : hrel);
       const bf16_t *tile_src = lat + trow0 * a.src_stride + ch0;  // wave-uniform
-      const int off = hrel * a.src_stride + half * 8;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) hA[kk] = *reinterpret_cast<const u32x4 *>(tile_src + off + kk * 16);
+      halo = *reinterpret_cast<const u32x4 *>(tile_src + hrel * a.src_stride + (lane % CPR) * 8);
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");  // LDS handles a wavefront's accesses in order
     __builtin_amdgcn_wave_barrier();
@@ -272,15 +269,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       const int rc = inside ? r : l32v;  // the lanes that take the halo read their own row and drop it
       u32x4 raw = *reinterpret_cast<const u32x4 *>(stg + rc * ROWB + (((2 * kk + half) ^ (rc & (CPR - 1))) * 16));
       if constexpr (back > 0) {
-        // the lane that needs row -back (adjoint: 31 + back ...) finds it in hA of the lane (D-1) - back further on
-        // (adjoint: back); both lie in the same row of 16 lanes
-        constexpr int sh = (D - 1) - back;
-        u32x4 h = hA[kk];
-        if constexpr (sh > 0) {
-          constexpr int ctrl = (BWD ? 0x110 : 0x100) + sh;  // row_shr : row_shl
+        // halo row of this lane's tap: index r + (D-1) (adjoint: r - 32); its chunk 2 kk + half sits in lane
+        // index * CPR + chunk (the index is clamped for the lanes that do not take the halo)
+        int hj = BWD ? r - 32 : r + (D - 1);
+        hj = hj < 0 ? 0 : (hj > D - 2 ? D - 2 : hj);
+        const int src = (hj * CPR + 2 * kk + half) * 4;
+        u32x4 h;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) h[e] = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hA[kk][e], ctrl, 0xf, 0xf, true);
-        }
+        for (int e = 0; e < 4; ++e) h[e] = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)halo[e]);
         if (!inside) raw = h;
       }
       return __builtin_bit_cast(bf16x8, raw);
@@ -309,16 +305,25 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         for (int kk = 0; kk < KK; ++kk)
           if (outside) uf[kk] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
       }
+      // the tap's KK * NTL products in a fixed order, the filter fragment of product i + PFW requested before product
+      // i is issued (left to the compiler each fragment is read, waited for and consumed one at a time, and the LDS
+      // latency of every read is paid in full)
+      constexpr int NPW = KK * NTL, PFW = 4;
+      bf16x8 wfr[PFW + 1];  // ring: fragment i lives in slot i mod (PFW + 1)
+      auto fetch_w = [&](int i) {
+        const int kk = i / NTL, nt = i % NTL;
+        const int o = nt * 32 + l32v;
+        const int c = d * CPR + kk * 2 + half;
+        wfr[i % (PFW + 1)] = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~(CPR - 1)) | ((c ^ o) & (CPR - 1)))]);
+      };
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
+      for (int i = 0; i < PFW; ++i) fetch_w(i);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int nt = 0; nt < NTL; ++nt) {
-          const int o = nt * 32 + l32v;
-          const int c = d * CPR + kk * 2 + half;
-          const bf16x8 wf = __builtin_bit_cast(bf16x8, sW[o * WROW + ((c & ~(CPR - 1)) | ((c ^ o) & (CPR - 1)))]);
-          acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, uf[kk], acc[nt], 0, 0, 0);
-        }
-        if (kk % 2 == 1) __builtin_amdgcn_sched_barrier(0);
+      for (int i = 0; i < NPW; ++i) {
+        if (i + PFW < NPW) fetch_w(i + PFW);
+        acc[i % NTL] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfr[i % (PFW + 1)], uf[i / NTL], acc[i % NTL], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
       __builtin_amdgcn_sched_barrier(0);  // one tap's fragments at a time: the next tap's reads stay behind this one's products
     };
