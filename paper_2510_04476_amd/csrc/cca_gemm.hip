@@ -113,8 +113,27 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
   issue_slab(0, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  // Within a slab the fragments of k-step kk+1 are requested before the MFMAs of k-step kk are issued (two register
+  // sets): only the first k-step of a slab, right after the slab barrier, pays its LDS latency in the open.
+  // Warm same-box A/B: the projections timed alone, back to back, are 2-5 % SLOWER this way (102 -> 104, 74 -> 78 us),
+  // the forward pass they are part of is 0.8 % faster (0.668 -> 0.6625 ms, repeated in both orders): inside a pass
+  // their operands come from further away than in a loop over the same GEMM.
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
+    bf16x8 fa[2][MI], fb[2][NI];
+    auto read_frags = [&](int kk, int set) {
+#pragma unroll
+      for (int mi = 0; mi < MI; ++mi) {
+        const int r = wm * WM + mi * 32 + l32;
+        fa[set][mi] = __builtin_bit_cast(bf16x8, sbase[buf * STAGE + swz(r, kk * 2 + half)]);
+      }
+#pragma unroll
+      for (int ni = 0; ni < NI; ++ni) {
+        const int r = wn * WN + ni * 32 + l32;
+        fb[set][ni] = __builtin_bit_cast(bf16x8, sbase[buf * STAGE + BM * 8 + swz(r, kk * 2 + half)]);
+      }
+    };
+    read_frags(0, 0);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       // the loads of slab kt+1 are issued over the first SPREAD k-steps: not in one burst (the LDS write port), not
@@ -127,29 +146,18 @@ __global__ __launch_bounds__(WAVES_M *WAVES_N * 64) void gemm_bf16_nt_kernel(con
           __builtin_amdgcn_global_load_lds((glb_void *)(g_src[u] + (kt + 1) * BK), (lds_void *)(sbase + (buf ^ 1) * STAGE + i * 64), 16, 0, 0);
         }
       }
-      bf16x8 fa[MI], fb[NI];
-#pragma unroll
-      for (int mi = 0; mi < MI; ++mi) {
-        const int r = wm * WM + mi * 32 + l32;
-        u32x4 t = sbase[buf * STAGE + swz(r, kk * 2 + half)];
-        fa[mi] = __builtin_bit_cast(bf16x8, t);
-      }
-#pragma unroll
-      for (int ni = 0; ni < NI; ++ni) {
-        const int r = wn * WN + ni * 32 + l32;
-        u32x4 t = sbase[buf * STAGE + BM * 8 + swz(r, kk * 2 + half)];
-        fb[ni] = __builtin_bit_cast(bf16x8, t);
-      }
+      if (kk + 1 < BK / 16) read_frags(kk + 1, (kk + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ni], fa[mi], acc[ni][mi], 0, 0, 0);
+          acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][ni], fa[kk & 1][mi], acc[ni][mi], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
-
   // Epilogue.  acc[ni][mi][r] = C[m][n] with m = wm*WM + mi*32 + l32 and
   // n = wn*WN + ni*32 + 8*(r/4) + 4*half + r%4.
   constexpr int ROW_BYTES = BN * 2 + 16;  // padded row: 8-byte column writes of 32 rows hit distinct banks
