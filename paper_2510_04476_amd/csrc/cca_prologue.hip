@@ -225,8 +225,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     //      in LDS (chunk c of row r at position c ^ (r mod CPR)) and read from there as MFMA fragments, tap by tap.
     //      Fetched as fragments straight from memory, each tap cost 8 load instructions that touch 32 rows with 32
     //      bytes each; the vector memory pipeline works per cache line touched (timing without the D-1 earlier taps'
-    //      loads: 56 -> 46 us).  The D-1 rows before the tile (adjoint: after it) go to the lanes that need them:
-    //      lane l32 < D-1 holds row l32 - (D-1) (adjoint: lane l32 >= 33-D holds row l32 + D-1) in hA.
+    //      loads: 56 -> 46 us).  The D-1 rows before the tile (adjoint: after it) are handled below (`halo`).
     constexpr int RPI = 64 / CPR, NLD = 32 / RPI, ROWB = DH * 2;
     unsigned char *const stg = smem + (size_t)DH * WROW * 16 + wave * (32 * ROWB);
     // Addresses of the whole-row transfers: a wave-uniform pointer to the tile's first row plus a 32-bit offset per
