@@ -26,10 +26,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 # HBM bytes per attn_fwd_kernel launch on the ccgqa_16k workload, from two rocprofv3 --pmc runs (FETCH_SIZE
-# 147.04 MiB after scaling by 2.000, WRITE_SIZE 32.06 MiB after scaling by 1.000, the factors a 256 MiB
+# 146.10 MiB after scaling by 2.000, WRITE_SIZE 32.05 MiB after scaling by 1.000, the factors a 256 MiB
 # device-to-device copy gives for the same counters); summary in profiles/ccgqa_16k_hbm_traffic_pmc.txt.
 # Algorithmic bytes of the kernel: 80 MiB (Q 32 + K,V 16 read, O 32 written).
-ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((146.42 + 32.05) * 2 ** 20)}
+ATTN_TRAFFIC_BYTES = {"ccgqa_16k": int((146.10 + 32.05) * 2 ** 20)}
 
 
 # Layouts of the grid, all at E = 2048 through the same entry points, head counts for d_h = 128 (at d_h = 64 there
