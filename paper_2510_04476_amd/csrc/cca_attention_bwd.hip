@@ -141,19 +141,22 @@ __global__ __launch_bounds__(256) void delta_kernel(const bf16_t *__restrict__ d
 // ---------------------------------------------------------------------------
 // dQ
 // ---------------------------------------------------------------------------
-constexpr int DQ_BQ = 256, DQ_NT = 512, BKV = 64;
+constexpr int DQ_NT = 512, BKV = 64;
 
-template <int DH, bool CAUSAL>
-__global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(
+// DQ_NT_ threads = DQ_NT_ / 64 wavefronts x 32 query rows per workgroup: 512 threads (two wavefronts per SIMD) for
+// d_h <= 128; 256 threads (one wavefront per SIMD, twice the registers: the 32 x 256 accumulator moves to the
+// accumulation registers) for d_h = 256.
+template <int DH, bool CAUSAL, int DQ_NT_>
+__device__ __forceinline__ void attn_bwd_dq_body(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
-    bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale) {
+    bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale, unsigned char *smem) {
   CCA_BWD_GEOMETRY(DH);
+  constexpr int DQ_BQ = DQ_NT_ / 2;
   constexpr int TILE = BKV * ROW;
-  constexpr int PER_THREAD = BKV * KCH / DQ_NT;  // 16-byte chunks of K (and of V) per thread per tile
-  constexpr int ROWS_PER_PASS = DQ_NT / KCH;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * TILE];  // K0 K1 V0 V1
-  unsigned char *const sK = smem, *const sV = smem + 2 * TILE;
+  constexpr int PER_THREAD = BKV * KCH / DQ_NT_;  // 16-byte chunks of K (and of V) per thread per tile
+  constexpr int ROWS_PER_PASS = DQ_NT_ / KCH;
+  unsigned char *const sK = smem, *const sV = smem + 2 * TILE;  // K0 K1 V0 V1
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, half = lane >> 5;
@@ -166,8 +169,11 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   const unsigned char *const Vg = reinterpret_cast<const unsigned char *>(V + ((long long)b * T * Hk + g) * DH);
 
   const int s_r0 = tid / KCH, s_ch = tid % KCH;
-  const uint32_t s_off = (uint32_t)s_r0 * ROW + ((s_ch ^ swz(s_r0)) << 4);  // rows of later passes: + multiples of 16
-  static_assert(ROWS_PER_PASS % 16 == 0, "the swizzle of a row depends on its index modulo 16");
+  // chunk i of this thread lies ROWS_PER_PASS * i rows further down; the swizzle of a row depends on its index
+  // modulo 16, so with 8 rows per pass the odd passes flip bit 1 of the chunk position
+  static_assert(ROWS_PER_PASS % 8 == 0, "the swizzle of a row depends on its index modulo 16");
+  const uint32_t s_off = (uint32_t)s_r0 * ROW + ((s_ch ^ swz(s_r0)) << 4);
+  const uint32_t s_off_odd = ROWS_PER_PASS % 16 == 0 ? s_off : (s_off ^ 32u);
   const LaneSwz LS = lane_swz<DH>(lane);
 
   u32x4 rk[PER_THREAD], rv[PER_THREAD];
@@ -182,8 +188,9 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
-      *reinterpret_cast<u32x4 *>(sK + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rk[i];
-      *reinterpret_cast<u32x4 *>(sV + buf * TILE + s_off + i * ROWS_PER_PASS * ROW) = rv[i];
+      const uint32_t o = ((i & 1) ? s_off_odd : s_off) + i * ROWS_PER_PASS * ROW;
+      *reinterpret_cast<u32x4 *>(sK + buf * TILE + o) = rk[i];
+      *reinterpret_cast<u32x4 *>(sV + buf * TILE + o) = rv[i];
     }
   };
 
@@ -322,6 +329,24 @@ __global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
   }  // pass
 }
 
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(DQ_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+    const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
+    bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BKV * (DH * 2 + 64)];
+  attn_bwd_dq_body<DH, CAUSAL, DQ_NT>(Q, K, V, dO, LSE, DELTA, dQ, T, Hq, Hk, BH, nqb, paired, scale, smem);
+}
+
+template <int DH, bool CAUSAL>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dq_wide_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+    const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
+    bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * BKV * (DH * 2 + 64)];
+  attn_bwd_dq_body<DH, CAUSAL, 256>(Q, K, V, dO, LSE, DELTA, dQ, T, Hq, Hk, BH, nqb, paired, scale, smem);
+}
+
 // q in log2 units, rounded to bf16 exactly as the forward kernel rounds it (see the note at the top): written once
 // so that the dK / dV kernel can move its Q tiles global -> LDS directly
 __global__ __launch_bounds__(256) void scale_q_kernel(const bf16_t *__restrict__ Q, bf16_t *__restrict__ Qs, long long n8,
@@ -339,7 +364,7 @@ __global__ __launch_bounds__(256) void scale_q_kernel(const bf16_t *__restrict__
 // ---------------------------------------------------------------------------
 // dK, dV
 // ---------------------------------------------------------------------------
-constexpr int KV_BK = 256, KV_NT = 512, BQT = 64;  // keys per workgroup, threads, query rows per LDS tile
+constexpr int KV_NT = 512, BQT = 64;  // threads, query rows per LDS tile; a workgroup owns KV_NT / 2 keys
 
 // PARTIAL = false (one query head per KV head): dK, dV written as bf16 (B,T,H_k,d_h).
 // PARTIAL = true: this head's contribution written as fp32 to dKp, dVp (B,T,H_q,d_h).
@@ -348,25 +373,31 @@ constexpr int KV_BK = 256, KV_NT = 512, BQT = 64;  // keys per workgroup, thread
 // staging registers; q arrives pre-scaled from scale_q_kernel), S is turned into bf16 P before dP is formed, and
 // dS is computed from that bf16 P.  (With register staging and fp32 P the pass spilled 98 registers; split into a
 // dV pass and a dK pass it cost a fifth contraction.)
-template <int DH, bool CAUSAL, bool PARTIAL>
-__global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(
+// KV_NT_ threads = KV_NT_ / 64 wavefronts x 32 keys per workgroup: 512 (two wavefronts per SIMD) for d_h <= 128; 256
+// (one wavefront per SIMD: dK and dV, 128 registers each, fill the accumulation registers, and the V fragments stay
+// in ordinary registers because the Q / dO tiles leave no LDS for them) for d_h = 256.
+// PARTS: 3 = dK and dV in one pass; 1 = dV only (S, P, dV); 2 = dK only (S, P, dP, dS, dK).  The one-wavefront form
+// runs the two halves as two launches: both 32 x 256 accumulators together fill every accumulation register, and
+// the compiler then has nowhere to put the S and dP chains (measured: 178 scratch accesses per loop iteration).
+template <int DH, bool CAUSAL, bool PARTIAL, int KV_NT_, int PARTS>
+__device__ __forceinline__ void attn_bwd_dkdv_body(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
     bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
-    int Hk, int BH, int nkb, float scale) {
+    int Hk, int BH, int nkb, float scale, unsigned char *smem) {
   CCA_BWD_GEOMETRY(DH);
+  constexpr int KV_NT = KV_NT_, KV_BK = KV_NT_ / 2;
+  constexpr bool V_IN_REGS = KV_NT_ == 256;
+  constexpr bool DO_V = (PARTS & 1) != 0, DO_K = (PARTS & 2) != 0;
   constexpr int TILE = BQT * ROW;
-  constexpr int PER_THREAD = BQT * KCH / KV_NT;
-  constexpr int ROWS_PER_PASS = KV_NT / KCH;
-  // Q0 Q1 dO0 dO1, 4 * TILE bytes of dynamic LDS: with a static array the compiler makes every LDS read wait for the
-  // tile loads in flight (vmcnt(0): a load into LDS might alias what is read), which puts the latency of the next
-  // tile's loads in front of each step
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // smem: Q0 Q1 dO0 dO1, 4 * TILE bytes of dynamic LDS (with a static array the compiler makes every LDS read wait
+  // for the tile loads in flight (vmcnt(0): a load into LDS might alias what is read), which puts the latency of the
+  // next tile's loads in front of each step)
   __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];                                      // [buf][lse2 | delta][row]
   // this workgroup's V rows as MFMA operand fragments, [wavefront][kk][lane] x 16 bytes: each wavefront keeps its own
-  // (read back one fragment per dP product; holding them in registers next to the K fragments and the two
-  // accumulators leaves no room for fragments requested ahead of their use)
-  __shared__ __attribute__((aligned(16))) u32x4 sVf[KV_NT / 64][KK][64];
+  // (read back one fragment per dP product; at two wavefronts per SIMD, holding them in registers next to the K
+  // fragments and the two accumulators leaves no room for fragments requested ahead of their use)
+  __shared__ __attribute__((aligned(16))) u32x4 sVf[V_IN_REGS ? 1 : KV_NT / 64][V_IN_REGS ? 1 : KK][64];
   unsigned char *const sQ = smem, *const sD = smem + 2 * TILE;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -382,6 +413,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 
   // this wavefront's 32 keys: K and V rows as second MFMA operands, resident in registers
   bf16x8 kf[KK];
+  u32x4 vreg[V_IN_REGS ? KK : 1];
   {
     const int s = min(kw0 + l32, T - 1);
     const bf16_t *pk = K + (((long long)b * T + s) * Hk + g) * DH + half * 8;
@@ -389,9 +421,15 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pk + kk * 16));
-      sVf[wave][kk][lane] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
+      if constexpr (!DO_K) continue;  // V enters dP only
+      if constexpr (V_IN_REGS) vreg[kk] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
+      else sVf[wave][kk][lane] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
     }
   }
+  auto v_frag = [&](int kk) {
+    if constexpr (V_IN_REGS) return vreg[kk];
+    else return sVf[wave][kk][lane];
+  };
   f32x16 dk[DT], dv[DT];  // dK^T, dV^T: lane = key, registers = channels
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
@@ -466,6 +504,13 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     };
     bf16x8 pf[2], dsf[2];
     u32x4 fr[PF], fd[PF], fv[PF];
+    // products of the last phase: dV (jj, dt), then dK (jj, dt), whichever of them this pass computes
+    constexpr int NP = (DO_V + DO_K) * 2 * DT;
+    auto frag_of = [&](int i) {  // i -> (dO | Q, jj, dt)
+      const int which = (DO_V && DO_K) ? i / (2 * DT) : (DO_K ? 1 : 0), jj = (i / DT) & 1, dt = i % DT;
+      return tr_frag<ROW>(which ? qp : dp_, LS, qs * 32 + jj * 16, dt);
+    };
+    bf16x8 tv[PF];  // transposed fragments of the first products of the last phase, requested under the chain before it
 #pragma unroll
     for (int i = 0; i < PF; ++i) fr[i] = col(qp, i);
     {  // S[t, key] -> P, packed to bf16 at once
@@ -476,9 +521,11 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
       for (int kk = 0; kk < KK; ++kk) {
         const bf16x8 qa = __builtin_bit_cast(bf16x8, fr[kk % PF]);
         if (kk + PF < KK) fr[kk % PF] = col(qp, kk + PF);
-        else {  // first fragments of the dP chain
+        else if constexpr (DO_K) {  // first fragments of the dP chain
           fd[kk + PF - KK] = col(dp_, kk + PF - KK);
-          fv[kk + PF - KK] = sVf[wave][kk + PF - KK][lane];
+          fv[kk + PF - KK] = v_frag(kk + PF - KK);
+        } else {  // no dP chain: first transposed fragments of the last phase
+          tv[kk + PF - KK] = frag_of(kk + PF - KK);
         }
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
@@ -507,13 +554,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
       pf[1] = __builtin_bit_cast(bf16x8, w[1]);
     }
     __builtin_amdgcn_sched_barrier(0);
-    constexpr int NP = 4 * DT;  // products of the last phase: dV (jj, dt), then dK (jj, dt)
-    auto frag_of = [&](int i) {  // i -> (dO | Q, jj, dt)
-      const int which = i / (2 * DT), jj = (i / DT) & 1, dt = i % DT;
-      return tr_frag<ROW>(which ? qp : dp_, LS, qs * 32 + jj * 16, dt);
-    };
-    bf16x8 tv[PF];  // transposed fragments of the first products of the last phase, requested under the dP chain
-    {  // dP[t, key] -> dS = P (dP - Delta), P taken back from its bf16 form
+    if constexpr (DO_K) {  // dP[t, key] -> dS = P (dP - Delta), P taken back from its bf16 form
       f32x16 dp;
 #pragma unroll
       for (int r = 0; r < 16; ++r) dp[r] = 0.f;
@@ -522,7 +563,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         const bf16x8 da = __builtin_bit_cast(bf16x8, fd[kk % PF]), vb = __builtin_bit_cast(bf16x8, fv[kk % PF]);
         if (kk + PF < KK) {
           fd[kk % PF] = col(dp_, kk + PF);
-          fv[kk % PF] = sVf[wave][kk + PF][lane];
+          fv[kk % PF] = v_frag(kk + PF);
         } else {
           tv[kk + PF - KK] = frag_of(kk + PF - KK);
         }
@@ -548,7 +589,7 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     for (int i = 0; i < NP; ++i) {
       const bf16x8 f = tv[i % PF];
       if (i + PF < NP) tv[i % PF] = frag_of(i + PF);
-      const int which = i / (2 * DT), jj = (i / DT) & 1, dt = i % DT;
+      const int which = (DO_V && DO_K) ? i / (2 * DT) : (DO_K ? 1 : 0), jj = (i / DT) & 1, dt = i % DT;
       if (which == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[jj], dv[dt], 0, 0, 0);
       else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[jj], dk[dt], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
@@ -591,8 +632,8 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
           const f32x4 w = {dk[dt][rg * 4 + 0] * LN2, dk[dt][rg * 4 + 1] * LN2, dk[dt][rg * 4 + 2] * LN2,
                            dk[dt][rg * 4 + 3] * LN2};
           const f32x4 x = {dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1], dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]};
-          *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-          *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+          if constexpr (DO_K) *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+          if constexpr (DO_V) *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
         }
     }
     return;
@@ -609,10 +650,30 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
         w.y = pack2(dk[dt][rg * 4 + 2] * LN2, dk[dt][rg * 4 + 3] * LN2);
         x.x = pack2(dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1]);
         x.y = pack2(dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]);
-        *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-        *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+        if constexpr (DO_K) *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+        if constexpr (DO_V) *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
       }
   }
+}
+
+template <int DH, bool CAUSAL, bool PARTIAL>
+__global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkdv_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+    const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
+    bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
+    int Hk, int BH, int nkb, float scale) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  attn_bwd_dkdv_body<DH, CAUSAL, PARTIAL, KV_NT, 3>(Q, K, V, dO, LSE, DELTA, dK, dV, dKp, dVp, T, Hq, Hk, BH, nkb, scale, smem);
+}
+
+template <int DH, bool CAUSAL, bool PARTIAL, int PARTS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dkdv_wide_kernel(
+    const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
+    const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
+    bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
+    int Hk, int BH, int nkb, float scale) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  attn_bwd_dkdv_body<DH, CAUSAL, PARTIAL, 256, PARTS>(Q, K, V, dO, LSE, DELTA, dK, dV, dKp, dVp, T, Hq, Hk, BH, nkb, scale, smem);
 }
 
 // out[(row, g), :] = bf16(sum_r part[(row, g*R + r), :]) for dK and dV, 4 channels per thread, fixed order
@@ -641,7 +702,7 @@ __global__ __launch_bounds__(256) void group_sum_kernel(const float *__restrict_
 }  // namespace
 
 bool attention_bwd_supported(const Dims &d) {
-  return d.bf16 && (d.dh == 128 || d.dh == 64) && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
+  return d.bf16 && (d.dh == 256 || d.dh == 128 || d.dh == 64) && (long long)d.T * d.Hq * d.dh * 2 < (1ll << 31);
 }
 
 // Delta (B,H_q,T) fp32, then (R > 1 only) the per-query-head fp32 contributions to dK and dV, (B,T,H_q,d_h) each,
@@ -664,8 +725,12 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
                                                              d.Hq);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int BH = d.B * d.Hq, nqb = (d.T + DQ_BQ - 1) / DQ_BQ;
-  const int nkb = (d.T + KV_BK - 1) / KV_BK;
+  constexpr bool WIDE = DH > 128;                 // one wavefront per SIMD, half as many rows per workgroup
+  constexpr int NTH = WIDE ? 256 : DQ_NT;         // threads of both kernels (DQ_NT == KV_NT)
+  constexpr int ROWS = NTH / 2;                   // query rows (dQ) or keys (dK / dV) per workgroup
+  static_assert(DQ_NT == KV_NT, "one thread count for both kernels");
+  const int BH = d.B * d.Hq, nqb = (d.T + ROWS - 1) / ROWS;
+  const int nkb = (d.T + ROWS - 1) / ROWS;
   float *pk = reinterpret_cast<float *>(reinterpret_cast<char *>(delta) + delta_bytes(d));
   float *pv = pk + (size_t)d.rows() * d.e_q;
   bf16_t *qs = reinterpret_cast<bf16_t *>(reinterpret_cast<char *>(delta) + delta_bytes(d) +
@@ -686,20 +751,30 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
   const bool partial = d.R > 1;
   // (the dynamic-LDS limit is raised once per kernel and device: raise_lds_limit)
 #define LAUNCH_KV(C_, P_)                                                                                     \
-  {                                                                                                           \
+  if constexpr (WIDE) { /* dV pass, then dK pass */                                                           \
+    e = raise_lds_limit<attn_bwd_dkdv_wide_kernel<DH, C_, P_, 1>>(kv_smem);                                   \
+    if (e != hipSuccess) return e;                                                                            \
+    e = raise_lds_limit<attn_bwd_dkdv_wide_kernel<DH, C_, P_, 2>>(kv_smem);                                   \
+    if (e != hipSuccess) return e;                                                                            \
+    attn_bwd_dkdv_wide_kernel<DH, C_, P_, 1><<<gkv, NTH, kv_smem, s>>>(ARGS_KV);                               \
+    attn_bwd_dkdv_wide_kernel<DH, C_, P_, 2><<<gkv, NTH, kv_smem, s>>>(ARGS_KV);                               \
+  } else {                                                                                                    \
     e = raise_lds_limit<attn_bwd_dkdv_kernel<DH, C_, P_>>(kv_smem);                                           \
     if (e != hipSuccess) return e;                                                                            \
-    attn_bwd_dkdv_kernel<DH, C_, P_><<<gkv, KV_NT, kv_smem, s>>>(ARGS_KV);                                     \
+    attn_bwd_dkdv_kernel<DH, C_, P_><<<gkv, NTH, kv_smem, s>>>(ARGS_KV);                                       \
   }
+#define LAUNCH_DQ(C_, G_)                                                                                     \
+  if constexpr (WIDE) attn_bwd_dq_wide_kernel<DH, C_><<<(unsigned)(G_), NTH, 0, s>>>(ARGS_DQ);                 \
+  else attn_bwd_dq_kernel<DH, C_><<<(unsigned)(G_), NTH, 0, s>>>(ARGS_DQ);
   if (causal) {
-    attn_bwd_dq_kernel<DH, true><<<(unsigned)((long long)BH * (paired ? (nqb + 1) / 2 : nqb)), DQ_NT, 0, s>>>(ARGS_DQ);
+    LAUNCH_DQ(true, (long long)BH * (paired ? (nqb + 1) / 2 : nqb));
     if (partial) {
       LAUNCH_KV(true, true);
     } else {
       LAUNCH_KV(true, false);
     }
   } else {
-    attn_bwd_dq_kernel<DH, false><<<(unsigned)((long long)BH * nqb), DQ_NT, 0, s>>>(ARGS_DQ);
+    LAUNCH_DQ(false, (long long)BH * nqb);
     if (partial) {
       LAUNCH_KV(false, true);
     } else {
@@ -707,6 +782,7 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
     }
   }
 #undef LAUNCH_KV
+#undef LAUNCH_DQ
 #undef ARGS_DQ
 #undef ARGS_KV
   if (partial) {
@@ -719,8 +795,9 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
 hipError_t attention_bwd_bf16(const Dims &d, const void *q, const void *k, const void *v, const void *o,
                               const void *o_lo, const float *lse, const void *d_o, void *d_q, void *d_k, void *d_v, float *delta,
                               hipStream_t s) {
-  return d.dh == 64 ? attention_bwd_run<64>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s)
-                    : attention_bwd_run<128>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s);
+  return d.dh == 64    ? attention_bwd_run<64>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s)
+         : d.dh == 128 ? attention_bwd_run<128>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s)
+                       : attention_bwd_run<256>(d, q, k, v, o, o_lo, lse, d_o, d_q, d_k, d_v, delta, s);
 }
 
 }  // namespace cca

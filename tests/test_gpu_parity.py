@@ -354,11 +354,16 @@ def test_forward_is_deterministic_and_causal_on_gpu():
 
 
 # ---- backward of the attention stage against the oracle's adjoint ------------------------------
-@pytest.mark.parametrize("T,Hq,Hk,causal", [(700, 8, 2, True), (333, 4, 4, True), (520, 4, 1, False), (64, 2, 2, True),
-                                            (450, 6, 2, True), (300, 6, 1, False)])
-def test_attention_backward_stage(T, Hq, Hk, causal):
-    say("case attention backward", T, Hq, Hk, causal)
-    dh, Bn = 128, 2
+@pytest.mark.parametrize("T,Hq,Hk,causal,dh", [
+    (700, 8, 2, True, 128), (333, 4, 4, True, 128), (520, 4, 1, False, 128), (64, 2, 2, True, 128), (450, 6, 2, True, 128),
+    (300, 6, 1, False, 128),
+    # d_h = 256: the one-wavefront-per-SIMD kernels (128 query rows / 128 keys per workgroup, dV and dK in two passes):
+    # several blocks with a ragged tail, R = 2 / 1 / 4 / 3, a single short block, non-causal
+    (700, 4, 2, True, 256), (333, 2, 2, True, 256), (520, 4, 1, False, 256), (64, 2, 2, True, 256), (390, 3, 1, True, 256),
+    (129, 2, 1, False, 256)])
+def test_attention_backward_stage(T, Hq, Hk, causal, dh):
+    say("case attention backward", T, Hq, Hk, causal, dh)
+    Bn = 2
     rng = np.random.default_rng(100 + T)
     q = rng.standard_normal((Bn, T, Hq, dh))
     k = rng.standard_normal((Bn, T, Hk, dh))
