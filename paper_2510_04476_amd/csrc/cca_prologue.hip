@@ -452,9 +452,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 // (one slab per tap and quarter of the head width), all 8 wavefronts of a workgroup walking the slabs in step.
 // Workgroup = one head x 256 tokens, wavefront = 32 tokens x all 256 outputs (8 accumulator tiles).  The token
 // operands of a slab (4 fragments) come straight from the latent rows as in the kernel above; the qk-mean, norm,
-// temperature, RoPE and the value role are the same code.  Forward only.
+// temperature, RoPE and the value role are the same code.  BWD = true is the adjoint, as for the kernel above:
+// transposed filter, taps reaching forward in time, the value shift running backwards; the host passes only the
+// qk-mean and value-shift flags, so the norm and RoPE steps are skipped.
 // ---------------------------------------------------------------------------
-template <int DH, int D>
+template <int DH, int D, bool BWD>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void prologue_stream_kernel(
     FusedArgs a, const bf16_t *__restrict__ lat, const bf16_t *__restrict__ vsrc, const u32x4 *__restrict__ wc,
     const float2 *__restrict__ ropeA, const float2 *__restrict__ ropeB, const float *__restrict__ temp,
@@ -484,7 +486,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
       const int t = (int)(row % a.T);
       u32x4 val = {0, 0, 0, 0};
       const bool shifted = (a.flags & CCA_V_SHIFT) && ch >= a.v_half;
-      if (!shifted || t > 0) val = *reinterpret_cast<const u32x4 *>(vsrc + (row - (shifted ? 1 : 0)) * a.vsrc_stride + ch);
+      const bool live = !shifted || (BWD ? t + 1 < a.T : t > 0);
+      if (live) val = *reinterpret_cast<const u32x4 *>(vsrc + (row + (shifted ? (BWD ? 1 : -1) : 0)) * a.vsrc_stride + ch);
       *reinterpret_cast<u32x4 *>(v + row * a.vdst_stride + ch) = val;
     }
     return;
@@ -552,17 +555,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(2, 2))) void
   for (int s_ = 0; s_ < NSLAB; ++s_) {
     const int d = s_ / NCH, c = s_ % NCH;
     if (s_ + 1 < NSLAB) load_slab(s_ + 1);
-    // token operands of this slab: row t - (D-1-d), channels c*64 .. c*64+63; rows before the sequence start are zero
+    // token operands of this slab: row t - (D-1-d) (adjoint: t + (D-1-d)), channels c*64 .. c*64+63; rows outside
+    // the token's sequence are zero
     const int back = D - 1 - d;
     bf16x8 uf[KCK];
     {
-      long long src_row = rowc - back;
-      src_row = src_row < 0 ? 0 : src_row;
+      long long src_row = BWD ? rowc + back : rowc - back;
+      src_row = src_row < 0 ? 0 : (src_row > a.rows - 1 ? a.rows - 1 : src_row);
       const bf16_t *p = lat + src_row * a.src_stride + ch0 + c * KC + half * 8;
 #pragma unroll
       for (int kk = 0; kk < KCK; ++kk) {
         u32x4 raw = *reinterpret_cast<const u32x4 *>(p + kk * 16);
-        if (tpos < back) raw = u32x4{0, 0, 0, 0};
+        if (BWD ? tpos + back >= a.T : tpos < back) raw = u32x4{0, 0, 0, 0};
         uf[kk] = __builtin_bit_cast(bf16x8, raw);
       }
     }
@@ -851,9 +855,9 @@ hipError_t prologue_fused_prepare(const Dims &d, const cca_weights &w, void *scr
   return run_setup(d, forward_args(d), w, carve(d, scratch, D), D, false, s);
 }
 
-template <int D>
-static hipError_t launch_stream(const Dims &d, FusedArgs a, const cca_weights &w, const void *lat, const FusedScratch &fs,
-                                void *q, void *k, void *v, float *rnorm, hipStream_t s) {
+template <int D, bool BWD>
+static hipError_t launch_stream(const Dims &d, FusedArgs a, const float *temp, const void *lat, const void *vsrc,
+                                const FusedScratch &fs, void *q, void *k, void *v, float *rnorm, hipStream_t s) {
   // one 256-token block per workgroup for every head, key heads first (the kernel's block map)
   const long long blocks = (d.rows() + 255) / 256;
   a.tiles_per_wave = a.tiles_per_wave_k = 1;
@@ -861,9 +865,9 @@ static hipError_t launch_stream(const Dims &d, FusedArgs a, const cca_weights &w
   a.n_conv_blocks = (int)((d.Hq + d.Hk) * blocks);
   const long long v_chunks = d.rows() * (d.e_kv / 8);
   const int grid = a.n_conv_blocks + (int)((v_chunks + NT * 4 - 1) / (NT * 4));
-  prologue_stream_kernel<256, D><<<grid, NT, 0, s>>>(a, (const bf16_t *)lat, (const bf16_t *)lat + d.e_q + d.e_kv,
-                                                   (const u32x4 *)fs.wc, fs.ropeA, fs.ropeB, w.temp, (bf16_t *)q,
-                                                   (bf16_t *)k, (bf16_t *)v, rnorm);
+  prologue_stream_kernel<256, D, BWD><<<grid, NT, 0, s>>>(a, (const bf16_t *)lat, (const bf16_t *)vsrc,
+                                                        (const u32x4 *)fs.wc, fs.ropeA, fs.ropeB, temp, (bf16_t *)q,
+                                                        (bf16_t *)k, (bf16_t *)v, rnorm);
   return hipGetLastError();
 }
 
@@ -872,15 +876,15 @@ hipError_t prologue_fused_run(const Dims &d, const cca_weights &w, const void *l
   const int D = taps(d);
   FusedArgs a = forward_args(d);
   const FusedScratch fs = carve(d, const_cast<void *>(scratch), D);
+  const bf16_t *vsrc = (const bf16_t *)lat + d.e_q + d.e_kv;
   if (d.dh == 256) {
     switch (D) {
-      case 1: return launch_stream<1>(d, a, w, lat, fs, q, k, v, rnorm, s);
-      case 2: return launch_stream<2>(d, a, w, lat, fs, q, k, v, rnorm, s);
-      default: return launch_stream<3>(d, a, w, lat, fs, q, k, v, rnorm, s);
+      case 1: return launch_stream<1, false>(d, a, w.temp, lat, vsrc, fs, q, k, v, rnorm, s);
+      case 2: return launch_stream<2, false>(d, a, w.temp, lat, vsrc, fs, q, k, v, rnorm, s);
+      default: return launch_stream<3, false>(d, a, w.temp, lat, vsrc, fs, q, k, v, rnorm, s);
     }
   }
   const int grid = plan_grid(d, a);
-  const bf16_t *vsrc = (const bf16_t *)lat + d.e_q + d.e_kv;
 #define LAUNCH_DH(D_, B_) (d.dh == 64 ? launch_main<64, D_, B_> : launch_main<128, D_, B_>)
   switch (D) {
     case 1: return LAUNCH_DH(1, false)(a, lat, vsrc, fs.wc, fs.ropeA, fs.ropeB, w.temp, q, k, v, rnorm, grid, s);
@@ -918,8 +922,15 @@ hipError_t prologue_fused_bwd_dlat(const Dims &d, const void *d3, const void *d_
               d.flags & (CCA_QK_MEAN | CCA_V_SHIFT), 0, 1, d.rope_base, 0.f, ld, d.n_lat, d.n_lat, d.e_kv, d.n_lat,
               0.5f / (float)d.R, 0.5f};
   const FusedScratch fs = carve(d, scratch, D);
-  const int grid = plan_grid(d, a);
   bf16_t *dl = (bf16_t *)d_lat;
+  if (d.dh == 256) {
+    switch (D) {
+      case 1: return launch_stream<1, true>(d, a, nullptr, d3, d_v, fs, dl, dl + d.e_q, dl + ld, nullptr, s);
+      case 2: return launch_stream<2, true>(d, a, nullptr, d3, d_v, fs, dl, dl + d.e_q, dl + ld, nullptr, s);
+      default: return launch_stream<3, true>(d, a, nullptr, d3, d_v, fs, dl, dl + d.e_q, dl + ld, nullptr, s);
+    }
+  }
+  const int grid = plan_grid(d, a);
   switch (D) {
     case 1: return LAUNCH_DH(1, true)(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);
     case 2: return LAUNCH_DH(2, true)(a, d3, d_v, fs.wc, fs.ropeA, fs.ropeB, nullptr, dl, dl + d.e_q, dl + ld, nullptr, grid, s);

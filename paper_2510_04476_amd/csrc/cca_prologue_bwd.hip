@@ -1,5 +1,5 @@
 // Backward of the fused latent-space prologue for gfx950, bf16 storage,
-// d_h = 128 or 64 (adjoint of the convolution, qk-mean and value-shift equations
+// d_h = 256, 128 or 64 (adjoint of the convolution, qk-mean and value-shift equations
 // and of the first two lines of the final equation block of Sec. 2.2; the
 // paper states these steps forward only).
 //
@@ -157,8 +157,9 @@ __global__ __launch_bounds__(256) void column_sum_f32_kernel(const float *__rest
 
 // ---------------------------------------------------------------------------
 // 3. folded-filter gradient, partial sums per chunk of tokens.
-//    Workgroup = (head, chunk of `chunk` tokens of one sequence), d_h / 16 wavefronts; wavefront w owns OX = d_h / 64
-//    output-channel tiles starting at OX*(w&1) and input-channel tile w>>1, for all D taps.
+//    Workgroup = (head, chunk of `chunk` tokens of one sequence[, slice of the output channels at d_h = 256]);
+//    wavefront w owns OX output-channel tiles starting at OX*(w&1) and IX input-channel tiles starting at
+//    IX*(w>>1), for all D taps (OX = d_h / 64 and IX = 1 up to d_h = 128).
 // ---------------------------------------------------------------------------
 // MFMA operand fragment of the TRANSPOSE of a row-major LDS tile: lane (c = lane & 31, half) receives
 // tile[r0 + 4*half + {0..3}][c0 + c] and tile[r0 + 8 + 4*half + {0..3}][c0 + c].  `base` already holds the
@@ -173,14 +174,26 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *base, int r0, int
 
 constexpr int DW_BT = 64;  // tokens per LDS tile
 
+// Output slices per head and threads per workgroup: at d_h <= 128 one workgroup of d_h * 4 threads owns all of a head's
+// d_h x D x d_h sums; at d_h = 256 they would not fit its registers, so 512 threads own a slice of 128 (D <= 2) or 64
+// (D = 3) output channels (blockIdx.y) and each such workgroup re-reads the token rows of all 256 input channels.
+constexpr int dwc_slices(int DH, int D) { return DH <= 128 ? 1 : (D <= 2 ? 2 : 4); }
+constexpr int dwc_threads(int DH) { return DH <= 128 ? DH * 4 : 512; }
+
 template <int DH, int D>
-__global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__restrict__ d3, const bf16_t *__restrict__ lat,
-                                                           float *__restrict__ part, int T, int Hq, int Hk, int e_q,
-                                                           int e_kv, int n_lat, int chunk, int chunks_per_seq) {
-  constexpr int DW_NT = DH * 4, ROW = DH * 2 + 64, CPW = DH / 8, OX = DH / 64;  // threads, LDS row (the 64-byte pad keeps
-                                                                               // the transposing reads conflict-free), chunks per row
+__global__ __launch_bounds__(dwc_threads(DH)) void pro_bwd_dwc_kernel(const bf16_t *__restrict__ d3,
+                                                                      const bf16_t *__restrict__ lat,
+                                                                      float *__restrict__ part, int T, int Hq, int Hk,
+                                                                      int e_q, int e_kv, int n_lat, int chunk,
+                                                                      int chunks_per_seq) {
+  constexpr int OS = dwc_slices(DH, D), DHO = DH / OS, DW_NT = dwc_threads(DH), NW = DW_NT / 64;
+  // LDS rows of the gradient tile (this slice's output channels) and of the token tile (all input channels); the
+  // 64-byte pad keeps the transposing reads conflict-free
+  constexpr int ROWY = DHO * 2 + 64, ROWU = DH * 2 + 64, CPWY = DHO / 8, CPWU = DH / 8;
+  constexpr int OX = DHO / 64, IX = (DH / 32) / (NW / 2);  // output / input channel tiles per wavefront
+  static_assert(OX >= 1 && IX >= 1 && OX * 2 * 32 == DHO && IX * (NW / 2) * 32 == DH, "wavefront tiling");
   constexpr int UROWS = DW_BT + D - 1;
-  constexpr int DY_TILE = DW_BT * ROW, U_TILE = UROWS * ROW;
+  constexpr int DY_TILE = DW_BT * ROWY, U_TILE = UROWS * ROWU;
   __shared__ __attribute__((aligned(16))) unsigned char smem[2 * (DY_TILE + U_TILE)];
   unsigned char *const sDy = smem, *const sU = smem + 2 * DY_TILE;
 
@@ -188,20 +201,22 @@ __global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__res
   const int l32 = lane & 31, half = lane >> 5;
   const int NH = Hq + Hk;
   const int head = blockIdx.x % NH, cid = blockIdx.x / NH;  // cid = b * chunks_per_seq + chunk index
+  const int o_base = (int)blockIdx.y * DHO;                 // first output channel of this slice
   const int b = cid / chunks_per_seq, t_begin = (cid % chunks_per_seq) * chunk;
   const int t_end = min(T, t_begin + chunk);
   const int ch0 = head < Hq ? head * DH : e_q + (head - Hq) * DH;
   const int ld3 = e_q + e_kv;
-  const bf16_t *const d3b = d3 + (long long)b * T * ld3 + ch0;
+  const bf16_t *const d3b = d3 + (long long)b * T * ld3 + ch0 + o_base;
   const bf16_t *const ub = lat + (long long)b * T * n_lat + ch0;
 
-  constexpr int DY_CHUNKS = DW_BT * CPW, U_CHUNKS = UROWS * CPW;  // 16-byte chunks per tile
+  constexpr int DY_CHUNKS = DW_BT * CPWY, U_CHUNKS = UROWS * CPWU;  // 16-byte chunks per tile
   constexpr int DY_PER = DY_CHUNKS / DW_NT, U_PER = (U_CHUNKS + DW_NT - 1) / DW_NT;
+  static_assert(DY_CHUNKS % DW_NT == 0, "gradient tile must divide over the threads");
   u32x4 rdy[DY_PER], ru[U_PER];
   auto load_tile = [&](int t0) {
 #pragma unroll
     for (int i = 0; i < DY_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
+      const int id = tid + i * DW_NT, r = id / CPWY, c = id % CPWY;
       const int t = t0 + r;
       u32x4 val = {0, 0, 0, 0};
       if (t < t_end) val = *reinterpret_cast<const u32x4 *>(d3b + (long long)t * ld3 + c * 8);
@@ -209,7 +224,7 @@ __global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__res
     }
 #pragma unroll
     for (int i = 0; i < U_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
+      const int id = tid + i * DW_NT, r = id / CPWU, c = id % CPWU;
       const int t = t0 - (D - 1) + r;  // row r of the tile holds token t0 - (D-1) + r
       u32x4 val = {0, 0, 0, 0};
       if (id < U_CHUNKS && t >= 0 && t < t_end) val = *reinterpret_cast<const u32x4 *>(ub + (long long)t * n_lat + c * 8);
@@ -219,26 +234,29 @@ __global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__res
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < DY_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
-      *reinterpret_cast<u32x4 *>(sDy + buf * DY_TILE + r * ROW + c * 16) = rdy[i];
+      const int id = tid + i * DW_NT, r = id / CPWY, c = id % CPWY;
+      *reinterpret_cast<u32x4 *>(sDy + buf * DY_TILE + r * ROWY + c * 16) = rdy[i];
     }
 #pragma unroll
     for (int i = 0; i < U_PER; ++i) {
-      const int id = tid + i * DW_NT, r = id / CPW, c = id % CPW;
-      if (id < U_CHUNKS) *reinterpret_cast<u32x4 *>(sU + buf * U_TILE + r * ROW + c * 16) = ru[i];
+      const int id = tid + i * DW_NT, r = id / CPWU, c = id % CPWU;
+      if (id < U_CHUNKS) *reinterpret_cast<u32x4 *>(sU + buf * U_TILE + r * ROWU + c * 16) = ru[i];
     }
   };
 
-  const uint32_t tr_off = (uint32_t)(4 * half + ((lane & 15) >> 2)) * ROW + (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
-  const int o_tile0 = OX * (wave & 1), i_tile = wave >> 1;
+  const uint32_t tr_row = (uint32_t)(4 * half + ((lane & 15) >> 2)), tr_col = (((lane >> 4) & 1) * 16 + 4 * (lane & 3)) * 2;
+  const uint32_t tr_off_y = tr_row * ROWY + tr_col, tr_off_u = tr_row * ROWU + tr_col;
+  const int o_tile0 = OX * (wave & 1), i_tile0 = IX * (wave >> 1);
 
-  f32x16 acc[OX][D];
+  f32x16 acc[OX][IX][D];
 #pragma unroll
   for (int x = 0; x < OX; ++x)
 #pragma unroll
-    for (int d = 0; d < D; ++d)
+    for (int y = 0; y < IX; ++y)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[x][d][r] = 0.f;
+      for (int d = 0; d < D; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[x][y][d][r] = 0.f;
 
   const int ntiles = (t_end - t_begin + DW_BT - 1) / DW_BT;
   load_tile(t_begin);
@@ -249,32 +267,39 @@ __global__ __launch_bounds__(DH * 4) void pro_bwd_dwc_kernel(const bf16_t *__res
     const int buf = it & 1;
     if (it + 1 < ntiles) store_tile(buf ^ 1);
     if (it + 2 < ntiles) load_tile(t_begin + (it + 2) * DW_BT);
-    const unsigned char *dyp = sDy + buf * DY_TILE + tr_off, *up = sU + buf * U_TILE + tr_off;
+    const unsigned char *dyp = sDy + buf * DY_TILE + tr_off_y, *up = sU + buf * U_TILE + tr_off_u;
 #pragma unroll
     for (int kk = 0; kk < DW_BT / 16; ++kk) {
-      bf16x8 fo[OX], fu[D];
+      bf16x8 fo[OX], fu[IX][D];
 #pragma unroll
-      for (int x = 0; x < OX; ++x) fo[x] = tr_frag<ROW>(dyp, kk * 16, (o_tile0 + x) * 32);
+      for (int x = 0; x < OX; ++x) fo[x] = tr_frag<ROWY>(dyp, kk * 16, (o_tile0 + x) * 32);
 #pragma unroll
-      for (int d = 0; d < D; ++d) fu[d] = tr_frag<ROW>(up, kk * 16 + d, i_tile * 32);  // token t - (D-1-d)
+      for (int y = 0; y < IX; ++y)
+#pragma unroll
+        for (int d = 0; d < D; ++d) fu[y][d] = tr_frag<ROWU>(up, kk * 16 + d, (i_tile0 + y) * 32);  // token t - (D-1-d)
 #pragma unroll
       for (int x = 0; x < OX; ++x)
 #pragma unroll
-        for (int d = 0; d < D; ++d) acc[x][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[x], fu[d], acc[x][d], 0, 0, 0);
+        for (int y = 0; y < IX; ++y)
+#pragma unroll
+          for (int d = 0; d < D; ++d)
+            acc[x][y][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fo[x], fu[y][d], acc[x][y][d], 0, 0, 0);
     }
     __syncthreads();
   }
-  // acc[x][d][r]: o = (o_tile0 + x)*32 + 8*(r/4) + 4*half + r%4,  i = i_tile*32 + l32
+  // acc[x][y][d][r]: o = o_base + (o_tile0 + x)*32 + 8*(r/4) + 4*half + r%4,  i = (i_tile0 + y)*32 + l32
   float *out = part + (long long)blockIdx.x * DH * D * DH;  // [o][d][i] of (cid, head); blockIdx.x = cid*NH + head
 #pragma unroll
   for (int x = 0; x < OX; ++x)
 #pragma unroll
-    for (int d = 0; d < D; ++d)
+    for (int y = 0; y < IX; ++y)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int o = (o_tile0 + x) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-        out[(o * D + d) * DH + i_tile * 32 + l32] = acc[x][d][r];
-      }
+      for (int d = 0; d < D; ++d)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int o = o_base + (o_tile0 + x) * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+          out[(o * D + d) * DH + (i_tile0 + y) * 32 + l32] = acc[x][y][d][r];
+        }
 }
 
 // dwc[h][o][d][i] = sum over chunks (fixed order); then d w1[h,o,i,j] = sum_jj dwc[h,o,j+jj,i] * w0[c(h,i),jj]
@@ -358,9 +383,9 @@ int taps(const Dims &d) { return ((d.flags & CCA_CONV_SEQ) ? d.k_seq : 1) + d.k_
 
 // tokens per chunk of the filter-gradient kernel: the largest of 512..64 that still gives >= 256 workgroups
 int dwc_chunk(const Dims &d) {
-  const int NH = d.Hq + d.Hk;
+  const int NH = d.Hq + d.Hk, os = dwc_slices(d.dh, taps(d));
   for (int c = 512; c > 64; c >>= 1)
-    if ((long long)d.B * ((d.T + c - 1) / c) * NH >= 256) return c;
+    if ((long long)d.B * ((d.T + c - 1) / c) * NH * os >= 256) return c;
   return 64;
 }
 
@@ -384,7 +409,7 @@ BwdScratch bwd_layout(const Dims &d) {
 
 }  // namespace
 
-bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d) && d.dh <= 128; }  // the adjoint kernels keep a head's filter in LDS
+bool prologue_bwd_fused_supported(const Dims &d) { return prologue_fused_supported(d); }
 
 size_t prologue_bwd_fused_scratch_bytes(const Dims &d) {
   return prologue_bwd_fused_supported(d) ? bwd_layout(d).total : 0;
@@ -425,8 +450,8 @@ static hipError_t prologue_bwd_run(const Dims &d, const cca_weights &w, const vo
   if (!want_w1 && !want_w0) return hipSuccess;
   const int chunk = dwc_chunk(d), cps = (d.T + chunk - 1) / chunk, n_chunks = d.B * cps;
 #define DWC(DD)                                                                                                     \
-  pro_bwd_dwc_kernel<DH, DD><<<n_chunks * NH, DH * 4, 0, s>>>(d3, (const bf16_t *)lat, part, d.T, d.Hq, d.Hk, d.e_q, d.e_kv, \
-                                                         d.n_lat, chunk, cps)
+  pro_bwd_dwc_kernel<DH, DD><<<dim3(n_chunks * NH, dwc_slices(DH, DD)), dwc_threads(DH), 0, s>>>(                    \
+      d3, (const bf16_t *)lat, part, d.T, d.Hq, d.Hk, d.e_q, d.e_kv, d.n_lat, chunk, cps)
   switch (D) {
     case 1: DWC(1); break;
     case 2: DWC(2); break;
@@ -447,8 +472,9 @@ static hipError_t prologue_bwd_run(const Dims &d, const cca_weights &w, const vo
 hipError_t prologue_bwd_fused_bf16(const Dims &d, const cca_weights &w, const void *lat, const void *q, const void *k,
                                    const float *rnorm, const void *d_q, const void *d_k, const void *d_v, void *d_lat,
                                    const cca_grads *gr, void *scratch, hipStream_t s) {
-  return d.dh == 64 ? prologue_bwd_run<64>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s)
-                    : prologue_bwd_run<128>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s);
+  return d.dh == 64    ? prologue_bwd_run<64>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s)
+         : d.dh == 128 ? prologue_bwd_run<128>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s)
+                       : prologue_bwd_run<256>(d, w, lat, q, k, rnorm, d_q, d_k, d_v, d_lat, gr, scratch, s);
 }
 
 }  // namespace cca

@@ -107,6 +107,11 @@ SMALL = [
     dict(B=1, T=520, E=768, Hq=6, Hk=1, dh=64, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
     dict(B=2, T=270, E=768, Hq=6, Hk=2, dh=64, k_seq=2, k_ch=1, dtype="bf16", paper_flags=True),
     dict(B=1, T=300, E=768, Hq=6, Hk=1, dh=128, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
+    # d_h = 256 (one-wavefront attention backward, streamed prologue adjoint, sliced filter gradient): three taps with
+    # R = 2 over several blocks and a ragged tail; two taps with R = 3; no channel taps beyond the first with R = 1
+    dict(B=2, T=700, E=2048, Hq=4, Hk=2, dh=256, k_seq=2, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=530, E=1536, Hq=3, Hk=1, dh=256, k_seq=1, k_ch=2, dtype="bf16", paper_flags=True),
+    dict(B=1, T=300, E=512, Hq=2, Hk=2, dh=256, k_seq=2, k_ch=1, dtype="bf16", paper_flags=True),
 ]
 
 
@@ -121,7 +126,7 @@ def test_backward_small_shapes(i):
     say(compare(got, ref, w["dtype"]))
 
 
-@pytest.mark.parametrize("i", [3, 4, 7, 9, 11, 12])
+@pytest.mark.parametrize("i", [3, 4, 7, 9, 11, 12, 15, 16])
 def test_backward_small_shapes_literal_weights(i):
     """0.02-scaled weights: the softmax is nearly flat, the regime in which <d_o, o> taken from the bf16-rounded o
     alone would put a 2 % error on d_q / d_k and, through them, on the convolution filter gradients."""
@@ -207,7 +212,7 @@ FLAG_CASES = {
 
 
 @pytest.mark.parametrize("name", sorted(FLAG_CASES))
-@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128), ("bf16", 64)])
+@pytest.mark.parametrize("dtype,dh", [("f32", 32), ("bf16", 128), ("bf16", 64), ("bf16", 256)])
 def test_backward_each_flag(name, dtype, dh):
     flags, okw, skip = FLAG_CASES[name]
     w = dict(B=2, T=200, E=4 * dh * 2, Hq=4, Hk=2, dh=dh, k_seq=2, k_ch=2, dtype=dtype, paper_flags=True)
