@@ -47,9 +47,7 @@ def run_grid(P, torch, dh=128) -> int:
     from paper_2510_04476_amd import binding as b
     dev = "cuda"
     rows = []
-    # d_h = 256 has matrix-core kernels for the forward pass only (its backward runs on the shape-generic kernels,
-    # seconds at S = 16384): that grid is forward-only
-    with_bwd = dh <= 128
+    with_bwd = True
     for causal in (True, False):
         for S in (512, 1024, 2048, 4096, 8192, 16384):
             base = {}
@@ -125,7 +123,7 @@ def main() -> int:
                                        "attention_backward", "prologue_backward", "decode"],
                     help="profiling aid: launch just this stage --steps times (after one full forward) and exit")
     ap.add_argument("--grid-dh", type=int, default=128, choices=[64, 128, 256],
-                    help="head width of the --grid run (256: forward only)")
+                    help="head width of the --grid run")
     ap.add_argument("--grid", action="store_true",
                     help="latency grid on the axes of the paper's kernel figures (App. D.1: E = 2048, bf16, S = 512..16384, "
                          "causal and non-causal, forward and forward+backward) for four layouts at d_h = --grid-dh, instead "

@@ -104,6 +104,50 @@ __device__ __forceinline__ bf16x8 tr_frag(const unsigned char *tile, const LaneS
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
+// S and dP chains of the one-wavefront dK / dV kernel, as inline assembly so that their accumulators live in ordinary
+// vector registers: in a kernel that may use more than 256 registers the compiler keeps every MFMA accumulator it
+// selects itself in the accumulation registers, and the two 32 x 256 accumulators of that kernel already fill those.
+// The compiler does not track matrix-core hazards through inline assembly: the result of a chain must not be touched
+// by another instruction until 11 issue slots after its last MFMA.  chain_fence() orders the readers of a chain
+// behind whatever was issued before it (the other chain; the arithmetic on the other chain's result).
+__device__ __forceinline__ f32x16 chain_mfma0(bf16x8 a, bf16x8 b) {
+  f32x16 d;
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "v"(b));
+  return d;
+}
+__device__ __forceinline__ f32x16 chain_mfma(bf16x8 a, bf16x8 b, f32x16 acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+  return acc;
+}
+// The same for the products that accumulate dK and dV, with the accumulator pinned to the accumulation registers
+// (left to the compiler, part of the 256 accumulator registers ends up in ordinary registers and the K fragments in
+// scratch memory).  Successive MFMAs on one accumulator are interlocked by the hardware; acc_settle() pads the one
+// place where other instructions read them: after the loop.
+__device__ __forceinline__ void acc_mfma(bf16x8 a, bf16x8 b, f32x16 &acc) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// 0 * 0 + 0: the accumulator is born in an accumulation register.  The compiler materialises the zero operand with
+// vector-ALU moves right in front of the statement; the idle slots keep the MFMA from reading it before it is
+// written (seen on the GPU: without them the first accumulator zeroed this way came out non-finite now and then).
+__device__ __forceinline__ f32x16 acc_zero() {
+  f32x16 d;
+  const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+  asm volatile("s_nop 7\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(d) : "v"(z));
+  return d;
+}
+__device__ __forceinline__ void acc_settle(f32x16 *x, f32x16 *y) {  // 8 + 8 accumulators
+  asm volatile("s_nop 15\n\ts_nop 1"
+               : "+a"(x[0]), "+a"(x[1]), "+a"(x[2]), "+a"(x[3]), "+a"(x[4]), "+a"(x[5]), "+a"(x[6]), "+a"(x[7]));
+  asm volatile("" : "+a"(y[0]), "+a"(y[1]), "+a"(y[2]), "+a"(y[3]), "+a"(y[4]), "+a"(y[5]), "+a"(y[6]), "+a"(y[7]));
+}
+__device__ __forceinline__ void acc_settle(f32x16 *x) {  // 8 accumulators
+  asm volatile("s_nop 15\n\ts_nop 1"
+               : "+a"(x[0]), "+a"(x[1]), "+a"(x[2]), "+a"(x[3]), "+a"(x[4]), "+a"(x[5]), "+a"(x[6]), "+a"(x[7]));
+}
+__device__ __forceinline__ void chain_fence(f32x16 &acc) { asm volatile("" : "+v"(acc)); }
+__device__ __forceinline__ void chain_fence(f32x16 &acc, f32x16 &other) { asm volatile("" : "+v"(acc), "+v"(other)); }
+__device__ __forceinline__ void chain_fence(f32x16 &acc, u32x4 &a, u32x4 &b) { asm volatile("" : "+v"(acc), "+v"(a), "+v"(b)); }
+
 // ---------------------------------------------------------------------------
 // Delta[b,h,t] = sum_d dO[b,t,h,d] * O[b,t,h,d]; d_h / 8 lanes x 16 bytes per (t,h) row
 // ---------------------------------------------------------------------------
@@ -153,6 +197,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(
     bf16_t *__restrict__ dQ, int T, int Hq, int Hk, int BH, int nqb, int paired, float scale, unsigned char *smem) {
   CCA_BWD_GEOMETRY(DH);
   constexpr int DQ_BQ = DQ_NT_ / 2;
+  constexpr bool WIDE = DQ_NT_ == 256;
   constexpr int TILE = BKV * ROW;
   constexpr int PER_THREAD = BKV * KCH / DQ_NT_;  // 16-byte chunks of K (and of V) per thread per tile
   constexpr int ROWS_PER_PASS = DQ_NT_ / KCH;
@@ -176,22 +221,31 @@ __device__ __forceinline__ void attn_bwd_dq_body(
   const uint32_t s_off_odd = ROWS_PER_PASS % 16 == 0 ? s_off : (s_off ^ 32u);
   const LaneSwz LS = lane_swz<DH>(lane);
 
-  u32x4 rk[PER_THREAD], rv[PER_THREAD];
-  auto load_tile = [&](int kv0) {
+  // Staging registers of the next tile.  One wavefront per SIMD: a single set carries K and V in turn (K of tile
+  // j+1 is put into LDS and V of tile j+1 requested before tile j is multiplied, V put down and K of tile j+2
+  // requested after), because the query and dO fragments alone take half of the ordinary registers.
+  u32x4 rk[PER_THREAD], rv[WIDE ? 1 : PER_THREAD];
+  auto load_half = [&](const unsigned char *src, u32x4 *r, int kv0) {
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
       const int s = min(kv0 + s_r0 + i * ROWS_PER_PASS, T - 1);  // clamped keys are masked below
-      rk[i] = *reinterpret_cast<const u32x4 *>(Kg + (long long)s * row_bytes + s_ch * 16);
-      rv[i] = *reinterpret_cast<const u32x4 *>(Vg + (long long)s * row_bytes + s_ch * 16);
+      r[i] = *reinterpret_cast<const u32x4 *>(src + (long long)s * row_bytes + s_ch * 16);
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_half = [&](unsigned char *dst, const u32x4 *r, int buf) {
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i) {
       const uint32_t o = ((i & 1) ? s_off_odd : s_off) + i * ROWS_PER_PASS * ROW;
-      *reinterpret_cast<u32x4 *>(sK + buf * TILE + o) = rk[i];
-      *reinterpret_cast<u32x4 *>(sV + buf * TILE + o) = rv[i];
+      *reinterpret_cast<u32x4 *>(dst + buf * TILE + o) = r[i];
     }
+  };
+  auto load_tile = [&](int kv0) {
+    load_half(Kg, rk, kv0);
+    load_half(Vg, rv, kv0);
+  };
+  auto store_tile = [&](int buf) {
+    store_half(sK, rk, buf);
+    store_half(sV, rv, buf);
   };
 
   // Causal work per query block grows with its index: heavy blocks are issued first (unpaired), or each
@@ -228,9 +282,15 @@ __device__ __forceinline__ void attn_bwd_dq_body(
 
   f32x16 acc[DT];  // dQ^T: lane = query row, registers = channels
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int dt = 0; dt < DT; ++dt) {
+    if constexpr (WIDE) {
+      acc[dt] = acc_zero();
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+      for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+    }
+  }
+  if constexpr (WIDE) acc_settle(acc);  // the compiler may move the fresh accumulators around
 
   // One block of 32 keys of the tile at kp / vp against this wavefront's 32 query rows.  LDS fragments are requested
   // PF products ahead of their use, the first transposed ones before the arithmetic that precedes their chain (left
@@ -246,30 +306,65 @@ __device__ __forceinline__ void attn_bwd_dq_body(
     static_assert(PT <= NP && PF <= KK, "prefetch depth");
     u32x4 fk[PF], fv[PF];
     bf16x8 tk[PT];
-#pragma unroll
-    for (int i = 0; i < PF; ++i) fk[i] = col(kp, i), fv[i] = col(vp, i);
     f32x16 s, dp;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, fk[kk % PF]), vf = __builtin_bit_cast(bf16x8, fv[kk % PF]);
-      if (kk + PF < KK) fk[kk % PF] = col(kp, kk + PF), fv[kk % PF] = col(vp, kk + PF);
-      else if (kk + PF - KK < PT) tk[kk + PF - KK] = frag_of(kk + PF - KK);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int i = PF; i < PT; ++i) tk[i] = frag_of(i);
     // lane (l32, half) holds keys kv0 + ks*32 + 8*(r/4) + 4*half + r%4 of query row qw0 + l32
     float ds[16];
     const int lim = (CAUSAL ? min(qw0 + l32, T - 1) : T - 1) - kv0 - ks * 32 - 4 * half;
+    if constexpr (WIDE) {
+      // the S chain, then the dP chain, as inline assembly on ordinary registers; S is first read after the whole dP
+      // chain was issued, dP after the probabilities were formed (chain_fence)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      float p = __builtin_amdgcn_exp2f(s[r] - lse2);
-      if (MASKED) p = (8 * (r >> 2) + (r & 3) <= lim) ? p : 0.f;
-      ds[r] = p * (dp[r] - delta);
+      for (int i = 0; i < PF; ++i) fk[i] = col(kp, i);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, fk[kk % PF]);
+        if (kk + PF < KK) fk[kk % PF] = col(kp, kk + PF);
+        else fv[kk + PF - KK] = col(vp, kk + PF - KK);
+        s = kk == 0 ? chain_mfma0(kf, qf[0]) : chain_mfma(kf, qf[kk], s);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, fv[kk % PF]);
+        if (kk + PF < KK) fv[kk % PF] = col(vp, kk + PF);
+        else if (kk + PF - KK < PT) tk[kk + PF - KK] = frag_of(kk + PF - KK);
+        dp = kk == 0 ? chain_mfma0(vf, dof[0]) : chain_mfma(vf, dof[kk], dp);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = PF; i < PT; ++i) tk[i] = frag_of(i);
+      chain_fence(s);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(s[r] - lse2);
+        if (MASKED) p = (8 * (r >> 2) + (r & 3) <= lim) ? p : 0.f;
+        s[r] = p;
+      }
+      chain_fence(dp, s);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) ds[r] = s[r] * (dp[r] - delta);
+    } else {
+#pragma unroll
+      for (int i = 0; i < PF; ++i) fk[i] = col(kp, i), fv[i] = col(vp, i);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f, dp[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 kf = __builtin_bit_cast(bf16x8, fk[kk % PF]), vf = __builtin_bit_cast(bf16x8, fv[kk % PF]);
+        if (kk + PF < KK) fk[kk % PF] = col(kp, kk + PF), fv[kk % PF] = col(vp, kk + PF);
+        else if (kk + PF - KK < PT) tk[kk + PF - KK] = frag_of(kk + PF - KK);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, dof[kk], dp, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = PF; i < PT; ++i) tk[i] = frag_of(i);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float p = __builtin_amdgcn_exp2f(s[r] - lse2);
+        if (MASKED) p = (8 * (r >> 2) + (r & 3) <= lim) ? p : 0.f;
+        ds[r] = p * (dp[r] - delta);
+      }
     }
     bf16x8 dsf[2];
 #pragma unroll
@@ -285,26 +380,42 @@ __device__ __forceinline__ void attn_bwd_dq_body(
     for (int i = 0; i < NP; ++i) {
       const bf16x8 f = tk[i % PT];
       if (i + PT < NP) tk[i % PT] = frag_of(i + PT);
-      acc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[i / DT], acc[i % DT], 0, 0, 0);
+      if constexpr (WIDE) acc_mfma(f, dsf[i / DT], acc[i % DT]);
+      else acc[i % DT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[i / DT], acc[i % DT], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
   const int kv_end = CAUSAL ? min(q0 + DQ_BQ, T) : T;
   const int ntiles = (kv_end + BKV - 1) / BKV;
-  load_tile(0);
-  store_tile(0);
-  if (ntiles > 1) load_tile(BKV);
+  if constexpr (WIDE) {
+    load_half(Kg, rk, 0);
+    store_half(sK, rk, 0);
+    load_half(Vg, rk, 0);
+    store_half(sV, rk, 0);
+    if (ntiles > 1) load_half(Kg, rk, BKV);
+  } else {
+    load_tile(0);
+    store_tile(0);
+    if (ntiles > 1) load_tile(BKV);
+  }
   __syncthreads();
   for (int j = 0; j < ntiles; ++j) {
     const int kv0 = j * BKV, buf = j & 1;
-    if (j + 1 < ntiles) store_tile(buf ^ 1);
-    if (j + 2 < ntiles) load_tile(kv0 + 2 * BKV);
+    if constexpr (WIDE) {
+      if (j + 1 < ntiles) {
+        store_half(sK, rk, buf ^ 1);
+        load_half(Vg, rk, kv0 + BKV);
+      }
+    } else {
+      if (j + 1 < ntiles) store_tile(buf ^ 1);
+      if (j + 2 < ntiles) load_tile(kv0 + 2 * BKV);
+    }
     if (wave_live && !(CAUSAL && kv0 > wave_last)) {
       const unsigned char *kp = sK + buf * TILE, *vp = sV + buf * TILE;
       // wave-uniform: tiles below the diagonal and inside the sequence need no mask
       const bool need_mask = (CAUSAL && kv0 + BKV - 1 > qw0) || (kv0 + BKV > T);
-      if (need_mask) {
+      if (WIDE || need_mask) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) block(kp, vp, kv0, ks, std::true_type{});
       } else {
@@ -312,7 +423,17 @@ __device__ __forceinline__ void attn_bwd_dq_body(
         for (int ks = 0; ks < 2; ++ks) block(kp, vp, kv0, ks, std::false_type{});
       }
     }
+    if constexpr (WIDE) {
+      if (j + 1 < ntiles) {
+        store_half(sV, rk, buf ^ 1);
+        if (j + 2 < ntiles) load_half(Kg, rk, kv0 + 2 * BKV);
+      }
+    }
     __syncthreads();
+  }
+  if constexpr (WIDE) {
+    static_assert(!WIDE || DT == 8, "acc_settle takes 8 accumulators");
+    acc_settle(acc);
   }
   if (wave_live && qw0 + l32 < T) {
     bf16_t *row = dQ + (((long long)b * T + qw0 + l32) * Hq + h) * DH;
@@ -364,7 +485,7 @@ __global__ __launch_bounds__(256) void scale_q_kernel(const bf16_t *__restrict__
 // ---------------------------------------------------------------------------
 // dK, dV
 // ---------------------------------------------------------------------------
-constexpr int KV_NT = 512, BQT = 64;  // threads, query rows per LDS tile; a workgroup owns KV_NT / 2 keys
+constexpr int KV_NT = 512;  // threads; a workgroup owns KV_NT / 2 keys
 
 // PARTIAL = false (one query head per KV head): dK, dV written as bf16 (B,T,H_k,d_h).
 // PARTIAL = true: this head's contribution written as fp32 to dKp, dVp (B,T,H_q,d_h).
@@ -373,31 +494,30 @@ constexpr int KV_NT = 512, BQT = 64;  // threads, query rows per LDS tile; a wor
 // staging registers; q arrives pre-scaled from scale_q_kernel), S is turned into bf16 P before dP is formed, and
 // dS is computed from that bf16 P.  (With register staging and fp32 P the pass spilled 98 registers; split into a
 // dV pass and a dK pass it cost a fifth contraction.)
-// KV_NT_ threads = KV_NT_ / 64 wavefronts x 32 keys per workgroup: 512 (two wavefronts per SIMD) for d_h <= 128; 256
-// (one wavefront per SIMD: dK and dV, 128 registers each, fill the accumulation registers, and the V fragments stay
-// in ordinary registers because the Q / dO tiles leave no LDS for them) for d_h = 256.
-// PARTS: 3 = dK and dV in one pass; 1 = dV only (S, P, dV); 2 = dK only (S, P, dP, dS, dK).  The one-wavefront form
-// runs the two halves as two launches: both 32 x 256 accumulators together fill every accumulation register, and
-// the compiler then has nowhere to put the S and dP chains (measured: 178 scratch accesses per loop iteration).
-template <int DH, bool CAUSAL, bool PARTIAL, int KV_NT_, int PARTS>
+// KV_NT_ threads = KV_NT_ / 64 wavefronts x 32 keys per workgroup: 512 (two wavefronts per SIMD, 64-row Q / dO tiles)
+// for d_h <= 128; 256 (one wavefront per SIMD, 32-row tiles so that tiles and V fragments fit the LDS) for d_h = 256,
+// where dK and dV, 128 registers each, fill the accumulation registers and the S and dP chains run as inline assembly
+// on ordinary registers (chain_mfma above).
+constexpr int kv_tile_rows(int threads) { return threads == 256 ? 32 : 64; }
+
+template <int DH, bool CAUSAL, bool PARTIAL, int KV_NT_>
 __device__ __forceinline__ void attn_bwd_dkdv_body(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
     bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
     int Hk, int BH, int nkb, float scale, unsigned char *smem) {
   CCA_BWD_GEOMETRY(DH);
-  constexpr int KV_NT = KV_NT_, KV_BK = KV_NT_ / 2;
-  constexpr bool V_IN_REGS = KV_NT_ == 256;
-  constexpr bool DO_V = (PARTS & 1) != 0, DO_K = (PARTS & 2) != 0;
+  constexpr int KV_NT = KV_NT_, KV_BK = KV_NT_ / 2, BQT = kv_tile_rows(KV_NT_);
+  constexpr bool WIDE = KV_NT_ == 256;
   constexpr int TILE = BQT * ROW;
   // smem: Q0 Q1 dO0 dO1, 4 * TILE bytes of dynamic LDS (with a static array the compiler makes every LDS read wait
   // for the tile loads in flight (vmcnt(0): a load into LDS might alias what is read), which puts the latency of the
   // next tile's loads in front of each step)
   __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];                                      // [buf][lse2 | delta][row]
   // this workgroup's V rows as MFMA operand fragments, [wavefront][kk][lane] x 16 bytes: each wavefront keeps its own
-  // (read back one fragment per dP product; at two wavefronts per SIMD, holding them in registers next to the K
-  // fragments and the two accumulators leaves no room for fragments requested ahead of their use)
-  __shared__ __attribute__((aligned(16))) u32x4 sVf[V_IN_REGS ? 1 : KV_NT / 64][V_IN_REGS ? 1 : KK][64];
+  // (read back one fragment per dP product; holding them in registers next to the K fragments and the two
+  // accumulators leaves no room for fragments requested ahead of their use)
+  __shared__ __attribute__((aligned(16))) u32x4 sVf[KV_NT / 64][KK][64];
   unsigned char *const sQ = smem, *const sD = smem + 2 * TILE;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -413,7 +533,6 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
 
   // this wavefront's 32 keys: K and V rows as second MFMA operands, resident in registers
   bf16x8 kf[KK];
-  u32x4 vreg[V_IN_REGS ? KK : 1];
   {
     const int s = min(kw0 + l32, T - 1);
     const bf16_t *pk = K + (((long long)b * T + s) * Hk + g) * DH + half * 8;
@@ -421,20 +540,20 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       kf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(pk + kk * 16));
-      if constexpr (!DO_K) continue;  // V enters dP only
-      if constexpr (V_IN_REGS) vreg[kk] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
-      else sVf[wave][kk][lane] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
+      sVf[wave][kk][lane] = *reinterpret_cast<const u32x4 *>(pv + kk * 16);
     }
   }
-  auto v_frag = [&](int kk) {
-    if constexpr (V_IN_REGS) return vreg[kk];
-    else return sVf[wave][kk][lane];
-  };
   f32x16 dk[DT], dv[DT];  // dK^T, dV^T: lane = key, registers = channels
 #pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
+  for (int dt = 0; dt < DT; ++dt) {
+    if constexpr (WIDE) {
+      dk[dt] = acc_zero(), dv[dt] = acc_zero();
+    } else {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) dk[dt][r] = 0.f, dv[dt][r] = 0.f;
+      for (int r = 0; r < 16; ++r) dk[dt][r] = 0.f, dv[dt][r] = 0.f;
+    }
+  }
+  if constexpr (WIDE) acc_settle(dk, dv);  // the compiler may move the fresh accumulators around
 
   // query tiles that see keys of this block
   const int qt_first = CAUSAL ? k0 / BQT : 0;
@@ -504,40 +623,40 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
     };
     bf16x8 pf[2], dsf[2];
     u32x4 fr[PF], fd[PF], fv[PF];
-    // products of the last phase: dV (jj, dt), then dK (jj, dt), whichever of them this pass computes
-    constexpr int NP = (DO_V + DO_K) * 2 * DT;
+    constexpr int NP = 4 * DT;  // products of the last phase: dV (jj, dt), then dK (jj, dt)
     auto frag_of = [&](int i) {  // i -> (dO | Q, jj, dt)
-      const int which = (DO_V && DO_K) ? i / (2 * DT) : (DO_K ? 1 : 0), jj = (i / DT) & 1, dt = i % DT;
+      const int which = i / (2 * DT), jj = (i / DT) & 1, dt = i % DT;
       return tr_frag<ROW>(which ? qp : dp_, LS, qs * 32 + jj * 16, dt);
     };
-    bf16x8 tv[PF];  // transposed fragments of the first products of the last phase, requested under the chain before it
+    bf16x8 tv[PF];  // transposed fragments of the first products of the last phase, requested under the dP chain
 #pragma unroll
     for (int i = 0; i < PF; ++i) fr[i] = col(qp, i);
-    {  // S[t, key] -> P, packed to bf16 at once
-      f32x16 s;
+    f32x16 s, dp;  // S[t, key], dP[t, key]
+    if constexpr (!WIDE) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    }
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 qa = __builtin_bit_cast(bf16x8, fr[kk % PF]);
-        if (kk + PF < KK) fr[kk % PF] = col(qp, kk + PF);
-        else if constexpr (DO_K) {  // first fragments of the dP chain
-          fd[kk + PF - KK] = col(dp_, kk + PF - KK);
-          fv[kk + PF - KK] = v_frag(kk + PF - KK);
-        } else {  // no dP chain: first transposed fragments of the last phase
-          tv[kk + PF - KK] = frag_of(kk + PF - KK);
-        }
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 qa = __builtin_bit_cast(bf16x8, fr[kk % PF]);
+      if (kk + PF < KK) fr[kk % PF] = col(qp, kk + PF);
+      else {  // first fragments of the dP chain
+        fd[kk + PF - KK] = col(dp_, kk + PF - KK);
+        fv[kk + PF - KK] = sVf[wave][kk + PF - KK][lane];
       }
-      // lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) + 4*half + r%4.  Masked tiles: the
-      // row index relative to t0 + qs*32 + 4*half must lie in [lo, hi] (lo: causal, hi: end of the sequence; a key
-      // past the end has an empty range).
+      if constexpr (WIDE) s = kk == 0 ? chain_mfma0(qa, kf[0]) : chain_mfma(qa, kf[kk], s);
+      else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // S -> P, packed to bf16 at once.  Lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) +
+    // 4*half + r%4.  Masked tiles: the row index relative to t0 + qs*32 + 4*half must lie in [lo, hi] (lo: causal,
+    // hi: end of the sequence; a key past the end has an empty range).
+    u32x4 w[2];
+    auto probabilities = [&]() __attribute__((always_inline)) {
       const int key = kw0 + l32, tb = t0 + qs * 32 + 4 * half;
       const int lo = CAUSAL ? key - tb : -(1 << 20);
       const unsigned span = key < T ? (unsigned)(T - 1 - tb - lo) : 0u;
       const bool none = MASKED && (key >= T || T - 1 - tb < lo);
-      u32x4 w[2];
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
@@ -550,32 +669,41 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
         w[rg >> 1][(rg & 1) * 2 + 0] = pack2(p[0], p[1]);
         w[rg >> 1][(rg & 1) * 2 + 1] = pack2(p[2], p[3]);
       }
-      pf[0] = __builtin_bit_cast(bf16x8, w[0]);
-      pf[1] = __builtin_bit_cast(bf16x8, w[1]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if constexpr (DO_K) {  // dP[t, key] -> dS = P (dP - Delta), P taken back from its bf16 form
-      f32x16 dp;
+    };
+    // two wavefronts per SIMD: P is formed between the chains (one accumulator live at a time); one wavefront: both
+    // chains first, so that each result rests while the other chain / the arithmetic on the other result issues
+    if constexpr (!WIDE) {
+      probabilities();
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < 16; ++r) dp[r] = 0.f;
+    }
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 da = __builtin_bit_cast(bf16x8, fd[kk % PF]), vb = __builtin_bit_cast(bf16x8, fv[kk % PF]);
-        if (kk + PF < KK) {
-          fd[kk % PF] = col(dp_, kk + PF);
-          fv[kk % PF] = v_frag(kk + PF);
-        } else {
-          tv[kk + PF - KK] = frag_of(kk + PF - KK);
-        }
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, dp, 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+    for (int kk = 0; kk < KK; ++kk) {  // dP[t, key]
+      const bf16x8 da = __builtin_bit_cast(bf16x8, fd[kk % PF]), vb = __builtin_bit_cast(bf16x8, fv[kk % PF]);
+      if (kk + PF < KK) {
+        fd[kk % PF] = col(dp_, kk + PF);
+        fv[kk % PF] = sVf[wave][kk + PF][lane];
+      } else {
+        tv[kk + PF - KK] = frag_of(kk + PF - KK);
       }
+      if constexpr (WIDE) dp = kk == 0 ? chain_mfma0(da, vb) : chain_mfma(da, vb, dp);
+      else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, dp, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if constexpr (WIDE) {
+      chain_fence(s);  // S is read from here on: the whole dP chain was issued since its last MFMA
+      probabilities();
+      chain_fence(dp, w[0], w[1]);  // dP is read from here on: P has been formed since its last MFMA
+    }
+    pf[0] = __builtin_bit_cast(bf16x8, w[0]);
+    pf[1] = __builtin_bit_cast(bf16x8, w[1]);
+    {  // dS = P (dP - Delta), P taken back from its bf16 form
       u32x4 x[2];
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
         const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
-        const u32x4 w = __builtin_bit_cast(u32x4, pf[rg >> 1]);
-        const uint32_t p01 = w[(rg & 1) * 2 + 0], p23 = w[(rg & 1) * 2 + 1];
+        const uint32_t p01 = w[rg >> 1][(rg & 1) * 2 + 0], p23 = w[rg >> 1][(rg & 1) * 2 + 1];
         x[rg >> 1][(rg & 1) * 2 + 0] = pack2(bf_lo(p01) * (dp[rg * 4 + 0] - d4[0]), bf_hi(p01) * (dp[rg * 4 + 1] - d4[1]));
         x[rg >> 1][(rg & 1) * 2 + 1] = pack2(bf_lo(p23) * (dp[rg * 4 + 2] - d4[2]), bf_hi(p23) * (dp[rg * 4 + 3] - d4[3]));
       }
@@ -589,9 +717,14 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
     for (int i = 0; i < NP; ++i) {
       const bf16x8 f = tv[i % PF];
       if (i + PF < NP) tv[i % PF] = frag_of(i + PF);
-      const int which = (DO_V && DO_K) ? i / (2 * DT) : (DO_K ? 1 : 0), jj = (i / DT) & 1, dt = i % DT;
-      if (which == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[jj], dv[dt], 0, 0, 0);
-      else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[jj], dk[dt], 0, 0, 0);
+      const int which = i / (2 * DT), jj = (i / DT) & 1, dt = i % DT;
+      if constexpr (WIDE) {
+        if (which == 0) acc_mfma(f, pf[jj], dv[dt]);
+        else acc_mfma(f, dsf[jj], dk[dt]);
+      } else {
+        if (which == 0) dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, pf[jj], dv[dt], 0, 0, 0);
+        else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[jj], dk[dt], 0, 0, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -612,14 +745,18 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
       const bool need_mask = (CAUSAL && t0 < kw0 + 31) || (t0 + BQT > T) || (kw0 + 32 > T);
       if (need_mask) {
 #pragma unroll
-        for (int qs = 0; qs < 2; ++qs) block(qp, dp_, buf, t0, qs, std::true_type{});
+        for (int qs = 0; qs < BQT / 32; ++qs) block(qp, dp_, buf, t0, qs, std::true_type{});
       } else {
 #pragma unroll
-        for (int qs = 0; qs < 2; ++qs) block(qp, dp_, buf, t0, qs, std::false_type{});
+        for (int qs = 0; qs < BQT / 32; ++qs) block(qp, dp_, buf, t0, qs, std::false_type{});
       }
     }
     if (step + 1 < steps) land_tile(buf ^ 1);
     __syncthreads();
+  }
+  if constexpr (WIDE) {
+    static_assert(!WIDE || DT == 8, "acc_settle takes 8 + 8 accumulators");
+    acc_settle(dk, dv);
   }
   if (PARTIAL) {
     if (wave_live && kw0 + l32 < T) {
@@ -632,8 +769,8 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
           const f32x4 w = {dk[dt][rg * 4 + 0] * LN2, dk[dt][rg * 4 + 1] * LN2, dk[dt][rg * 4 + 2] * LN2,
                            dk[dt][rg * 4 + 3] * LN2};
           const f32x4 x = {dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1], dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]};
-          if constexpr (DO_K) *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-          if constexpr (DO_V) *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+          *reinterpret_cast<f32x4 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+          *reinterpret_cast<f32x4 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
         }
     }
     return;
@@ -650,8 +787,8 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
         w.y = pack2(dk[dt][rg * 4 + 2] * LN2, dk[dt][rg * 4 + 3] * LN2);
         x.x = pack2(dv[dt][rg * 4 + 0], dv[dt][rg * 4 + 1]);
         x.y = pack2(dv[dt][rg * 4 + 2], dv[dt][rg * 4 + 3]);
-        if constexpr (DO_K) *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
-        if constexpr (DO_V) *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
+        *reinterpret_cast<u32x2 *>(rk_ + dt * 32 + rg * 8 + half * 4) = w;
+        *reinterpret_cast<u32x2 *>(rv_ + dt * 32 + rg * 8 + half * 4) = x;
       }
   }
 }
@@ -663,17 +800,17 @@ __global__ __launch_bounds__(KV_NT) __attribute__((amdgpu_waves_per_eu(2, 2))) v
     bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
     int Hk, int BH, int nkb, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  attn_bwd_dkdv_body<DH, CAUSAL, PARTIAL, KV_NT, 3>(Q, K, V, dO, LSE, DELTA, dK, dV, dKp, dVp, T, Hq, Hk, BH, nkb, scale, smem);
+  attn_bwd_dkdv_body<DH, CAUSAL, PARTIAL, KV_NT>(Q, K, V, dO, LSE, DELTA, dK, dV, dKp, dVp, T, Hq, Hk, BH, nkb, scale, smem);
 }
 
-template <int DH, bool CAUSAL, bool PARTIAL, int PARTS>
+template <int DH, bool CAUSAL, bool PARTIAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void attn_bwd_dkdv_wide_kernel(
     const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K, const bf16_t *__restrict__ V,
     const bf16_t *__restrict__ dO, const float *__restrict__ LSE, const float *__restrict__ DELTA,
     bf16_t *__restrict__ dK, bf16_t *__restrict__ dV, float *__restrict__ dKp, float *__restrict__ dVp, int T, int Hq,
     int Hk, int BH, int nkb, float scale) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  attn_bwd_dkdv_body<DH, CAUSAL, PARTIAL, 256, PARTS>(Q, K, V, dO, LSE, DELTA, dK, dV, dKp, dVp, T, Hq, Hk, BH, nkb, scale, smem);
+  attn_bwd_dkdv_body<DH, CAUSAL, PARTIAL, 256>(Q, K, V, dO, LSE, DELTA, dK, dV, dKp, dVp, T, Hq, Hk, BH, nkb, scale, smem);
 }
 
 // out[(row, g), :] = bf16(sum_r part[(row, g*R + r), :]) for dK and dV, 4 channels per thread, fixed order
@@ -744,20 +881,17 @@ static hipError_t attention_bwd_run(const Dims &d, const void *q, const void *k,
 #define ARGS_KV (const bf16_t *)qs, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)d_o, lse, delta, (bf16_t *)d_k, \
                 (bf16_t *)d_v, pk, pv, d.T, d.Hq, d.Hk, BH, nkb, d.scale
   const unsigned gkv = (unsigned)((long long)BH * nkb);
-  constexpr size_t kv_smem = 4ull * BQT * (DH * 2 + 64);  // the Q / dO tiles of attn_bwd_dkdv_kernel
+  constexpr size_t kv_smem = 4ull * kv_tile_rows(NTH) * (DH * 2 + 64);  // the Q / dO tiles of the dK / dV kernel
   // pairing query blocks only pays while it still leaves a workgroup for each of the 256 CUs; the dK / dV kernel
   // gains nothing from it (measured)
   const int paired = causal && (long long)BH * ((nqb + 1) / 2) >= 256 ? 1 : 0;
   const bool partial = d.R > 1;
   // (the dynamic-LDS limit is raised once per kernel and device: raise_lds_limit)
 #define LAUNCH_KV(C_, P_)                                                                                     \
-  if constexpr (WIDE) { /* dV pass, then dK pass */                                                           \
-    e = raise_lds_limit<attn_bwd_dkdv_wide_kernel<DH, C_, P_, 1>>(kv_smem);                                   \
+  if constexpr (WIDE) {                                                                                       \
+    e = raise_lds_limit<attn_bwd_dkdv_wide_kernel<DH, C_, P_>>(kv_smem);                                      \
     if (e != hipSuccess) return e;                                                                            \
-    e = raise_lds_limit<attn_bwd_dkdv_wide_kernel<DH, C_, P_, 2>>(kv_smem);                                   \
-    if (e != hipSuccess) return e;                                                                            \
-    attn_bwd_dkdv_wide_kernel<DH, C_, P_, 1><<<gkv, NTH, kv_smem, s>>>(ARGS_KV);                               \
-    attn_bwd_dkdv_wide_kernel<DH, C_, P_, 2><<<gkv, NTH, kv_smem, s>>>(ARGS_KV);                               \
+    attn_bwd_dkdv_wide_kernel<DH, C_, P_><<<gkv, NTH, kv_smem, s>>>(ARGS_KV);                                  \
   } else {                                                                                                    \
     e = raise_lds_limit<attn_bwd_dkdv_kernel<DH, C_, P_>>(kv_smem);                                           \
     if (e != hipSuccess) return e;                                                                            \

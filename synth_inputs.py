@@ -40,6 +40,9 @@ WORKLOADS = {
                        dtype="bf16", paper_flags=False),
     "mha_16k": dict(B=1, T=16384, E=2048, Hq=16, Hk=16, dh=128, k_seq=1, k_ch=1,
                     dtype="bf16", paper_flags=False),
+    # the CCGQA layout at the widest head of the paper's kernel figures: same latent widths, 4 / 1 heads x 256
+    "ccgqa_16k_dh256": dict(B=1, T=16384, E=2048, Hq=4, Hk=1, dh=256, k_seq=2, k_ch=2,
+                            dtype="bf16", paper_flags=True),
 }
 
 
