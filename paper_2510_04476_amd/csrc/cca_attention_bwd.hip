@@ -295,7 +295,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(
   // One block of 32 keys of the tile at kp / vp against this wavefront's 32 query rows.  LDS fragments are requested
   // PF products ahead of their use, the first transposed ones before the arithmetic that precedes their chain (left
   // to itself the compiler issues read, wait, MFMA one at a time).
-  constexpr int PF = 2, PT = 3;
+  constexpr int PF = WIDE ? 4 : 2, PT = WIDE ? 4 : 3;  // deeper with one wavefront per SIMD: nothing else hides the LDS latency
   auto block = [&](const unsigned char *kp, const unsigned char *vp, int kv0, int ks, auto masked_t) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_t)::value;
     auto col = [&](const unsigned char *tile, int kk) {
@@ -615,7 +615,7 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
   // requested PF MFMAs ahead of their use (the compiler on its own issues read, wait, MFMA one at a time, and the
   // wavefronts then spend most of their cycles waiting for LDS), the first ones of a chain before the arithmetic
   // that precedes it.
-  constexpr int PF = 2;
+  constexpr int PF = WIDE ? 4 : 2;  // one wavefront per SIMD: nothing else hides the LDS latency
   auto block = [&](const unsigned char *qp, const unsigned char *dp_, int buf, int t0, int qs, auto masked_t) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_t)::value;
     auto col = [&](const unsigned char *tile, int kk) {
@@ -651,29 +651,42 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
     // S -> P, packed to bf16 at once.  Lane (l32, half) holds key kw0 + l32 and query rows t0 + qs*32 + 8*(r/4) +
     // 4*half + r%4.  Masked tiles: the row index relative to t0 + qs*32 + 4*half must lie in [lo, hi] (lo: causal,
     // hi: end of the sequence; a key past the end has an empty range).
-    u32x4 w[2];
-    auto probabilities = [&]() __attribute__((always_inline)) {
-      const int key = kw0 + l32, tb = t0 + qs * 32 + 4 * half;
-      const int lo = CAUSAL ? key - tb : -(1 << 20);
-      const unsigned span = key < T ? (unsigned)(T - 1 - tb - lo) : 0u;
-      const bool none = MASKED && (key >= T || T - 1 - tb < lo);
+    u32x4 w[2], x[2];
+    const int key = kw0 + l32, tb = t0 + qs * 32 + 4 * half;
+    const int lo = CAUSAL ? key - tb : -(1 << 20);
+    const unsigned span = key < T ? (unsigned)(T - 1 - tb - lo) : 0u;
+    const bool none = MASKED && (key >= T || T - 1 - tb < lo);
+    f32x4 st[4];  // log-sum-exp (then Delta) of this lane's 16 query rows
+    auto load_stats = [&](int which) __attribute__((always_inline)) {
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][0][qs * 32 + rg * 8 + half * 4]);
-        float p[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          p[e] = __builtin_amdgcn_exp2f(s[rg * 4 + e] - l4[e]);
-          if (MASKED) p[e] = (!none & ((unsigned)(rg * 8 + e - lo) <= span)) ? p[e] : 0.f;
-        }
-        w[rg >> 1][(rg & 1) * 2 + 0] = pack2(p[0], p[1]);
-        w[rg >> 1][(rg & 1) * 2 + 1] = pack2(p[2], p[3]);
-      }
+      for (int rg = 0; rg < 4; ++rg) st[rg] = *reinterpret_cast<const f32x4 *>(&sStat[buf][which][qs * 32 + rg * 8 + half * 4]);
     };
-    // two wavefronts per SIMD: P is formed between the chains (one accumulator live at a time); one wavefront: both
-    // chains first, so that each result rests while the other chain / the arithmetic on the other result issues
+    // slice g = 0..7 of the arithmetic on S / dP: values 2g, 2g+1 of this lane -> one packed word
+    auto p_slice = [&](int g) __attribute__((always_inline)) {
+      const int rg = g >> 1, pr = g & 1;
+      float pv[2];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        pv[e] = __builtin_amdgcn_exp2f(s[rg * 4 + 2 * pr + e] - st[rg][2 * pr + e]);
+        if (MASKED) pv[e] = (!none & ((unsigned)(rg * 8 + 2 * pr + e - lo) <= span)) ? pv[e] : 0.f;
+      }
+      w[rg >> 1][(rg & 1) * 2 + pr] = pack2(pv[0], pv[1]);
+    };
+    auto ds_slice = [&](int g) __attribute__((always_inline)) {  // dS = P (dP - Delta), P taken back from its bf16 form
+      const int rg = g >> 1, pr = g & 1;
+      const uint32_t pw = w[rg >> 1][(rg & 1) * 2 + pr];
+      x[rg >> 1][(rg & 1) * 2 + pr] = pack2(bf_lo(pw) * (dp[rg * 4 + 2 * pr] - st[rg][2 * pr]),
+                                           bf_hi(pw) * (dp[rg * 4 + 2 * pr + 1] - st[rg][2 * pr + 1]));
+    };
+    // Two wavefronts per SIMD: P is formed between the chains (one accumulator live at a time) and dS after the dP
+    // chain.  One wavefront: nothing else fills the matrix core while this wavefront does arithmetic, so the
+    // arithmetic on S is issued in slices between the MFMAs of the dP chain and the arithmetic on dP between the
+    // dV products (which need P only); each chain's result is first touched behind an MFMA that had to wait for
+    // one issued after the chain's last.
+    load_stats(0);
     if constexpr (!WIDE) {
-      probabilities();
+#pragma unroll
+      for (int g = 0; g < 8; ++g) p_slice(g);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int r = 0; r < 16; ++r) dp[r] = 0.f;
@@ -690,23 +703,23 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
       if constexpr (WIDE) dp = kk == 0 ? chain_mfma0(da, vb) : chain_mfma(da, vb, dp);
       else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, dp, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
+      if constexpr (WIDE) {
+        // S is first read after the third MFMA of this chain: each link waits for the one before it, so two whole
+        // MFMAs have run since the S chain's last one was issued
+        static_assert(!WIDE || KK >= 11, "eight slices after the third MFMA of the chain");
+        if (kk == 2) chain_fence(s);
+        if (kk >= 3 && kk < 11) {
+          p_slice(kk - 3);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
-    if constexpr (WIDE) {
-      chain_fence(s);  // S is read from here on: the whole dP chain was issued since its last MFMA
-      probabilities();
-      chain_fence(dp, w[0], w[1]);  // dP is read from here on: P has been formed since its last MFMA
-    }
+    load_stats(1);
     pf[0] = __builtin_bit_cast(bf16x8, w[0]);
     pf[1] = __builtin_bit_cast(bf16x8, w[1]);
-    {  // dS = P (dP - Delta), P taken back from its bf16 form
-      u32x4 x[2];
+    if constexpr (!WIDE) {
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][1][qs * 32 + rg * 8 + half * 4]);
-        const uint32_t p01 = w[rg >> 1][(rg & 1) * 2 + 0], p23 = w[rg >> 1][(rg & 1) * 2 + 1];
-        x[rg >> 1][(rg & 1) * 2 + 0] = pack2(bf_lo(p01) * (dp[rg * 4 + 0] - d4[0]), bf_hi(p01) * (dp[rg * 4 + 1] - d4[1]));
-        x[rg >> 1][(rg & 1) * 2 + 1] = pack2(bf_lo(p23) * (dp[rg * 4 + 2] - d4[2]), bf_hi(p23) * (dp[rg * 4 + 3] - d4[3]));
-      }
+      for (int g = 0; g < 8; ++g) ds_slice(g);
       dsf[0] = __builtin_bit_cast(bf16x8, x[0]);
       dsf[1] = __builtin_bit_cast(bf16x8, x[1]);
     }
@@ -726,6 +739,24 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
         else dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f, dsf[jj], dk[dt], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);
+      if constexpr (WIDE) {
+        // dP is first read after dV product DT: it waits for product 0 on the same accumulator, which entered the
+        // matrix core behind the dP chain's last MFMA.  (Independent MFMAs do not wait for one another at issue:
+        // reading dP after two of them gave wrong dK on the GPU.)
+        static_assert(!WIDE || DT == 8, "eight slices under the second half of the dV products");
+        if (i == DT) chain_fence(dp);
+        if (i >= DT && i < 2 * DT) {
+          ds_slice(i - DT);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        if (i == 2 * DT - 1) {
+          // both halves of dS packed here, in registers of their own: packed later, the second half landed in the
+          // registers of the first right behind the last MFMA that read them, and dK came out wrong on the GPU
+          asm volatile("" : "+v"(x[0]), "+v"(x[1]));
+          dsf[0] = __builtin_bit_cast(bf16x8, x[0]);
+          dsf[1] = __builtin_bit_cast(bf16x8, x[1]);
+        }
+      }
     }
   };
 

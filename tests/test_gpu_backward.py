@@ -233,8 +233,9 @@ def test_backward_mha_flags():
     say(compare(got, oracle_backward(w, inp, d_out), "bf16", skip=("d_w_conv_seq", "d_w_conv_ch", "d_temp")))
 
 
-def test_backward_is_deterministic():
-    w = SMALL[3]
+@pytest.mark.parametrize("i", [3, 15])
+def test_backward_is_deterministic(i):
+    w = SMALL[i]
     inp = make_inputs(w, seed=43, conv_visible=True)
     d_out = make_upstream_grad(w, seed=1)
     got1, (cfg, x, wt, saved, g) = gpu_backward(w, inp, d_out)

@@ -387,6 +387,34 @@ def test_attention_backward_stage(T, Hq, Hk, causal, dh):
     say("dv", check_tap(to_np(g_v), r_v, "bf16", "d_v"))
 
 
+def test_attention_head_width_256_is_bit_identical_from_run_to_run():
+    """The d_h = 256 attention kernels (forward and backward) issue MFMAs as inline assembly, whose hazards the
+    compiler does not pad; a violated hazard shows as results that change from run to run (seen during development:
+    an operand written by the vector ALU directly in front of such an MFMA).  Twelve runs over several blocks per
+    head must give the same bits."""
+    T, Hq, Hk, dh = 3000, 4, 2, 256
+    say("case determinism d_h 256", T, Hq, Hk)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    rn = lambda *sh: torch.randn(*sh, device="cuda", generator=g)
+    unit = lambda t, H: (t.view(1, T, H, dh) * dh ** 0.5 / t.view(1, T, H, dh).norm(dim=-1, keepdim=True)).to(torch.bfloat16).view(1, T, -1)
+    q, k = unit(rn(1, T, Hq * dh), Hq), unit(rn(1, T, Hk * dh), Hk)
+    v, d_o = rn(1, T, Hk * dh).to(torch.bfloat16), rn(1, T, Hq * dh).to(torch.bfloat16)
+    cfg = P.CCAConfig(B=1, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh)
+    temp = torch.zeros(Hk, device="cuda")
+    first = None
+    for _ in range(12):
+        o_lo = torch.empty_like(q)
+        o, lse = P.cca_attention(cfg, q, k, v, want_lse=True, temp=temp, o_lo=o_lo)
+        g_q, g_k, g_v = P.cca_attention_backward(cfg, q, k, v, o, lse, d_o, o_lo=o_lo)
+        torch.cuda.synchronize()
+        cur = (o, lse, o_lo, g_q, g_k, g_v)
+        assert all(bool(torch.isfinite(t.float()).all()) for t in cur)
+        if first is None:
+            first = cur
+        else:
+            assert all(torch.equal(a, b) for a, b in zip(first, cur))
+
+
 # ---- config 4: CCGQA vs MHA head-to-head at B = 4, T = 16384, both through the same kernels.  The HIP path runs
 #      the full batch; the oracle (batch items are independent) checks the first and the last item on sampled rows.
 @pytest.mark.parametrize("name", ["ccgqa_16k_b4", "mha_16k_b4"])
