@@ -260,10 +260,12 @@ def test_backward_ccgqa_4k_dense():
 # ---- config 5 at full size (T = 16384): the backward is linear in d_out, so an upstream gradient supported on a
 #      sample of rows is checked exactly: the oracle visits only those query rows, the HIP path runs its
 #      ordinary full-size launch configuration ------------------------------------------------------------------
-@pytest.mark.parametrize("conv_visible", [False, True])
-def test_backward_ccgqa_16k_sampled_rows(conv_visible):
-    w = WORKLOADS["ccgqa_16k"]
-    say("case backward ccgqa_16k, d_out on sampled rows, conv_visible", conv_visible)
+@pytest.mark.parametrize("name,conv_visible", [("ccgqa_16k", False), ("ccgqa_16k", True), ("ccgqa_16k_dh256", True)])
+def test_backward_ccgqa_16k_sampled_rows(name, conv_visible):
+    """(ccgqa_16k_dh256: the same layer with 4 / 1 heads of width 256: the launch that pairs query blocks in the
+    one-wavefront dQ kernel, 128 blocks of 128 rows per head.)"""
+    w = WORKLOADS[name]
+    say("case backward", name, "d_out on sampled rows, conv_visible", conv_visible)
     inp = make_inputs(w, seed=0, conv_visible=conv_visible)
     rows = sample_rows(w["T"], 96)
     d_out = np.zeros((w["B"], w["T"], w["E"]), np.float32)

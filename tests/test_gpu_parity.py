@@ -276,10 +276,11 @@ def test_cca_4k(conv_visible):
 
 # ---- config 3: CCGQA prefill bf16, T = 16384: prologue taps on every token,
 #      attention / out on sampled rows (row t needs only keys <= t) -----------
-def test_ccgqa_16k_sampled_rows():
-    w = WORKLOADS["ccgqa_16k"]
-    say("case ccgqa_16k")
-    inp = make_inputs(w, seed=0)
+@pytest.mark.parametrize("name", ["ccgqa_16k", "ccgqa_16k_dh256"])
+def test_ccgqa_16k_sampled_rows(name):
+    w = WORKLOADS[name]
+    say("case", name)
+    inp = make_inputs(w, seed=0, conv_visible=name != "ccgqa_16k")
     _, out, saved = run_gpu(w, inp)
     rows = sample_rows(w["T"], 192)
     ref = oracle_forward(w, inp, rows=rows)
