@@ -513,7 +513,9 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
   // smem: Q0 Q1 dO0 dO1, 4 * TILE bytes of dynamic LDS (with a static array the compiler makes every LDS read wait
   // for the tile loads in flight (vmcnt(0): a load into LDS might alias what is read), which puts the latency of the
   // next tile's loads in front of each step)
-  __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];                                      // [buf][lse2 | delta][row]
+  // [buf][-lse2 | -Delta][row]: the S and dP chains START from these (lane = key, register = query row), so that the
+  // chains deliver S - lse and dP - Delta and the arithmetic needs no subtraction
+  __shared__ __attribute__((aligned(16))) float sStat[2][2][BQT];
   // this workgroup's V rows as MFMA operand fragments, [wavefront][kk][lane] x 16 bytes: each wavefront keeps its own
   // (read back one fragment per dP product; holding them in registers next to the K fragments and the two
   // accumulators leaves no room for fragments requested ahead of their use)
@@ -607,7 +609,7 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
     }
   };
   auto land_tile = [&](int buf) {  // before the barrier that publishes the tile
-    if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = tid < BQT ? rstat * LOG2E : rstat;
+    if (tid < 2 * BQT) sStat[buf][tid / BQT][tid & (BQT - 1)] = tid < BQT ? -rstat * LOG2E : -rstat;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   };
 
@@ -631,11 +633,18 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
     bf16x8 tv[PF];  // transposed fragments of the first products of the last phase, requested under the dP chain
 #pragma unroll
     for (int i = 0; i < PF; ++i) fr[i] = col(qp, i);
-    f32x16 s, dp;  // S[t, key], dP[t, key]
-    if constexpr (!WIDE) {
+    // S[t, key] - lse[t] and dP[t, key] - Delta[t]: the chains start from minus the row statistics
+    auto stats = [&](int which) __attribute__((always_inline)) {
+      f32x16 v;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
-    }
+      for (int rg = 0; rg < 4; ++rg) {
+        const f32x4 q4 = *reinterpret_cast<const f32x4 *>(&sStat[buf][which][qs * 32 + rg * 8 + half * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[rg * 4 + e] = q4[e];
+      }
+      return v;
+    };
+    f32x16 s = stats(0), dp;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       const bf16x8 qa = __builtin_bit_cast(bf16x8, fr[kk % PF]);
@@ -644,7 +653,7 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
         fd[kk + PF - KK] = col(dp_, kk + PF - KK);
         fv[kk + PF - KK] = sVf[wave][kk + PF - KK][lane];
       }
-      if constexpr (WIDE) s = kk == 0 ? chain_mfma0(qa, kf[0]) : chain_mfma(qa, kf[kk], s);
+      if constexpr (WIDE) s = chain_mfma(qa, kf[kk], s);
       else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, kf[kk], s, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -656,41 +665,33 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
     const int lo = CAUSAL ? key - tb : -(1 << 20);
     const unsigned span = key < T ? (unsigned)(T - 1 - tb - lo) : 0u;
     const bool none = MASKED && (key >= T || T - 1 - tb < lo);
-    f32x4 st[4];  // log-sum-exp (then Delta) of this lane's 16 query rows
-    auto load_stats = [&](int which) __attribute__((always_inline)) {
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) st[rg] = *reinterpret_cast<const f32x4 *>(&sStat[buf][which][qs * 32 + rg * 8 + half * 4]);
-    };
     // slice g = 0..7 of the arithmetic on S / dP: values 2g, 2g+1 of this lane -> one packed word
     auto p_slice = [&](int g) __attribute__((always_inline)) {
       const int rg = g >> 1, pr = g & 1;
       float pv[2];
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
-        pv[e] = __builtin_amdgcn_exp2f(s[rg * 4 + 2 * pr + e] - st[rg][2 * pr + e]);
+        pv[e] = __builtin_amdgcn_exp2f(s[rg * 4 + 2 * pr + e]);
         if (MASKED) pv[e] = (!none & ((unsigned)(rg * 8 + 2 * pr + e - lo) <= span)) ? pv[e] : 0.f;
       }
       w[rg >> 1][(rg & 1) * 2 + pr] = pack2(pv[0], pv[1]);
     };
-    auto ds_slice = [&](int g) __attribute__((always_inline)) {  // dS = P (dP - Delta), P taken back from its bf16 form
+    auto ds_slice = [&](int g) __attribute__((always_inline)) {  // dS = P (dP - Delta): P taken back from its bf16 form, times the chain's result
       const int rg = g >> 1, pr = g & 1;
       const uint32_t pw = w[rg >> 1][(rg & 1) * 2 + pr];
-      x[rg >> 1][(rg & 1) * 2 + pr] = pack2(bf_lo(pw) * (dp[rg * 4 + 2 * pr] - st[rg][2 * pr]),
-                                           bf_hi(pw) * (dp[rg * 4 + 2 * pr + 1] - st[rg][2 * pr + 1]));
+      x[rg >> 1][(rg & 1) * 2 + pr] = pack2(bf_lo(pw) * dp[rg * 4 + 2 * pr], bf_hi(pw) * dp[rg * 4 + 2 * pr + 1]);
     };
     // Two wavefronts per SIMD: P is formed between the chains (one accumulator live at a time) and dS after the dP
     // chain.  One wavefront: nothing else fills the matrix core while this wavefront does arithmetic, so the
     // arithmetic on S is issued in slices between the MFMAs of the dP chain and the arithmetic on dP between the
     // dV products (which need P only); each chain's result is first touched behind an MFMA that had to wait for
     // one issued after the chain's last.
-    load_stats(0);
     if constexpr (!WIDE) {
 #pragma unroll
       for (int g = 0; g < 8; ++g) p_slice(g);
       __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) dp[r] = 0.f;
     }
+    dp = stats(1);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {  // dP[t, key]
       const bf16x8 da = __builtin_bit_cast(bf16x8, fd[kk % PF]), vb = __builtin_bit_cast(bf16x8, fv[kk % PF]);
@@ -700,7 +701,7 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
       } else {
         tv[kk + PF - KK] = frag_of(kk + PF - KK);
       }
-      if constexpr (WIDE) dp = kk == 0 ? chain_mfma0(da, vb) : chain_mfma(da, vb, dp);
+      if constexpr (WIDE) dp = chain_mfma(da, vb, dp);
       else dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, vb, dp, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (WIDE) {
@@ -714,7 +715,6 @@ __device__ __forceinline__ void attn_bwd_dkdv_body(
         }
       }
     }
-    load_stats(1);
     pf[0] = __builtin_bit_cast(bf16x8, w[0]);
     pf[1] = __builtin_bit_cast(bf16x8, w[1]);
     if constexpr (!WIDE) {
