@@ -388,19 +388,21 @@ def test_attention_backward_stage(T, Hq, Hk, causal, dh):
     say("dv", check_tap(to_np(g_v), r_v, "bf16", "d_v"))
 
 
-def test_attention_head_width_256_is_bit_identical_from_run_to_run():
+@pytest.mark.parametrize("Hq,Hk,causal", [(4, 2, True), (2, 2, True), (4, 1, False), (3, 3, False)])
+def test_attention_head_width_256_is_bit_identical_from_run_to_run(Hq, Hk, causal):
     """The d_h = 256 attention kernels (forward and backward) issue MFMAs as inline assembly, whose hazards the
     compiler does not pad; a violated hazard shows as results that change from run to run (seen during development:
     an operand written by the vector ALU directly in front of such an MFMA).  Twelve runs over several blocks per
     head must give the same bits."""
-    T, Hq, Hk, dh = 3000, 4, 2, 256
-    say("case determinism d_h 256", T, Hq, Hk)
+    T, dh = 3000, 256  # (every compiled form of the backward kernels: causal or not, one or several query heads per KV head)
+    say("case determinism d_h 256", T, Hq, Hk, causal)
     g = torch.Generator(device="cuda").manual_seed(5)
     rn = lambda *sh: torch.randn(*sh, device="cuda", generator=g)
     unit = lambda t, H: (t.view(1, T, H, dh) * dh ** 0.5 / t.view(1, T, H, dh).norm(dim=-1, keepdim=True)).to(torch.bfloat16).view(1, T, -1)
     q, k = unit(rn(1, T, Hq * dh), Hq), unit(rn(1, T, Hk * dh), Hk)
     v, d_o = rn(1, T, Hk * dh).to(torch.bfloat16), rn(1, T, Hq * dh).to(torch.bfloat16)
-    cfg = P.CCAConfig(B=1, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh)
+    flags = B.CCA_FLAGS_PAPER if causal else B.CCA_FLAGS_PAPER & ~B.CCA_CAUSAL
+    cfg = P.CCAConfig(B=1, T=T, d_model=Hq * dh, n_q_heads=Hq, n_kv_heads=Hk, head_dim=dh, flags=flags)
     temp = torch.zeros(Hk, device="cuda")
     first = None
     for _ in range(12):
