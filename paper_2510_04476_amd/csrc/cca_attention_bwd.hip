@@ -239,13 +239,17 @@ __device__ __forceinline__ void attn_bwd_dq_body(
       *reinterpret_cast<u32x4 *>(dst + buf * TILE + o) = r[i];
     }
   };
-  auto load_tile = [&](int kv0) {
-    load_half(Kg, rk, kv0);
-    load_half(Vg, rv, kv0);
+  auto load_tile = [&](int kv0) {  // two wavefronts per SIMD only
+    if constexpr (!WIDE) {
+      load_half(Kg, rk, kv0);
+      load_half(Vg, rv, kv0);
+    }
   };
   auto store_tile = [&](int buf) {
-    store_half(sK, rk, buf);
-    store_half(sV, rv, buf);
+    if constexpr (!WIDE) {
+      store_half(sK, rk, buf);
+      store_half(sV, rv, buf);
+    }
   };
 
   // Causal work per query block grows with its index: heavy blocks are issued first (unpaired), or each
